@@ -1,0 +1,11 @@
+"""fp64 CPU oracle for tree attention (test infrastructure only).
+
+Only tests, the smoke check and the bench's cpu_baseline leg may import this
+package.  It shares no code with the HIP path and never imports it.
+"""
+from .treeattn_oracle import (  # noqa: F401
+    build_oracle,
+    oracle_threads,
+    tree_attn_oracle,
+    tree_attn_oracle_sample,
+)

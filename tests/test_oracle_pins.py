@@ -1,0 +1,351 @@
+"""Pins of the fp64 oracle against things other than itself (CPU only).
+
+Each test fixes one part of the definition in paper section 3.1 ("Tree attention": a node sees the
+cached context plus its own root-to-node path, equivalent to unrolling every path into a causal
+prefill) or section 3.4 ("Paged KV with tree attention": paging only relocates blocks).
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from oracle.brute_force import brute_force_tree_attention
+from paper_2508_08192_amd import workloads as W
+
+from .helpers import ancestors_inclusive, logical_kv, run_oracle, widen
+
+
+def _sdpa(q, K, V, mask, scale):
+    """Library attention in fp64: q [H, Tq, D], K/V [H, n, D], mask bool [Tq, n] or None."""
+    qt, kt, vt = (torch.from_numpy(np.ascontiguousarray(x)) for x in (q, K, V))
+    m = None if mask is None else torch.from_numpy(mask)
+    out = F.scaled_dot_product_attention(qt, kt, vt, attn_mask=m, scale=scale)
+    s = torch.einsum("htd,hnd->htn", qt, kt) * scale
+    if m is not None:
+        s = s.masked_fill(~m, float("-inf"))
+    return out.numpy(), torch.logsumexp(s, dim=-1).numpy()
+
+
+def _expand_heads(K, G):
+    return np.repeat(K, G, axis=0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L", [0, 1, 37, 130])
+def test_chain_tree_is_causal_attention(dtype, L):
+    B, T, Hq, Hkv, D = 2, 9, 4, 2, 16
+    w = W.make_workload("chain", B=B, T=T, Hq=Hq, Hkv=Hkv, D=D, seq_lens=[L, L + 3], trees=W.chain_tree(T),
+                        page_size=8, dtype=dtype, seed=11)
+    out, lse = run_oracle(w)
+    for b in range(B):
+        Lb = int(w.seq_lens[b])
+        K, V = logical_kv(w, b)
+        q = np.transpose(widen(w.q[b]), (1, 0, 2))                      # [Hq, T, D]
+        mask = np.zeros((T, Lb + T), dtype=bool)
+        for i in range(T):
+            mask[i, : Lb + i + 1] = True                                 # bottom-right aligned causal mask
+        ref, ref_lse = _sdpa(q, _expand_heads(K, Hq // Hkv), _expand_heads(V, Hq // Hkv), mask, w.scale)
+        np.testing.assert_allclose(np.transpose(out[b], (1, 0, 2)), ref, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(lse[b], ref_lse, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("paged", [True, False])
+def test_single_node_is_decode_attention(paged):
+    B, Hq, Hkv, D = 3, 6, 3, 32
+    w = W.make_workload("decode", B=B, T=1, Hq=Hq, Hkv=Hkv, D=D, seq_lens=[0, 17, 64], trees=np.int32([-1]),
+                        page_size=16, dtype="bf16", seed=5, paged=paged)
+    out, lse = run_oracle(w)
+    for b in range(B):
+        K, V = logical_kv(w, b)
+        q = np.transpose(widen(w.q[b]), (1, 0, 2))
+        ref, ref_lse = _sdpa(q, _expand_heads(K, 2), _expand_heads(V, 2), None, w.scale)
+        np.testing.assert_allclose(np.transpose(out[b], (1, 0, 2)), ref, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(lse[b], ref_lse, rtol=0, atol=1e-12)
+
+
+def _all_forests(T):
+    """Every parent array with parent[i] in {-1, 0..i-1} and parent[0] = -1."""
+    for rest in itertools.product(*[range(-1, i) for i in range(1, T)]):
+        yield np.asarray((-1,) + rest, dtype=np.int32)
+
+
+def _brute(w):
+    ps = w.page_size
+
+    def fetch(cache):
+        def f(b, g, pos):
+            if w.page_table is None:
+                page, slot = b, pos
+            else:
+                page, slot = int(w.page_table[b, pos // ps]), pos % ps
+            return [float(x) for x in widen(cache[page, g, slot, :])]
+        return f
+
+    q = [[[[float(x) for x in widen(w.q[b, i, h])] for h in range(w.Hq)] for i in range(w.T)] for b in range(w.B)]
+    par = w.parents_2d()
+    return brute_force_tree_attention(q, fetch(w.k_cache), fetch(w.v_cache), [int(x) for x in w.seq_lens],
+                                      [list(map(int, par[b])) for b in range(w.B)], w.Hq // w.Hkv, w.scale)
+
+
+def _assert_matches_brute(w):
+    out, lse = run_oracle(w)
+    bo, bl = _brute(w)
+    np.testing.assert_allclose(out, np.asarray(bo), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(lse, np.asarray(bl), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 4, 5])
+def test_brute_force_every_tree_shape(T):
+    rng = np.random.default_rng(T)
+    shapes = list(_all_forests(T))
+    for n, parent in enumerate(shapes):
+        trees = np.stack([parent, shapes[(n * 7 + 3) % len(shapes)]])
+        if n % 3 == 2:                      # also non-topological node numbering
+            trees = np.stack([W.shuffle_tree(t, rng)[0] for t in trees])
+        w = W.make_workload("tiny", B=2, T=T, Hq=2, Hkv=1, D=8, seq_lens=[[0, 5], [1, 0], [5, 1]][n % 3],
+                            trees=trees, page_size=4, dtype="f32" if n % 2 else "bf16", seed=100 + n)
+        _assert_matches_brute(w)
+
+
+def test_brute_force_gqa_and_seven_node_binary_tree():
+    tree = np.int32([-1, 0, 0, 1, 1, 2, 2])
+    w = W.make_workload("tiny7", B=2, T=7, Hq=4, Hkv=2, D=8, seq_lens=[6, 3], trees=tree, page_size=4,
+                        dtype="bf16", seed=3)
+    _assert_matches_brute(w)
+    w = W.make_workload("tiny7c", B=1, T=7, Hq=4, Hkv=1, D=8, seq_lens=[9], trees=tree, page_size=0,
+                        dtype="f32", seed=4, paged=False)
+    _assert_matches_brute(w)
+
+
+def test_zero_query_counts_attended_keys():
+    """q = 0 makes every score 0: lse = ln(#attended keys) = ln(L_b + level(i)), out = mean of attended V."""
+    rng = np.random.default_rng(0)
+    B, T = 3, 12
+    trees = np.stack([W.random_tree(T, 5, rng), W.chain_tree(T), W.bfs_tree(T, [3, 2], 4)])
+    w = W.make_workload("zq", B=B, T=T, Hq=4, Hkv=2, D=16, seq_lens=[0, 7, 33], trees=trees, page_size=8,
+                        dtype="bf16", seed=8)
+    w.q[...] = 0
+    out, lse = run_oracle(w)
+    for b in range(B):
+        lv = W.node_levels(trees[b])
+        K, V = logical_kv(w, b)
+        Lb = int(w.seq_lens[b])
+        for i in range(T):
+            np.testing.assert_allclose(lse[b, :, i], math.log(Lb + lv[i]), rtol=0, atol=1e-13)
+            rows = list(range(Lb)) + [Lb + j for j in ancestors_inclusive(trees[b], i)]
+            for h in range(4):
+                np.testing.assert_allclose(out[b, i, h], V[h // 2][rows].mean(axis=0), rtol=0, atol=1e-13)
+
+
+def test_non_ancestors_are_invisible_and_ancestors_are_not():
+    rng = np.random.default_rng(1)
+    T = 10
+    tree = W.random_tree(T, 4, rng)
+    w = W.make_workload("blind", B=1, T=T, Hq=2, Hkv=1, D=16, seq_lens=[3], trees=tree, page_size=4,
+                        dtype="f32", seed=9)
+    base, base_lse = run_oracle(w)
+    L = 3
+    for j in range(T):
+        w2 = W.make_workload("blind", B=1, T=T, Hq=2, Hkv=1, D=16, seq_lens=[3], trees=tree, page_size=4,
+                             dtype="f32", seed=9)
+        pos = L + j
+        page, slot = int(w2.page_table[0, pos // 4]), pos % 4
+        w2.k_cache[page, :, slot, :] += 1.5
+        w2.v_cache[page, :, slot, :] -= 2.5
+        out, lse = run_oracle(w2)
+        for i in range(T):
+            if j in ancestors_inclusive(tree, i):
+                assert np.abs(out[0, i] - base[0, i]).max() > 1e-6
+            else:
+                assert np.array_equal(out[0, i], base[0, i]) and np.array_equal(lse[0, :, i], base_lse[0, :, i])
+
+
+def test_planted_key_selects_its_value_row():
+    tree = np.int32([-1, 0, 0, 1, 1, 2, 2])
+    kw = dict(B=1, T=7, Hq=1, Hkv=1, D=16, seq_lens=[5], trees=tree, page_size=4, dtype="f32", seed=21)
+    w = W.make_workload("plant", **kw)
+    # node 4's ancestors: 0, 1, 4.  Plant on ancestor 1: K_1 = 50 * q_4  -> out_4 ~= V_1
+    pos = 5 + 1
+    page, slot = int(w.page_table[0, pos // 4]), pos % 4
+    w.k_cache[page, 0, slot, :] = 50.0 * w.q[0, 4, 0, :]
+    out, _ = run_oracle(w)
+    np.testing.assert_allclose(out[0, 4, 0], w.v_cache[page, 0, slot, :], atol=1e-6)
+    # plant on node 2 (not an ancestor of 4): node 4 must not move
+    w0 = W.make_workload("plant", **kw)
+    base, _ = run_oracle(w0)
+    pos = 5 + 2
+    page, slot = int(w0.page_table[0, pos // 4]), pos % 4
+    w0.k_cache[page, 0, slot, :] = 50.0 * w0.q[0, 4, 0, :]
+    out2, _ = run_oracle(w0)
+    assert np.array_equal(out2[0, 4], base[0, 4])
+    assert np.abs(out2[0, 5] - base[0, 5]).max() > 1e-9       # node 5 does descend from node 2
+
+
+def test_path_unrolling_equals_causal_prefill():
+    """Each root-to-leaf path, laid out behind the prefix and run as causal attention (library routine),
+    reproduces the outputs of the nodes on that path (section 3.1, the naive formulation)."""
+    rng = np.random.default_rng(2)
+    T, Hq, Hkv, D = 16, 4, 2, 16
+    for ps, L in [(8, 7), (8, 8), (8, 9), (8, 0), (8, 1), (16, 40)]:
+        tree = W.random_tree(T, 5, rng)
+        w = W.make_workload("unroll", B=1, T=T, Hq=Hq, Hkv=Hkv, D=D, seq_lens=[L], trees=tree, page_size=ps,
+                            dtype="bf16", seed=31 + L)
+        out, lse = run_oracle(w)
+        K, V = logical_kv(w, 0)
+        leaves = [i for i in range(T) if i not in set(tree.tolist())]
+        covered = set()
+        for leaf in leaves:
+            path = ancestors_inclusive(tree, leaf)
+            rows = list(range(L)) + [L + j for j in path]
+            q = np.transpose(widen(w.q[0, path]), (1, 0, 2))
+            n = len(path)
+            mask = np.zeros((n, L + n), dtype=bool)
+            for a in range(n):
+                mask[a, : L + a + 1] = True
+            ref, ref_lse = _sdpa(q, _expand_heads(K[:, rows], 2), _expand_heads(V[:, rows], 2), mask, w.scale)
+            np.testing.assert_allclose(np.transpose(out[0, path], (1, 0, 2)), ref, rtol=0, atol=1e-12)
+            np.testing.assert_allclose(lse[0][:, path], ref_lse, rtol=0, atol=1e-12)
+            covered.update(path)
+        assert covered == set(range(T))
+
+
+def test_relabelling_nodes_permutes_outputs():
+    rng = np.random.default_rng(3)
+    T, L, ps = 12, 6, 4
+    tree = W.random_tree(T, 5, rng)
+    w = W.make_workload("relabel", B=1, T=T, Hq=2, Hkv=2, D=8, seq_lens=[L], trees=tree, page_size=ps,
+                        dtype="bf16", seed=41, permute=False)
+    out, lse = run_oracle(w)
+    new_parent, perm = W.shuffle_tree(tree, rng)
+    w2 = W.make_workload("relabel", B=1, T=T, Hq=2, Hkv=2, D=8, seq_lens=[L], trees=new_parent, page_size=ps,
+                         dtype="bf16", seed=41, permute=False)
+
+    def slot(pos):
+        return int(w.page_table[0, pos // ps]), pos % ps
+
+    for i in range(T):
+        w2.q[0, perm[i]] = w.q[0, i]
+        (p_old, s_old), (p_new, s_new) = slot(L + i), slot(L + int(perm[i]))
+        w2.k_cache[p_new, :, s_new] = w.k_cache[p_old, :, s_old]
+        w2.v_cache[p_new, :, s_new] = w.v_cache[p_old, :, s_old]
+    out2, lse2 = run_oracle(w2)
+    for i in range(T):
+        np.testing.assert_allclose(out2[0, perm[i]], out[0, i], rtol=0, atol=1e-13)
+        np.testing.assert_allclose(lse2[0, :, perm[i]], lse[0, :, i], rtol=0, atol=1e-13)
+
+
+def test_page_permutation_and_layout_do_not_matter():
+    rng = np.random.default_rng(4)
+    B, T, Hq, Hkv, D, ps = 3, 8, 4, 2, 16, 8
+    trees = np.stack([W.random_tree(T, 4, rng) for _ in range(B)])
+    lens = [5, 23, 16]
+    w = W.make_workload("perm", B=B, T=T, Hq=Hq, Hkv=Hkv, D=D, seq_lens=lens, trees=trees, page_size=ps,
+                        dtype="bf16", seed=51, permute=True)
+    out, lse = run_oracle(w)
+    # same logical content in a contiguous cache [B, Hkv, S, D]
+    S = max(lens) + T
+    kc = np.zeros((B, Hkv, S, D), dtype=np.uint16)
+    vc = np.zeros_like(kc)
+    for b in range(B):
+        for pos in range(lens[b] + T):
+            page, slot = int(w.page_table[b, pos // ps]), pos % ps
+            kc[b, :, pos] = w.k_cache[page, :, slot]
+            vc[b, :, pos] = w.v_cache[page, :, slot]
+    out2, lse2 = oracle.tree_attn_oracle(w.q, kc, vc, None, w.seq_lens, w.tree_parent, scale=w.scale)
+    assert np.array_equal(out, out2) and np.array_equal(lse, lse2)
+    # token-major physical layout [num_pages, ps, Hkv, D] viewed as [num_pages, Hkv, ps, D]
+    kt = np.ascontiguousarray(np.transpose(w.k_cache, (0, 2, 1, 3))).transpose(0, 2, 1, 3)
+    vt = np.ascontiguousarray(np.transpose(w.v_cache, (0, 2, 1, 3))).transpose(0, 2, 1, 3)
+    out3, lse3 = oracle.tree_attn_oracle(w.q, kt, vt, w.page_table, w.seq_lens, w.tree_parent, scale=w.scale)
+    assert np.array_equal(out, out3) and np.array_equal(lse, lse3)
+
+
+def test_query_head_reads_kv_head_h_div_g():
+    B, T, Hq, Hkv, D = 2, 5, 8, 4, 8
+    w = W.make_workload("gqa", B=B, T=T, Hq=Hq, Hkv=Hkv, D=D, seq_lens=[9, 2], trees=W.bfs_tree(T, [2], 3),
+                        page_size=4, dtype="f32", seed=61)
+    for g in range(Hkv):
+        w.v_cache[:, g] = float(g)
+    out, _ = run_oracle(w)
+    for h in range(Hq):
+        np.testing.assert_allclose(out[:, :, h, :], h // 2, rtol=0, atol=1e-13)
+
+
+def test_constant_values_and_no_garbage_leak():
+    """Unowned cache slots hold 3e4; any leak would push an output far outside the range of the owned V rows."""
+    rng = np.random.default_rng(6)
+    T, ps = 6, 8
+    for L in [0, 1, ps - 1, ps, ps + 1, 2 * ps - T, 2 * ps - T + 1]:
+        w = W.make_workload("leak", B=2, T=T, Hq=2, Hkv=1, D=8, seq_lens=[L, L + 2], trees=W.random_tree(T, 3, rng),
+                            page_size=ps, dtype="bf16", seed=71 + L)
+        out, lse = run_oracle(w)
+        for b in range(2):
+            _, V = logical_kv(w, b)
+            assert out[b].max() <= V.max() + 1e-12 and out[b].min() >= V.min() - 1e-12
+        assert np.isfinite(lse).all()
+
+
+def test_scale_is_applied_to_scores():
+    tree = W.chain_tree(3)
+    w = W.make_workload("scale", B=1, T=3, Hq=1, Hkv=1, D=4, seq_lens=[2], trees=tree, page_size=4, dtype="f32",
+                        seed=81, scale=0.37)
+    out, lse = run_oracle(w)
+    K, V = logical_kv(w, 0)
+    q = widen(w.q[0, 2, 0])
+    s = 0.37 * K[0] @ q
+    p = np.exp(s - s.max())
+    np.testing.assert_allclose(out[0, 2, 0], (p / p.sum()) @ V[0], atol=1e-13)
+    np.testing.assert_allclose(lse[0, 0, 2], s.max() + math.log(p.sum()), atol=1e-13)
+
+
+def test_malformed_requests_are_poisoned_alone():
+    T = 4
+    trees = np.int32([[-1, 0, 1, 2], [-1, 0, 3, 2], [-1, 0, 7, 1], [-1, 0, 0, 0]])   # ok, cycle, out of range, ok
+    w = W.make_workload("bad", B=4, T=T, Hq=2, Hkv=1, D=8, seq_lens=[3, 3, 3, 3], trees=trees, page_size=4,
+                        dtype="f32", seed=91)
+    out, lse = run_oracle(w)
+    assert np.isfinite(out[0]).all() and np.isfinite(out[3]).all()
+    assert np.isnan(out[1]).all() and np.isnan(out[2]).all() and np.isnan(lse[1]).all()
+    w.seq_lens[3] = -1
+    w.seq_lens[0] = w.page_table.shape[1] * 4 - T + 1
+    out, _ = run_oracle(w)
+    assert np.isnan(out[0]).all() and np.isnan(out[3]).all()
+
+
+def test_sampled_entry_point_matches_full():
+    w = W.make_config(2, length_div=64)
+    out, lse = run_oracle(w)
+    rng = np.random.default_rng(7)
+    tri = np.stack([rng.integers(0, w.B, 50), rng.integers(0, w.T, 50), rng.integers(0, w.Hq, 50)], axis=1)
+    so, sl = oracle.tree_attn_oracle_sample(w.q, w.k_cache, w.v_cache, w.page_table, w.seq_lens, w.tree_parent,
+                                            tri, scale=w.scale)
+    for n, (b, i, h) in enumerate(tri):
+        assert np.array_equal(so[n], out[b, i, h]) and sl[n] == lse[b, h, i]
+
+
+def test_merging_partials_over_disjoint_key_chunks_is_full_attention():
+    """The identity behind split-KV and the prefix/suffix split (section 3.1, merge of partial attentions):
+    with per-chunk (o_c, lse_c), out = sum_c exp(lse_c - lse) o_c and lse = log sum_c exp(lse_c)."""
+    rng = np.random.default_rng(8)
+    n, D = 57, 8
+    s = rng.standard_normal(n) * 3
+    V = rng.standard_normal((n, D))
+    p = np.exp(s - s.max())
+    full = (p / p.sum()) @ V
+    full_lse = s.max() + math.log(p.sum())
+    cuts = [0, 5, 5, 20, 57]                  # includes an empty chunk
+    os_, ls_ = [], []
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        if a == b:
+            os_.append(np.zeros(D)); ls_.append(-math.inf); continue
+        pc = np.exp(s[a:b] - s[a:b].max())
+        os_.append((pc / pc.sum()) @ V[a:b]); ls_.append(s[a:b].max() + math.log(pc.sum()))
+    ls_ = np.asarray(ls_)
+    lse = ls_.max() + math.log(np.exp(ls_ - ls_.max()).sum())
+    merged = sum(math.exp(l - lse) * o for l, o in zip(ls_, os_))
+    np.testing.assert_allclose(merged, full, atol=1e-14)
+    assert abs(lse - full_lse) < 1e-14
