@@ -1,0 +1,171 @@
+/*
+ * libtreeattn -- tree attention for the verification step of tree-based
+ * speculative decoding, hand-written for AMD MI355X (gfx950).
+ *
+ * The operation (paper section 3.1, "Tree attention"): the T draft tokens of a
+ * speculation tree are flattened into one query sequence; node i of request b
+ * must attend to the request's cached context (the prefix, L_b tokens) and to
+ * the tree nodes on its own root-to-node path, itself included -- the result a
+ * causal prefill over the unrolled path would give.  The paper computes it as
+ * a mask-free prefix attention over the paged cache, a small tree-masked
+ * suffix attention among the T tree tokens, and a merge of the partial results
+ * through their log-sum-exp.  Paging applies to the cache (section 3.4, "Paged
+ * KV with tree attention"); the tree tokens' K/V are expected at logical cache
+ * positions L_b .. L_b+T-1, i.e. after they have been written back, and the
+ * page table must already cover them (the paper's "tree padding").
+ *
+ * Conventions
+ *   - Every `data` pointer is a DEVICE pointer unless stated otherwise; the
+ *     caller owns all buffers, the library never frees or keeps them.
+ *   - Strides are in ELEMENTS.  The innermost (head_dim) stride must be 1.
+ *   - All entry points are asynchronous on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream), perform no device synchronisation and
+ *     no device-to-host copy, and read seq_lens / page_table / tree_parent on
+ *     the device only.
+ *   - Return value: TA_OK (0) or a negative ta_status.  Nothing throws or aborts.
+ *     Problems visible on the host (null pointers, ranks, dtypes, shapes,
+ *     strides) are reported before anything is launched.  Problems that only
+ *     the data shows (a parent id outside [-1, T), a parent cycle, L_b < 0,
+ *     L_b + T beyond max_pages*page_size) cannot be seen without a
+ *     synchronisation: the request's rows of `out` and `lse` are filled with NaN
+ *     and a bit is set in a sticky per-device status word (tree_attn_last_status).
+ */
+#ifndef TREEATTN_H
+#define TREEATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TREEATTN_VERSION 100      /* 0.1.0 */
+#define TA_MAX_TREE 64            /* one 64-bit ancestor mask per node */
+#define TA_MAX_HEAD_DIM 256
+#define TA_MAX_BATCH 4096
+
+typedef enum {
+    TA_F32 = 0,
+    TA_BF16 = 1,
+    TA_I32 = 2,
+    TA_U64 = 3
+} ta_dtype;
+
+typedef enum {
+    TA_OK = 0,
+    TA_ERR_NULL = -1,        /* a required descriptor or data pointer is NULL */
+    TA_ERR_DTYPE = -2,       /* unsupported or mismatching element type */
+    TA_ERR_RANK = -3,        /* wrong number of dimensions */
+    TA_ERR_SHAPE = -4,       /* shapes disagree with each other */
+    TA_ERR_STRIDE = -5,      /* innermost stride is not 1, or a stride is negative */
+    TA_ERR_HEADS = -6,       /* Hq is not a multiple of Hkv */
+    TA_ERR_HEAD_DIM = -7,    /* head_dim outside [1, TA_MAX_HEAD_DIM] */
+    TA_ERR_TREE_SIZE = -8,   /* T outside [1, TA_MAX_TREE] */
+    TA_ERR_PAGE_TABLE = -9,  /* max_pages * page_size cannot hold even the T tree tokens */
+    TA_ERR_WORKSPACE = -10,  /* caller workspace too small or misaligned */
+    TA_ERR_HIP = -11,        /* a HIP runtime call failed (no device, launch failure, allocation) */
+    TA_ERR_BATCH = -12,      /* B outside [0, TA_MAX_BATCH] */
+    TA_ERR_OPTS = -13        /* invalid field in ta_opts */
+} ta_status;
+
+/* Bits of the sticky device status word. */
+#define TA_STATUS_BAD_PARENT 1   /* parent id outside [-1, T) or a parent cycle */
+#define TA_STATUS_BAD_SEQLEN 2   /* L_b < 0 or L_b + T > max_pages * page_size */
+
+typedef struct {
+    void *data;           /* device pointer */
+    int32_t dtype;        /* ta_dtype */
+    int32_t ndim;
+    int64_t shape[5];
+    int64_t stride[5];    /* in elements */
+} ta_tensor;
+
+/* Kernel families (ta_opts.kernel).  AUTO picks MFMA when the shape allows it. */
+#define TA_KERNEL_AUTO 0
+#define TA_KERNEL_GENERIC 1   /* scalar fp32-accumulating kernel: any dtype, head_dim, page size */
+#define TA_KERNEL_MFMA 2      /* bf16 matrix-core kernel: head_dim 128, power-of-two page size (or contiguous) */
+
+typedef struct {
+    float scale;              /* softmax scale; <= 0 or NaN selects 1/sqrt(head_dim) */
+    int32_t num_splits;       /* 0 = automatic; n > 0 = cut the batch's KV work into at most n workgroup shares */
+    int32_t kernel;           /* TA_KERNEL_* */
+    int32_t reserved;         /* must be 0 */
+    void *workspace;          /* device scratch, 256-byte aligned, or NULL = library-owned per-device buffer */
+    size_t workspace_bytes;   /* size of `workspace` */
+} ta_opts;
+
+/*
+ * Tree attention forward (section 3.1; cache addressing per section 3.4).
+ *
+ *   q           [B, T, Hq, D]  TA_BF16 or TA_F32; node i of request b, query head h
+ *   k_cache     [num_pages, Hkv, page_size, D] -- any 4-D strided view with unit D stride, dtype of q.
+ *               Token at logical position t of request b, KV head g lives in page page_table[b][t / page_size],
+ *               slot t % page_size.  Logical positions 0..L_b-1 are the prefix, L_b+i is tree node i.
+ *   v_cache     same shape and dtype as k_cache (strides may differ)
+ *   page_table  TA_I32 [B, max_pages], or NULL for the contiguous layout: request b owns page b, and
+ *               page_size (the cache's slot dimension) is that request's capacity
+ *   seq_lens    TA_I32 [B], prefix lengths L_b; the T tree tokens are NOT counted
+ *   tree_parent TA_I32 [B, T] (stride[0] may be 0: one tree for the batch) or [T]; a negative parent marks a
+ *               root; any node numbering is accepted (parents need not precede children)
+ *   out         [B, T, Hq, D], dtype of q: softmax(scale * q K^T) V over prefix + path, rounded once
+ *               (round to nearest even) from an fp32 accumulator
+ *   lse         TA_F32 [B, Hq, T] or NULL: natural log of the sum of exp of the scaled scores
+ *   stream      hipStream_t
+ *
+ * Query head h reads KV head h / (Hq / Hkv).  B == 0 is a no-op.  Uses the library-owned workspace of
+ * the current device, grown on demand with hipMalloc: call tree_attn_reserve first (or pass a workspace
+ * through tree_attn_fwd_ex) wherever allocation is not allowed, e.g. under stream capture.
+ */
+int tree_attn_fwd(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
+                  const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
+                  ta_tensor *out, ta_tensor *lse, void *stream);
+
+/* Same operation with explicit options (NULL opts = defaults). */
+int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
+                     const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
+                     ta_tensor *out, ta_tensor *lse, void *stream, const ta_opts *opts);
+
+/*
+ * Upper bound, in bytes, of the scratch a call with these sizes needs (split-KV partial outputs and
+ * their log-sum-exps; section 3.1, the partial results that the merge combines).  Host-only.
+ * `num_cus` is the compute-unit count of the target device (0 = query the current device, 256 when
+ * no device is present).  Returns 0 for invalid sizes.
+ */
+size_t tree_attn_workspace_bytes(int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t D,
+                                 int32_t dtype, int32_t num_cus);
+
+/* Grow the library-owned workspace of the current device to at least `bytes` (allocates; call outside
+ * stream capture).  Synchronises the device if it has to replace an existing buffer. */
+int tree_attn_reserve(size_t bytes);
+
+/*
+ * Tree-topology encoder alone (section 3.1: the tree mask, here one 64-bit word per node instead of an
+ * explicit query x context mask tensor): masks[b][i] has bit j set iff node j lies on the path from a
+ * root to node i, i included.  tree_parent TA_I32 [B,T] or [T]; masks TA_U64 of the same shape,
+ * contiguous.  A malformed tree yields all-zero masks for that request and sets TA_STATUS_BAD_PARENT.
+ */
+int tree_attn_encode(const ta_tensor *tree_parent, ta_tensor *masks, void *stream);
+
+/* Read and clear the sticky status word of the current device.  Synchronises `stream`.
+ * *host_status receives an OR of TA_STATUS_* bits (HOST pointer). */
+int tree_attn_last_status(int32_t *host_status, void *stream);
+
+/*
+ * Host-only launch plan for a call (no device access): which kernel family would run and how the work
+ * is cut.  `sum_tiles_hint` is unused (0).  plan[0] = kernel family, plan[1] = workgroups of the KV pass,
+ * plan[2] = threads per workgroup, plan[3] = KV tokens per tile, plan[4] = row groups, plan[5] = padded
+ * rows per group, plan[6] = partial slots, plan[7] = workgroups of the merge pass.  HOST pointers.
+ */
+int tree_attn_plan(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
+                   const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
+                   const ta_tensor *out, const ta_tensor *lse, const ta_opts *opts, int32_t num_cus,
+                   int64_t plan[8]);
+
+const char *tree_attn_strerror(int status);
+int tree_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TREEATTN_H */

@@ -1,0 +1,440 @@
+// C-ABI of libtreeattn: descriptor validation on the host, launch planning, per-device state.
+// See include/treeattn.h for the contract of every entry point.
+#include <math.h>
+#include <mutex>
+#include <string.h>
+
+#include "ta_common.h"
+
+namespace {
+
+struct DeviceState {
+    bool init = false;
+    int num_cus = 0;
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    int32_t *status = nullptr;
+};
+
+constexpr int kMaxDevices = 64;
+DeviceState g_dev[kMaxDevices];
+std::mutex g_mu;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Plan {
+    int kernel;
+    int n_wg, threads, n_rg, rows_grp, n_slots, min_q, merge_wgs;
+};
+
+struct Problem {
+    TAParams p;
+    Plan plan;
+    size_t ws_o_bytes, ws_bytes;
+};
+
+bool strides_ok(const ta_tensor *t)
+{
+    for (int i = 0; i < t->ndim; ++i)
+        if (t->stride[i] < 0)
+            return false;
+    return t->stride[t->ndim - 1] == 1 || t->shape[t->ndim - 1] <= 1;
+}
+
+int mfma_rows_group(int rows)
+{
+    // Padded to whole 32-row MFMA blocks, at most TA_ROW_GROUP rows per workgroup.
+    int padded = (rows + 31) / 32 * 32;
+    return padded < TA_ROW_GROUP ? padded : TA_ROW_GROUP;
+}
+
+// Everything that can be decided from the descriptors alone.  No HIP call in here.
+int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, const ta_tensor *pt,
+                  const ta_tensor *sl, const ta_tensor *par, const ta_tensor *out, const ta_tensor *lse,
+                  const ta_opts *opts, int num_cus, Problem *pr)
+{
+    if (!q || !k || !v || !sl || !par || !out)
+        return TA_ERR_NULL;
+    if (q->dtype != TA_BF16 && q->dtype != TA_F32)
+        return TA_ERR_DTYPE;
+    if (k->dtype != q->dtype || v->dtype != q->dtype || out->dtype != q->dtype)
+        return TA_ERR_DTYPE;
+    if (sl->dtype != TA_I32 || par->dtype != TA_I32 || (pt && pt->dtype != TA_I32) || (lse && lse->dtype != TA_F32))
+        return TA_ERR_DTYPE;
+    if (q->ndim != 4 || k->ndim != 4 || v->ndim != 4 || out->ndim != 4 || sl->ndim != 1 ||
+        (par->ndim != 1 && par->ndim != 2) || (pt && pt->ndim != 2) || (lse && lse->ndim != 3))
+        return TA_ERR_RANK;
+    const int64_t B = q->shape[0], T = q->shape[1], Hq = q->shape[2], D = q->shape[3];
+    const int64_t n_pages = k->shape[0], Hkv = k->shape[1], ps = k->shape[2];
+    if (B < 0 || B > TA_MAX_BATCH)
+        return TA_ERR_BATCH;
+    if (T < 1 || T > TA_MAX_TREE)
+        return TA_ERR_TREE_SIZE;
+    if (D < 1 || D > TA_MAX_HEAD_DIM)
+        return TA_ERR_HEAD_DIM;
+    if (Hq < 1 || Hkv < 1 || Hq % Hkv != 0)
+        return TA_ERR_HEADS;
+    if (Hq > 65535 || ps < 1 || ps > (1 << 30) || n_pages < 0)
+        return TA_ERR_SHAPE;
+    if (k->shape[3] != D)
+        return TA_ERR_SHAPE;
+    for (int i = 0; i < 4; ++i)
+        if (v->shape[i] != k->shape[i] || out->shape[i] != q->shape[i])
+            return TA_ERR_SHAPE;
+    if (sl->shape[0] != B)
+        return TA_ERR_SHAPE;
+    if (par->ndim == 2 ? (par->shape[0] != B || par->shape[1] != T) : (par->shape[0] != T))
+        return TA_ERR_SHAPE;
+    if (lse && (lse->shape[0] != B || lse->shape[1] != Hq || lse->shape[2] != T))
+        return TA_ERR_SHAPE;
+    if (pt && pt->shape[0] != B)
+        return TA_ERR_SHAPE;
+    if (!pt && n_pages < B)
+        return TA_ERR_SHAPE;
+    if (!strides_ok(q) || !strides_ok(k) || !strides_ok(v) || !strides_ok(out) || !strides_ok(par) ||
+        (pt && !strides_ok(pt)))
+        return TA_ERR_STRIDE;
+    if (lse)
+        for (int i = 0; i < 3; ++i)
+            if (lse->stride[i] < 0)
+                return TA_ERR_STRIDE;
+    if (sl->stride[0] < 0)
+        return TA_ERR_STRIDE;
+    const int64_t capacity = pt ? pt->shape[1] * ps : ps;
+    if (capacity < T)
+        return TA_ERR_PAGE_TABLE;
+    if (capacity > INT32_MAX)
+        return TA_ERR_SHAPE;
+    if (B > 0) {
+        if (!q->data || !k->data || !v->data || !sl->data || !par->data || !out->data ||
+            (pt && !pt->data) || (lse && !lse->data))
+            return TA_ERR_NULL;
+    }
+    int kernel = TA_KERNEL_AUTO, num_splits = 0;
+    float scale = 0.f;
+    void *user_ws = nullptr;
+    size_t user_ws_bytes = 0;
+    if (opts) {
+        if (opts->reserved != 0 || opts->num_splits < 0 || opts->kernel < TA_KERNEL_AUTO ||
+            opts->kernel > TA_KERNEL_MFMA)
+            return TA_ERR_OPTS;
+        kernel = opts->kernel;
+        num_splits = opts->num_splits;
+        scale = opts->scale;
+        user_ws = opts->workspace;
+        user_ws_bytes = opts->workspace_bytes;
+        if (user_ws && ((uintptr_t)user_ws % 256) != 0)
+            return TA_ERR_WORKSPACE;
+    }
+    if (!(scale > 0.f) || !isfinite(scale))
+        scale = 1.0f / sqrtf((float)D);
+
+    int ps_shift = -1;
+    for (int s = 0; s <= 30; ++s)
+        if (((int64_t)1 << s) == ps)
+            ps_shift = s;
+    const bool mfma_ok = q->dtype == TA_BF16 && D == 128 && (!pt || ps_shift >= 0) &&
+                         q->stride[2] % 8 == 0 && q->stride[1] % 8 == 0 && q->stride[0] % 8 == 0 &&
+                         k->stride[0] % 8 == 0 && k->stride[1] % 8 == 0 && k->stride[2] % 8 == 0 &&
+                         v->stride[0] % 8 == 0 && v->stride[1] % 8 == 0 && v->stride[2] % 8 == 0 &&
+                         ((uintptr_t)q->data % 16) == 0 && ((uintptr_t)k->data % 16) == 0 &&
+                         ((uintptr_t)v->data % 16) == 0;
+    if (kernel == TA_KERNEL_MFMA && !mfma_ok)
+        return TA_ERR_OPTS;
+    if (kernel == TA_KERNEL_AUTO)
+        kernel = mfma_ok ? TA_KERNEL_MFMA : TA_KERNEL_GENERIC;
+
+    TAParams &p = pr->p;
+    memset(&p, 0, sizeof p);
+    p.q = q->data; p.k = k->data; p.v = v->data; p.out = out->data;
+    p.lse = lse ? (float *)lse->data : nullptr;
+    p.page_table = pt ? (const int32_t *)pt->data : nullptr;
+    p.seq_lens = (const int32_t *)sl->data;
+    p.parent = (const int32_t *)par->data;
+    p.q_sb = q->stride[0]; p.q_st = q->stride[1]; p.q_sh = q->stride[2];
+    p.o_sb = out->stride[0]; p.o_st = out->stride[1]; p.o_sh = out->stride[2];
+    p.k_sp = k->stride[0]; p.k_sh = k->stride[1]; p.k_ss = k->stride[2];
+    p.v_sp = v->stride[0]; p.v_sh = v->stride[1]; p.v_ss = v->stride[2];
+    if (lse) { p.lse_sb = lse->stride[0]; p.lse_sh = lse->stride[1]; p.lse_st = lse->stride[2]; }
+    p.pt_sb = pt ? pt->stride[0] : 0;
+    p.par_sb = par->ndim == 2 ? par->stride[0] : 0;
+    p.sl_s = sl->stride[0];
+    p.B = (int)B; p.T = (int)T; p.Hq = (int)Hq; p.Hkv = (int)Hkv; p.G = (int)(Hq / Hkv); p.D = (int)D;
+    p.ps = (int)ps; p.ps_shift = ps_shift; p.capacity = (int)capacity;
+    p.rows = p.T * p.G;
+    p.is_bf16 = q->dtype == TA_BF16;
+    p.scale_log2e = scale * 1.4426950408889634f;
+
+    Plan &pl = pr->plan;
+    pl.kernel = kernel;
+    const int64_t tiles_cap = (int64_t)B * Hkv * ((capacity - T + TA_TILE - 1) / TA_TILE + 1);
+    if (tiles_cap > INT32_MAX)
+        return TA_ERR_SHAPE;
+    if (kernel == TA_KERNEL_MFMA) {
+        pl.rows_grp = mfma_rows_group(p.rows);
+        pl.threads = pl.rows_grp / 32 * TA_WAVE;
+        pl.n_rg = (p.rows + pl.rows_grp - 1) / pl.rows_grp;
+        // A workgroup's partial result costs rows*D*4 bytes written and read again; a tile of keys and
+        // values costs TA_TILE*D*4 bytes.  Keep a share at least as long as the rows are many, so the
+        // partials stay a small fraction of the cache traffic.
+        const int per_cu = pl.threads >= 512 ? 1 : (pl.threads >= 256 ? 2 : 4);
+        int64_t want = (int64_t)num_cus * per_cu / pl.n_rg;
+        if (want < 1)
+            want = 1;
+        pl.n_wg = (int)(num_splits > 0 ? num_splits : want);
+        pl.min_q = num_splits > 0 ? 1 : (pl.rows_grp >= 128 ? 4 : 2);
+    } else {
+        pl.rows_grp = p.rows < TA_ROW_GROUP ? p.rows : TA_ROW_GROUP;
+        pl.threads = 256;
+        pl.n_rg = (p.rows + pl.rows_grp - 1) / pl.rows_grp;
+        pl.n_wg = num_splits > 0 ? num_splits : num_cus * 4;
+        pl.min_q = 1;
+    }
+    if (pl.n_wg > tiles_cap)
+        pl.n_wg = (int)(tiles_cap > 0 ? tiles_cap : 1);
+    pl.n_slots = pl.n_wg + (int)(B * Hkv);
+    pl.merge_wgs = (int)(B * Hkv) * ((p.rows + TA_MERGE_ROWS - 1) / TA_MERGE_ROWS);
+    p.rows_grp = pl.rows_grp; p.n_rg = pl.n_rg; p.n_wg = pl.n_wg; p.min_q = pl.min_q;
+
+    const size_t rows_total = (size_t)pl.n_slots * pl.n_rg * pl.rows_grp;
+    pr->ws_o_bytes = align_up(rows_total * D * sizeof(float), 256);
+    pr->ws_bytes = pr->ws_o_bytes + align_up(rows_total * sizeof(float), 256);
+    if (user_ws) {
+        if (user_ws_bytes < pr->ws_bytes)
+            return TA_ERR_WORKSPACE;
+        p.ws_o = (float *)user_ws;
+        p.ws_lse = (float *)((char *)user_ws + pr->ws_o_bytes);
+    }
+    return TA_OK;
+}
+
+int device_state(DeviceState **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return TA_ERR_HIP;
+    }
+    DeviceState &s = g_dev[dev];
+    if (!s.init) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            return TA_ERR_HIP;
+        if (hipMalloc((void **)&s.status, 256) != hipSuccess)
+            return TA_ERR_HIP;
+        if (hipMemset(s.status, 0, 256) != hipSuccess)
+            return TA_ERR_HIP;
+        s.num_cus = cus;
+        s.init = true;
+    }
+    *out = &s;
+    return TA_OK;
+}
+
+int reserve_locked(DeviceState *s, size_t bytes)
+{
+    if (bytes <= s->ws_bytes)
+        return TA_OK;
+    if (s->ws) {
+        if (hipDeviceSynchronize() != hipSuccess)
+            return TA_ERR_HIP;
+        (void)hipFree(s->ws);
+        s->ws = nullptr;
+        s->ws_bytes = 0;
+    }
+    bytes = align_up(bytes, (size_t)1 << 20);
+    if (hipMalloc(&s->ws, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return TA_ERR_HIP;
+    }
+    s->ws_bytes = bytes;
+    return TA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tree_attn_version(void) { return TREEATTN_VERSION; }
+
+const char *tree_attn_strerror(int status)
+{
+    switch (status) {
+    case TA_OK: return "ok";
+    case TA_ERR_NULL: return "a required descriptor or data pointer is NULL";
+    case TA_ERR_DTYPE: return "unsupported or mismatching element type";
+    case TA_ERR_RANK: return "wrong number of dimensions";
+    case TA_ERR_SHAPE: return "shapes disagree";
+    case TA_ERR_STRIDE: return "innermost stride must be 1 and strides must be non-negative";
+    case TA_ERR_HEADS: return "query heads must be a multiple of KV heads";
+    case TA_ERR_HEAD_DIM: return "head_dim out of range";
+    case TA_ERR_TREE_SIZE: return "tree size must be in [1, 64]";
+    case TA_ERR_PAGE_TABLE: return "page table cannot hold the tree tokens";
+    case TA_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case TA_ERR_HIP: return "HIP runtime call failed";
+    case TA_ERR_BATCH: return "batch size out of range";
+    case TA_ERR_OPTS: return "invalid option";
+    default: return "unknown status";
+    }
+}
+
+int tree_attn_plan(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
+                   const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
+                   const ta_tensor *out, const ta_tensor *lse, const ta_opts *opts, int32_t num_cus,
+                   int64_t plan[8])
+{
+    if (!plan)
+        return TA_ERR_NULL;
+    Problem pr;
+    ta_opts o;
+    if (opts) {
+        o = *opts;
+        o.workspace = nullptr;      // planning never needs the scratch itself
+        o.workspace_bytes = 0;
+    }
+    int rc = build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts ? &o : nullptr,
+                           num_cus > 0 ? num_cus : 256, &pr);
+    if (rc != TA_OK)
+        return rc;
+    plan[0] = pr.plan.kernel;
+    plan[1] = pr.plan.n_wg;
+    plan[2] = pr.plan.threads;
+    plan[3] = TA_TILE;
+    plan[4] = pr.plan.n_rg;
+    plan[5] = pr.plan.rows_grp;
+    plan[6] = pr.plan.n_slots;
+    plan[7] = pr.plan.merge_wgs;
+    return TA_OK;
+}
+
+size_t tree_attn_workspace_bytes(int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t D, int32_t dtype,
+                                 int32_t num_cus)
+{
+    if (B < 0 || B > TA_MAX_BATCH || T < 1 || T > TA_MAX_TREE || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || D < 1 ||
+        D > TA_MAX_HEAD_DIM || (dtype != TA_BF16 && dtype != TA_F32))
+        return 0;
+    if (num_cus <= 0) {
+        DeviceState *s = nullptr;
+        std::lock_guard<std::mutex> lk(g_mu);
+        num_cus = device_state(&s) == TA_OK ? s->num_cus : 256;
+    }
+    // Worst case over both kernel families: 4 workgroups per CU, rows padded to the MFMA row group.
+    const int rows = T * (Hq / Hkv);
+    const int rows_grp = mfma_rows_group(rows);
+    const size_t n_rg = (rows + rows_grp - 1) / rows_grp;
+    const size_t slots = (size_t)num_cus * 4 + (size_t)B * Hkv;
+    const size_t rows_total = slots * n_rg * rows_grp;
+    return align_up(rows_total * D * sizeof(float), 256) + align_up(rows_total * sizeof(float), 256);
+}
+
+int tree_attn_reserve(size_t bytes)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    DeviceState *s = nullptr;
+    int rc = device_state(&s);
+    if (rc != TA_OK)
+        return rc;
+    return reserve_locked(s, bytes);
+}
+
+int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
+                     const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
+                     ta_tensor *out, ta_tensor *lse, void *stream, const ta_opts *opts)
+{
+    Problem pr;
+    // First pass with a nominal CU count: host-visible errors are reported before any HIP call.
+    int rc = build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts, 256, &pr);
+    if (rc != TA_OK)
+        return rc;
+    if (pr.p.B == 0)
+        return TA_OK;
+    DeviceState *s = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        rc = device_state(&s);
+        if (rc != TA_OK)
+            return rc;
+        rc = build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts, s->num_cus, &pr);
+        if (rc != TA_OK)
+            return rc;
+        if (!pr.p.ws_o) {
+            rc = reserve_locked(s, pr.ws_bytes);
+            if (rc != TA_OK)
+                return rc;
+            pr.p.ws_o = (float *)s->ws;
+            pr.p.ws_lse = (float *)((char *)s->ws + pr.ws_o_bytes);
+        }
+    }
+    pr.p.status = s->status;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = pr.plan.kernel == TA_KERNEL_MFMA ? ta_launch_mfma(pr.p, st) : ta_launch_generic(pr.p, st);
+    if (e != hipSuccess)
+        return TA_ERR_HIP;
+    e = ta_launch_merge(pr.p, st);
+    return e == hipSuccess ? TA_OK : TA_ERR_HIP;
+}
+
+int tree_attn_fwd(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
+                  const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
+                  ta_tensor *out, ta_tensor *lse, void *stream)
+{
+    return tree_attn_fwd_ex(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, stream, nullptr);
+}
+
+int tree_attn_encode(const ta_tensor *tree_parent, ta_tensor *masks, void *stream)
+{
+    if (!tree_parent || !masks)
+        return TA_ERR_NULL;
+    if (tree_parent->dtype != TA_I32 || masks->dtype != TA_U64)
+        return TA_ERR_DTYPE;
+    if ((tree_parent->ndim != 1 && tree_parent->ndim != 2) || masks->ndim != tree_parent->ndim)
+        return TA_ERR_RANK;
+    const int nd = tree_parent->ndim;
+    const int64_t B = nd == 2 ? tree_parent->shape[0] : 1, T = tree_parent->shape[nd - 1];
+    if (T < 1 || T > TA_MAX_TREE)
+        return TA_ERR_TREE_SIZE;
+    if (B < 0 || B > TA_MAX_BATCH)
+        return TA_ERR_BATCH;
+    for (int i = 0; i < nd; ++i)
+        if (masks->shape[i] != tree_parent->shape[i])
+            return TA_ERR_SHAPE;
+    if (!strides_ok(tree_parent) || !strides_ok(masks) || (nd == 2 && masks->stride[0] != T && B > 1))
+        return TA_ERR_STRIDE;
+    if (B == 0)
+        return TA_OK;
+    if (!tree_parent->data || !masks->data)
+        return TA_ERR_NULL;
+    DeviceState *s = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        int rc = device_state(&s);
+        if (rc != TA_OK)
+            return rc;
+    }
+    hipError_t e = ta_launch_encode((const int32_t *)tree_parent->data, nd == 2 ? tree_parent->stride[0] : 0, (int)B,
+                                    (int)T, (unsigned long long *)masks->data, s->status, (hipStream_t)stream);
+    return e == hipSuccess ? TA_OK : TA_ERR_HIP;
+}
+
+int tree_attn_last_status(int32_t *host_status, void *stream)
+{
+    if (!host_status)
+        return TA_ERR_NULL;
+    DeviceState *s = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        int rc = device_state(&s);
+        if (rc != TA_OK)
+            return rc;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (hipMemcpyAsync(host_status, s->status, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return TA_ERR_HIP;
+    if (hipMemsetAsync(s->status, 0, sizeof(int32_t), st) != hipSuccess)
+        return TA_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess)
+        return TA_ERR_HIP;
+    return TA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,196 @@
+// Shared declarations of the libtreeattn device code: kernel parameters and the device-side work
+// schedule.  Everything here is specific to gfx950 (64-wide wavefronts).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/treeattn.h"
+
+#define TA_WAVE 64
+#define TA_TILE 64            // KV tokens per tile of the KV pass (the tree tokens form one more tile)
+#define TA_MERGE_ROWS 8       // rows per workgroup of the merge pass
+#define TA_ROW_GROUP 256      // rows (tree nodes x query heads of one KV head) one workgroup keeps
+
+struct TAParams {
+    const void *q, *k, *v;
+    void *out;
+    float *lse;
+    const int32_t *page_table, *seq_lens, *parent;
+    int64_t q_sb, q_st, q_sh;
+    int64_t o_sb, o_st, o_sh;
+    int64_t k_sp, k_sh, k_ss;
+    int64_t v_sp, v_sh, v_ss;
+    int64_t lse_sb, lse_sh, lse_st;
+    int64_t pt_sb, par_sb, sl_s;
+    int32_t B, T, Hq, Hkv, G, D;
+    int32_t ps, ps_shift;      // page size; log2 of it, or -1 when it is not a power of two
+    int32_t capacity;          // logical positions one request can address
+    int32_t rows;              // T * G
+    int32_t rows_grp;          // rows per row group (the last group may hold fewer)
+    int32_t n_rg;              // row groups
+    int32_t n_wg;              // workgroups of the KV pass along x
+    int32_t min_q;             // smallest share of tiles a workgroup takes
+    int32_t is_bf16;
+    float scale_log2e;         // softmax scale * log2(e): scores are kept in the base-2 domain
+    float *ws_o;               // partial outputs  [slot][rg][rows_grp][D], normalised, fp32
+    float *ws_lse;             // partial log2-sum-exp2 [slot][rg][rows_grp]
+    int32_t *status;           // sticky status word
+};
+
+// ---------------------------------------------------------------------------------------------
+// Work schedule.  The KV pass walks, for every (request b, KV head g), a list of tiles:
+// ceil(L_b / TA_TILE) prefix tiles followed by one tile holding the T tree tokens.  A malformed
+// request owns a single tile (it only poisons its outputs).  All tile lists are laid end to end,
+// (b major, g minor), and workgroup w takes the contiguous share [w*share, (w+1)*share).  A share
+// may start or end inside a list; every (workgroup, list) overlap produces one partial result in
+// slot w + (b*Hkv + g), which is unique because both terms grow along the walk.
+// The prefix lengths live on the device, so every workgroup derives the schedule itself.
+// ---------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ bool ta_request_ok(const TAParams &p, int L)
+{
+    return L >= 0 && (int64_t)L + p.T <= (int64_t)p.capacity;
+}
+
+__device__ __forceinline__ int ta_request_tiles(const TAParams &p, int b)
+{
+    int L = p.seq_lens[(int64_t)b * p.sl_s];
+    return ta_request_ok(p, L) ? (L + TA_TILE - 1) / TA_TILE + 1 : 1;
+}
+
+// cum[0..B]: exclusive prefix sums of the per-request tile counts.  Needs blockDim.x >= 64; ends
+// with a barrier.
+__device__ __forceinline__ void ta_build_schedule(const TAParams &p, int *cum)
+{
+    const int tid = threadIdx.x;
+    for (int b = tid; b < p.B; b += blockDim.x)
+        cum[b + 1] = ta_request_tiles(p, b);
+    if (tid == 0)
+        cum[0] = 0;
+    __syncthreads();
+    if (tid < TA_WAVE) {
+        int carry = 0;
+        for (int base = 0; base < p.B; base += TA_WAVE) {
+            int idx = base + tid;
+            int x = idx < p.B ? cum[idx + 1] : 0;
+            for (int off = 1; off < TA_WAVE; off <<= 1) {
+                int y = __shfl_up(x, off, TA_WAVE);
+                if (tid >= off)
+                    x += y;
+            }
+            if (idx < p.B)
+                cum[idx + 1] = x + carry;
+            carry += __shfl(x, TA_WAVE - 1, TA_WAVE);
+        }
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ int ta_share(const TAParams &p, int total)
+{
+    int share = (total + p.n_wg - 1) / p.n_wg;
+    return share < p.min_q ? p.min_q : share;
+}
+
+// Request whose tile lists contain global tile t (0 <= t < Hkv * cum[B]).
+__device__ __forceinline__ int ta_find_request(const TAParams &p, const int *cum, int t)
+{
+    int lo = 0, hi = p.B;                 // invariant: Hkv*cum[lo] <= t < Hkv*cum[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if ((int64_t)p.Hkv * cum[mid] <= t)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ int64_t ta_ws_row(const TAParams &p, int slot, int rg, int r)
+{
+    return ((int64_t)slot * p.n_rg + rg) * p.rows_grp + r;
+}
+
+// Element offset of logical position pos of request b, KV head g in a cache with strides (sp, sh, ss).
+__device__ __forceinline__ int64_t ta_cache_offset(const TAParams &p, int b, int g, int pos,
+                                                   int64_t sp, int64_t sh, int64_t ss)
+{
+    int64_t page, slot;
+    if (p.page_table) {
+        int pi = p.ps_shift >= 0 ? (pos >> p.ps_shift) : (pos / p.ps);
+        slot = p.ps_shift >= 0 ? (pos & (p.ps - 1)) : (pos - pi * p.ps);
+        page = p.page_table[(int64_t)b * p.pt_sb + pi];
+    } else {
+        page = b;
+        slot = pos;
+    }
+    return page * sp + (int64_t)g * sh + slot * ss;
+}
+
+// Ancestor masks of one request's tree into masks[0..T): bit j of masks[i] is set iff node j is on the
+// path from a root to node i (i included).  Threads 0..T-1 each walk one node upwards; a parent id
+// >= T or a walk longer than T nodes marks the tree as malformed.  Returns (to every thread, after a
+// barrier) whether the tree is well formed; `flag` is one int of shared memory.
+__device__ __forceinline__ bool ta_encode_tree(const int32_t *parent, int T, unsigned long long *masks, int *flag)
+{
+    const int tid = threadIdx.x;
+    if (tid == 0)
+        *flag = 0;
+    __syncthreads();
+    if (tid < T) {
+        unsigned long long m = 0;
+        int cur = tid, steps = 0;
+        bool bad = false;
+        while (cur >= 0) {
+            if (cur >= T || steps >= T) {
+                bad = true;
+                break;
+            }
+            m |= 1ull << cur;
+            cur = parent[cur];
+            ++steps;
+        }
+        masks[tid] = bad ? 0ull : m;
+        if (bad)
+            atomicOr(flag, 1);
+    }
+    __syncthreads();
+    return *flag == 0;
+}
+
+__device__ __forceinline__ float ta_wave_max(float x)
+{
+    for (int off = TA_WAVE / 2; off > 0; off >>= 1)
+        x = fmaxf(x, __shfl_xor(x, off, TA_WAVE));
+    return x;
+}
+
+__device__ __forceinline__ float ta_wave_sum(float x)
+{
+    for (int off = TA_WAVE / 2; off > 0; off >>= 1)
+        x += __shfl_xor(x, off, TA_WAVE);
+    return x;
+}
+
+__device__ __forceinline__ float ta_bf16_to_f32(uint16_t b)
+{
+    return __uint_as_float((uint32_t)b << 16);
+}
+
+// Round to nearest, ties to even; NaN stays NaN.
+__device__ __forceinline__ uint16_t ta_f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Launchers implemented next to their kernels.
+hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream);
+hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream);
+hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream);
+hipError_t ta_launch_encode(const int32_t *parent, int64_t par_sb, int B, int T, unsigned long long *masks,
+                            int32_t *status, hipStream_t stream);

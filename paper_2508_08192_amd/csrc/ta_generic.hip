@@ -1,0 +1,256 @@
+// Scalar (vector-ALU, fp32-accumulating) kernels of libtreeattn: the any-shape KV pass, the merge pass
+// and the stand-alone tree encoder.  The KV pass here is the portable path (fp32 inputs, head dims other
+// than 128, page sizes that are not powers of two); the matrix-core path lives in ta_mfma.hip and shares
+// the schedule and the merge.
+#include "ta_common.h"
+
+#define GEN_THREADS 256
+#define GEN_WAVES (GEN_THREADS / TA_WAVE)
+#define GEN_DCHUNKS (TA_MAX_HEAD_DIM / TA_WAVE)
+
+template <bool BF16>
+__device__ __forceinline__ float load_elem(const void *base, int64_t idx)
+{
+    if (BF16)
+        return ta_bf16_to_f32(((const uint16_t *)base)[idx]);
+    return ((const float *)base)[idx];
+}
+
+// KV pass, one wave per query row at a time: lanes are the 64 tokens of a tile for the scores
+// (section 3.1: prefix tiles are mask-free, the tree tile keeps only the row's ancestors), then lanes
+// are head-dim columns for the weighted sum of V.  Running max / sum per row (base-2 domain).
+template <bool BF16>
+__global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
+{
+    extern __shared__ int smem_i[];
+    int *cum = smem_i;                                                   // [B + 1]
+    unsigned long long *masks = (unsigned long long *)(cum + ((p.B + 2) & ~1));   // [64]
+    float *qrow = (float *)(masks + TA_MAX_TREE);                        // [GEN_WAVES][TA_MAX_HEAD_DIM]
+    int *flag = (int *)(qrow + GEN_WAVES * TA_MAX_HEAD_DIM);
+
+    ta_build_schedule(p, cum);
+    const int total = p.Hkv * cum[p.B];
+    const int share = ta_share(p, total);
+    const int w = blockIdx.x, rg = blockIdx.y;
+    const int lane = threadIdx.x % TA_WAVE, wave = threadIdx.x / TA_WAVE;
+    int t = w * share;
+    const int t_end = min(total, t + share);
+    const int rows_here = min(p.rows_grp, p.rows - rg * p.rows_grp);
+
+    while (t < t_end) {
+        const int b = ta_find_request(p, cum, t);
+        const int n_b = cum[b + 1] - cum[b];
+        const int g = (t - p.Hkv * cum[b]) / n_b;
+        const int seg_start = p.Hkv * cum[b] + g * n_b;
+        const int j0 = t - seg_start;
+        const int j1 = min(n_b, t_end - seg_start);
+        const int slot = w + b * p.Hkv + g;
+        const int L = p.seq_lens[(int64_t)b * p.sl_s];
+        bool poison = !ta_request_ok(p, L);
+        if (poison && threadIdx.x == 0)
+            atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
+        const bool has_tree_tile = (j1 == n_b);
+        if (has_tree_tile && !poison) {
+            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag)) {
+                poison = true;
+                if (threadIdx.x == 0)
+                    atomicOr(p.status, TA_STATUS_BAD_PARENT);
+            }
+        }
+        for (int r = wave; r < rows_here; r += GEN_WAVES) {
+            const int R = rg * p.rows_grp + r;
+            const int node = R / p.G, h = g * p.G + R % p.G;
+            const int64_t wrow = ta_ws_row(p, slot, rg, r);
+            if (poison) {
+                for (int d = lane; d < p.D; d += TA_WAVE)
+                    p.ws_o[wrow * p.D + d] = 0.f;
+                if (lane == 0)
+                    p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
+                continue;
+            }
+            float *qs = qrow + wave * TA_MAX_HEAD_DIM;
+            const int64_t qoff = (int64_t)b * p.q_sb + (int64_t)node * p.q_st + (int64_t)h * p.q_sh;
+            for (int d = lane; d < p.D; d += TA_WAVE)
+                qs[d] = load_elem<BF16>(p.q, qoff + d);
+            __builtin_amdgcn_wave_barrier();
+            const unsigned long long mask = has_tree_tile ? masks[node] : 0ull;
+            float m = -INFINITY, l = 0.f;
+            float acc[GEN_DCHUNKS];
+#pragma unroll
+            for (int c = 0; c < GEN_DCHUNKS; ++c)
+                acc[c] = 0.f;
+            for (int j = j0; j < j1; ++j) {
+                const bool tree_tile = (j == n_b - 1);
+                bool valid;
+                int pos;
+                if (tree_tile) {
+                    valid = lane < p.T && ((mask >> lane) & 1ull);
+                    pos = L + lane;
+                } else {
+                    pos = j * TA_TILE + lane;
+                    valid = pos < L;
+                }
+                float s = -INFINITY;
+                int64_t voff = 0;
+                if (valid) {
+                    const int64_t koff = ta_cache_offset(p, b, g, pos, p.k_sp, p.k_sh, p.k_ss);
+                    voff = ta_cache_offset(p, b, g, pos, p.v_sp, p.v_sh, p.v_ss);
+                    float dot = 0.f;
+                    for (int d = 0; d < p.D; ++d)
+                        dot = fmaf(qs[d], load_elem<BF16>(p.k, koff + d), dot);
+                    s = dot * p.scale_log2e;
+                }
+                const float m_new = fmaxf(m, ta_wave_max(s));       // finite: every tile has a valid token
+                const float alpha = exp2f(m - m_new);
+                const float pr = valid ? exp2f(s - m_new) : 0.f;
+                l = l * alpha + ta_wave_sum(pr);
+                m = m_new;
+#pragma unroll
+                for (int c = 0; c < GEN_DCHUNKS; ++c)
+                    acc[c] *= alpha;
+                for (int jj = 0; jj < TA_TILE; ++jj) {
+                    const float pj = __shfl(pr, jj, TA_WAVE);
+                    if (pj == 0.f)
+                        continue;                                    // wave-uniform
+                    const int64_t vj = ((int64_t)__shfl((int)(voff >> 32), jj, TA_WAVE) << 32) |
+                                       (uint32_t)__shfl((int)(voff & 0xffffffff), jj, TA_WAVE);
+#pragma unroll
+                    for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                        const int d = lane + c * TA_WAVE;
+                        if (d < p.D)
+                            acc[c] = fmaf(pj, load_elem<BF16>(p.v, vj + d), acc[c]);
+                    }
+                }
+            }
+            const float inv = 1.f / l;
+#pragma unroll
+            for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                const int d = lane + c * TA_WAVE;
+                if (d < p.D)
+                    p.ws_o[wrow * p.D + d] = acc[c] * inv;
+            }
+            if (lane == 0)
+                p.ws_lse[wrow] = m + log2f(l);
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();               // masks / flag are reused by the next item
+        t = seg_start + j1;
+    }
+}
+
+hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream)
+{
+    const size_t smem = sizeof(int) * ((p.B + 2) & ~1) + sizeof(unsigned long long) * TA_MAX_TREE +
+                        sizeof(float) * GEN_WAVES * TA_MAX_HEAD_DIM + 16;
+    dim3 grid(p.n_wg, p.n_rg);
+    if (p.is_bf16)
+        hipLaunchKernelGGL(ta_generic_kv_kernel<true>, grid, dim3(GEN_THREADS), smem, stream, p);
+    else
+        hipLaunchKernelGGL(ta_generic_kv_kernel<false>, grid, dim3(GEN_THREADS), smem, stream, p);
+    return hipGetLastError();
+}
+
+// Merge pass (section 3.1: full attention from partial attentions over disjoint chunks of the keys,
+// through their log-sum-exps).  One wave per output row: lanes first span the partials of the row
+// (wave-wide max and sum of the partial log-sum-exps), then span head-dim columns.
+__global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
+{
+    extern __shared__ int smem_i[];
+    int *cum = smem_i;
+    ta_build_schedule(p, cum);
+    const int total = p.Hkv * cum[p.B];
+    const int share = ta_share(p, total);
+    const int seg = blockIdx.x;
+    const int b = seg / p.Hkv, g = seg % p.Hkv;
+    const int lane = threadIdx.x % TA_WAVE, wave = threadIdx.x / TA_WAVE;
+    const int n_b = cum[b + 1] - cum[b];
+    const int seg_start = p.Hkv * cum[b] + g * n_b;
+    const int w_first = seg_start / share;
+    const int n_parts = (seg_start + n_b - 1) / share - w_first + 1;
+    const float LN2 = 0.6931471805599453f;
+
+    for (int rr = wave; rr < TA_MERGE_ROWS; rr += GEN_WAVES) {
+        const int R = blockIdx.y * TA_MERGE_ROWS + rr;
+        if (R >= p.rows)
+            break;
+        const int rg = R / p.rows_grp, r = R % p.rows_grp;
+        const int node = R / p.G, h = g * p.G + R % p.G;
+        // pass 1: max of the partial lse (base 2)
+        float mx = -INFINITY;
+        bool nan_seen = false;
+        for (int q0 = 0; q0 < n_parts; q0 += TA_WAVE) {
+            const int part = q0 + lane;
+            if (part < n_parts) {
+                const float v = p.ws_lse[ta_ws_row(p, w_first + part + seg, rg, r)];
+                nan_seen |= (v != v);
+                mx = fmaxf(mx, v);
+            }
+        }
+        mx = ta_wave_max(mx);
+        nan_seen = __any(nan_seen);
+        float den = 0.f;
+        for (int q0 = 0; q0 < n_parts; q0 += TA_WAVE) {
+            const int part = q0 + lane;
+            if (part < n_parts)
+                den += exp2f(p.ws_lse[ta_ws_row(p, w_first + part + seg, rg, r)] - mx);
+        }
+        den = ta_wave_sum(den);
+        const float lse2 = nan_seen ? __uint_as_float(0x7fc00000u) : mx + log2f(den);
+        float acc[GEN_DCHUNKS];
+#pragma unroll
+        for (int c = 0; c < GEN_DCHUNKS; ++c)
+            acc[c] = 0.f;
+        for (int part = 0; part < n_parts; ++part) {
+            const int64_t wrow = ta_ws_row(p, w_first + part + seg, rg, r);
+            const float wgt = exp2f(p.ws_lse[wrow] - lse2);          // same address in every lane
+#pragma unroll
+            for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                const int d = lane + c * TA_WAVE;
+                if (d < p.D)
+                    acc[c] = fmaf(wgt, p.ws_o[wrow * p.D + d], acc[c]);
+            }
+        }
+        const int64_t ooff = (int64_t)b * p.o_sb + (int64_t)node * p.o_st + (int64_t)h * p.o_sh;
+#pragma unroll
+        for (int c = 0; c < GEN_DCHUNKS; ++c) {
+            const int d = lane + c * TA_WAVE;
+            if (d < p.D) {
+                if (p.is_bf16)
+                    ((uint16_t *)p.out)[ooff + d] = ta_f32_to_bf16(acc[c]);
+                else
+                    ((float *)p.out)[ooff + d] = acc[c];
+            }
+        }
+        if (p.lse && lane == 0)
+            p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + (int64_t)node * p.lse_st] = lse2 * LN2;
+    }
+}
+
+hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream)
+{
+    const size_t smem = sizeof(int) * (p.B + 2);
+    dim3 grid(p.B * p.Hkv, (p.rows + TA_MERGE_ROWS - 1) / TA_MERGE_ROWS);
+    hipLaunchKernelGGL(ta_merge_kernel, grid, dim3(GEN_THREADS), smem, stream, p);
+    return hipGetLastError();
+}
+
+// Stand-alone tree encoder: one workgroup per request.
+__global__ __launch_bounds__(TA_WAVE) void ta_encode_kernel(const int32_t *parent, int64_t par_sb, int T,
+                                                            unsigned long long *masks, int32_t *status)
+{
+    __shared__ unsigned long long sm[TA_MAX_TREE];
+    __shared__ int flag;
+    const int b = blockIdx.x;
+    const bool ok = ta_encode_tree(parent + (int64_t)b * par_sb, T, sm, &flag);
+    if (threadIdx.x < T)
+        masks[(int64_t)b * T + threadIdx.x] = ok ? sm[threadIdx.x] : 0ull;
+    if (!ok && threadIdx.x == 0)
+        atomicOr(status, TA_STATUS_BAD_PARENT);
+}
+
+hipError_t ta_launch_encode(const int32_t *parent, int64_t par_sb, int B, int T, unsigned long long *masks,
+                            int32_t *status, hipStream_t stream)
+{
+    hipLaunchKernelGGL(ta_encode_kernel, dim3(B), dim3(TA_WAVE), 0, stream, parent, par_sb, T, masks, status);
+    return hipGetLastError();
+}

@@ -1,0 +1,230 @@
+"""Thin ctypes binding of libtreeattn (argument marshalling only; every step runs in the HIP kernels).
+
+Function names and argument order follow include/treeattn.h.  Tensors are torch tensors on the GPU
+(torch is used for device memory and streams only) or `Desc` objects (raw pointer + shape + strides,
+used to exercise the host-side validation without a GPU).  There is no CPU fallback: if the shared
+library is missing, importing the entry points fails loudly.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtreeattn.so")
+
+TA_F32, TA_BF16, TA_I32, TA_U64 = 0, 1, 2, 3
+TA_KERNEL_AUTO, TA_KERNEL_GENERIC, TA_KERNEL_MFMA = 0, 1, 2
+TA_STATUS_BAD_PARENT, TA_STATUS_BAD_SEQLEN = 1, 2
+
+TA_OK = 0
+TA_ERR_NULL, TA_ERR_DTYPE, TA_ERR_RANK, TA_ERR_SHAPE, TA_ERR_STRIDE, TA_ERR_HEADS = -1, -2, -3, -4, -5, -6
+TA_ERR_HEAD_DIM, TA_ERR_TREE_SIZE, TA_ERR_PAGE_TABLE, TA_ERR_WORKSPACE, TA_ERR_HIP = -7, -8, -9, -10, -11
+TA_ERR_BATCH, TA_ERR_OPTS = -12, -13
+
+EXPORTS = (
+    "tree_attn_fwd", "tree_attn_fwd_ex", "tree_attn_workspace_bytes", "tree_attn_reserve", "tree_attn_encode",
+    "tree_attn_last_status", "tree_attn_plan", "tree_attn_strerror", "tree_attn_version",
+)
+
+
+class ta_tensor(ctypes.Structure):
+    _fields_ = [
+        ("data", ctypes.c_void_p),
+        ("dtype", ctypes.c_int32),
+        ("ndim", ctypes.c_int32),
+        ("shape", ctypes.c_int64 * 5),
+        ("stride", ctypes.c_int64 * 5),
+    ]
+
+
+class ta_opts(ctypes.Structure):
+    _fields_ = [
+        ("scale", ctypes.c_float),
+        ("num_splits", ctypes.c_int32),
+        ("kernel", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+        ("workspace", ctypes.c_void_p),
+        ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+class Desc:
+    """A tensor descriptor without storage behind it (host-side validation tests)."""
+
+    def __init__(self, shape, dtype, stride=None, ptr=0x1000):
+        self.shape = tuple(shape)
+        self.dtype = dtype
+        if stride is None:
+            stride, acc = [], 1
+            for s in reversed(self.shape):
+                stride.append(acc)
+                acc *= max(int(s), 1)
+            stride = tuple(reversed(stride))
+        self.stride = tuple(stride)
+        self.ptr = ptr
+
+
+class TreeAttnError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, tree_attn_strerror(status), status))
+
+
+_lib = None
+
+
+def load_library():
+    """Load libtreeattn.so (built in-tree by paper_2508_08192_amd.build).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "libtreeattn.so is not built: run `python -m paper_2508_08192_amd.build` "
+                "(there is no CPU fallback for the tree-attention kernels)")
+        lib = ctypes.CDLL(LIB_PATH)
+        T = ctypes.POINTER(ta_tensor)
+        lib.tree_attn_fwd.restype = ctypes.c_int
+        lib.tree_attn_fwd.argtypes = [T, T, T, T, T, T, T, T, ctypes.c_void_p]
+        lib.tree_attn_fwd_ex.restype = ctypes.c_int
+        lib.tree_attn_fwd_ex.argtypes = [T, T, T, T, T, T, T, T, ctypes.c_void_p, ctypes.POINTER(ta_opts)]
+        lib.tree_attn_workspace_bytes.restype = ctypes.c_size_t
+        lib.tree_attn_workspace_bytes.argtypes = [ctypes.c_int32] * 7
+        lib.tree_attn_reserve.restype = ctypes.c_int
+        lib.tree_attn_reserve.argtypes = [ctypes.c_size_t]
+        lib.tree_attn_encode.restype = ctypes.c_int
+        lib.tree_attn_encode.argtypes = [T, T, ctypes.c_void_p]
+        lib.tree_attn_last_status.restype = ctypes.c_int
+        lib.tree_attn_last_status.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
+        lib.tree_attn_plan.restype = ctypes.c_int
+        lib.tree_attn_plan.argtypes = [T, T, T, T, T, T, T, T, ctypes.POINTER(ta_opts), ctypes.c_int32,
+                                       ctypes.POINTER(ctypes.c_int64)]
+        lib.tree_attn_strerror.restype = ctypes.c_char_p
+        lib.tree_attn_strerror.argtypes = [ctypes.c_int]
+        lib.tree_attn_version.restype = ctypes.c_int
+        lib.tree_attn_version.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _torch_dtype_code(t):
+    import torch
+    table = {torch.float32: TA_F32, torch.bfloat16: TA_BF16, torch.int32: TA_I32, torch.int64: TA_U64,
+             torch.uint64: TA_U64}
+    if t.dtype not in table:
+        return -1
+    return table[t.dtype]
+
+
+def _desc(t):
+    """torch tensor | Desc | None -> (ta_tensor or None)."""
+    if t is None:
+        return None
+    d = ta_tensor()
+    if isinstance(t, Desc):
+        shape, stride, d.data, d.dtype = t.shape, t.stride, t.ptr, t.dtype
+    else:
+        shape, stride, d.data, d.dtype = tuple(t.shape), tuple(t.stride()), t.data_ptr(), _torch_dtype_code(t)
+    if len(shape) > 5:
+        raise ValueError("at most 5 dimensions")
+    d.ndim = len(shape)
+    for i, (s, st) in enumerate(zip(shape, stride)):
+        d.shape[i] = s
+        d.stride[i] = st
+    return d
+
+
+def _ref(d):
+    return ctypes.byref(d) if d is not None else None
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _opts(scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None):
+    o = ta_opts()
+    o.scale = 0.0 if scale is None else float(scale)
+    o.num_splits = int(num_splits)
+    o.kernel = int(kernel)
+    o.reserved = 0
+    if workspace is not None:
+        o.workspace = workspace.data_ptr()
+        o.workspace_bytes = workspace.numel() * workspace.element_size()
+    return o
+
+
+def tree_attn_version():
+    return int(load_library().tree_attn_version())
+
+
+def tree_attn_strerror(status):
+    return load_library().tree_attn_strerror(int(status)).decode()
+
+
+def tree_attn_fwd(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse=None, stream=None, check=True):
+    """include/treeattn.h: tree_attn_fwd.  Returns the status code (raises TreeAttnError if check)."""
+    ds = [_desc(x) for x in (q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse)]
+    rc = load_library().tree_attn_fwd(*[_ref(d) for d in ds], _stream_ptr(stream) if stream != 0 else None)
+    if check and rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_fwd")
+    return rc
+
+
+def tree_attn_fwd_ex(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse=None, stream=None,
+                     scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, check=True):
+    """include/treeattn.h: tree_attn_fwd_ex."""
+    ds = [_desc(x) for x in (q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse)]
+    o = _opts(scale, num_splits, kernel, workspace)
+    rc = load_library().tree_attn_fwd_ex(*[_ref(d) for d in ds], _stream_ptr(stream) if stream != 0 else None,
+                                         ctypes.byref(o))
+    if check and rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_fwd_ex")
+    return rc
+
+
+def tree_attn_workspace_bytes(B, T, Hq, Hkv, D, dtype, num_cus=0):
+    return int(load_library().tree_attn_workspace_bytes(B, T, Hq, Hkv, D, dtype, num_cus))
+
+
+def tree_attn_reserve(nbytes, check=True):
+    rc = load_library().tree_attn_reserve(int(nbytes))
+    if check and rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_reserve")
+    return rc
+
+
+def tree_attn_encode(tree_parent, masks, stream=None, check=True):
+    a, b = _desc(tree_parent), _desc(masks)
+    rc = load_library().tree_attn_encode(_ref(a), _ref(b), _stream_ptr(stream) if stream != 0 else None)
+    if check and rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_encode")
+    return rc
+
+
+def tree_attn_last_status(stream=None):
+    """Reads and clears the device status word (synchronises the stream)."""
+    val = ctypes.c_int32(0)
+    rc = load_library().tree_attn_last_status(ctypes.byref(val), _stream_ptr(stream) if stream != 0 else None)
+    if rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_last_status")
+    return int(val.value)
+
+
+def tree_attn_plan(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse=None, num_cus=256,
+                   scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, check=True):
+    """Host-only launch plan; returns a dict (or the negative status if check is False and it failed)."""
+    ds = [_desc(x) for x in (q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse)]
+    o = _opts(scale, num_splits, kernel, None)
+    plan = (ctypes.c_int64 * 8)()
+    rc = load_library().tree_attn_plan(*[_ref(d) for d in ds], ctypes.byref(o), num_cus, plan)
+    if rc != TA_OK:
+        if check:
+            raise TreeAttnError(rc, "tree_attn_plan")
+        return rc
+    keys = ("kernel", "kv_workgroups", "threads", "tile", "row_groups", "rows_per_group", "partial_slots",
+            "merge_workgroups")
+    return dict(zip(keys, [int(x) for x in plan]))

@@ -1,0 +1,235 @@
+"""Parity of the HIP path (through the C-ABI) against the fp64 oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+from paper_2508_08192_amd import workloads as W
+
+from .helpers import assert_parity, run_hip, run_oracle, to_device
+
+pytestmark = pytest.mark.gpu
+
+GENERIC, MFMA = 1, 2
+
+
+def _announce(name):
+    print("\n[case] %s" % name, flush=True)
+
+
+def _check(w, what=None, **opts):
+    _announce(what or w.name)
+    ref, ref_lse = run_oracle(w)
+    got, got_lse = run_hip(w, **opts)
+    assert_parity(got, got_lse, ref, ref_lse, w.dtype, what or w.name)
+    return got, got_lse
+
+
+def test_c1_tiny_fp32_exact_config():
+    w = W.make_config(0)
+    _check(w)
+    _check(w, "c1 with 3 shares", num_splits=3)
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA])
+@pytest.mark.parametrize("L", [0, 1, 63, 64, 65, 200, 777])
+def test_bf16_prefix_length_sweep(kernel, L):
+    rng = np.random.default_rng(L)
+    B, T = 3, 16
+    trees = np.stack([W.random_tree(T, 5, rng) for _ in range(B)])
+    w = W.make_workload("sweep", B=B, T=T, Hq=8, Hkv=2, D=128, seq_lens=[L, L + 17, max(L - 1, 0)], trees=trees,
+                        page_size=16, dtype="bf16", seed=200 + L)
+    _check(w, "L=%d kernel=%d" % (L, kernel), kernel=kernel)
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA])
+def test_tree_straddles_a_page_boundary(kernel):
+    rng = np.random.default_rng(5)
+    ps, T = 64, 32
+    trees = np.stack([W.random_deep_tree(T, 9, rng) for _ in range(4)])
+    w = W.make_workload("straddle", B=4, T=T, Hq=4, Hkv=1, D=128, seq_lens=[ps - 1, 2 * ps - 5, 3 * ps, 3 * ps - T],
+                        trees=trees, page_size=ps, dtype="bf16", seed=301)
+    _check(w, kernel=kernel)
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA])
+@pytest.mark.parametrize("shape", [
+    dict(T=1, Hq=4, Hkv=4),          # single node: decode attention, one row per KV head
+    dict(T=3, Hq=8, Hkv=1),          # chain of three, 24 rows
+    dict(T=8, Hq=8, Hkv=1),          # 64 rows
+    dict(T=12, Hq=10, Hkv=2),        # 60 rows, ragged row block
+    dict(T=64, Hq=8, Hkv=2),         # 256 rows
+    dict(T=64, Hq=12, Hkv=1),        # 768 rows: three row groups
+    dict(T=33, Hq=7, Hkv=1),         # 231 rows
+])
+def test_bf16_row_shapes(kernel, shape):
+    rng = np.random.default_rng(shape["T"])
+    T = shape["T"]
+    B = 2
+    trees = np.stack([W.random_tree(T, 6, rng) for _ in range(B)])
+    w = W.make_workload("rows", B=B, T=T, D=128, seq_lens=[150, 333], trees=trees, page_size=32, dtype="bf16",
+                        seed=400 + T, **{k: v for k, v in shape.items() if k != "T"})
+    _check(w, "rows %r kernel=%d" % (shape, kernel), kernel=kernel)
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA])
+def test_contiguous_layout_and_chain_tree(kernel):
+    w = W.make_workload("contig", B=3, T=24, Hq=4, Hkv=2, D=128, seq_lens=[90, 0, 301], trees=W.chain_tree(24),
+                        page_size=0, dtype="bf16", seed=501, paged=False)
+    _check(w, kernel=kernel)
+
+
+def test_generic_kernel_shapes_the_matrix_core_path_does_not_take():
+    rng = np.random.default_rng(6)
+    for D, ps, dtype in [(64, 16, "bf16"), (80, 48, "bf16"), (256, 8, "bf16"), (128, 48, "bf16"), (128, 16, "f32"),
+                         (96, 10, "f32")]:
+        T = 9
+        w = W.make_workload("gen", B=2, T=T, Hq=6, Hkv=3, D=D, seq_lens=[70, 129], trees=W.random_tree(T, 4, rng),
+                            page_size=ps, dtype=dtype, seed=600 + D)
+        _check(w, "D=%d ps=%d %s" % (D, ps, dtype))
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA])
+def test_result_does_not_depend_on_the_split(kernel):
+    rng = np.random.default_rng(7)
+    T = 16
+    trees = np.stack([W.random_tree(T, 5, rng) for _ in range(4)])
+    w = W.make_workload("splits", B=4, T=T, Hq=8, Hkv=2, D=128, seq_lens=[500, 64, 1030, 3], trees=trees,
+                        page_size=64, dtype="bf16", seed=701)
+    ref, ref_lse = run_oracle(w)
+    dev = to_device(w)
+    for n in (1, 2, 3, 7, 64, 0):
+        _announce("num_splits=%d kernel=%d" % (n, kernel))
+        got, got_lse = run_hip(w, dev, kernel=kernel, num_splits=n)
+        assert_parity(got, got_lse, ref, ref_lse, "bf16", "num_splits=%d" % n)
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA])
+def test_non_topological_node_numbering_and_forest(kernel):
+    rng = np.random.default_rng(8)
+    T = 20
+    base = W.random_tree(T, 6, rng)
+    base[5] = -1                                   # a second root
+    shuffled, _ = W.shuffle_tree(base, rng)
+    w = W.make_workload("shuffled", B=2, T=T, Hq=4, Hkv=2, D=128, seq_lens=[100, 7], trees=np.stack([base, shuffled]),
+                        page_size=16, dtype="bf16", seed=801)
+    _check(w, kernel=kernel)
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA])
+def test_mask_dominated_cases_short_prefix(kernel):
+    """With L in {0,1,2} the tree tokens carry almost all the weight: a wrong ancestor mask cannot hide."""
+    rng = np.random.default_rng(9)
+    T = 64
+    trees = np.stack([W.bfs_tree(T, [4], 6), W.random_deep_tree(T, 12, rng), W.chain_tree(T)])
+    w = W.make_workload("maskdom", B=3, T=T, Hq=4, Hkv=1, D=128, seq_lens=[0, 1, 2], trees=trees, page_size=128,
+                        dtype="bf16", seed=901)
+    _check(w, kernel=kernel)
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA])
+def test_nan_in_unowned_slots_does_not_leak(kernel):
+    rng = np.random.default_rng(10)
+    T = 8
+    w = W.make_workload("nanjunk", B=2, T=T, Hq=8, Hkv=2, D=128, seq_lens=[70, 120], trees=W.random_tree(T, 4, rng),
+                        page_size=64, dtype="bf16", seed=1001, garbage=float("nan"))
+    _check(w, kernel=kernel)
+
+
+@pytest.mark.parametrize("idx,div", [(1, 1), (2, 8), (3, 16), (4, 64)])
+def test_benchmark_configs_reduced_lengths_all_outputs(idx, div):
+    w = W.make_config(idx, length_div=div)
+    _check(w)
+
+
+def test_strided_views_token_major_cache():
+    rng = np.random.default_rng(11)
+    import torch
+    T = 16
+    w = W.make_workload("tokmajor", B=2, T=T, Hq=8, Hkv=2, D=128, seq_lens=[130, 64], trees=W.random_tree(T, 5, rng),
+                        page_size=32, dtype="bf16", seed=1101)
+    ref, ref_lse = run_oracle(w)
+    dev = to_device(w)
+    for key in ("k_cache", "v_cache"):
+        dev[key] = dev[key].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)    # [pages, ps, Hkv, D] storage
+        assert not dev[key].is_contiguous()
+    q_wide = torch.zeros((2, T, 8, 256), dtype=torch.bfloat16, device="cuda:0")      # q as a slice of a wider buffer
+    q_wide[..., :128] = dev["q"]
+    dev["q"] = q_wide[..., :128]
+    for kernel in (GENERIC, MFMA):
+        _announce("strided kernel=%d" % kernel)
+        got, got_lse = run_hip(w, dev, kernel=kernel)
+        assert_parity(got, got_lse, ref, ref_lse, "bf16", "strided kernel=%d" % kernel)
+
+
+def test_repeat_calls_are_bit_identical():
+    w = W.make_config(2, length_div=16)
+    dev = to_device(w)
+    a, al = run_hip(w, dev)
+    b, bl = run_hip(w, dev)
+    assert np.array_equal(a, b) and np.array_equal(al, bl)
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA])
+def test_malformed_requests_get_nan_and_a_status_bit(kernel):
+    from paper_2508_08192_amd import treeattn as ta
+    T = 8
+    trees = np.int32([[-1, 0, 1, 2, 3, 4, 5, 6], [-1, 0, 3, 2, 0, 0, 0, 0], [-1, 0, 9, 1, 1, 1, 1, 1],
+                      [-1, 0, 0, 0, 1, 1, 2, 2]])
+    w = W.make_workload("bad", B=4, T=T, Hq=4, Hkv=2, D=128, seq_lens=[40, 40, 40, 40], trees=trees, page_size=16,
+                        dtype="bf16", seed=1201)
+    ta.tree_attn_last_status()
+    ref, ref_lse = run_oracle(w)
+    got, got_lse = run_hip(w, kernel=kernel)
+    assert ta.tree_attn_last_status() == ta.TA_STATUS_BAD_PARENT
+    assert np.isnan(got[1]).all() and np.isnan(got[2]).all() and np.isnan(got_lse[1]).all()
+    assert_parity(got[[0, 3]], got_lse[[0, 3]], ref[[0, 3]], ref_lse[[0, 3]], "bf16", "healthy requests")
+    w.seq_lens[0] = -3
+    w.seq_lens[3] = w.page_table.shape[1] * 16 - T + 1
+    w.tree_parent[1] = trees[0]
+    w.tree_parent[2] = trees[0]
+    ref, ref_lse = run_oracle(w)
+    got, got_lse = run_hip(w, kernel=kernel)
+    assert ta.tree_attn_last_status() == ta.TA_STATUS_BAD_SEQLEN
+    assert np.isnan(got[0]).all() and np.isnan(got[3]).all()
+    assert_parity(got[[1, 2]], got_lse[[1, 2]], ref[[1, 2]], ref_lse[[1, 2]], "bf16", "healthy requests")
+    assert ta.tree_attn_last_status() == 0
+
+
+def test_encoder_masks():
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+    from .helpers import ancestors_inclusive
+    rng = np.random.default_rng(12)
+    T = 64
+    trees = np.stack([W.random_tree(T, 9, rng), W.chain_tree(T), W.shuffle_tree(W.bfs_tree(T, [4, 2], 8), rng)[0]])
+    par = torch.from_numpy(trees).cuda()
+    masks = torch.zeros((3, T), dtype=torch.int64, device="cuda")
+    ta.tree_attn_encode(par, masks)
+    torch.cuda.synchronize()
+    got = masks.cpu().numpy().view(np.uint64)
+    for b in range(3):
+        for i in range(T):
+            want = 0
+            for j in ancestors_inclusive(trees[b], i):
+                want |= 1 << j
+            assert int(got[b, i]) == want
+    one = torch.zeros((T,), dtype=torch.int64, device="cuda")
+    ta.tree_attn_encode(par[1], one)
+    torch.cuda.synchronize()
+    assert np.array_equal(one.cpu().numpy().view(np.uint64), got[1])
+
+
+def test_empty_batch_and_no_lse():
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+    w = W.make_config(2, length_div=64)
+    dev = to_device(w)
+    ref, _ = run_oracle(w)
+    dev["out"].fill_(float("nan"))
+    ta.tree_attn_fwd(dev["q"], dev["k_cache"], dev["v_cache"], dev["page_table"], dev["seq_lens"], dev["tree_parent"],
+                     dev["out"], None)
+    torch.cuda.synchronize()
+    got = dev["out"].float().cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref).max() <= 1e-2
+    e = {k: (v[:0] if v is not None and k != "k_cache" and k != "v_cache" else v) for k, v in dev.items()}
+    assert ta.tree_attn_fwd(e["q"], e["k_cache"], e["v_cache"], e["page_table"], e["seq_lens"], e["tree_parent"],
+                            e["out"], e["lse"]) == 0

@@ -1,0 +1,132 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header declares, rejects bad
+descriptors before touching a device, and plans launches sensibly."""
+import os
+import re
+
+import pytest
+
+from paper_2508_08192_amd import treeattn as ta
+from paper_2508_08192_amd.treeattn import Desc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(ta.LIB_PATH):
+        from paper_2508_08192_amd.build import build_library
+        build_library()
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "treeattn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(tree_attn_\w+)\s*\(", header))
+    assert declared == set(ta.EXPORTS)
+    lib = ta.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert ta.tree_attn_version() == 100
+    assert ta.tree_attn_strerror(0) == "ok" and "NULL" in ta.tree_attn_strerror(ta.TA_ERR_NULL)
+
+
+def _good(B=2, T=8, Hq=8, Hkv=2, D=128, ps=64, max_pages=5, dtype=ta.TA_BF16, pages=16):
+    return dict(
+        q=Desc((B, T, Hq, D), dtype), k_cache=Desc((pages, Hkv, ps, D), dtype), v_cache=Desc((pages, Hkv, ps, D), dtype),
+        page_table=Desc((B, max_pages), ta.TA_I32), seq_lens=Desc((B,), ta.TA_I32),
+        tree_parent=Desc((B, T), ta.TA_I32), out=Desc((B, T, Hq, D), dtype), lse=Desc((B, Hq, T), ta.TA_F32))
+
+
+def _rc(**over):
+    a = _good()
+    a.update(over)
+    # tree_attn_fwd must refuse these before any device call, so it is safe to call it without a GPU
+    return ta.tree_attn_fwd(a["q"], a["k_cache"], a["v_cache"], a["page_table"], a["seq_lens"], a["tree_parent"],
+                            a["out"], a["lse"], stream=0, check=False)
+
+
+def test_descriptor_errors_are_reported_before_any_launch():
+    assert _rc(q=None) == ta.TA_ERR_NULL
+    assert _rc(out=None) == ta.TA_ERR_NULL
+    assert _rc(q=Desc((2, 8, 8, 128), ta.TA_BF16, ptr=0)) == ta.TA_ERR_NULL
+    assert _rc(q=Desc((2, 8, 8, 128), ta.TA_I32)) == ta.TA_ERR_DTYPE
+    assert _rc(k_cache=Desc((16, 2, 64, 128), ta.TA_F32)) == ta.TA_ERR_DTYPE
+    assert _rc(seq_lens=Desc((2,), ta.TA_F32)) == ta.TA_ERR_DTYPE
+    assert _rc(lse=Desc((2, 8, 8), ta.TA_BF16)) == ta.TA_ERR_DTYPE
+    assert _rc(q=Desc((2, 8, 1024), ta.TA_BF16)) == ta.TA_ERR_RANK
+    assert _rc(page_table=Desc((10,), ta.TA_I32)) == ta.TA_ERR_RANK
+    assert _rc(out=Desc((2, 8, 8, 64), ta.TA_BF16)) == ta.TA_ERR_SHAPE
+    assert _rc(v_cache=Desc((16, 2, 32, 128), ta.TA_BF16)) == ta.TA_ERR_SHAPE
+    assert _rc(seq_lens=Desc((3,), ta.TA_I32)) == ta.TA_ERR_SHAPE
+    assert _rc(tree_parent=Desc((2, 7), ta.TA_I32)) == ta.TA_ERR_SHAPE
+    assert _rc(lse=Desc((2, 8, 7), ta.TA_F32)) == ta.TA_ERR_SHAPE
+    assert _rc(page_table=Desc((3, 5), ta.TA_I32)) == ta.TA_ERR_SHAPE
+    assert _rc(q=Desc((2, 8, 8, 128), ta.TA_BF16, stride=(8192, 1024, 128, 2))) == ta.TA_ERR_STRIDE
+    assert _rc(k_cache=Desc((16, 2, 64, 128), ta.TA_BF16, stride=(16384, 8192, -128, 1))) == ta.TA_ERR_STRIDE
+    a = _good(Hq=6, Hkv=4)
+    assert ta.tree_attn_fwd(*[a[k] for k in ("q", "k_cache", "v_cache", "page_table", "seq_lens", "tree_parent",
+                                             "out", "lse")], stream=0, check=False) == ta.TA_ERR_HEADS
+    a = _good(D=512)
+    assert ta.tree_attn_fwd(*[a[k] for k in ("q", "k_cache", "v_cache", "page_table", "seq_lens", "tree_parent",
+                                             "out", "lse")], stream=0, check=False) == ta.TA_ERR_HEAD_DIM
+    a = _good(T=65)
+    assert ta.tree_attn_fwd(*[a[k] for k in ("q", "k_cache", "v_cache", "page_table", "seq_lens", "tree_parent",
+                                             "out", "lse")], stream=0, check=False) == ta.TA_ERR_TREE_SIZE
+    a = _good(T=8, ps=4, max_pages=1)
+    assert ta.tree_attn_fwd(*[a[k] for k in ("q", "k_cache", "v_cache", "page_table", "seq_lens", "tree_parent",
+                                             "out", "lse")], stream=0, check=False) == ta.TA_ERR_PAGE_TABLE
+    a = _good(B=5000)
+    assert ta.tree_attn_fwd(*[a[k] for k in ("q", "k_cache", "v_cache", "page_table", "seq_lens", "tree_parent",
+                                             "out", "lse")], stream=0, check=False) == ta.TA_ERR_BATCH
+    # contiguous layout needs one cache row per request
+    assert _rc(page_table=None, k_cache=Desc((1, 2, 64, 128), ta.TA_BF16),
+               v_cache=Desc((1, 2, 64, 128), ta.TA_BF16)) == ta.TA_ERR_SHAPE
+
+
+def _plan(a, **kw):
+    return ta.tree_attn_plan(a["q"], a["k_cache"], a["v_cache"], a["page_table"], a["seq_lens"], a["tree_parent"],
+                             a["out"], a["lse"], **kw)
+
+
+def test_option_errors():
+    a = _good()
+    assert _plan(a, kernel=7, check=False) == ta.TA_ERR_OPTS
+    assert _plan(a, num_splits=-1, check=False) == ta.TA_ERR_OPTS
+    # the matrix-core kernel is bf16, head_dim 128, power-of-two pages only
+    assert _plan(_good(dtype=ta.TA_F32), kernel=ta.TA_KERNEL_MFMA, check=False) == ta.TA_ERR_OPTS
+    assert _plan(_good(D=64), kernel=ta.TA_KERNEL_MFMA, check=False) == ta.TA_ERR_OPTS
+    assert _plan(_good(ps=48), kernel=ta.TA_KERNEL_MFMA, check=False) == ta.TA_ERR_OPTS
+
+
+def test_plan_picks_kernel_family_and_sizes():
+    p = _plan(_good(B=1, T=64, Hq=32, Hkv=8, max_pages=65))
+    assert p["kernel"] == ta.TA_KERNEL_MFMA and p["rows_per_group"] == 256 and p["row_groups"] == 1
+    assert p["threads"] == 512 and p["tile"] == 64
+    assert p["partial_slots"] == p["kv_workgroups"] + 8
+    p = _plan(_good(B=32, T=16, Hq=32, Hkv=8, max_pages=129))
+    assert p["kernel"] == ta.TA_KERNEL_MFMA and p["rows_per_group"] == 64 and p["threads"] == 128
+    p = _plan(_good(B=1, T=64, Hq=64, Hkv=8, max_pages=65))       # 512 rows -> two row groups
+    assert p["row_groups"] == 2 and p["rows_per_group"] == 256
+    p = _plan(_good(B=1, T=7, Hq=4, Hkv=1, D=64, dtype=ta.TA_F32))
+    assert p["kernel"] == ta.TA_KERNEL_GENERIC and p["rows_per_group"] == 28
+    p = _plan(_good(ps=48))
+    assert p["kernel"] == ta.TA_KERNEL_GENERIC
+    p = _plan(_good(), num_splits=3)
+    assert p["kv_workgroups"] == 3
+    # never more workgroups than tiles that can exist: B*Hkv*(ceil((capacity-T)/64)+1)
+    p = _plan(_good(B=1, T=8, Hq=8, Hkv=1, ps=64, max_pages=2))
+    assert p["kv_workgroups"] <= 1 * 1 * (2 + 1)
+
+
+def test_workspace_bound_covers_every_plan():
+    for kw in (dict(B=1, T=64, Hq=32, Hkv=8, max_pages=65), dict(B=32, T=16, Hq=32, Hkv=8, max_pages=129),
+               dict(B=64, T=32, Hq=8, Hkv=1, max_pages=513), dict(B=3, T=5, Hq=6, Hkv=3, D=64, dtype=ta.TA_F32)):
+        a = _good(**kw)
+        B, T, Hq, D = a["q"].shape
+        Hkv = a["k_cache"].shape[1]
+        bound = ta.tree_attn_workspace_bytes(B, T, Hq, Hkv, D, a["q"].dtype, 256)
+        for kern in (ta.TA_KERNEL_AUTO, ta.TA_KERNEL_GENERIC):
+            p = _plan(a, kernel=kern)
+            need = p["partial_slots"] * p["row_groups"] * p["rows_per_group"] * (D + 1) * 4
+            assert need <= bound
+    assert ta.tree_attn_workspace_bytes(1, 65, 8, 8, 128, ta.TA_BF16, 256) == 0
