@@ -43,9 +43,11 @@ bool strides_ok(const ta_tensor *t)
 
 int mfma_rows_group(int rows)
 {
-    // Padded to whole 32-row MFMA blocks, at most TA_ROW_GROUP rows per workgroup.
-    int padded = (rows + 31) / 32 * 32;
-    return padded < TA_ROW_GROUP ? padded : TA_ROW_GROUP;
+    // 32 rows per wave; workgroups of 1, 2, 4 or 8 such waves, at most TA_ROW_GROUP rows.
+    int grp = 32;
+    while (grp < rows && grp < TA_ROW_GROUP)
+        grp *= 2;
+    return grp;
 }
 
 // Everything that can be decided from the descriptors alone.  No HIP call in here.
@@ -172,7 +174,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
         return TA_ERR_SHAPE;
     if (kernel == TA_KERNEL_MFMA) {
         pl.rows_grp = mfma_rows_group(p.rows);
-        pl.threads = pl.rows_grp / 32 * TA_WAVE;
+        pl.threads = pl.rows_grp <= 64 ? 128 : pl.rows_grp / 32 * TA_WAVE;
         pl.n_rg = (p.rows + pl.rows_grp - 1) / pl.rows_grp;
         // A workgroup's partial result costs rows*D*4 bytes written and read again; a tile of keys and
         // values costs TA_TILE*D*4 bytes.  Keep a share at least as long as the rows are many, so the

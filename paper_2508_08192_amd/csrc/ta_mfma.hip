@@ -1,3 +1,384 @@
-// placeholder until the matrix-core kernel lands
+// Matrix-core KV pass of libtreeattn for gfx950: bf16 inputs, head_dim 128, fp32 accumulation.
+//
+// One workgroup keeps up to 256 query rows of one (request, KV head) -- the T tree nodes times the
+// G query heads that share the KV head (GQA packing) -- and streams its share of that head's tile
+// list through LDS: prefix tiles of 64 cached tokens (mask-free; section 3.1, prefix attention) and,
+// last in every list, the tile of the T tree tokens, whose scores are masked in registers with the
+// row's 64-bit ancestor mask (section 3.1, suffix attention).  Prefix and suffix partials that meet in
+// one workgroup are merged on the fly by the running softmax, which is the same log-sum-exp merge the
+// merge pass applies across workgroups.
+//
+// Each wave owns 32 rows.  Both contractions are issued in transposed form so that a lane owns one
+// query row throughout (row statistics never leave the lane):
+//     S^T[token, row] = K[token, :] . Q[row, :]      A = K fragment (LDS),  B = Q fragment (registers)
+//     O^T[d, row]    += V^T[d, token] . P^T[token, row]   A = V^T fragment (LDS), B = P (registers)
+// with v_mfma_f32_32x32x16_bf16.  The accumulator layout of S^T (lane = row, registers = tokens) is,
+// up to a fixed permutation of the 16 contraction slots, the B-operand layout the second product
+// needs; V is stored in LDS with the same slot permutation, token-minor, so its A fragments are
+// single 16-byte reads.
 #include "ta_common.h"
-hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream) { return ta_launch_generic(p, stream); }
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define MF_D 128
+#define MF_TILE_BYTES (TA_TILE * MF_D * 2)       // one K or V tile in LDS: 16 KB
+#define MF_STAGES 2
+#define MF_UNITS 512                             // staging units per tile: 256 for K, 256 for V
+
+static_assert(TA_TILE == 64, "the fragment maps below assume 64-token tiles");
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v)
+{
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    f32x2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+
+// Staging unit u of a tile: 4 consecutive tokens (quad) x 8 consecutive head-dim elements (chunk),
+// i.e. four 16-byte global loads.  Units 0..255 carry K, 256..511 carry V.
+struct Unit {
+    uint4 r[4];
+};
+
+// Loads one unit.  pos0 = logical position of the unit's first token, n_valid = how many of its four
+// tokens exist (the others are staged as zeros, so stale cache contents -- NaN included -- never
+// reach a product).
+__device__ __forceinline__ void load_unit(const TAParams &p, Unit &u, const uint16_t *base, int64_t sp, int64_t sh,
+                                          int64_t ss, int b, int g, int pos0, int n_valid, int chunk)
+{
+    int64_t off[4];
+    if (n_valid > 0) {
+        if (!p.page_table) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                off[k] = (int64_t)b * sp + (int64_t)g * sh + (int64_t)(pos0 + k) * ss;
+        } else if (p.ps_shift >= 2 && (pos0 & 3) == 0) {
+            const int64_t page = p.page_table[(int64_t)b * p.pt_sb + (pos0 >> p.ps_shift)];
+            const int64_t o0 = page * sp + (int64_t)g * sh + (int64_t)(pos0 & (p.ps - 1)) * ss;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                off[k] = o0 + k * ss;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int pos = pos0 + (k < n_valid ? k : 0);
+                const int64_t page = p.page_table[(int64_t)b * p.pt_sb + (pos >> p.ps_shift)];
+                off[k] = page * sp + (int64_t)g * sh + (int64_t)(pos & (p.ps - 1)) * ss;
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        if (k < n_valid)
+            u.r[k] = *(const uint4 *)(base + off[k] + chunk * 8);
+        else
+            u.r[k] = make_uint4(0, 0, 0, 0);
+    }
+}
+
+// K tile in LDS: [token 0..63][16 chunks of 16 B], chunk index XOR-swizzled with (token & 15) so that
+// the 16-byte fragment reads of 16 different tokens at one chunk hit distinct banks.
+__device__ __forceinline__ void store_k_unit(char *ktile, const Unit &u, int quad, int chunk)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int row = quad * 4 + k;
+        *(uint4 *)(ktile + row * 256 + ((chunk ^ (row & 15)) << 4)) = u.r[k];
+    }
+}
+
+// V tile in LDS, token-minor: [kb 0..3][half 0..1][128 head-dim slots][8 tokens] of bf16, where the 8
+// tokens of (kb, half) are 16kb + 4half + {0,1,2,3} and 16kb + 8 + 4half + {0,1,2,3}: exactly the
+// contraction slots a lane of that half feeds to the second MFMA.  The head-dim slot of column d is
+// d ^ ((d >> 4) & 7), which spreads the eight 8-byte writes of a staging thread over the banks.
+__device__ __forceinline__ void store_v_unit(char *vtile, const Unit &u, int quad, int chunk)
+{
+    const int kb = quad >> 2, half = quad & 1, sec = (quad >> 1) & 1;
+    char *base = vtile + ((kb * 2 + half) * 128) * 16 + sec * 8;
+    const uint32_t *r0 = (const uint32_t *)&u.r[0], *r1 = (const uint32_t *)&u.r[1];
+    const uint32_t *r2 = (const uint32_t *)&u.r[2], *r3 = (const uint32_t *)&u.r[3];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        // dword w of every token holds columns 8*chunk + 2w (low half) and 2w+1 (high half)
+        uint2 lo, hi;
+        lo.x = (r0[w] & 0xffffu) | (r1[w] << 16);
+        lo.y = (r2[w] & 0xffffu) | (r3[w] << 16);
+        hi.x = (r0[w] >> 16) | (r1[w] & 0xffff0000u);
+        hi.y = (r2[w] >> 16) | (r3[w] & 0xffff0000u);
+        const int d_lo = chunk * 8 + 2 * w, d_hi = d_lo + 1;
+        *(uint2 *)(base + ((d_lo ^ ((d_lo >> 4) & 7)) << 4)) = lo;
+        *(uint2 *)(base + ((d_hi ^ ((d_hi >> 4) & 7)) << 4)) = hi;
+    }
+}
+
+template <int NWAVES, int NT>
+__global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
+{
+    constexpr int UPT = MF_UNITS / NT;            // staging units per thread
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char *tiles = smem;                                                   // [MF_STAGES][K tile | V tile]
+    unsigned long long *masks = (unsigned long long *)(smem + MF_STAGES * 2 * MF_TILE_BYTES);   // [64]
+    int *flag = (int *)(masks + TA_MAX_TREE);
+    int *cum = flag + 4;                                                  // [B + 1]
+
+    ta_build_schedule(p, cum);
+    const int total = p.Hkv * cum[p.B];
+    const int share = ta_share(p, total);
+    const int w = blockIdx.x, rg = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r32 = lane & 31, hf = lane >> 5;
+    const bool compute_wave = wave < NWAVES;
+    int t = w * share;
+    const int t_end = min(total, t + share);
+    const int rows_here = min(p.rows_grp, p.rows - rg * p.rows_grp);
+    const uint16_t *kbase = (const uint16_t *)p.k, *vbase = (const uint16_t *)p.v;
+
+    while (t < t_end) {
+        const int b = ta_find_request(p, cum, t);
+        const int n_b = cum[b + 1] - cum[b];
+        const int g = (t - p.Hkv * cum[b]) / n_b;
+        const int seg_start = p.Hkv * cum[b] + g * n_b;
+        const int j0 = t - seg_start;
+        const int j1 = min(n_b, t_end - seg_start);
+        const int slot = w + b * p.Hkv + g;
+        const int L = p.seq_lens[(int64_t)b * p.sl_s];
+        bool poison = !ta_request_ok(p, L);
+        if (poison && tid == 0)
+            atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
+        const bool has_tree_tile = (j1 == n_b);
+        if (has_tree_tile && !poison) {
+            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag)) {
+                poison = true;
+                if (tid == 0)
+                    atomicOr(p.status, TA_STATUS_BAD_PARENT);
+            }
+        }
+        const int row = wave * 32 + r32;                   // row inside the row group
+        const int R = rg * p.rows_grp + row;               // row of the (request, KV head)
+        const bool row_ok = compute_wave && row < rows_here;
+        const int node = row_ok ? R / p.G : 0;
+        const int64_t wrow = ta_ws_row(p, slot, rg, row);
+
+        if (poison) {
+            if (row_ok) {
+                for (int d = hf * 64; d < hf * 64 + 64; d += 4)
+                    *(float4 *)(p.ws_o + wrow * MF_D + d) = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (hf == 0)
+                    p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
+            }
+            __syncthreads();
+            t = seg_start + j1;
+            continue;
+        }
+
+        // Q fragments (B operand of the first product): row r32 of this wave, head-dim 16kk + 8hf .. +8.
+        uint4 qf[8];
+        if (row_ok) {
+            const uint16_t *qp = (const uint16_t *)p.q + (int64_t)b * p.q_sb + (int64_t)node * p.q_st +
+                                 (int64_t)(g * p.G + R % p.G) * p.q_sh + hf * 8;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                qf[kk] = *(const uint4 *)(qp + kk * 16);
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                qf[kk] = make_uint4(0, 0, 0, 0);
+        }
+        // Rows of padding keep an all-ones mask so that their (discarded) softmax stays finite.
+        const unsigned long long tree_mask = (has_tree_tile && row_ok) ? masks[node] : ~0ull;
+
+        f32x16 acc_o[4];
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                acc_o[db][i] = 0.f;
+        float m_run = -INFINITY, l_run = 0.f;
+
+        // ---- staging: which units this thread carries, and loading tile j into registers
+        Unit stage[UPT];
+        auto load_tile = [&](int j) {
+            const bool tree_tile = (j == n_b - 1);
+            const int tile_pos0 = tree_tile ? L : j * TA_TILE;
+            const int limit = tree_tile ? L + p.T : L;
+#pragma unroll
+            for (int s = 0; s < UPT; ++s) {
+                const int u = tid + s * NT;
+                const int uu = u & 255, quad = uu >> 4, chunk = uu & 15;
+                const int pos0 = tile_pos0 + quad * 4;
+                const int n_valid = max(0, min(4, limit - pos0));
+                if (u < 256)
+                    load_unit(p, stage[s], kbase, p.k_sp, p.k_sh, p.k_ss, b, g, pos0, n_valid, chunk);
+                else
+                    load_unit(p, stage[s], vbase, p.v_sp, p.v_sh, p.v_ss, b, g, pos0, n_valid, chunk);
+            }
+        };
+        auto store_tile = [&](int buf) {
+            char *kt = tiles + buf * 2 * MF_TILE_BYTES, *vt = kt + MF_TILE_BYTES;
+#pragma unroll
+            for (int s = 0; s < UPT; ++s) {
+                const int u = tid + s * NT;
+                const int uu = u & 255, quad = uu >> 4, chunk = uu & 15;
+                if (u < 256)
+                    store_k_unit(kt, stage[s], quad, chunk);
+                else
+                    store_v_unit(vt, stage[s], quad, chunk);
+            }
+        };
+
+        load_tile(j0);
+        store_tile(0);
+        __syncthreads();
+
+        for (int j = j0; j < j1; ++j) {
+            const int buf = (j - j0) & 1;
+            if (j + 1 < j1)
+                load_tile(j + 1);                              // in flight while this tile is computed
+
+            if (compute_wave) {
+                const char *kt = tiles + buf * 2 * MF_TILE_BYTES, *vt = kt + MF_TILE_BYTES;
+                // ---- S^T = K . Q^T for the two 32-token blocks of the tile
+                f32x16 acc_s[2];
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        acc_s[tb][i] = 0.f;
+                const int sw = r32 & 15;
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) {
+#pragma unroll
+                    for (int tb = 0; tb < 2; ++tb) {
+                        const uint4 kf = *(const uint4 *)(kt + (tb * 32 + r32) * 256 + (((2 * kk + hf) ^ sw) << 4));
+                        acc_s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf), as_bf16x8(qf[kk]),
+                                                                            acc_s[tb], 0, 0, 0);
+                    }
+                }
+                // ---- which of this lane's 32 tokens count.  Register i of block tb is token
+                //      32tb + 8(i/4) + 4hf + (i%4) of the tile.
+                const bool tree_tile = (j == n_b - 1);
+                const int rem = L - j * TA_TILE;                   // tokens of a prefix tile that exist
+                const bool masked = tree_tile || rem < TA_TILE;
+                unsigned long long vm = ~0ull;
+                if (masked)
+                    vm = (tree_tile ? tree_mask : ((1ull << rem) - 1ull)) >> (4 * hf);
+                float s[2][16];
+                float tmax = -INFINITY;
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        float x = acc_s[tb][i] * p.scale_log2e;
+                        if (masked && !((vm >> (tb * 32 + 8 * (i / 4) + (i % 4))) & 1ull))
+                            x = -INFINITY;
+                        s[tb][i] = x;
+                        tmax = fmaxf(tmax, x);
+                    }
+                }
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, TA_WAVE));
+                const float m_new = fmaxf(m_run, tmax);
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                m_run = m_new;
+                float psum = 0.f;
+                uint4 pb[4];                                       // P as B operand, one per 16-token block
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb) {
+                    float e[8];
+#pragma unroll
+                    for (int jj = 0; jj < 8; ++jj) {
+                        e[jj] = __builtin_amdgcn_exp2f(s[kb >> 1][8 * (kb & 1) + jj] - m_new);
+                        psum += e[jj];
+                    }
+                    pb[kb].x = pack_bf16(e[0], e[1]);
+                    pb[kb].y = pack_bf16(e[2], e[3]);
+                    pb[kb].z = pack_bf16(e[4], e[5]);
+                    pb[kb].w = pack_bf16(e[6], e[7]);
+                }
+                l_run = l_run * alpha + psum;
+                if (__any(alpha != 1.0f)) {
+#pragma unroll
+                    for (int db = 0; db < 4; ++db)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            acc_o[db][i] *= alpha;
+                }
+                // ---- O^T += V^T . P^T
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb) {
+#pragma unroll
+                    for (int db = 0; db < 4; ++db) {
+                        const int d = db * 32 + r32;
+                        const uint4 vf = *(const uint4 *)(vt + (((kb * 2 + hf) * 128 + (d ^ ((d >> 4) & 7))) << 4));
+                        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vf), as_bf16x8(pb[kb]),
+                                                                            acc_o[db], 0, 0, 0);
+                    }
+                }
+            }
+
+            if (j + 1 < j1)
+                store_tile(buf ^ 1);
+            __syncthreads();
+        }
+
+        // ---- partial result of this (workgroup, list) overlap: normalised O and base-2 log-sum-exp
+        if (row_ok) {
+            const float l_tot = l_run + __shfl_xor(l_run, 32, TA_WAVE);
+            const float inv = 1.f / l_tot;
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    float4 o;
+                    o.x = acc_o[db][4 * i4 + 0] * inv;
+                    o.y = acc_o[db][4 * i4 + 1] * inv;
+                    o.z = acc_o[db][4 * i4 + 2] * inv;
+                    o.w = acc_o[db][4 * i4 + 3] * inv;
+                    *(float4 *)(p.ws_o + wrow * MF_D + db * 32 + 8 * i4 + 4 * hf) = o;
+                }
+            }
+            if (hf == 0)
+                p.ws_lse[wrow] = m_run + log2f(l_tot);
+        }
+        __syncthreads();                                       // masks and tiles are reused by the next item
+        t = seg_start + j1;
+    }
+}
+
+template <int NWAVES, int NT>
+static hipError_t launch_variant(const TAParams &p, hipStream_t stream)
+{
+    const size_t smem = MF_STAGES * 2 * MF_TILE_BYTES + sizeof(unsigned long long) * TA_MAX_TREE + 16 +
+                        sizeof(int) * (p.B + 2);
+    static bool attr_set[64] = {};      // per device and variant; setting it twice is harmless
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
+        hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_kv_kernel<NWAVES, NT>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+        if (e != hipSuccess)
+            return e;
+        attr_set[dev] = true;
+    }
+    hipLaunchKernelGGL((ta_mfma_kv_kernel<NWAVES, NT>), dim3(p.n_wg, p.n_rg), dim3(NT), smem, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
+{
+    switch (p.rows_grp) {
+    case 32: return launch_variant<1, 128>(p, stream);
+    case 64: return launch_variant<2, 128>(p, stream);
+    case 128: return launch_variant<4, 256>(p, stream);
+    case 256: return launch_variant<8, 512>(p, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
