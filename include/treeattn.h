@@ -93,6 +93,9 @@ typedef struct {
     int32_t reserved;         /* must be 0 */
     void *workspace;          /* device scratch, 256-byte aligned, or NULL = library-owned per-device buffer */
     size_t workspace_bytes;   /* size of `workspace` */
+    void *events[3];          /* optional hipEvent_t handles (HOST values) recorded on `stream`: [0] before the
+                                 KV pass, [1] between KV pass and merge pass, [2] after the merge pass; NULL
+                                 entries are skipped.  For measurement harnesses. */
 } ta_opts;
 
 /*

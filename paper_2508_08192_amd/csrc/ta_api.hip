@@ -369,11 +369,20 @@ int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tens
     }
     pr.p.status = s->status;
     hipStream_t st = (hipStream_t)stream;
+    void *const *ev = opts ? opts->events : nullptr;
+    if (ev && ev[0] && hipEventRecord((hipEvent_t)ev[0], st) != hipSuccess)
+        return TA_ERR_HIP;
     hipError_t e = pr.plan.kernel == TA_KERNEL_MFMA ? ta_launch_mfma(pr.p, st) : ta_launch_generic(pr.p, st);
     if (e != hipSuccess)
         return TA_ERR_HIP;
+    if (ev && ev[1] && hipEventRecord((hipEvent_t)ev[1], st) != hipSuccess)
+        return TA_ERR_HIP;
     e = ta_launch_merge(pr.p, st);
-    return e == hipSuccess ? TA_OK : TA_ERR_HIP;
+    if (e != hipSuccess)
+        return TA_ERR_HIP;
+    if (ev && ev[2] && hipEventRecord((hipEvent_t)ev[2], st) != hipSuccess)
+        return TA_ERR_HIP;
+    return TA_OK;
 }
 
 int tree_attn_fwd(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
