@@ -140,7 +140,8 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
                          k->stride[0] % 8 == 0 && k->stride[1] % 8 == 0 && k->stride[2] % 8 == 0 &&
                          v->stride[0] % 8 == 0 && v->stride[1] % 8 == 0 && v->stride[2] % 8 == 0 &&
                          ((uintptr_t)q->data % 16) == 0 && ((uintptr_t)k->data % 16) == 0 &&
-                         ((uintptr_t)v->data % 16) == 0;
+                         ((uintptr_t)v->data % 16) == 0 && k->stride[0] < INT32_MAX && k->stride[2] < INT32_MAX &&
+                         v->stride[0] < INT32_MAX && v->stride[2] < INT32_MAX;
     if (kernel == TA_KERNEL_MFMA && !mfma_ok)
         return TA_ERR_OPTS;
     if (kernel == TA_KERNEL_AUTO)
@@ -174,7 +175,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
         return TA_ERR_SHAPE;
     if (kernel == TA_KERNEL_MFMA) {
         pl.rows_grp = mfma_rows_group(p.rows);
-        pl.threads = pl.rows_grp <= 64 ? 128 : pl.rows_grp / 32 * TA_WAVE;
+        pl.threads = pl.rows_grp <= 64 ? 128 : (pl.rows_grp == 128 ? 256 : 512);
         pl.n_rg = (p.rows + pl.rows_grp - 1) / pl.rows_grp;
         // A workgroup's partial result costs rows*D*4 bytes written and read again; a tile of keys and
         // values costs TA_TILE*D*4 bytes.  Keep a share at least as long as the rows are many, so the

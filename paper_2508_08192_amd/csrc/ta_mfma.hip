@@ -8,14 +8,16 @@
 // one workgroup are merged on the fly by the running softmax, which is the same log-sum-exp merge the
 // merge pass applies across workgroups.
 //
-// Each wave owns 32 rows.  Both contractions are issued in transposed form so that a lane owns one
-// query row throughout (row statistics never leave the lane):
+// Each wave owns one or two blocks of 32 rows.  Both contractions are issued in transposed form so that
+// a lane owns one query row per block throughout (row statistics never leave the lane):
 //     S^T[token, row] = K[token, :] . Q[row, :]      A = K fragment (LDS),  B = Q fragment (registers)
 //     O^T[d, row]    += V^T[d, token] . P^T[token, row]   A = V^T fragment (LDS), B = P (registers)
 // with v_mfma_f32_32x32x16_bf16.  The accumulator layout of S^T (lane = row, registers = tokens) is,
 // up to a fixed permutation of the 16 contraction slots, the B-operand layout the second product
 // needs; V is stored in LDS with the same slot permutation, token-minor, so its A fragments are
 // single 16-byte reads.
+#include <stdlib.h>
+
 #include "ta_common.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -47,37 +49,39 @@ struct Unit {
     uint4 r[4];
 };
 
-// Loads one unit.  pos0 = logical position of the unit's first token, n_valid = how many of its four
-// tokens exist (the others are staged as zeros, so stale cache contents -- NaN included -- never
-// reach a product).
-__device__ __forceinline__ void load_unit(const TAParams &p, Unit &u, const uint16_t *base, int64_t sp, int64_t sh,
-                                          int64_t ss, int b, int g, int pos0, int n_valid, int chunk)
+// Loads one unit.  tbase already points at (KV head, 8-element chunk) of the cache; pos0 = logical
+// position of the unit's first token, n_valid = how many of its four tokens exist (the others are
+// staged as zeros, so stale cache contents -- NaN included -- never reach a product).  Page and slot
+// strides fit 32 bits (checked on the host), which keeps the address arithmetic to a few instructions.
+__device__ __forceinline__ void load_unit(const TAParams &p, Unit &u, const uint16_t *tbase, uint32_t sp, uint32_t ss,
+                                          int b, int pos0, int n_valid)
 {
-    int64_t off[4];
+    const uint16_t *ptr[4];
     if (n_valid > 0) {
         if (!p.page_table) {
+            const uint16_t *p0 = tbase + (uint64_t)(uint32_t)b * sp + (uint64_t)(uint32_t)pos0 * ss;
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                off[k] = (int64_t)b * sp + (int64_t)g * sh + (int64_t)(pos0 + k) * ss;
+                ptr[k] = p0 + (uint32_t)k * ss;
         } else if (p.ps_shift >= 2 && (pos0 & 3) == 0) {
-            const int64_t page = p.page_table[(int64_t)b * p.pt_sb + (pos0 >> p.ps_shift)];
-            const int64_t o0 = page * sp + (int64_t)g * sh + (int64_t)(pos0 & (p.ps - 1)) * ss;
+            const uint32_t page = (uint32_t)p.page_table[(int64_t)b * p.pt_sb + (pos0 >> p.ps_shift)];
+            const uint16_t *p0 = tbase + (uint64_t)page * sp + (uint32_t)(pos0 & (p.ps - 1)) * ss;
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                off[k] = o0 + k * ss;
+                ptr[k] = p0 + (uint32_t)k * ss;
         } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int pos = pos0 + (k < n_valid ? k : 0);
-                const int64_t page = p.page_table[(int64_t)b * p.pt_sb + (pos >> p.ps_shift)];
-                off[k] = page * sp + (int64_t)g * sh + (int64_t)(pos & (p.ps - 1)) * ss;
+                const uint32_t page = (uint32_t)p.page_table[(int64_t)b * p.pt_sb + (pos >> p.ps_shift)];
+                ptr[k] = tbase + (uint64_t)page * sp + (uint32_t)(pos & (p.ps - 1)) * ss;
             }
         }
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         if (k < n_valid)
-            u.r[k] = *(const uint4 *)(base + off[k] + chunk * 8);
+            u.r[k] = *(const uint4 *)ptr[k];
         else
             u.r[k] = make_uint4(0, 0, 0, 0);
     }
@@ -118,7 +122,85 @@ __device__ __forceinline__ void store_v_unit(char *vtile, const Unit &u, int qua
     }
 }
 
-template <int NWAVES, int NT>
+
+__device__ __forceinline__ void lds_barrier()
+{
+    // LDS traffic of this wave must have landed before the others proceed; global loads stay in flight.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    // one instruction; the generic fmaxf would first quiet every operand
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+__device__ __forceinline__ float half_swap_max(float x)
+{
+    // max over the two lanes that share a query row (lane and lane ^ 32)
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// Scores of tokens that do not exist for this lane's row become -inf.  Bit k of vm covers the register
+// with token offset k = 32tb + 8(i/4) + (i%4) (the lane's half offset 4hf is already shifted out).
+__device__ __forceinline__ void mask_scores(f32x16 (&acc_s)[2], unsigned long long vm)
+{
+    const uint32_t lo = (uint32_t)vm, hi = (uint32_t)(vm >> 32);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int bit = 8 * (i / 4) + (i % 4);
+        if (!((lo >> bit) & 1u))
+            acc_s[0][i] = -INFINITY;
+        if (!((hi >> bit) & 1u))
+            acc_s[1][i] = -INFINITY;
+    }
+}
+
+// Running-softmax bookkeeping of one 64-token tile for one 32-row block: s holds the lane's 32 raw
+// (unscaled) scores, c = softmax scale * log2(e).  Produces P as four bf16 B-operands and updates the
+// running max (raw units), the lane's share of the running sum, and (rarely) rescales O.
+__device__ __forceinline__ void softmax_tile(const f32x16 (&s)[2], float c, float &m_run, float &l_run,
+                                             f32x16 (&acc_o)[4], uint4 (&pb)[4])
+{
+    float tmax = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+    for (int i = 1; i < 16; ++i)
+        tmax = max3(tmax, s[0][i], s[1][i]);
+    tmax = half_swap_max(tmax);
+    const float m_new = fmaxf(m_run, tmax);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+    const float neg_mc = -m_new * c;
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+        float e[8];
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            e[jj] = __builtin_amdgcn_exp2f(fmaf(s[kb >> 1][8 * (kb & 1) + jj], c, neg_mc));
+            psum += e[jj];
+        }
+        pb[kb].x = pack_bf16(e[0], e[1]);
+        pb[kb].y = pack_bf16(e[2], e[3]);
+        pb[kb].z = pack_bf16(e[4], e[5]);
+        pb[kb].w = pack_bf16(e[6], e[7]);
+    }
+    l_run = l_run * alpha + psum;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                acc_o[db][i] *= alpha;
+    }
+}
+
+// NCW compute waves of RB 32-row blocks each (rows per workgroup = 32*RB*NCW), NT threads in all
+// (NT/64 - NCW waves only help with staging).
+template <int NCW, int RB, int NT>
 __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
 {
     constexpr int UPT = MF_UNITS / NT;            // staging units per thread
@@ -133,13 +215,23 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
     const int share = ta_share(p, total);
     const int w = blockIdx.x, rg = blockIdx.y;
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // wave-uniform, lives in SGPRs
     const int r32 = lane & 31, hf = lane >> 5;
-    const bool compute_wave = wave < NWAVES;
+    const bool compute_wave = wave < NCW;
     int t = w * share;
     const int t_end = min(total, t + share);
     const int rows_here = min(p.rows_grp, p.rows - rg * p.rows_grp);
-    const uint16_t *kbase = (const uint16_t *)p.k, *vbase = (const uint16_t *)p.v;
+    const float c = p.scale_log2e;
+    // LDS byte offsets of this lane's fragments inside a tile
+    const int sw = r32 & 15;
+    const int krow_off = r32 * 256;                                       // + tb*8192 + (((2kk+hf)^sw) << 4)
+    int vcol_off[4];                                                      // + kb*4096
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+        const int d = db * 32 + r32;
+        vcol_off[db] = (hf * 128 + (d ^ ((d >> 4) & 7))) << 4;
+    }
 
     while (t < t_end) {
         const int b = ta_find_request(p, cum, t);
@@ -161,47 +253,62 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                     atomicOr(p.status, TA_STATUS_BAD_PARENT);
             }
         }
-        const int row = wave * 32 + r32;                   // row inside the row group
-        const int R = rg * p.rows_grp + row;               // row of the (request, KV head)
-        const bool row_ok = compute_wave && row < rows_here;
-        const int node = row_ok ? R / p.G : 0;
-        const int64_t wrow = ta_ws_row(p, slot, rg, row);
 
         if (poison) {
-            if (row_ok) {
-                for (int d = hf * 64; d < hf * 64 + 64; d += 4)
-                    *(float4 *)(p.ws_o + wrow * MF_D + d) = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (hf == 0)
-                    p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
+            if (compute_wave) {
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    const int row = (wave * RB + rb) * 32 + r32;
+                    if (row < rows_here) {
+                        const int64_t wrow = ta_ws_row(p, slot, rg, row);
+                        for (int d = hf * 64; d < hf * 64 + 64; d += 4)
+                            *(float4 *)(p.ws_o + wrow * MF_D + d) = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (hf == 0)
+                            p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
+                    }
+                }
             }
             __syncthreads();
             t = seg_start + j1;
             continue;
         }
 
-        // Q fragments (B operand of the first product): row r32 of this wave, head-dim 16kk + 8hf .. +8.
-        uint4 qf[8];
-        if (row_ok) {
-            const uint16_t *qp = (const uint16_t *)p.q + (int64_t)b * p.q_sb + (int64_t)node * p.q_st +
-                                 (int64_t)(g * p.G + R % p.G) * p.q_sh + hf * 8;
+        // Q fragments (B operand of the first product): row r32 of each block, head-dim 16kk + 8hf .. +8.
+        uint4 qf[RB][8];
+        unsigned long long tree_mask[RB];
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                qf[kk] = *(const uint4 *)(qp + kk * 16);
-        } else {
+        for (int rb = 0; rb < RB; ++rb) {
+            const int row = (wave * RB + rb) * 32 + r32;
+            const int R = rg * p.rows_grp + row;
+            const bool row_ok = compute_wave && row < rows_here;
+            const int node = row_ok ? R / p.G : 0;
+            if (row_ok) {
+                const uint16_t *qp = (const uint16_t *)p.q + (int64_t)b * p.q_sb + (int64_t)node * p.q_st +
+                                     (int64_t)(g * p.G + R % p.G) * p.q_sh + hf * 8;
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                qf[kk] = make_uint4(0, 0, 0, 0);
+                for (int kk = 0; kk < 8; ++kk)
+                    qf[rb][kk] = *(const uint4 *)(qp + kk * 16);
+            } else {
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk)
+                    qf[rb][kk] = make_uint4(0, 0, 0, 0);
+            }
+            // Rows of padding keep an all-ones mask so that their (discarded) softmax stays finite.
+            tree_mask[rb] = (has_tree_tile && row_ok) ? masks[node] : ~0ull;
         }
-        // Rows of padding keep an all-ones mask so that their (discarded) softmax stays finite.
-        const unsigned long long tree_mask = (has_tree_tile && row_ok) ? masks[node] : ~0ull;
 
-        f32x16 acc_o[4];
+        f32x16 acc_o[RB][4];
+        float m_run[RB], l_run[RB];
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int rb = 0; rb < RB; ++rb) {
+            m_run[rb] = -INFINITY;
+            l_run[rb] = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-                acc_o[db][i] = 0.f;
-        float m_run = -INFINITY, l_run = 0.f;
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    acc_o[rb][db][i] = 0.f;
+        }
 
         // ---- staging: which units this thread carries, and loading tile j into registers
         Unit stage[UPT];
@@ -216,9 +323,11 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                 const int pos0 = tile_pos0 + quad * 4;
                 const int n_valid = max(0, min(4, limit - pos0));
                 if (u < 256)
-                    load_unit(p, stage[s], kbase, p.k_sp, p.k_sh, p.k_ss, b, g, pos0, n_valid, chunk);
+                    load_unit(p, stage[s], (const uint16_t *)p.k + (int64_t)g * p.k_sh + chunk * 8, (uint32_t)p.k_sp,
+                              (uint32_t)p.k_ss, b, pos0, n_valid);
                 else
-                    load_unit(p, stage[s], vbase, p.v_sp, p.v_sh, p.v_ss, b, g, pos0, n_valid, chunk);
+                    load_unit(p, stage[s], (const uint16_t *)p.v + (int64_t)g * p.v_sh + chunk * 8, (uint32_t)p.v_sp,
+                              (uint32_t)p.v_ss, b, pos0, n_valid);
             }
         };
         auto store_tile = [&](int buf) {
@@ -236,7 +345,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
 
         load_tile(j0);
         store_tile(0);
-        __syncthreads();
+        lds_barrier();
 
         for (int j = j0; j < j1; ++j) {
             const int buf = (j - j0) & 1;
@@ -245,114 +354,94 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
 
             if (compute_wave) {
                 const char *kt = tiles + buf * 2 * MF_TILE_BYTES, *vt = kt + MF_TILE_BYTES;
-                // ---- S^T = K . Q^T for the two 32-token blocks of the tile
-                f32x16 acc_s[2];
+                // ---- S^T = K . Q^T for the two 32-token blocks of the tile, each K fragment feeding RB blocks
+                f32x16 acc_s[RB][2];
+                const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                uint4 kf[3][2];
 #pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        acc_s[tb][i] = 0.f;
-                const int sw = r32 & 15;
+                for (int kk = 0; kk < 2; ++kk) {
+                    const int co = ((2 * kk + hf) ^ sw) << 4;
+                    kf[kk][0] = *(const uint4 *)(kt + krow_off + co);
+                    kf[kk][1] = *(const uint4 *)(kt + 8192 + krow_off + co);
+                }
 #pragma unroll
                 for (int kk = 0; kk < 8; ++kk) {
-#pragma unroll
-                    for (int tb = 0; tb < 2; ++tb) {
-                        const uint4 kf = *(const uint4 *)(kt + (tb * 32 + r32) * 256 + (((2 * kk + hf) ^ sw) << 4));
-                        acc_s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf), as_bf16x8(qf[kk]),
-                                                                            acc_s[tb], 0, 0, 0);
+                    if (kk + 2 < 8) {
+                        const int co = ((2 * (kk + 2) + hf) ^ sw) << 4;
+                        kf[(kk + 2) % 3][0] = *(const uint4 *)(kt + krow_off + co);
+                        kf[(kk + 2) % 3][1] = *(const uint4 *)(kt + 8192 + krow_off + co);
                     }
+#pragma unroll
+                    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb)
+                            acc_s[rb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                as_bf16x8(kf[kk % 3][tb]), as_bf16x8(qf[rb][kk]), kk == 0 ? zero16 : acc_s[rb][tb],
+                                0, 0, 0);
                 }
-                // ---- which of this lane's 32 tokens count.  Register i of block tb is token
-                //      32tb + 8(i/4) + 4hf + (i%4) of the tile.
+                // ---- which of this lane's 32 tokens count, then the running softmax per row block
                 const bool tree_tile = (j == n_b - 1);
                 const int rem = L - j * TA_TILE;                   // tokens of a prefix tile that exist
-                const bool masked = tree_tile || rem < TA_TILE;
-                unsigned long long vm = ~0ull;
-                if (masked)
-                    vm = (tree_tile ? tree_mask : ((1ull << rem) - 1ull)) >> (4 * hf);
-                float s[2][16];
-                float tmax = -INFINITY;
+                uint4 pb[RB][4];
 #pragma unroll
-                for (int tb = 0; tb < 2; ++tb) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        float x = acc_s[tb][i] * p.scale_log2e;
-                        if (masked && !((vm >> (tb * 32 + 8 * (i / 4) + (i % 4))) & 1ull))
-                            x = -INFINITY;
-                        s[tb][i] = x;
-                        tmax = fmaxf(tmax, x);
-                    }
+                for (int rb = 0; rb < RB; ++rb) {
+                    if (tree_tile || rem < TA_TILE)
+                        mask_scores(acc_s[rb], (tree_tile ? tree_mask[rb] : ((1ull << rem) - 1ull)) >> (4 * hf));
+                    softmax_tile(acc_s[rb], c, m_run[rb], l_run[rb], acc_o[rb], pb[rb]);
                 }
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, TA_WAVE));
-                const float m_new = fmaxf(m_run, tmax);
-                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-                m_run = m_new;
-                float psum = 0.f;
-                uint4 pb[4];                                       // P as B operand, one per 16-token block
+                // ---- O^T += V^T . P^T, each V fragment feeding RB blocks
+                uint4 vf[4];
 #pragma unroll
-                for (int kb = 0; kb < 4; ++kb) {
-                    float e[8];
+                for (int s = 0; s < 3; ++s)
+                    vf[s] = *(const uint4 *)(vt + (s >> 2) * 4096 + vcol_off[s & 3]);
 #pragma unroll
-                    for (int jj = 0; jj < 8; ++jj) {
-                        e[jj] = __builtin_amdgcn_exp2f(s[kb >> 1][8 * (kb & 1) + jj] - m_new);
-                        psum += e[jj];
-                    }
-                    pb[kb].x = pack_bf16(e[0], e[1]);
-                    pb[kb].y = pack_bf16(e[2], e[3]);
-                    pb[kb].z = pack_bf16(e[4], e[5]);
-                    pb[kb].w = pack_bf16(e[6], e[7]);
-                }
-                l_run = l_run * alpha + psum;
-                if (__any(alpha != 1.0f)) {
+                for (int s = 0; s < 16; ++s) {
+                    if (s + 3 < 16)
+                        vf[(s + 3) & 3] = *(const uint4 *)(vt + ((s + 3) >> 2) * 4096 + vcol_off[(s + 3) & 3]);
 #pragma unroll
-                    for (int db = 0; db < 4; ++db)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i)
-                            acc_o[db][i] *= alpha;
-                }
-                // ---- O^T += V^T . P^T
-#pragma unroll
-                for (int kb = 0; kb < 4; ++kb) {
-#pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        const int d = db * 32 + r32;
-                        const uint4 vf = *(const uint4 *)(vt + (((kb * 2 + hf) * 128 + (d ^ ((d >> 4) & 7))) << 4));
-                        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vf), as_bf16x8(pb[kb]),
-                                                                            acc_o[db], 0, 0, 0);
-                    }
+                    for (int rb = 0; rb < RB; ++rb)
+                        acc_o[rb][s & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            as_bf16x8(vf[s & 3]), as_bf16x8(pb[rb][s >> 2]), acc_o[rb][s & 3], 0, 0, 0);
                 }
             }
 
             if (j + 1 < j1)
                 store_tile(buf ^ 1);
-            __syncthreads();
+            lds_barrier();
         }
 
         // ---- partial result of this (workgroup, list) overlap: normalised O and base-2 log-sum-exp
-        if (row_ok) {
-            const float l_tot = l_run + __shfl_xor(l_run, 32, TA_WAVE);
-            const float inv = 1.f / l_tot;
+        if (compute_wave) {
 #pragma unroll
-            for (int db = 0; db < 4; ++db) {
+            for (int rb = 0; rb < RB; ++rb) {
+                const int row = (wave * RB + rb) * 32 + r32;
+                if (row < rows_here) {
+                    const int64_t wrow = ta_ws_row(p, slot, rg, row);
+                    const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32, TA_WAVE);
+                    const float inv = 1.f / l_tot;
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    float4 o;
-                    o.x = acc_o[db][4 * i4 + 0] * inv;
-                    o.y = acc_o[db][4 * i4 + 1] * inv;
-                    o.z = acc_o[db][4 * i4 + 2] * inv;
-                    o.w = acc_o[db][4 * i4 + 3] * inv;
-                    *(float4 *)(p.ws_o + wrow * MF_D + db * 32 + 8 * i4 + 4 * hf) = o;
+                    for (int db = 0; db < 4; ++db) {
+#pragma unroll
+                        for (int i4 = 0; i4 < 4; ++i4) {
+                            float4 o;
+                            o.x = acc_o[rb][db][4 * i4 + 0] * inv;
+                            o.y = acc_o[rb][db][4 * i4 + 1] * inv;
+                            o.z = acc_o[rb][db][4 * i4 + 2] * inv;
+                            o.w = acc_o[rb][db][4 * i4 + 3] * inv;
+                            *(float4 *)(p.ws_o + wrow * MF_D + db * 32 + 8 * i4 + 4 * hf) = o;
+                        }
+                    }
+                    if (hf == 0)
+                        p.ws_lse[wrow] = m_run[rb] * c + log2f(l_tot);
                 }
             }
-            if (hf == 0)
-                p.ws_lse[wrow] = m_run + log2f(l_tot);
         }
         __syncthreads();                                       // masks and tiles are reused by the next item
         t = seg_start + j1;
     }
 }
 
-template <int NWAVES, int NT>
+template <int NCW, int RB, int NT>
 static hipError_t launch_variant(const TAParams &p, hipStream_t stream)
 {
     const size_t smem = MF_STAGES * 2 * MF_TILE_BYTES + sizeof(unsigned long long) * TA_MAX_TREE + 16 +
@@ -362,23 +451,23 @@ static hipError_t launch_variant(const TAParams &p, hipStream_t stream)
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
     if (!attr_set[dev]) {
-        hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_kv_kernel<NWAVES, NT>,
+        hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_kv_kernel<NCW, RB, NT>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
         if (e != hipSuccess)
             return e;
         attr_set[dev] = true;
     }
-    hipLaunchKernelGGL((ta_mfma_kv_kernel<NWAVES, NT>), dim3(p.n_wg, p.n_rg), dim3(NT), smem, stream, p);
+    hipLaunchKernelGGL((ta_mfma_kv_kernel<NCW, RB, NT>), dim3(p.n_wg, p.n_rg), dim3(NT), smem, stream, p);
     return hipGetLastError();
 }
 
 hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
 {
     switch (p.rows_grp) {
-    case 32: return launch_variant<1, 128>(p, stream);
-    case 64: return launch_variant<2, 128>(p, stream);
-    case 128: return launch_variant<4, 256>(p, stream);
-    case 256: return launch_variant<8, 512>(p, stream);
+    case 32: return launch_variant<1, 1, 128>(p, stream);
+    case 64: return launch_variant<2, 1, 128>(p, stream);
+    case 128: return launch_variant<4, 1, 256>(p, stream);
+    case 256: return launch_variant<8, 1, 512>(p, stream);
     default: return hipErrorInvalidValue;
     }
 }
