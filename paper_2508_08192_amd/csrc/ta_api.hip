@@ -3,6 +3,7 @@
 #include <math.h>
 #include <mutex>
 #include <string.h>
+#include <stdlib.h>
 
 #include "ta_common.h"
 
@@ -369,6 +370,10 @@ int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tens
         }
     }
     pr.p.status = s->status;
+    {
+        static const char *dbg = getenv("TREEATTN_DBG");
+        pr.p.dbg = dbg ? atoi(dbg) : 0;
+    }
     hipStream_t st = (hipStream_t)stream;
     void *const *ev = opts ? opts->events : nullptr;
     if (ev && ev[0] && hipEventRecord((hipEvent_t)ev[0], st) != hipSuccess)

@@ -36,6 +36,7 @@ struct TAParams {
     float *ws_o;               // partial outputs  [slot][rg][rows_grp][D], normalised, fp32
     float *ws_lse;             // partial log2-sum-exp2 [slot][rg][rows_grp]
     int32_t *status;           // sticky status word
+    int32_t dbg;               // tuning aid: bit flags that switch parts of a kernel off (results become wrong)
 };
 
 // ---------------------------------------------------------------------------------------------
