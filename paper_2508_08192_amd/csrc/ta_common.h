@@ -9,7 +9,7 @@
 
 #define TA_WAVE 64
 #define TA_TILE 64            // KV tokens per tile of the KV pass (the tree tokens form one more tile)
-#define TA_MERGE_ROWS 8       // rows per workgroup of the merge pass
+#define TA_MERGE_ROWS 4       // rows per workgroup of the merge pass (one per wave)
 #define TA_ROW_GROUP 256      // rows (tree nodes x query heads of one KV head) one workgroup keeps
 
 struct TAParams {
@@ -130,14 +130,18 @@ __device__ __forceinline__ int64_t ta_cache_offset(const TAParams &p, int b, int
 }
 
 // Ancestor masks of one request's tree into masks[0..T): bit j of masks[i] is set iff node j is on the
-// path from a root to node i (i included).  Threads 0..T-1 each walk one node upwards; a parent id
-// >= T or a walk longer than T nodes marks the tree as malformed.  Returns (to every thread, after a
-// barrier) whether the tree is well formed; `flag` is one int of shared memory.
-__device__ __forceinline__ bool ta_encode_tree(const int32_t *parent, int T, unsigned long long *masks, int *flag)
+// path from a root to node i (i included).  The T parent ids are first copied to shared memory in one
+// round trip (`par_s`, T ints), then threads 0..T-1 each walk one node upwards there; a parent id >= T
+// or a walk longer than T nodes marks the tree as malformed.  Returns (to every thread, after a barrier)
+// whether the tree is well formed; `flag` is one int of shared memory.
+__device__ __forceinline__ bool ta_encode_tree(const int32_t *parent, int T, unsigned long long *masks, int *flag,
+                                               int *par_s)
 {
     const int tid = threadIdx.x;
     if (tid == 0)
         *flag = 0;
+    if (tid < T)
+        par_s[tid] = parent[tid];
     __syncthreads();
     if (tid < T) {
         unsigned long long m = 0;
@@ -149,7 +153,7 @@ __device__ __forceinline__ bool ta_encode_tree(const int32_t *parent, int T, uns
                 break;
             }
             m |= 1ull << cur;
-            cur = parent[cur];
+            cur = par_s[cur];
             ++steps;
         }
         masks[tid] = bad ? 0ull : m;

@@ -26,7 +26,8 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
     int *cum = smem_i;                                                   // [B + 1]
     unsigned long long *masks = (unsigned long long *)(cum + ((p.B + 2) & ~1));   // [64]
     float *qrow = (float *)(masks + TA_MAX_TREE);                        // [GEN_WAVES][TA_MAX_HEAD_DIM]
-    int *flag = (int *)(qrow + GEN_WAVES * TA_MAX_HEAD_DIM);
+    int *flag = (int *)(qrow + GEN_WAVES * TA_MAX_HEAD_DIM);             // flag[4], then par_s[TA_MAX_TREE]
+    int *par_s = flag + 4;
 
     ta_build_schedule(p, cum);
     const int total = p.Hkv * cum[p.B];
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
             atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
         if (has_tree_tile && !poison) {
-            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag)) {
+            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag, par_s)) {
                 poison = true;
                 if (threadIdx.x == 0)
                     atomicOr(p.status, TA_STATUS_BAD_PARENT);
@@ -141,7 +142,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
 hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream)
 {
     const size_t smem = sizeof(int) * ((p.B + 2) & ~1) + sizeof(unsigned long long) * TA_MAX_TREE +
-                        sizeof(float) * GEN_WAVES * TA_MAX_HEAD_DIM + 16;
+                        sizeof(float) * GEN_WAVES * TA_MAX_HEAD_DIM + 16 + sizeof(int) * TA_MAX_TREE;
     dim3 grid(p.n_wg, p.n_rg);
     if (p.is_bf16)
         hipLaunchKernelGGL(ta_generic_kv_kernel<true>, grid, dim3(GEN_THREADS), smem, stream, p);
@@ -152,7 +153,8 @@ hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream)
 
 // Merge pass (section 3.1: full attention from partial attentions over disjoint chunks of the keys,
 // through their log-sum-exps).  One wave per output row: lanes first span the partials of the row
-// (wave-wide max and sum of the partial log-sum-exps), then span head-dim columns.
+// (wave-wide max and sum of the partial log-sum-exps give every partial its weight), then span
+// head-dim columns, with the loads of several partials in flight at once.
 __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
 {
     extern __shared__ int smem_i[];
@@ -168,20 +170,65 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
     const int w_first = seg_start / share;
     const int n_parts = (seg_start + n_b - 1) / share - w_first + 1;
     const float LN2 = 0.6931471805599453f;
+    const float QNAN = __uint_as_float(0x7fc00000u);
 
-    for (int rr = wave; rr < TA_MERGE_ROWS; rr += GEN_WAVES) {
-        const int R = blockIdx.y * TA_MERGE_ROWS + rr;
-        if (R >= p.rows)
-            break;
-        const int rg = R / p.rows_grp, r = R % p.rows_grp;
-        const int node = R / p.G, h = g * p.G + R % p.G;
-        // pass 1: max of the partial lse (base 2)
+    const int R = blockIdx.y * TA_MERGE_ROWS + wave;
+    if (R >= p.rows)
+        return;
+    const int rg = R / p.rows_grp, r = R % p.rows_grp;
+    const int node = R / p.G, h = g * p.G + R % p.G;
+    const int64_t row0 = ta_ws_row(p, w_first + seg, rg, r);              // partial k of this row: row0 + k*pstride
+    const int64_t pstride = (int64_t)p.n_rg * p.rows_grp;
+
+    float acc[GEN_DCHUNKS];
+#pragma unroll
+    for (int c = 0; c < GEN_DCHUNKS; ++c)
+        acc[c] = 0.f;
+    float lse2;
+    if (n_parts <= TA_WAVE) {
+        // lane k owns partial k
+        const float lk = lane < n_parts ? p.ws_lse[row0 + lane * pstride] : -INFINITY;
+        const bool nan_seen = __any(lk != lk);
+        const float mx = ta_wave_max(lk);
+        const float ek = exp2f(lk - mx);                                  // 0 for the idle lanes
+        const float den = ta_wave_sum(ek);
+        lse2 = nan_seen ? QNAN : mx + log2f(den);
+        const float wk = nan_seen ? QNAN : ek / den;
+        int k = 0;
+        for (; k + 4 <= n_parts; k += 4) {
+            float v[4][GEN_DCHUNKS];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                    const int d = lane + c * TA_WAVE;
+                    v[u][c] = d < p.D ? p.ws_o[(row0 + (k + u) * pstride) * p.D + d] : 0.f;
+                }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float wgt = __shfl(wk, k + u, TA_WAVE);
+#pragma unroll
+                for (int c = 0; c < GEN_DCHUNKS; ++c)
+                    acc[c] = fmaf(wgt, v[u][c], acc[c]);
+            }
+        }
+        for (; k < n_parts; ++k) {
+            const float wgt = __shfl(wk, k, TA_WAVE);
+#pragma unroll
+            for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                const int d = lane + c * TA_WAVE;
+                if (d < p.D)
+                    acc[c] = fmaf(wgt, p.ws_o[(row0 + k * pstride) * p.D + d], acc[c]);
+            }
+        }
+    } else {
+        // more partials than lanes: two sweeps over the log-sum-exps, then one over the outputs
         float mx = -INFINITY;
         bool nan_seen = false;
         for (int q0 = 0; q0 < n_parts; q0 += TA_WAVE) {
-            const int part = q0 + lane;
-            if (part < n_parts) {
-                const float v = p.ws_lse[ta_ws_row(p, w_first + part + seg, rg, r)];
+            const int k = q0 + lane;
+            if (k < n_parts) {
+                const float v = p.ws_lse[row0 + k * pstride];
                 nan_seen |= (v != v);
                 mx = fmaxf(mx, v);
             }
@@ -190,40 +237,35 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
         nan_seen = __any(nan_seen);
         float den = 0.f;
         for (int q0 = 0; q0 < n_parts; q0 += TA_WAVE) {
-            const int part = q0 + lane;
-            if (part < n_parts)
-                den += exp2f(p.ws_lse[ta_ws_row(p, w_first + part + seg, rg, r)] - mx);
+            const int k = q0 + lane;
+            if (k < n_parts)
+                den += exp2f(p.ws_lse[row0 + k * pstride] - mx);
         }
         den = ta_wave_sum(den);
-        const float lse2 = nan_seen ? __uint_as_float(0x7fc00000u) : mx + log2f(den);
-        float acc[GEN_DCHUNKS];
-#pragma unroll
-        for (int c = 0; c < GEN_DCHUNKS; ++c)
-            acc[c] = 0.f;
-        for (int part = 0; part < n_parts; ++part) {
-            const int64_t wrow = ta_ws_row(p, w_first + part + seg, rg, r);
-            const float wgt = exp2f(p.ws_lse[wrow] - lse2);          // same address in every lane
+        lse2 = nan_seen ? QNAN : mx + log2f(den);
+        for (int k = 0; k < n_parts; ++k) {
+            const float wgt = exp2f(p.ws_lse[row0 + k * pstride] - lse2);  // same address in every lane
 #pragma unroll
             for (int c = 0; c < GEN_DCHUNKS; ++c) {
                 const int d = lane + c * TA_WAVE;
                 if (d < p.D)
-                    acc[c] = fmaf(wgt, p.ws_o[wrow * p.D + d], acc[c]);
+                    acc[c] = fmaf(wgt, p.ws_o[(row0 + k * pstride) * p.D + d], acc[c]);
             }
         }
-        const int64_t ooff = (int64_t)b * p.o_sb + (int64_t)node * p.o_st + (int64_t)h * p.o_sh;
-#pragma unroll
-        for (int c = 0; c < GEN_DCHUNKS; ++c) {
-            const int d = lane + c * TA_WAVE;
-            if (d < p.D) {
-                if (p.is_bf16)
-                    ((uint16_t *)p.out)[ooff + d] = ta_f32_to_bf16(acc[c]);
-                else
-                    ((float *)p.out)[ooff + d] = acc[c];
-            }
-        }
-        if (p.lse && lane == 0)
-            p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + (int64_t)node * p.lse_st] = lse2 * LN2;
     }
+    const int64_t ooff = (int64_t)b * p.o_sb + (int64_t)node * p.o_st + (int64_t)h * p.o_sh;
+#pragma unroll
+    for (int c = 0; c < GEN_DCHUNKS; ++c) {
+        const int d = lane + c * TA_WAVE;
+        if (d < p.D) {
+            if (p.is_bf16)
+                ((uint16_t *)p.out)[ooff + d] = ta_f32_to_bf16(acc[c]);
+            else
+                ((float *)p.out)[ooff + d] = acc[c];
+        }
+    }
+    if (p.lse && lane == 0)
+        p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + (int64_t)node * p.lse_st] = lse2 * LN2;
 }
 
 hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream)
@@ -240,8 +282,9 @@ __global__ __launch_bounds__(TA_WAVE) void ta_encode_kernel(const int32_t *paren
 {
     __shared__ unsigned long long sm[TA_MAX_TREE];
     __shared__ int flag;
+    __shared__ int par_s[TA_MAX_TREE];
     const int b = blockIdx.x;
-    const bool ok = ta_encode_tree(parent + (int64_t)b * par_sb, T, sm, &flag);
+    const bool ok = ta_encode_tree(parent + (int64_t)b * par_sb, T, sm, &flag, par_s);
     if (threadIdx.x < T)
         masks[(int64_t)b * T + threadIdx.x] = ok ? sm[threadIdx.x] : 0ull;
     if (!ok && threadIdx.x == 0)

@@ -208,7 +208,8 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
     char *tiles = smem;                                                   // [MF_STAGES][K tile | V tile]
     unsigned long long *masks = (unsigned long long *)(smem + MF_STAGES * 2 * MF_TILE_BYTES);   // [64]
     int *flag = (int *)(masks + TA_MAX_TREE);
-    int *cum = flag + 4;                                                  // [B + 1]
+    int *par_s = flag + 4;                                                // [TA_MAX_TREE]
+    int *cum = par_s + TA_MAX_TREE;                                       // [B + 1]
 
     ta_build_schedule(p, cum);
     const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
@@ -249,7 +250,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
             atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
         if (has_tree_tile && !poison) {
-            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag)) {
+            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag, par_s)) {
                 poison = true;
                 if (tid == 0)
                     atomicOr(p.status, TA_STATUS_BAD_PARENT);
@@ -521,7 +522,8 @@ __global__ __launch_bounds__(512) void ta_mfma_pp_kernel(TAParams p)
     char *vtr = smem + PP_VT_OFF;                                         // [PP_VT][16 KB]
     unsigned long long *masks = (unsigned long long *)(vtr + PP_VT * MF_TILE_BYTES);
     int *flag = (int *)(masks + TA_MAX_TREE);
-    int *pcache = flag + 4;                                               // [PP_PAGES] page ids of the current span
+    int *par_s = flag + 4;                                                // [TA_MAX_TREE]
+    int *pcache = par_s + TA_MAX_TREE;                                    // [PP_PAGES] page ids of the current span
     int *cum = pcache + PP_PAGES;
     const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
 
@@ -574,7 +576,7 @@ __global__ __launch_bounds__(512) void ta_mfma_pp_kernel(TAParams p)
             atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
         if (has_tree_tile && !poison) {
-            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag)) {
+            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag, par_s)) {
                 poison = true;
                 if (tid == 0)
                     atomicOr(p.status, TA_STATUS_BAD_PARENT);
@@ -697,51 +699,62 @@ __global__ __launch_bounds__(512) void ta_mfma_pp_kernel(TAParams p)
                 vm_wait<0>();
             }
             lds_barrier();
-            if (grp == 1)
-                lds_barrier();
+            if (grp == 1) {
+                if (!(p.dbg & 8))
+                    relayout_v(s0, 0);                         // the trailing waves are idle in this slot
+                if (!(p.dbg & 16))
+                    lds_barrier();
+            }
 
-            // start of M(i): the cache loads of tile i+2
-            auto m_head = [&](int i) {
-                if (i + 2 < ns)
-                    issue_dma(s0 + i + 2, (i + 2) % PP_RAW);
-            };
-            // end of M(i): V re-layout by the leading waves; then tile i+1 (issued one M phase ago) must be
-            // in LDS before anyone starts M(i+1) -- only the four loads of tile i+2 may stay in flight
+            // end of M(i).  Tile i+1 must be in LDS before anyone starts M(i+1): the trailing waves, whose
+            // M(i) ends at that point, wait here for their share of it (nothing younger is in flight).
             auto m_tail = [&](int i) {
                 advance_addresses(i);
-                if (grp == 0)
-                    relayout_v(s0 + i, i);
-                if (i + 2 < ns)
-                    vm_wait<4>();
-                else
+                if (grp == 1)
                     vm_wait<0>();
                 lds_barrier();
             };
+            // SM(i): first the cache loads of tile i+2 (their latency hides behind the softmax and the next
+            // matrix phase), then the running softmax; the trailing waves also re-lay V of tile i+1 out.
+            // The leading waves end SM(i) where the trailing ones end M(i): they wait for tile i+1 here,
+            // leaving only the four loads of tile i+2 in flight.
             auto sm_phase = [&](int i) {
+                const bool issued = i + 2 < ns && !(p.dbg & 4);
+                if (issued)
+                    issue_dma(s0 + i + 2, (i + 2) % PP_RAW);
                 const int j = j0 + s0 + i;
                 const bool tree_tile = (j == n_b - 1);
                 const int rem = L - j * TA_TILE;
-                if (tree_tile || rem < TA_TILE)
-                    mask_scores(acc_s, (tree_tile ? tree_mask : ((1ull << rem) - 1ull)) >> (4 * hf));
-                softmax_tile_pp(acc_s, c, m_run, l_run, acc_o, pb);
+                if (!(p.dbg & 1)) {
+                    if (tree_tile || rem < TA_TILE)
+                        mask_scores(acc_s, (tree_tile ? tree_mask : ((1ull << rem) - 1ull)) >> (4 * hf));
+                    softmax_tile_pp(acc_s, c, m_run, l_run, acc_o, pb);
+                }
+                if (grp == 1) {
+                    if (i + 1 < ns && !(p.dbg & 8))
+                        relayout_v(s0 + i + 1, i + 1);
+                } else if (issued) {
+                    vm_wait<4>();
+                } else {
+                    vm_wait<0>();
+                }
                 lds_barrier();
             };
 
-            m_head(0);
             pp_phase_s(acc_s, qf, ka, kbase);
             m_tail(0);
             sm_phase(0);
 #pragma unroll 1
             for (int i = 1; i < ns; ++i) {
-                m_head(i);
-                pp_phase_pv_s(acc_o, pb, vaddr, acc_s, qf, ka, kbase);
+                if (!(p.dbg & 2))
+                    pp_phase_pv_s(acc_o, pb, vaddr, acc_s, qf, ka, kbase);
                 m_tail(i);
                 sm_phase(i);
             }
             pp_phase_pv(acc_o, pb, vaddr);
             lds_barrier();
             lds_barrier();
-            if (grp == 0)
+            if (grp == 0 && !(p.dbg & 16))
                 lds_barrier();
         }
 
@@ -773,7 +786,7 @@ template <int NCW, int RB, int NT>
 static hipError_t launch_variant(const TAParams &p, hipStream_t stream)
 {
     const size_t smem = MF_STAGES * 2 * MF_TILE_BYTES + sizeof(unsigned long long) * TA_MAX_TREE + 16 +
-                        sizeof(int) * (p.B + 2);
+                        sizeof(int) * TA_MAX_TREE + sizeof(int) * (p.B + 2);
     static bool attr_set[64] = {};      // per device and variant; setting it twice is harmless
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
@@ -798,7 +811,7 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
     case 256: {
         static const bool simple = getenv("TREEATTN_MFMA_SIMPLE") != nullptr;      // tuning aid
         const size_t smem = PP_RAW * PP_RAW_BYTES + PP_VT * MF_TILE_BYTES + sizeof(unsigned long long) * TA_MAX_TREE +
-                            16 + sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
+                            16 + sizeof(int) * TA_MAX_TREE + sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
         if (simple || smem > 160 * 1024 - 512)
             return launch_variant<8, 1, 512>(p, stream);
         static bool attr_set[64] = {};
