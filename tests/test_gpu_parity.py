@@ -77,6 +77,28 @@ def test_contiguous_layout_and_chain_tree(kernel):
     _check(w, kernel=kernel)
 
 
+@pytest.mark.parametrize("ps,L,splits", [(8, 20000, 1), (1, 700, 1), (2, 2500, 2), (4, 5000, 1), (16, 9000, 3),
+                                          (256, 3000, 0)])
+def test_256_row_kernel_page_sizes_and_long_shares(ps, L, splits):
+    """256 rows take the pipelined kernel: tiny pages, shares longer than one page-id span, several spans."""
+    rng = np.random.default_rng(ps)
+    T = 32
+    w = W.make_workload("pp_ps%d" % ps, B=2, T=T, Hq=8, Hkv=1, D=128, seq_lens=[L, L // 3 + 5],
+                        trees=np.stack([W.random_tree(T, 6, rng), W.chain_tree(T)]), page_size=ps, dtype="bf16",
+                        seed=1300 + ps)
+    _check(w, "ps=%d L=%d splits=%d" % (ps, L, splits), kernel=MFMA, num_splits=splits)
+
+
+def test_256_row_kernel_contiguous_layout():
+    rng = np.random.default_rng(13)
+    T = 64
+    w = W.make_workload("pp_contig", B=2, T=T, Hq=4, Hkv=1, D=128, seq_lens=[1000, 63],
+                        trees=np.stack([W.random_deep_tree(T, 10, rng), W.bfs_tree(T, [4, 2], 8)]), page_size=0,
+                        dtype="bf16", seed=1400, paged=False)
+    _check(w, kernel=MFMA)
+    _check(w, "pp contiguous one share", kernel=MFMA, num_splits=1)
+
+
 def test_generic_kernel_shapes_the_matrix_core_path_does_not_take():
     rng = np.random.default_rng(6)
     for D, ps, dtype in [(64, 16, "bf16"), (80, 48, "bf16"), (256, 8, "bf16"), (128, 48, "bf16"), (128, 16, "f32"),
@@ -140,12 +162,43 @@ def test_benchmark_configs_reduced_lengths_all_outputs(idx, div):
     _check(w)
 
 
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_full_size_configs_sampled_outputs(idx):
+    """The benchmark configurations at full size, in the launch configuration the bench times: sampled
+    (request, node, head) outputs against the oracle, plus whole-output sanity (finite, bounded by V)."""
+    import oracle
+    w = W.make_config(idx)
+    _announce(w.name)
+    got, got_lse = run_hip(w)
+    rng = np.random.default_rng(100 + idx)
+    n = 300
+    tri = np.stack([rng.integers(0, w.B, n), rng.integers(0, w.T, n), rng.integers(0, w.Hq, n)], axis=1)
+    tri[:w.B, 0] = np.arange(w.B)                      # every request at least once
+    tri[:w.B, 1] = w.T - 1                             # ... at its last node
+    ref, ref_lse = oracle.tree_attn_oracle_sample(w.q, w.k_cache, w.v_cache, w.page_table, w.seq_lens,
+                                                  w.tree_parent, tri, scale=w.scale)
+    g = got[tri[:, 0], tri[:, 1], tri[:, 2]]
+    gl = got_lse[tri[:, 0], tri[:, 2], tri[:, 1]]
+    assert_parity(g, gl, ref, ref_lse, "bf16", w.name)
+    assert np.isfinite(got).all() and np.isfinite(got_lse).all()
+    from .helpers import widen
+    assert np.abs(got).max() <= np.abs(widen(w.v_cache[w.page_table[0, :4]])).max() * 4
+
+
 def test_strided_views_token_major_cache():
     rng = np.random.default_rng(11)
     import torch
     T = 16
-    w = W.make_workload("tokmajor", B=2, T=T, Hq=8, Hkv=2, D=128, seq_lens=[130, 64], trees=W.random_tree(T, 5, rng),
-                        page_size=32, dtype="bf16", seed=1101)
+    _strided_case(W.make_workload("tokmajor", B=2, T=T, Hq=8, Hkv=2, D=128, seq_lens=[130, 64],
+                                  trees=W.random_tree(T, 5, rng), page_size=32, dtype="bf16", seed=1101))
+    T = 64                                             # 256 rows: the pipelined kernel
+    _strided_case(W.make_workload("tokmajor256", B=2, T=T, Hq=8, Hkv=2, D=128, seq_lens=[700, 64],
+                                  trees=W.random_tree(T, 7, rng), page_size=32, dtype="bf16", seed=1102))
+
+
+def _strided_case(w):
+    import torch
+    T = w.T
     ref, ref_lse = run_oracle(w)
     dev = to_device(w)
     for key in ("k_cache", "v_cache"):
@@ -160,12 +213,14 @@ def test_strided_views_token_major_cache():
         assert_parity(got, got_lse, ref, ref_lse, "bf16", "strided kernel=%d" % kernel)
 
 
-def test_repeat_calls_are_bit_identical():
-    w = W.make_config(2, length_div=16)
+@pytest.mark.parametrize("idx,div", [(2, 16), (3, 16), (1, 1)])
+def test_repeat_calls_are_bit_identical(idx, div):
+    w = W.make_config(idx, length_div=div)
     dev = to_device(w)
     a, al = run_hip(w, dev)
-    b, bl = run_hip(w, dev)
-    assert np.array_equal(a, b) and np.array_equal(al, bl)
+    for _ in range(6):
+        b, bl = run_hip(w, dev)
+        assert np.array_equal(a, b) and np.array_equal(al, bl)
 
 
 @pytest.mark.parametrize("kernel", [GENERIC, MFMA])
