@@ -93,6 +93,89 @@ def cpu_baseline(w, budget_s, log):
                       "scaled by %d/%d" % (n, total, dt, total, n)}
 
 
+def measure(w, steps, warmup, log, num_splits=0, kernel=0, rotate=0, check=False):
+    """Times `steps` verify steps of workload w (after `warmup` untimed ones).  Returns a dict with the step
+    time, per-kernel times from HIP events recorded inside the timed region, and roofline figures."""
+    import numpy as np
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+
+    dev = upload(w, torch)
+    alg_bytes = w.algorithmic_bytes()
+    flops = w.useful_flops()
+    pool_bytes = dev["k_cache"].numel() * dev["k_cache"].element_size() * 2
+    # Small workloads would be served from the 256 MB last-level cache on repeated calls; cycle through
+    # enough copies of the KV pool that every step streams from HBM.
+    if rotate > 0:
+        n_pools = rotate
+    elif pool_bytes >= 600e6:
+        n_pools = 1
+    else:
+        n_pools = max(1, min(64, int(np.ceil(600e6 / max(pool_bytes, 1)))))
+    pools = [(dev["k_cache"], dev["v_cache"])]
+    for _ in range(n_pools - 1):
+        pools.append((dev["k_cache"].clone(), dev["v_cache"].clone()))
+    log("%s: KV pool %.1f MB x %d copies" % (w.name, pool_bytes / 1e6, n_pools))
+
+    plan = ta.tree_attn_plan(dev["q"], dev["k_cache"], dev["v_cache"], dev["page_table"], dev["seq_lens"],
+                             dev["tree_parent"], dev["out"], dev["lse"],
+                             num_cus=torch.cuda.get_device_properties(0).multi_processor_count,
+                             num_splits=num_splits, kernel=kernel)
+    log("plan %r" % plan)
+    ta.tree_attn_reserve(ta.tree_attn_workspace_bytes(w.B, w.T, w.Hq, w.Hkv, w.D,
+                                                      ta.TA_F32 if w.dtype == "f32" else ta.TA_BF16))
+    stream = torch.cuda.current_stream()
+
+    def step(i, events=None):
+        k, v = pools[i % n_pools]
+        ta.tree_attn_fwd_ex(dev["q"], k, v, dev["page_table"], dev["seq_lens"], dev["tree_parent"], dev["out"],
+                            dev["lse"], stream=stream, scale=w.scale, num_splits=num_splits, kernel=kernel,
+                            events=events)
+
+    if check:
+        import oracle
+        step(0)
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(7)
+        tri = np.stack([rng.integers(0, w.B, 64), rng.integers(0, w.T, 64), rng.integers(0, w.Hq, 64)], axis=1)
+        ref, ref_lse = oracle.tree_attn_oracle_sample(w.q, w.k_cache, w.v_cache, w.page_table, w.seq_lens,
+                                                      w.tree_parent, tri, scale=w.scale)
+        got = dev["out"].float().cpu().numpy()[tri[:, 0], tri[:, 1], tri[:, 2]]
+        log("check: max-abs err %.3g (oracle max %.3g)" % (np.abs(got - ref).max(), np.abs(ref).max()))
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    hev = HipEvents()
+    evs = [[hev.create() for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i, evs[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / steps * 1e3
+    kv_ms = [hev.elapsed_ms(e[0], e[1]) for e in evs]
+    mg_ms = [hev.elapsed_ms(e[1], e[2]) for e in evs]
+    for e in evs:
+        for x in e:
+            hev.destroy(x)
+    kv_avg = sum(kv_ms) / len(kv_ms)
+    mg_avg = sum(mg_ms) / len(mg_ms)
+    log("%s: KV pass avg %.1f us (min %.1f), merge pass avg %.1f us, step %.1f us" %
+        (w.name, kv_avg * 1e3, min(kv_ms) * 1e3, mg_avg * 1e3, ms_per_step * 1e3))
+
+    # Roofline of the dominant kernel (KV pass).  Its algorithmic bytes per launch: every K and V element
+    # of prefix and tree once, plus q and the ids it reads (the output and lse belong to the merge pass).
+    es = 4 if w.dtype == "f32" else 2
+    kv_alg = alg_bytes - w.B * w.T * w.Hq * (w.D * es + 4)
+    hbm_frac = kv_alg / (kv_avg * 1e-3) / 1e9 / HBM_PEAK_GBS
+    mfma_frac = flops / (kv_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else 0.0
+    return dict(w=w, plan=plan, n_pools=n_pools, ms_per_step=ms_per_step, kv_us=kv_avg * 1e3, merge_us=mg_avg * 1e3,
+                alg_bytes=alg_bytes, kv_alg=kv_alg, flops=flops, hbm_frac=hbm_frac, mfma_frac=mfma_frac)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,7 +188,21 @@ def main():
     ap.add_argument("--rotate", type=int, default=0,
                     help="distinct KV pools to cycle through (0 = enough to exceed the 256 MB last-level cache)")
     ap.add_argument("--check", action="store_true", help="compare sampled outputs with the oracle before timing")
+    ap.add_argument("--others", type=int, default=1,
+                    help="also time the other configurations briefly and list them under other_workloads (0 = no)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="instead of the benchmark, run a plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB) "
+                         "five times: the known traffic against which HBM byte counters are scaled")
     args = ap.parse_args()
+    if args.calibrate_copy:
+        import torch
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"launches": 5, "read_bytes": 1 << 30, "write_bytes": 1 << 30}}))
+        return 0
     if args.gpus != 1:
         print("bench.py measures one GPU: every box in this build has a single MI355X and the path needs no "
               "collective (it shards by KV head or by request without communication). Run with --gpus 1.",
@@ -125,89 +222,27 @@ def main():
     t0 = time.time()
     w = W.make_config(WORKLOADS[args.workload])
     log("workload %s generated in %.1f s" % (w.name, time.time() - t0))
-    dev = upload(w, torch)
-    alg_bytes = w.algorithmic_bytes()
-    flops = w.useful_flops()
-    pool_bytes = dev["k_cache"].numel() * dev["k_cache"].element_size() * 2
+    m = measure(w, args.steps, args.warmup, log, args.num_splits, args.kernel, args.rotate, args.check)
+    ms_per_step, kv_us, plan = m["ms_per_step"], m["kv_us"], m["plan"]
+    alg_bytes, kv_alg, flops = m["alg_bytes"], m["kv_alg"], m["flops"]
 
-    # Small workloads would be served from the 256 MB last-level cache on repeated calls; cycle through
-    # enough copies of the KV pool that every step streams from HBM.
-    n_pools = args.rotate if args.rotate > 0 else max(1, min(64, int(np.ceil(600e6 / max(pool_bytes, 1)))))
-    if pool_bytes >= 600e6:
-        n_pools = 1 if args.rotate <= 0 else args.rotate
-    pools = [(dev["k_cache"], dev["v_cache"])]
-    for _ in range(n_pools - 1):
-        pools.append((dev["k_cache"].clone(), dev["v_cache"].clone()))
-    log("KV pool %.1f MB x %d copies" % (pool_bytes / 1e6, n_pools))
-
-    plan = ta.tree_attn_plan(dev["q"], dev["k_cache"], dev["v_cache"], dev["page_table"], dev["seq_lens"],
-                             dev["tree_parent"], dev["out"], dev["lse"],
-                             num_cus=torch.cuda.get_device_properties(0).multi_processor_count,
-                             num_splits=args.num_splits, kernel=args.kernel)
-    log("plan %r" % plan)
-    ta.tree_attn_reserve(ta.tree_attn_workspace_bytes(w.B, w.T, w.Hq, w.Hkv, w.D,
-                                                      ta.TA_F32 if w.dtype == "f32" else ta.TA_BF16))
-    stream = torch.cuda.current_stream()
-
-    def step(i, events=None):
-        k, v = pools[i % n_pools]
-        ta.tree_attn_fwd_ex(dev["q"], k, v, dev["page_table"], dev["seq_lens"], dev["tree_parent"], dev["out"],
-                            dev["lse"], stream=stream, scale=w.scale, num_splits=args.num_splits, kernel=args.kernel,
-                            events=events)
-
-    if args.check:
-        import oracle
-        step(0)
-        torch.cuda.synchronize()
-        rng = np.random.default_rng(7)
-        tri = np.stack([rng.integers(0, w.B, 64), rng.integers(0, w.T, 64), rng.integers(0, w.Hq, 64)], axis=1)
-        ref, ref_lse = oracle.tree_attn_oracle_sample(w.q, w.k_cache, w.v_cache, w.page_table, w.seq_lens,
-                                                      w.tree_parent, tri, scale=w.scale)
-        got = dev["out"].float().cpu().numpy()[tri[:, 0], tri[:, 1], tri[:, 2]]
-        log("check: max-abs err %.3g (oracle max %.3g)" % (np.abs(got - ref).max(), np.abs(ref).max()))
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-
-    hev = HipEvents()
-    evs = [[hev.create() for _ in range(3)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i, evs[i])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-    kv_ms = [hev.elapsed_ms(e[0], e[1]) for e in evs]
-    mg_ms = [hev.elapsed_ms(e[1], e[2]) for e in evs]
-    for e in evs:
-        for x in e:
-            hev.destroy(x)
-    kv_avg = sum(kv_ms) / len(kv_ms)
-    mg_avg = sum(mg_ms) / len(mg_ms)
-    log("KV pass avg %.1f us (min %.1f), merge pass avg %.1f us, step %.1f us" %
-        (kv_avg * 1e3, min(kv_ms) * 1e3, mg_avg * 1e3, ms_per_step * 1e3))
-
-    # Roofline of the dominant kernel (KV pass).  Its algorithmic bytes per launch: every K and V element
-    # of prefix and tree once, plus q and the ids it reads (the output and lse belong to the merge pass).
-    es = 4 if w.dtype == "f32" else 2
-    kv_alg = alg_bytes - w.B * w.T * w.Hq * (w.D * es + 4)
-    hbm_frac = kv_alg / (kv_avg * 1e-3) / 1e9 / HBM_PEAK_GBS
-    mfma_frac = flops / (kv_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else 0.0
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    # HBM bytes per KV-pass launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by a copy of
+    # known size); the counter runs are separate, their summary sits under profiles/.
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(w.name, {}).get("kv_pass_bytes_per_launch")
-    if hbm_frac >= mfma_frac:
-        roof = {"bound": "hbm", "achieved": kv_alg / (kv_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": hbm_frac, "traffic": traffic}
+        body = "".join(l for l in open(tpath) if not l.startswith("#"))
+        traffic = json.loads(body).get(w.name, {}).get("kv_pass_bytes_per_launch")
+    if m["hbm_frac"] >= m["mfma_frac"]:
+        roof = {"bound": "hbm", "achieved": kv_alg / (kv_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": m["hbm_frac"], "traffic": traffic}
     else:
-        roof = {"bound": "mfma", "achieved": flops / (kv_avg * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": mfma_frac, "traffic": traffic}
-    roof.update({"kernel": "ta_mfma_kv_kernel" if plan["kernel"] == 2 else "ta_generic_kv_kernel",
-                 "avg_launch_us": kv_avg * 1e3, "algorithmic_bytes_per_launch": kv_alg,
-                 "useful_flops_per_launch": flops, "hbm_frac": hbm_frac, "mfma_frac": mfma_frac})
+        roof = {"bound": "mfma", "achieved": flops / (kv_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": m["mfma_frac"], "traffic": traffic}
+    roof.update({"kernel": "ta_generic_kv_kernel" if plan["kernel"] != 2 else
+                 ("ta_mfma_pp_kernel" if plan["rows_per_group"] == 256 else "ta_mfma_kv_kernel"),
+                 "avg_launch_us": kv_us, "algorithmic_bytes_per_launch": kv_alg,
+                 "useful_flops_per_launch": flops, "hbm_frac": m["hbm_frac"], "mfma_frac": m["mfma_frac"]})
 
     result = {
         "metric": "tree-attn us/verify step; achieved HBM GB/s & MFMA util vs MI355X peak",
@@ -224,7 +259,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "T": w.T, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
                    "page_size": w.page_size if w.page_table is not None else 0,
-                   "sum_prefix_tokens": int(w.seq_lens.astype(np.int64).sum()), "kv_pools_rotated": n_pools,
+                   "sum_prefix_tokens": int(w.seq_lens.astype(np.int64).sum()), "kv_pools_rotated": m["n_pools"],
                    "kv_std": w.meta["kv_std"], "plan": plan},
         "tree_tokens_per_s": w.B * w.T / (ms_per_step * 1e-3),
         "kv_tokens_per_s": float(w.seq_lens.astype(np.int64).sum() + w.B * w.T) / (ms_per_step * 1e-3),
@@ -232,11 +267,28 @@ def main():
         "step_TFLOPs": flops / (ms_per_step * 1e-3) / 1e12,
         "step_frac_of_roofline": max(alg_bytes / 1e9 / HBM_PEAK_GBS, flops / 1e12 / MFMA_BF16_PEAK_TFLOPS) /
                                  (ms_per_step * 1e-3),
-        "kernels_us": {"kv_pass": kv_avg * 1e3, "merge_pass": mg_avg * 1e3},
+        "kernels_us": {"kv_pass": kv_us, "merge_pass": m["merge_us"]},
         "roofline": roof,
     }
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds, log)
+    del m, w
+    torch.cuda.empty_cache()
+    if args.others:
+        # the remaining configurations, briefly (context for the headline line; not separate bench lines)
+        others = {}
+        for name, idx in sorted(WORKLOADS.items()):
+            if name == args.workload:
+                continue
+            wo = W.make_config(idx)
+            mo = measure(wo, 15, 3, log)
+            others[wo.name] = {"us_per_step": mo["ms_per_step"] * 1e3, "kv_pass_us": mo["kv_us"],
+                               "merge_pass_us": mo["merge_us"], "hbm_frac": mo["hbm_frac"],
+                               "mfma_frac": mo["mfma_frac"], "algorithmic_bytes": mo["alg_bytes"],
+                               "useful_flops": mo["flops"]}
+            del mo, wo
+            torch.cuda.empty_cache()
+        result["other_workloads"] = others
     print(json.dumps(result), flush=True)
     return 0
 

@@ -22,6 +22,8 @@ def build_library(verbose=False, extra_flags=()):
     """Compile every HIP source for gfx950 and link the C-ABI shared library; returns its path."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp%d" % os.getpid()
+    if os.environ.get("TREEATTN_TUNING"):      # ablation switches of the 256-row kernel (see TA_OFF)
+        extra_flags = list(extra_flags) + ["-DTA_TUNING"]
     cmd = [hipcc] + FLAGS + list(extra_flags) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -119,7 +119,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     size_t user_ws_bytes = 0;
     if (opts) {
         if (opts->reserved != 0 || opts->num_splits < 0 || opts->kernel < TA_KERNEL_AUTO ||
-            opts->kernel > TA_KERNEL_MFMA)
+            opts->kernel > TA_KERNEL_MFMA_BASIC)
             return TA_ERR_OPTS;
         kernel = opts->kernel;
         num_splits = opts->num_splits;
@@ -143,6 +143,9 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
                          ((uintptr_t)q->data % 16) == 0 && ((uintptr_t)k->data % 16) == 0 &&
                          ((uintptr_t)v->data % 16) == 0 && k->stride[0] < INT32_MAX && k->stride[2] < INT32_MAX &&
                          v->stride[0] < INT32_MAX && v->stride[2] < INT32_MAX;
+    const bool basic = kernel == TA_KERNEL_MFMA_BASIC;
+    if (basic)
+        kernel = TA_KERNEL_MFMA;
     if (kernel == TA_KERNEL_MFMA && !mfma_ok)
         return TA_ERR_OPTS;
     if (kernel == TA_KERNEL_AUTO)
@@ -150,6 +153,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
 
     TAParams &p = pr->p;
     memset(&p, 0, sizeof p);
+    p.basic = basic;
     p.q = q->data; p.k = k->data; p.v = v->data; p.out = out->data;
     p.lse = lse ? (float *)lse->data : nullptr;
     p.page_table = pt ? (const int32_t *)pt->data : nullptr;
@@ -370,10 +374,12 @@ int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tens
         }
     }
     pr.p.status = s->status;
+#ifdef TA_TUNING
     {
         static const char *dbg = getenv("TREEATTN_DBG");
         pr.p.dbg = dbg ? atoi(dbg) : 0;
     }
+#endif
     hipStream_t st = (hipStream_t)stream;
     void *const *ev = opts ? opts->events : nullptr;
     if (ev && ev[0] && hipEventRecord((hipEvent_t)ev[0], st) != hipSuccess)

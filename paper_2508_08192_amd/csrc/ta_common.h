@@ -36,8 +36,20 @@ struct TAParams {
     float *ws_o;               // partial outputs  [slot][rg][rows_grp][D], normalised, fp32
     float *ws_lse;             // partial log2-sum-exp2 [slot][rg][rows_grp]
     int32_t *status;           // sticky status word
-    int32_t dbg;               // tuning aid: bit flags that switch parts of a kernel off (results become wrong)
+    int32_t basic;             // 256-row groups: use the register-staged MFMA kernel, not the pipelined one
+#ifdef TA_TUNING
+    int32_t dbg;               // bit flags that switch parts of a kernel off (results become wrong)
+#endif
 };
+
+// Ablation switches for tuning builds (-DTA_TUNING, flags from the TREEATTN_DBG environment variable): a set
+// bit removes one part of the 256-row KV kernel so that its share of the time can be read off.  A regular
+// build compiles every switch to `false`.
+#ifdef TA_TUNING
+#define TA_OFF(bit) ((p.dbg & (bit)) != 0)
+#else
+#define TA_OFF(bit) false
+#endif
 
 // ---------------------------------------------------------------------------------------------
 // Work schedule.  The KV pass walks, for every (request b, KV head g), a list of tiles:

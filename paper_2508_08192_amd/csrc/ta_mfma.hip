@@ -700,9 +700,9 @@ __global__ __launch_bounds__(512) void ta_mfma_pp_kernel(TAParams p)
             }
             lds_barrier();
             if (grp == 1) {
-                if (!(p.dbg & 8))
+                if (!TA_OFF(8))
                     relayout_v(s0, 0);                         // the trailing waves are idle in this slot
-                if (!(p.dbg & 16))
+                if (!TA_OFF(16))
                     lds_barrier();
             }
 
@@ -719,19 +719,19 @@ __global__ __launch_bounds__(512) void ta_mfma_pp_kernel(TAParams p)
             // The leading waves end SM(i) where the trailing ones end M(i): they wait for tile i+1 here,
             // leaving only the four loads of tile i+2 in flight.
             auto sm_phase = [&](int i) {
-                const bool issued = i + 2 < ns && !(p.dbg & 4);
+                const bool issued = i + 2 < ns && !TA_OFF(4);
                 if (issued)
                     issue_dma(s0 + i + 2, (i + 2) % PP_RAW);
                 const int j = j0 + s0 + i;
                 const bool tree_tile = (j == n_b - 1);
                 const int rem = L - j * TA_TILE;
-                if (!(p.dbg & 1)) {
+                if (!TA_OFF(1)) {
                     if (tree_tile || rem < TA_TILE)
                         mask_scores(acc_s, (tree_tile ? tree_mask : ((1ull << rem) - 1ull)) >> (4 * hf));
                     softmax_tile_pp(acc_s, c, m_run, l_run, acc_o, pb);
                 }
                 if (grp == 1) {
-                    if (i + 1 < ns && !(p.dbg & 8))
+                    if (i + 1 < ns && !TA_OFF(8))
                         relayout_v(s0 + i + 1, i + 1);
                 } else if (issued) {
                     vm_wait<4>();
@@ -746,7 +746,7 @@ __global__ __launch_bounds__(512) void ta_mfma_pp_kernel(TAParams p)
             sm_phase(0);
 #pragma unroll 1
             for (int i = 1; i < ns; ++i) {
-                if (!(p.dbg & 2))
+                if (!TA_OFF(2))
                     pp_phase_pv_s(acc_o, pb, vaddr, acc_s, qf, ka, kbase);
                 m_tail(i);
                 sm_phase(i);
@@ -754,7 +754,7 @@ __global__ __launch_bounds__(512) void ta_mfma_pp_kernel(TAParams p)
             pp_phase_pv(acc_o, pb, vaddr);
             lds_barrier();
             lds_barrier();
-            if (grp == 0 && !(p.dbg & 16))
+            if (grp == 0 && !TA_OFF(16))
                 lds_barrier();
         }
 
@@ -809,10 +809,9 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
     case 64: return launch_variant<2, 1, 128>(p, stream);
     case 128: return launch_variant<4, 1, 256>(p, stream);
     case 256: {
-        static const bool simple = getenv("TREEATTN_MFMA_SIMPLE") != nullptr;      // tuning aid
         const size_t smem = PP_RAW * PP_RAW_BYTES + PP_VT * MF_TILE_BYTES + sizeof(unsigned long long) * TA_MAX_TREE +
                             16 + sizeof(int) * TA_MAX_TREE + sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
-        if (simple || smem > 160 * 1024 - 512)
+        if (p.basic || smem > 160 * 1024 - 512)
             return launch_variant<8, 1, 512>(p, stream);
         static bool attr_set[64] = {};
         int dev = 0;

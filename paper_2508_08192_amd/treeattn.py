@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtreeattn.so")
 
 TA_F32, TA_BF16, TA_I32, TA_U64 = 0, 1, 2, 3
-TA_KERNEL_AUTO, TA_KERNEL_GENERIC, TA_KERNEL_MFMA = 0, 1, 2
+TA_KERNEL_AUTO, TA_KERNEL_GENERIC, TA_KERNEL_MFMA, TA_KERNEL_MFMA_BASIC = 0, 1, 2, 3
 TA_STATUS_BAD_PARENT, TA_STATUS_BAD_SEQLEN = 1, 2
 
 TA_OK = 0

@@ -8,7 +8,7 @@ from .helpers import assert_parity, run_hip, run_oracle, to_device
 
 pytestmark = pytest.mark.gpu
 
-GENERIC, MFMA = 1, 2
+GENERIC, MFMA, MFMA_BASIC = 1, 2, 3
 
 
 def _announce(name):
@@ -97,6 +97,17 @@ def test_256_row_kernel_contiguous_layout():
                         dtype="bf16", seed=1400, paged=False)
     _check(w, kernel=MFMA)
     _check(w, "pp contiguous one share", kernel=MFMA, num_splits=1)
+
+
+@pytest.mark.parametrize("splits", [0, 3])
+def test_256_row_groups_on_the_register_staged_kernel(splits):
+    """The fallback for 256-row groups (taken by itself when the pipelined kernel's LDS need is too large)."""
+    rng = np.random.default_rng(14)
+    T = 64
+    w = W.make_workload("basic256", B=3, T=T, Hq=8, Hkv=2, D=128, seq_lens=[1500, 0, 777],
+                        trees=np.stack([W.random_deep_tree(T, 9, rng), W.chain_tree(T), W.bfs_tree(T, [4, 2], 8)]),
+                        page_size=32, dtype="bf16", seed=1500)
+    _check(w, "basic splits=%d" % splits, kernel=MFMA_BASIC, num_splits=splits)
 
 
 def test_generic_kernel_shapes_the_matrix_core_path_does_not_take():
