@@ -1,0 +1,365 @@
+#!/usr/bin/env python3
+"""Writes ta_sp_block.inc: the per-tile blocks of the 256-row KV-pass kernel as single inline-asm statements.
+
+    python gen_sp_block.py > ta_sp_block.inc
+
+One block of tile i holds up to three streams, merged into one in-order instruction sequence so that a wave keeps
+the matrix pipe and the vector ALU busy at the same time:
+
+  PV   O^T += V^T(i-1) . P^T(i-1)        16 MFMAs (kb = r/4, db = r%4), A fragments from the token-minor V tile
+  S    S^T(i+1) = K(i+1) . Q^T           16 MFMAs (kk = r/2, tb = r%2), A fragments from the swizzled K tile
+  SM   running softmax of S^T(i) -> P(i) about 140 vector instructions
+
+The large operands live in fixed physical VGPRs that the compiler never sees: the kernel is compiled with
+amdgpu_num_vgpr(16), which confines the register allocator to v0..v31 (the attribute counts in units of two on
+this target), and everything from v32 up belongs to these blocks from the first to the last of a walk.  (The
+softmax addresses single registers of the score and probability tuples, which asm operands cannot express.)
+
+  v[48:111] O (4 x 16)   v[112:143] score buffer A   v[144:175] score buffer B   v[176:191] P   v[192:223] Q
+  v[224:247] ring of 6 LDS fragments   v[248:255] softmax temporaries   v[38:47] re-layout temporaries
+  v[32:35] lane constants: LDS offsets of the lane's V fragments, K fragments, re-layout reads and writes
+  v[36:37] K fragment address and re-layout write address of the current block
+
+Small helpers move values between the two worlds: sp_zero_o, sp_set_q_lo/hi, sp_set_bases, sp_get_rl, sp_scale_o,
+sp_mask_A/B, sp_get_o0..3.
+
+S^T(i) and S^T(i+1) alternate between buffers A and B, so every block exists in an "A current" and a "B current"
+flavour.  P has one buffer: the PV MFMAs, which read P(i-1), come first in program order and the conversion that
+overwrites a quarter of P is emitted only after the last MFMA reading that quarter (MFMA reads its A/B operands
+when it issues).  Each MFMA consumes one 16-byte LDS fragment read issued DIST steps earlier.
+
+Running softmax in base 2 with a lazily moved reference M (scaled units): M changes only when the tile maximum
+exceeds M + 4, so P <= 16 and the rescaling of O (done by the caller when alpha != 1) is rare.
+"""
+O, SA, SB, P, Q, FR, TMP = 48, 112, 144, 176, 192, 224, 248
+NF = 6
+DIST = NF - 1
+TM_A, TM_B, T_SWAP, T_MC, T_THR, T_TK, PS0, PS1 = (TMP + i for i in range(8))
+NTMP = 8
+
+
+RL = 38                    # v[38:47]: re-layout temporaries of the fast blocks (four 8-byte rows, two outputs);
+                           # v[38:41] double as the four V fragment addresses while the PV reads are being issued
+VA_BASE, KA_BASE, RD_BASE, WR_BASE, KADDR, WRT = 32, 33, 34, 35, 36, 37   # lane constants and per-block addresses
+
+
+
+def v(n):
+    return "v%d" % n
+
+
+def vr(n, k):
+    return "v[%d:%d]" % (n, n + k - 1)
+
+
+def frag(r):
+    return vr(FR + 4 * (r % NF), 4)
+
+
+def softmax_ops(sc):
+    """(instruction, index of the PV MFMA that must already be issued or -1) in program order."""
+    s = lambda t: v(sc + t)
+    ops = []
+    add = lambda ins, need=-1: ops.append((ins, need))
+    add("v_max_f32 %s, %s, %s" % (v(TM_A), s(0), s(1)))
+    add("v_max_f32 %s, %s, %s" % (v(TM_B), s(16), s(17)))
+    for j in range(1, 8):
+        add("v_max3_f32 %s, %s, %s, %s" % (v(TM_A), v(TM_A), s(2 * j), s(2 * j + 1)))
+        add("v_max3_f32 %s, %s, %s, %s" % (v(TM_B), v(TM_B), s(16 + 2 * j), s(17 + 2 * j)))
+    add("v_max_f32 %s, %s, %s" % (v(TM_A), v(TM_A), v(TM_B)))
+    add("v_mov_b32 %s, %s" % (v(T_SWAP), v(TM_A)))
+    add("s_nop 1")                                           # VALU write -> permlane swap read
+    add("v_permlane32_swap_b32 %s, %s" % (v(TM_A), v(T_SWAP)))  # both halves of a row see both maxima
+    add("s_nop 1")
+    add("v_max_f32 %s, %s, %s" % (v(TM_A), v(TM_A), v(T_SWAP)))
+    add("v_mul_f32 %s, %%[c], %s" % (v(T_MC), v(TM_A)))      # tile maximum in scaled units
+    add("v_add_f32 %s, 4.0, %%[m]" % v(T_THR))
+    add("v_cmp_gt_f32 vcc, %s, %s" % (v(T_MC), v(T_THR)))
+    add("v_cndmask_b32 %s, %%[m], %s, vcc" % (v(T_THR), v(T_MC)))   # new reference
+    add("v_sub_f32 %%[al], %%[m], %s" % v(T_THR))
+    add("v_exp_f32 %[al], %[al]")                            # alpha = 2^(M_old - M_new); 1 when unchanged
+    add("v_mov_b32 %%[m], %s" % v(T_THR))
+
+    def stage_a(g):                                          # x = 2^(s*c - M) for scores 4g..4g+3, in place
+        xs = [sc + 4 * g + k for k in range(4)]
+        for k in range(4):
+            add("v_fma_f32 %s, %s, %%[c], -%%[m]" % (v(xs[k]), s(4 * g + k)))
+        for k in range(4):
+            add("v_exp_f32 %s, %s" % (v(xs[k]), v(xs[k])))
+
+    def stage_b(g):                                          # row sum (unrounded) and the two packed P registers
+        xs = [sc + 4 * g + k for k in range(4)]
+        need = 4 * (g // 2) + 3                              # last PV MFMA reading P quarter g/2
+        if g == 0:
+            add("v_add_f32 %s, %s, %s" % (v(PS0), v(xs[0]), v(xs[1])))
+            add("v_add_f32 %s, %s, %s" % (v(PS1), v(xs[2]), v(xs[3])))
+        else:
+            add("v_add_f32 %s, %s, %s" % (v(PS0), v(PS0), v(xs[0])))
+            add("v_add_f32 %s, %s, %s" % (v(PS1), v(PS1), v(xs[1])))
+            add("v_add_f32 %s, %s, %s" % (v(PS0), v(PS0), v(xs[2])))
+            add("v_add_f32 %s, %s, %s" % (v(PS1), v(PS1), v(xs[3])))
+        add("v_cvt_pk_bf16_f32 %s, %s, %s" % (v(P + 2 * g), v(xs[0]), v(xs[1])), need)
+        add("v_cvt_pk_bf16_f32 %s, %s, %s" % (v(P + 2 * g + 1), v(xs[2]), v(xs[3])), need)
+
+    stage_a(0)
+    for g in range(1, 8):
+        stage_a(g)
+        stage_b(g - 1)
+    stage_b(7)
+    add("v_add_f32 %s, %s, %s" % (v(PS0), v(PS0), v(PS1)))
+    add("v_fma_f32 %%[l], %%[l], %%[al], %s" % v(PS0))
+    return ops
+
+
+def address_setup(has_pv, has_s):
+    """Fragment addresses of this block: lane constants plus the ring slots' byte offsets (SGPR operands)."""
+    out = []
+    if has_pv:
+        out.append("v_add_u32 %s, %%[sva], %s" % (v(RL), v(VA_BASE)))
+        for db in range(1, 4):
+            out.append("v_xor_b32 %s, %d, %s" % (v(RL + db), 32 * db, v(RL)))      # head-dim block db: see V tile layout
+    if has_s:
+        out.append("v_add_u32 %s, %%[ska], %s" % (v(KADDR), v(KA_BASE)))
+    return out
+
+
+def mfma_steps(has_pv, has_s, sn):
+    """Per MFMA: (LDS read lines, mfma line, is_pv)."""
+    steps = []
+    if has_pv:
+        for r in range(16):
+            kb, db = r >> 2, r & 3
+            rd = ["ds_read_b128 {f}, %s offset:%d" % (v(RL + db), kb * 4096 + 512 * db)]
+            mf = "v_mfma_f32_32x32x16_bf16 %s, {f}, %s, %s" % (vr(O + 16 * db, 16), vr(P + 4 * kb, 4), vr(O + 16 * db, 16))
+            steps.append((rd, mf, True))
+    if has_s:
+        for r in range(16):
+            kk, tb = r >> 1, r & 1
+            rd = []
+            if tb == 0 and kk > 0:
+                rd.append("v_xor_b32 %s, %d, %s" % (v(T_TK), kk * 32, v(KADDR)))
+            rd.append("ds_read_b128 {f}, %s offset:%d" % (v(KADDR) if kk == 0 else v(T_TK), tb * 8192))
+            dst = vr(sn + 16 * tb, 16)
+            mf = "v_mfma_f32_32x32x16_bf16 %s, {f}, %s, %s" % (dst, vr(Q + 4 * kk, 4), "0" if kk == 0 else dst)
+            steps.append((rd, mf, False))
+    return steps
+
+
+def block(name, cur, has_pv, has_s, has_sm):
+    sc, sn = (SA, SB) if cur == "A" else (SB, SA)
+    steps = mfma_steps(has_pv, has_s, sn)
+    ops = softmax_ops(sc) if has_sm else []
+    n = len(steps)
+    lines = ["s_nop 7"] + address_setup(has_pv, has_s)
+    reads = lambda r: [x.replace("{f}", frag(r)) for x in steps[r][0]]
+    for r in range(min(DIST, n)):
+        lines += reads(r)
+    vi = 0
+    pre = 10 if n else len(ops)                      # vector work that hides the latency of the first fragments
+    while vi < min(pre, len(ops)) and ops[vi][1] < 0:
+        lines.append(ops[vi][0])
+        vi += 1
+    n_pv = 16 if has_pv else 0
+    for r in range(n):
+        if r + DIST < n:
+            lines += reads(r + DIST)
+        lines.append("s_waitcnt lgkmcnt(%d)" % min(DIST, n - 1 - r))
+        lines.append(steps[r][1].replace("{f}", frag(r)))
+        target = pre + (len(ops) - pre) * (r + 1) // n
+        while vi < len(ops) and vi < target:
+            need = ops[vi][1]
+            if has_pv and need >= 0 and need >= r and r < n - 1:
+                break                                 # this P quarter is still being read
+            lines.append(ops[vi][0])
+            vi += 1
+    while vi < len(ops):
+        lines.append(ops[vi][0])
+        vi += 1
+    if has_pv and not has_s:
+        lines += ["s_nop 15", "s_nop 7"]              # O is read by ordinary code next
+    outs, ins, sig = [], [], []
+    if has_pv:
+        ins += ['[sva] "s"(sva)']
+        sig += ["uint32_t sva"]
+    if has_sm:
+        outs += ['[m] "+v"(m)', '[l] "+v"(l)', '[al] "=&v"(alpha)']
+        sig += ["float &m", "float &l", "float &alpha"]
+        ins += ['[c] "s"(c)']
+        sig += ["float c"]
+    if has_s:
+        ins += ['[ska] "s"(ska)']
+        sig += ["uint32_t ska"]
+    return emit(name, sig, lines, outs, ins, ['"memory"', '"vcc"'])
+
+
+def fast_block(name, cur):
+    """Full block (PV, S, softmax) that also issues the cache loads of tile i+3 and re-lays V(i) out in place.
+
+    All LDS traffic of the block is in one in-order queue, so every consumer waits with the exact count of
+    younger operations that may still be outstanding.
+    """
+    sc, sn = (SA, SB) if cur == "A" else (SB, SA)
+    steps = mfma_steps(True, True, sn)
+    n = len(steps)
+    sm = softmax_ops(sc)
+    rx = lambda k: RL + 2 * k          # row k, columns 0..1 (dword x)
+    ry = lambda k: RL + 2 * k + 1      # row k, columns 2..3 (dword y)
+    t0, t1 = RL + 8, RL + 9
+    # auxiliary stream: (text, kind, lds id or None, ids it needs, PV MFMA it must follow)
+    aux = []
+    dma = ["s_mov_b32 m0, %[kdst]", "s_nop 0", "global_load_lds_dwordx4 %[koff0], %[kb]",
+           "s_add_u32 m0, %[kdst], 0x400", "s_nop 0", "global_load_lds_dwordx4 %[koff1], %[kb]",
+           "s_mov_b32 m0, %[vdst]", "s_nop 0", "global_load_lds_dwordx4 %[voff0], %[vb]",
+           "s_add_u32 m0, %[vdst], 0x400", "s_nop 0", "global_load_lds_dwordx4 %[voff1], %[vb]"]
+    for t, need in sm[:12]:
+        aux.append(dict(t=t, mf=need))
+    rl_reads = [dict(t="v_add_u32 %s, %%[srl], %s" % (v(t1), v(RD_BASE))),
+                dict(t="v_add_u32 %s, %%[srl], %s" % (v(WRT), v(WR_BASE)))]
+    for k in range(4):
+        rl_reads.append(dict(t="ds_read_b64 %s, %s offset:%d" % (vr(rx(k), 2), v(t1), 256 * k), lds=("r", k)))
+    relay = [
+        dict(t="v_perm_b32 %s, %s, %s, %%[slo]" % (v(t0), v(rx(1)), v(rx(0))), needs=[("r", 0), ("r", 1)]),
+        dict(t="v_perm_b32 %s, %s, %s, %%[slo]" % (v(t1), v(rx(3)), v(rx(2))), needs=[("r", 2), ("r", 3)]),
+        dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(WRT), v(t0), v(t1)), lds=("w", 0)),
+        dict(t="v_perm_b32 %s, %s, %s, %%[shi]" % (v(rx(0)), v(rx(1)), v(rx(0)))),
+        dict(t="v_perm_b32 %s, %s, %s, %%[shi]" % (v(rx(2)), v(rx(3)), v(rx(2)))),
+        dict(t="v_xor_b32 %s, 16, %s" % (v(rx(1)), v(WRT))),
+        dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(rx(1)), v(rx(0)), v(rx(2))), lds=("w", 1)),
+        dict(t="v_perm_b32 %s, %s, %s, %%[slo]" % (v(t0), v(ry(1)), v(ry(0)))),
+        dict(t="v_perm_b32 %s, %s, %s, %%[slo]" % (v(t1), v(ry(3)), v(ry(2)))),
+        dict(t="v_xor_b32 %s, 32, %s" % (v(rx(3)), v(WRT))),
+        dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(rx(3)), v(t0), v(t1)), lds=("w", 2)),
+        dict(t="v_perm_b32 %s, %s, %s, %%[shi]" % (v(ry(0)), v(ry(1)), v(ry(0)))),
+        dict(t="v_perm_b32 %s, %s, %s, %%[shi]" % (v(ry(2)), v(ry(3)), v(ry(2)))),
+        dict(t="v_xor_b32 %s, 48, %s" % (v(ry(1)), v(WRT))),
+        dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(ry(1)), v(ry(0)), v(ry(2))), lds=("w", 3)),
+    ]
+    rest = sm[12:]
+    # The re-layout shares v[38:41] with the V fragment addresses, so it starts once the last PV read is out
+    # (MFMA 11 issued); then one of its instructions after every fourth softmax instruction.
+    ri, started = 0, False
+    for j, (t, need) in enumerate(rest):
+        aux.append(dict(t=t, mf=need))
+        if j >= 50 and not started:
+            for it in rl_reads:
+                aux.append(dict(it, mf=11))
+            started = True
+        elif started and (j - 50) % 4 == 0 and ri < len(relay):
+            aux.append(dict(relay[ri], mf=11))
+            ri += 1
+    assert started
+    for it in relay[ri:]:
+        aux.append(dict(it, mf=11))
+
+    seq = [dict(t="s_nop 7")] + [dict(t=t) for t in address_setup(True, True)]
+    def put_reads(r):
+        for x in steps[r][0]:
+            seq.append(dict(t=x.replace("{f}", frag(r)), lds=("f", r) if x.startswith("ds_read") else None))
+    for r in range(DIST):
+        put_reads(r)
+    vi = 0
+    pre = 12
+    while vi < pre:
+        seq.append(aux[vi])
+        vi += 1
+    for r in range(n):
+        if r + DIST < n:
+            put_reads(r + DIST)
+        seq.append(dict(t=steps[r][1].replace("{f}", frag(r)), needs=[("f", r)]))
+        if r % 8 == 1:
+            for t in dma[3 * (r // 8):3 * (r // 8) + 3]:
+                seq.append(dict(t=t))
+        target = pre + (len(aux) - pre) * (r + 1) // n
+        while vi < len(aux) and vi < target:
+            need = aux[vi].get("mf", -1)
+            if need >= 0 and need >= r and r < n - 1:
+                break
+            seq.append(aux[vi])
+            vi += 1
+    seq += aux[vi:]
+    # wait insertion
+    lines, issued, done = [], [], -1
+    for it in seq:
+        needs = it.get("needs")
+        if needs:
+            pos = max(issued.index(x) for x in needs)
+            if pos > done:
+                lines.append("s_waitcnt lgkmcnt(%d)" % (len(issued) - 1 - pos))
+                done = pos
+        lines.append(it["t"])
+        if it.get("lds"):
+            issued.append(it["lds"])
+    sig = ["uint32_t sva", "float &m", "float &l", "float &alpha", "float c", "uint32_t ska", "const void *kb",
+           "const void *vb", "uint32_t kdst", "uint32_t vdst", "uint32_t koff0", "uint32_t koff1", "uint32_t voff0",
+           "uint32_t voff1", "uint32_t srl"]
+    outs = ['[m] "+v"(m)', '[l] "+v"(l)', '[al] "=&v"(alpha)']
+    ins = ['[sva] "s"(sva)', '[c] "s"(c)', '[ska] "s"(ska)', '[kb] "s"(kb)', '[vb] "s"(vb)',
+           '[kdst] "s"(kdst)', '[vdst] "s"(vdst)', '[koff0] "v"(koff0)', '[koff1] "v"(koff1)', '[voff0] "v"(voff0)',
+           '[voff1] "v"(voff1)', '[srl] "s"(srl)', '[slo] "s"(0x05040100u)', '[shi] "s"(0x07060302u)']
+    return emit(name, sig, lines, outs, ins, ['"memory"', '"vcc"', '"scc"'])
+
+
+def emit(name, sig, lines, outs, ins, clob):
+    code = ["__device__ __forceinline__ void %s(%s)" % (name, ", ".join(sig)), "{", "    asm volatile("]
+    for ln in lines:
+        code.append('        "%s\\n\\t"' % ln)
+    code.append("        : " + ", ".join(outs))
+    code.append("        : " + ", ".join(ins))
+    code.append("        : " + ", ".join(clob) + ");")
+    code.append("}")
+    return "\n".join(code)
+
+
+def helpers():
+    out = []
+    # O = 0.  Naming v255 as clobbered makes the compiler size the kernel's register file for all 256 VGPRs.
+    out.append(emit("sp_zero_o", [], ["v_mov_b32 %s, 0" % v(O + k) for k in range(64)], [], [], ['"memory"', '"v255"']))
+    for half, name in ((0, "sp_set_q_lo"), (1, "sp_set_q_hi")):
+        lines = ["v_mov_b32 %s, %%%d" % (v(Q + 16 * half + k), k) for k in range(16)]
+        out.append(emit(name, ["const uint32_t (&x)[16]"], lines, [], ['"v"(x[%d])' % k for k in range(16)], ['"memory"']))
+    out.append(emit("sp_set_bases", ["uint32_t va", "uint32_t ka", "uint32_t rd", "uint32_t wr"],
+                    ["v_mov_b32 %s, %%%d" % (v(r), k) for k, r in enumerate((VA_BASE, KA_BASE, RD_BASE, WR_BASE))], [],
+                    ['"v"(va)', '"v"(ka)', '"v"(rd)', '"v"(wr)'], ['"memory"']))
+    out.append(emit("sp_get_rl", ["uint32_t &rd", "uint32_t &wr"],
+                    ["v_mov_b32 %%0, %s" % v(RD_BASE), "v_mov_b32 %%1, %s" % v(WR_BASE)], ['"=v"(rd)', '"=v"(wr)'], [],
+                    ['"memory"']))
+    lines = ["s_nop 15", "s_nop 7"] + ["v_mul_f32 %s, %%[al], %s" % (v(O + k), v(O + k)) for k in range(64)] + ["s_nop 3"]
+    out.append(emit("sp_scale_o", ["float alpha"], lines, [], ['[al] "v"(alpha)'], ['"memory"']))
+    for cur, base in (("A", SA), ("B", SB)):
+        lines = ["s_nop 15", "s_nop 7", "v_mov_b32 %s, 0xff800000" % v(TMP)]
+        for tb in range(2):
+            for i in range(16):
+                bit = 8 * (i // 4) + (i % 4)
+                lines.append("v_and_b32 %s, 0x%x, %%[%s]" % (v(TMP + 1), 1 << bit, "lo" if tb == 0 else "hi"))
+                lines.append("v_cmp_eq_u32 vcc, 0, %s" % v(TMP + 1))
+                lines.append("v_cndmask_b32 %s, %s, %s, vcc" % (v(base + 16 * tb + i), v(base + 16 * tb + i), v(TMP)))
+        out.append(emit("sp_mask_" + cur, ["uint32_t lo", "uint32_t hi"], lines, [], ['[lo] "v"(lo)', '[hi] "v"(hi)'],
+                        ['"memory"', '"vcc"']))
+    for db in range(4):
+        lines = (["s_nop 15", "s_nop 7"] if db == 0 else []) + \
+                ["v_mul_f32 %%%d, %%[inv], %s" % (k, v(O + 16 * db + k)) for k in range(16)]
+        out.append(emit("sp_get_o%d" % db, ["float inv", "float (&o)[16]"], lines, ['"=&v"(o[%d])' % k for k in range(16)],
+                        ['[inv] "v"(inv)'], ['"memory"']))
+    return "\n\n".join(out)
+
+
+if __name__ == "__main__":
+    print("// Generated by gen_sp_block.py -- do not edit.")
+    print(block("sp_s_first", "B", False, True, False))          # S^T(0) into buffer A ("current" B is unused)
+    for cur in "AB":
+        print()
+        print(block("sp_full_" + cur, cur, True, True, True))
+        print()
+        print(block("sp_last_" + cur, cur, True, False, True))    # no tile after this one
+    print()
+    print(block("sp_head_A", "A", False, True, True))            # tile 0 when a tile 1 follows
+    print()
+    print(block("sp_only_A", "A", False, False, True))           # tile 0 of a one-tile walk
+    print()
+    print(block("sp_pv", "A", True, False, False))               # drain: the last tile's P . V
+    print()
+    print(fast_block("sp_fast_A", "A"))
+    print()
+    print(fast_block("sp_fast_B", "B"))
+    print()
+    print(helpers())

@@ -119,7 +119,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     size_t user_ws_bytes = 0;
     if (opts) {
         if (opts->reserved != 0 || opts->num_splits < 0 || opts->kernel < TA_KERNEL_AUTO ||
-            opts->kernel > TA_KERNEL_MFMA_BASIC)
+            opts->kernel > TA_KERNEL_MFMA_BASIC + 1)
             return TA_ERR_OPTS;
         kernel = opts->kernel;
         num_splits = opts->num_splits;
@@ -143,7 +143,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
                          ((uintptr_t)q->data % 16) == 0 && ((uintptr_t)k->data % 16) == 0 &&
                          ((uintptr_t)v->data % 16) == 0 && k->stride[0] < INT32_MAX && k->stride[2] < INT32_MAX &&
                          v->stride[0] < INT32_MAX && v->stride[2] < INT32_MAX;
-    const bool basic = kernel == TA_KERNEL_MFMA_BASIC;
+    const int basic = kernel == TA_KERNEL_MFMA_BASIC ? 1 : (kernel == TA_KERNEL_MFMA_BASIC + 1 ? 2 : 0);
     if (basic)
         kernel = TA_KERNEL_MFMA;
     if (kernel == TA_KERNEL_MFMA && !mfma_ok)
@@ -228,9 +228,9 @@ int device_state(DeviceState **out)
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             return TA_ERR_HIP;
-        if (hipMalloc((void **)&s.status, 256) != hipSuccess)
+        if (hipMalloc((void **)&s.status, TA_STATUS_BYTES) != hipSuccess)
             return TA_ERR_HIP;
-        if (hipMemset(s.status, 0, 256) != hipSuccess)
+        if (hipMemset(s.status, 0, TA_STATUS_BYTES) != hipSuccess)
             return TA_ERR_HIP;
         s.num_cus = cus;
         s.init = true;
@@ -461,3 +461,16 @@ int tree_attn_last_status(int32_t *host_status, void *stream)
 }
 
 }  // extern "C"
+
+#ifdef TA_TUNING
+// tuning builds only: copies the status area (synchronously) to the host
+extern "C" int ta_tuning_read(void *host256)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *s = nullptr;
+    int rc = device_state(&s);
+    if (rc != TA_OK)
+        return rc;
+    return hipMemcpy(host256, s->status, TA_STATUS_BYTES, hipMemcpyDeviceToHost) == hipSuccess ? TA_OK : TA_ERR_HIP;
+}
+#endif

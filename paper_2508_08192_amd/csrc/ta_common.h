@@ -10,7 +10,12 @@
 #define TA_WAVE 64
 #define TA_TILE 64            // KV tokens per tile of the KV pass (the tree tokens form one more tile)
 #define TA_MERGE_ROWS 4       // rows per workgroup of the merge pass (one per wave)
-#define TA_ROW_GROUP 256      // rows (tree nodes x query heads of one KV head) one workgroup keeps
+#define TA_ROW_GROUP 256
+#ifdef TA_TUNING
+#define TA_STATUS_BYTES 65536   // room for per-workgroup timestamps
+#else
+#define TA_STATUS_BYTES 256
+#endif      // rows (tree nodes x query heads of one KV head) one workgroup keeps
 
 struct TAParams {
     const void *q, *k, *v;

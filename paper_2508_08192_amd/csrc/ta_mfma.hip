@@ -782,6 +782,448 @@ __global__ __launch_bounds__(512) void ta_mfma_pp_kernel(TAParams p)
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// 256-row variant, software-pipelined inside every wave: 8 waves of 32 rows, two per SIMD.
+//
+// Block i of a wave is one instruction stream that interleaves the 16 MFMAs of O^T += V^T(i-1).P^T(i-1), the
+// 16 MFMAs of S^T(i+1) = K(i+1).Q^T and the running softmax of S^T(i) (see gen_sp_block.py), so the wave feeds the
+// matrix pipe and the vector ALU at once and needs no phase skew; one workgroup barrier per tile remains.
+// K and V tiles travel global -> LDS without touching registers (global_load_lds_dwordx4), three blocks
+// ahead of their first use, into a ring of 3 K tiles and a ring of 5 V tiles.  A V tile is re-laid out
+// token-minor IN PLACE, one 8-token group per wave: the load already puts the two token quads of a group side
+// by side, so the 2 KB a wave reads are the 2 KB it writes.
+//
+//   start of block i : issue the loads of tile i+3        (K slot (i+3)%3: last read by S(i) in block i-1,
+//                                                          V slot (i+3)%5: last read by PV(i-2) in block i-1)
+//   block i          : PV(i-1) | S(i+1) | softmax(i)
+//   tail i           : re-lay V(i); rescale O if the softmax reference moved; mask S(i+1) if tile i+1 is
+//                      ragged or the tree tile; wait for this wave's part of tile i+2; barrier
+// ---------------------------------------------------------------------------------------------
+#define SP_RK 3
+#define SP_RV 5
+#define SP_V_OFF (SP_RK * MF_TILE_BYTES)
+#define SP_AUX_OFF ((SP_RK + SP_RV) * MF_TILE_BYTES)
+
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+
+#include "ta_sp_block.inc"
+
+// every lane moves 16 bytes from base + off to LDS offset lds_wave_base + 16*lane (base is wave-uniform)
+__device__ __forceinline__ void dma16s(const void *base, uint32_t off, uint32_t lds_wave_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base),
+                 "s"(lds_wave_base)
+                 : "memory");
+}
+
+template <bool V>
+struct SpTag {
+    static constexpr bool value = V;
+};
+
+// amdgpu_num_vgpr(16): the register allocator stays in v0..v31; v32..v255 belong to the asm blocks (see gen_sp_block.py)
+__global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_mfma_sp_kernel(TAParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    unsigned long long *masks = (unsigned long long *)(smem + SP_AUX_OFF);
+    int *flag = (int *)(masks + TA_MAX_TREE);
+    int *par_s = flag + 4;                                                // [TA_MAX_TREE]
+    int *pcache = par_s + TA_MAX_TREE;                                    // [PP_PAGES] page ids of the current span
+    int *cum = pcache + PP_PAGES;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
+
+#ifdef TA_TUNING
+    const unsigned long long tun_c0 = __builtin_readcyclecounter(), tun_r0 = __builtin_amdgcn_s_memrealtime();
+#endif
+    ta_build_schedule(p, cum);
+    const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
+    const int share = ta_share(p, total);
+    const int w = blockIdx.x, rg = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r32 = lane & 31, hf = lane >> 5;
+    int t = w * share;
+    const int t_end = min(total, t + share);
+    const int rows_here = min(p.rows_grp, p.rows - rg * p.rows_grp);
+    const float c = p.scale_log2e;
+    const bool paged = p.page_table != nullptr;
+    const uint32_t ksp = (uint32_t)p.k_sp, kss = (uint32_t)p.k_ss, vsp = (uint32_t)p.v_sp, vss = (uint32_t)p.v_ss;
+    // Lane constants of the blocks (LDS byte offsets), kept in their fixed registers:
+    //   K fragment of step kk: row r32, 16-byte slot (2kk + hf) ^ (r32 & 15), i.e. base ^ 32kk inside the tile
+    //   V fragment of head-dim block db: (base ^ 32db) + 512db inside the token-minor tile
+    //   re-layout: token quad sec of the wave's 8-token group, head-dim columns 4*c4 .. 4*c4+3 (column e: write ^ 16e)
+    {
+        const int sec = lane >> 5, c4 = lane & 31;
+        sp_set_bases(lds0 + SP_V_OFF + (uint32_t)((hf * 128 + (r32 ^ (r32 >> 4))) << 4),
+                     lds0 + (uint32_t)(r32 * 256 + ((hf ^ (r32 & 15)) << 4)),
+                     lds0 + (uint32_t)(SP_V_OFF + wave * 2048 + 4 * sec * 256 + c4 * 8),
+                     lds0 + (uint32_t)(SP_V_OFF + wave * 2048 + (((4 * c4) ^ ((c4 >> 2) & 7)) << 4) + sec * 8));
+    }
+    // Cache-load role of a lane.  K: tile rows drow and drow+4, 16-byte slot dslot (source chunk swizzled).
+    // V: LDS rows drow and drow+4 hold tokens tv0 and tv0+8 (bits 2 and 3 of the row index swapped), so that
+    // the two token quads of every 8-token group of the second product are neighbours.
+    // Only the byte offsets of the common case stay in registers; the rare paths derive their lane roles again
+    // from the thread id (fresh_tid keeps the compiler from hoisting them into long-lived registers).
+    auto fresh_tid = [&]() {
+        int x = tid;
+        asm volatile("" : "+v"(x));
+        return x;
+    };
+    uint32_t koff0, koff1, voff0, voff1;
+    {
+        const int drow = wave * 8 + (lane >> 4), dslot = lane & 15;
+        const int tv0 = 16 * (wave >> 1) + 4 * (wave & 1) + (lane >> 4);
+        koff0 = (uint32_t)(drow * kss + (dslot ^ (drow & 15)) * 8) * 2u;
+        koff1 = (uint32_t)((drow + 4) * kss + (dslot ^ ((drow + 4) & 15)) * 8) * 2u;
+        voff0 = (uint32_t)(tv0 * vss + dslot * 8) * 2u;
+        voff1 = (uint32_t)((tv0 + 8) * vss + dslot * 8) * 2u;
+    }
+    // one page (or the contiguous cache) holds a whole aligned tile, and lane offsets fit 32 bits
+    const bool fast_geom = (!paged || p.ps_shift >= 6) && kss < (1u << 22) && vss < (1u << 22);
+
+    while (t < t_end) {
+        const int b = __builtin_amdgcn_readfirstlane(ta_find_request(p, cum, t));
+        const int n_b = __builtin_amdgcn_readfirstlane(cum[b + 1] - cum[b]);
+        const int cum_b = __builtin_amdgcn_readfirstlane(cum[b]);
+        const int g = (t - p.Hkv * cum_b) / n_b;
+        const int seg_start = p.Hkv * cum_b + g * n_b;
+        const int j0 = t - seg_start;
+        const int j1 = min(n_b, t_end - seg_start);
+        const int n = j1 - j0;
+        const int slot = w + b * p.Hkv + g;
+        const int L = __builtin_amdgcn_readfirstlane(p.seq_lens[(int64_t)b * p.sl_s]);
+        bool poison = !ta_request_ok(p, L);
+        if (poison && tid == 0)
+            atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
+        const bool has_tree_tile = (j1 == n_b);
+        if (has_tree_tile && !poison) {
+            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag, par_s)) {
+                poison = true;
+                if (tid == 0)
+                    atomicOr(p.status, TA_STATUS_BAD_PARENT);
+            }
+        }
+        const int row = wave * 32 + r32;
+        const bool row_ok = row < rows_here;
+
+        if (poison) {
+            if (row_ok) {
+                const int64_t wrow = ta_ws_row(p, slot, rg, row);
+                for (int d = hf * 64; d < hf * 64 + 64; d += 4)
+                    *(float4 *)(p.ws_o + wrow * MF_D + d) = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (hf == 0)
+                    p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
+            }
+            __syncthreads();
+            t = seg_start + j1;
+            continue;
+        }
+
+        {
+            // Q fragments of this lane's row into their fixed registers, 16 dwords at a time
+            const int R = rg * p.rows_grp + row;
+            const uint16_t *qp = (const uint16_t *)p.q + (int64_t)b * p.q_sb + (int64_t)(R / p.G) * p.q_st +
+                                 (int64_t)(g * p.G + R % p.G) * p.q_sh + hf * 8;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                uint32_t x[16];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    u32x4 f = (u32x4){0u, 0u, 0u, 0u};
+                    if (row_ok)
+                        f = *(const u32x4 *)(qp + (4 * half + kk) * 16);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        x[4 * kk + e] = f[e];
+                }
+                if (half == 0)
+                    sp_set_q_lo(x);
+                else
+                    sp_set_q_hi(x);
+            }
+        }
+        const uint16_t *kgp = (const uint16_t *)p.k + (int64_t)g * p.k_sh;
+        const uint16_t *vgp = (const uint16_t *)p.v + (int64_t)g * p.v_sh;
+
+        // tile ti of this item: first logical position and number of tokens it holds
+        auto tile_pos0 = [&](int ti) { return TA_OFF(32) ? 0 : ((j0 + ti == n_b - 1) ? L : (j0 + ti) * TA_TILE); };
+        auto tile_count = [&](int ti) { return (j0 + ti == n_b - 1) ? p.T : min(TA_TILE, L - (j0 + ti) * TA_TILE); };
+        // bits of the tokens tile ti really holds for this lane's half, or all ones when nothing is to mask
+        auto tile_mask = [&](int ti) -> unsigned long long {
+            const int x = fresh_tid();
+            const int rw = (x >> 6) * 32 + (x & 31), h = (x >> 5) & 1;
+            const int j = j0 + ti;
+            if (j == n_b - 1)
+                return (rw < rows_here ? masks[(rg * p.rows_grp + rw) / p.G] : ~0ull) >> (4 * h);
+            const int rem = L - j * TA_TILE;
+            return (rem < TA_TILE ? ((1ull << rem) - 1ull) : ~0ull) >> (4 * h);
+        };
+        auto tile_ragged = [&](int ti) { return j0 + ti == n_b - 1 || L - (j0 + ti) * TA_TILE < TA_TILE; };
+        int span_first_page = 0;
+        const int span_tiles = !paged ? n
+                               : (p.ps_shift >= 6 ? PP_PAGES - 2 : max(1, ((PP_PAGES - 2) << p.ps_shift) / TA_TILE));
+        // Cache loads of tile ti into K slot ks and V slot vs: four 16-byte loads per lane.  Rows past the tile's
+        // end re-read its first token (their probabilities are exactly zero).
+        auto issue_tile = [&](int ti, int ks, int vs) {
+            const uint32_t kdst = lds0 + ks * MF_TILE_BYTES + wave * 2048;
+            const uint32_t vdst = lds0 + SP_V_OFF + vs * MF_TILE_BYTES + wave * 2048;
+            const int pos0 = tile_pos0(ti), cnt = tile_count(ti);
+            if (fast_geom && !tile_ragged(ti)) {
+                uint32_t pg = (uint32_t)b, sl = (uint32_t)pos0;
+                if (paged) {
+                    pg = (uint32_t)__builtin_amdgcn_readfirstlane(pcache[(pos0 >> p.ps_shift) - span_first_page]);
+                    sl = (uint32_t)(pos0 & (p.ps - 1));
+                }
+                const uint16_t *kb_ = kgp + (uint64_t)pg * ksp + (uint64_t)sl * kss;
+                const uint16_t *vb_ = vgp + (uint64_t)pg * vsp + (uint64_t)sl * vss;
+                dma16s(kb_, koff0, kdst);
+                dma16s(kb_, koff1, kdst + 1024);
+                dma16s(vb_, voff0, vdst);
+                dma16s(vb_, voff1, vdst + 1024);
+            } else {
+                const int x = fresh_tid();
+                const int drow = (x >> 6) * 8 + ((x & 63) >> 4), dslot = x & 15;
+                const int tv0 = 16 * (x >> 7) + 4 * ((x >> 6) & 1) + ((x & 63) >> 4);
+                const int pk[2] = {pos0 + (drow < cnt ? drow : 0), pos0 + (drow + 4 < cnt ? drow + 4 : 0)};
+                const int pv[2] = {pos0 + (tv0 < cnt ? tv0 : 0), pos0 + (tv0 + 8 < cnt ? tv0 + 8 : 0)};
+                uint64_t ke[2], ve[2];
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    uint32_t pgk = (uint32_t)b, slk = (uint32_t)pk[k], pgv = (uint32_t)b, slv = (uint32_t)pv[k];
+                    if (paged) {
+                        pgk = (uint32_t)pcache[(pk[k] >> p.ps_shift) - span_first_page];
+                        pgv = (uint32_t)pcache[(pv[k] >> p.ps_shift) - span_first_page];
+                        slk = (uint32_t)(pk[k] & (p.ps - 1));
+                        slv = (uint32_t)(pv[k] & (p.ps - 1));
+                    }
+                    ke[k] = (uint64_t)pgk * ksp + (uint64_t)slk * kss + (dslot ^ ((drow + 4 * k) & 15)) * 8;
+                    ve[k] = (uint64_t)pgv * vsp + (uint64_t)slv * vss + dslot * 8;
+                }
+                dma16(kgp + ke[0], kdst);
+                dma16(kgp + ke[1], kdst + 1024);
+                dma16(vgp + ve[0], vdst);
+                dma16(vgp + ve[1], vdst + 1024);
+            }
+        };
+        // this wave's 8-token group of the V tile in slot vs: raw rows -> token-minor, in place
+        auto relayout_v = [&](int vs) {
+            uint32_t rl_rd, rl_wr;
+            sp_get_rl(rl_rd, rl_wr);
+            char *rd = smem + vs * MF_TILE_BYTES + (rl_rd - lds0), *wr = smem + vs * MF_TILE_BYTES;
+            rl_wr -= lds0;
+            uint2 r[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                r[k] = *(const uint2 *)(rd + k * 256);
+            asm volatile("" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]));      // all reads before any write
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                uint2 o;
+                if (e < 2) {
+                    o.x = __builtin_amdgcn_perm(r[1].x, r[0].x, sel);
+                    o.y = __builtin_amdgcn_perm(r[3].x, r[2].x, sel);
+                } else {
+                    o.x = __builtin_amdgcn_perm(r[1].y, r[0].y, sel);
+                    o.y = __builtin_amdgcn_perm(r[3].y, r[2].y, sel);
+                }
+                *(uint2 *)(wr + (rl_wr ^ (16u * e))) = o;
+            }
+        };
+        auto wait_loads = [&](int tiles_in_flight) {       // all but the youngest tiles_in_flight*4 loads are done
+            if (tiles_in_flight >= 2)
+                vm_wait<8>();
+            else if (tiles_in_flight == 1)
+                vm_wait<4>();
+            else
+                vm_wait<0>();
+        };
+
+        sp_zero_o();
+        float m_run = -INFINITY, l_run = 0.f;
+
+        for (int s0 = 0; s0 < n; s0 += span_tiles) {
+            const int ns = min(span_tiles, n - s0);            // tiles s0 .. s0+ns-1 of the item; i is span-local
+            if (paged) {
+                span_first_page = tile_pos0(s0) >> p.ps_shift;
+                const int last_page = (tile_pos0(s0 + ns - 1) + tile_count(s0 + ns - 1) - 1) >> p.ps_shift;
+                for (int k = tid; k <= last_page - span_first_page; k += 512)
+                    pcache[k] = p.page_table[(int64_t)b * p.pt_sb + span_first_page + k];
+                __syncthreads();
+            }
+            // ring positions: next slots to load into, K slot of tile i+1, V slots of tiles i and i-1
+            int ik = 0, iv = 0, issued = 0;
+            for (; issued < min(ns, 3); ++issued) {
+                issue_tile(s0 + issued, ik, iv);
+                ik = ik == SP_RK - 1 ? 0 : ik + 1;
+                iv = iv == SP_RV - 1 ? 0 : iv + 1;
+            }
+            wait_loads(issued - 1);                            // tile 0 has landed
+            lds_barrier();
+            sp_s_first(0u);
+            if (tile_ragged(s0)) {
+                const unsigned long long vm = tile_mask(s0);
+                sp_mask_A((uint32_t)vm, (uint32_t)(vm >> 32));
+            }
+            if (ns > 1)
+                wait_loads(issued - 2);                        // tile 1 has landed
+            lds_barrier();
+
+            int kn = 1, vc = 0, vp = SP_RV - 1;                // K slot of tile i+1, V slot of tile i, of tile i-1
+            auto step = [&](auto tag, int i) {
+                constexpr bool A = decltype(tag)::value;       // S^T(i) sits in buffer A
+                if (i + 3 < ns && !TA_OFF(4)) {
+                    issue_tile(s0 + i + 3, ik, iv);
+                    ik = ik == SP_RK - 1 ? 0 : ik + 1;
+                    iv = iv == SP_RV - 1 ? 0 : iv + 1;
+                }
+                const bool has_next = i + 1 < ns;
+                const uint32_t ska = kn * MF_TILE_BYTES, sva = vp * MF_TILE_BYTES;
+                float alpha = 1.f;
+                if (TA_OFF(1)) {
+                } else if constexpr (A) {
+                    if (i == 0) {
+                        if (has_next)
+                            sp_head_A(m_run, l_run, alpha, c, ska);
+                        else
+                            sp_only_A(m_run, l_run, alpha, c);
+                    } else if (has_next) {
+                        sp_full_A(sva, m_run, l_run, alpha, c, ska);
+                    } else {
+                        sp_last_A(sva, m_run, l_run, alpha, c);
+                    }
+                } else {
+                    if (has_next)
+                        sp_full_B(sva, m_run, l_run, alpha, c, ska);
+                    else
+                        sp_last_B(sva, m_run, l_run, alpha, c);
+                }
+                if (!TA_OFF(8))
+                    relayout_v(vc);
+                if (__any(alpha != 1.0f))
+                    sp_scale_o(alpha);             // O still holds sums relative to the old reference
+                if (has_next && tile_ragged(s0 + i + 1)) {
+                    const unsigned long long vm = tile_mask(s0 + i + 1);
+                    if constexpr (A)
+                        sp_mask_B((uint32_t)vm, (uint32_t)(vm >> 32));
+                    else
+                        sp_mask_A((uint32_t)vm, (uint32_t)(vm >> 32));
+                }
+                if (i + 2 < ns && !TA_OFF(64))
+                    wait_loads(i + 3 < ns ? 1 : 0);            // this wave's part of tile i+2 has landed
+                lds_barrier();
+                kn = kn == SP_RK - 1 ? 0 : kn + 1;
+                vp = vc;
+                vc = vc == SP_RV - 1 ? 0 : vc + 1;
+            };
+            // Steady state, two tiles per turn: every tile involved is a full prefix tile inside one page, so the
+            // block itself issues the loads of tile i+3 and re-lays V(i) out (sp_fast_*); no masks, no choices.
+            // The page id of the tile a fast step loads comes out of the LDS cache one step ahead (pg_ahead holds
+            // the raw value; it has long arrived when the next step reads it).
+            int pg_ahead = 0;
+            bool ahead_valid = false;
+            auto page_of = [&](int pos0) {
+                return pcache[min((pos0 >> p.ps_shift) - span_first_page, PP_PAGES - 1)];
+            };
+            auto fast_step = [&](auto tag, int i) {
+                constexpr bool A = decltype(tag)::value;
+                const int pos0 = TA_OFF(32) ? 0 : (j0 + s0 + i + 3) * TA_TILE;
+                uint32_t pg = (uint32_t)b, sl = (uint32_t)pos0;
+                if (paged) {
+                    pg = (uint32_t)__builtin_amdgcn_readfirstlane(ahead_valid ? pg_ahead : page_of(pos0));
+                    sl = (uint32_t)(pos0 & (p.ps - 1));
+                    pg_ahead = page_of(pos0 + TA_TILE);
+                    ahead_valid = true;
+                }
+                const uint16_t *kb_ = kgp + (uint64_t)pg * ksp + (uint64_t)sl * kss;
+                const uint16_t *vb_ = vgp + (uint64_t)pg * vsp + (uint64_t)sl * vss;
+                const uint32_t kdst = lds0 + ik * MF_TILE_BYTES + wave * 2048;
+                const uint32_t vdst = lds0 + SP_V_OFF + iv * MF_TILE_BYTES + wave * 2048;
+                ik = ik == SP_RK - 1 ? 0 : ik + 1;
+                iv = iv == SP_RV - 1 ? 0 : iv + 1;
+                float alpha;
+                if constexpr (A)
+                    sp_fast_A(vp * MF_TILE_BYTES, m_run, l_run, alpha, c, kn * MF_TILE_BYTES, kb_, vb_, kdst, vdst, koff0,
+                              koff1, voff0, voff1, vc * MF_TILE_BYTES);
+                else
+                    sp_fast_B(vp * MF_TILE_BYTES, m_run, l_run, alpha, c, kn * MF_TILE_BYTES, kb_, vb_, kdst, vdst, koff0,
+                              koff1, voff0, voff1, vc * MF_TILE_BYTES);
+                if (__any(alpha != 1.0f))
+                    sp_scale_o(alpha);
+                if (!TA_OFF(64))
+                    vm_wait<4>();                              // this wave's part of tile i+2 has landed
+                if (!TA_OFF(128))
+                    lds_barrier();
+                kn = kn == SP_RK - 1 ? 0 : kn + 1;
+                vp = vc;
+                vc = vc == SP_RV - 1 ? 0 : vc + 1;
+            };
+            int i = 0;
+#pragma unroll 1
+            while (i < ns) {
+                if (!(i & 1) && i >= 2 && fast_geom && i + 4 < ns && !tile_ragged(s0 + i + 4)) {
+                    fast_step(SpTag<true>{}, i);
+                    fast_step(SpTag<false>{}, i + 1);
+                    i += 2;
+                } else {
+                    ahead_valid = false;
+                    if (i & 1)
+                        step(SpTag<false>{}, i);
+                    else
+                        step(SpTag<true>{}, i);
+                    ++i;
+                }
+            }
+            sp_pv(vp * MF_TILE_BYTES);
+            lds_barrier();                                     // the rings are free for the next span or item
+        }
+
+        {
+            const int x = fresh_tid();
+            const int rw = (x >> 6) * 32 + (x & 31), h = (x >> 5) & 1;
+            const float l_tot = l_run + __shfl_xor(l_run, 32, TA_WAVE);
+            if (rw < rows_here) {
+                const int64_t wrow = ta_ws_row(p, slot, rg, rw);
+                const float inv = 1.f / l_tot;
+                float *dst = p.ws_o + wrow * MF_D + 4 * h;
+                float o[16];
+                sp_get_o0(inv, o);
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4)
+                    *(float4 *)(dst + 8 * i4) = make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
+                sp_get_o1(inv, o);
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4)
+                    *(float4 *)(dst + 32 + 8 * i4) = make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
+                sp_get_o2(inv, o);
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4)
+                    *(float4 *)(dst + 64 + 8 * i4) = make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
+                sp_get_o3(inv, o);
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4)
+                    *(float4 *)(dst + 96 + 8 * i4) = make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
+                if (h == 0)
+                    p.ws_lse[wrow] = m_run + log2f(l_tot);
+            }
+        }
+        __syncthreads();
+        t = seg_start + j1;
+    }
+#ifdef TA_TUNING
+    if (blockIdx.y == 0 && threadIdx.x == 0 && blockIdx.x < 1024) {
+        unsigned long long *dbg = (unsigned long long *)(p.status + 16) + 4 * blockIdx.x;
+        unsigned xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        dbg[0] = tun_r0;
+        dbg[1] = __builtin_amdgcn_s_memrealtime();
+        dbg[2] = __builtin_readcyclecounter() - tun_c0;
+        dbg[3] = xcc;
+    }
+#endif
+}
+
 template <int NCW, int RB, int NT>
 static hipError_t launch_variant(const TAParams &p, hipStream_t stream)
 {
@@ -811,8 +1253,25 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
     case 256: {
         const size_t smem = PP_RAW * PP_RAW_BYTES + PP_VT * MF_TILE_BYTES + sizeof(unsigned long long) * TA_MAX_TREE +
                             16 + sizeof(int) * TA_MAX_TREE + sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
-        if (p.basic || smem > 160 * 1024 - 512)
+        if (p.basic == 1 || smem > 160 * 1024 - 512)
             return launch_variant<8, 1, 512>(p, stream);
+        if (p.basic == 2) {
+            static bool sp_attr_set[64] = {};
+            int d2 = 0;
+            if (hipGetDevice(&d2) != hipSuccess || d2 < 0 || d2 >= 64)
+                return hipErrorInvalidDevice;
+            if (!sp_attr_set[d2]) {
+                hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_sp_kernel,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+                if (e != hipSuccess)
+                    return e;
+                sp_attr_set[d2] = true;
+            }
+            const size_t sm2 = SP_AUX_OFF + sizeof(unsigned long long) * TA_MAX_TREE + 16 + sizeof(int) * TA_MAX_TREE +
+                               sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
+            hipLaunchKernelGGL(ta_mfma_sp_kernel, dim3(p.n_wg, p.n_rg), dim3(512), sm2, stream, p);
+            return hipGetLastError();
+        }
         static bool attr_set[64] = {};
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
