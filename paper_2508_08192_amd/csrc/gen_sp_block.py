@@ -29,7 +29,9 @@ overwrites a quarter of P is emitted only after the last MFMA reading that quart
 when it issues).  Each MFMA consumes one 16-byte LDS fragment read issued DIST steps earlier.
 
 Running softmax in base 2 with a lazily moved reference M (scaled units): M changes only when the tile maximum
-exceeds M + 4, so P <= 16 and the rescaling of O (done by the caller when alpha != 1) is rare.
+exceeds M + 4, so P <= 16 and the rescaling of O (done by the caller when alpha != 1) is rare.  Two row sums are
+kept: l of the fp32 probabilities (for the log-sum-exp) and l2 of their bf16 roundings, which are the weights the PV
+product actually applies -- normalising O by l2 makes the output an exact weighted mean of V rows.
 """
 O, SA, SB, P, Q, FR, TMP = 48, 112, 144, 176, 192, 224, 248
 NF = 6
@@ -79,6 +81,7 @@ def softmax_ops(sc):
     add("v_sub_f32 %%[al], %%[m], %s" % v(T_THR))
     add("v_exp_f32 %[al], %[al]")                            # alpha = 2^(M_old - M_new); 1 when unchanged
     add("v_mov_b32 %%[m], %s" % v(T_THR))
+    add("v_mov_b32 %s, 0x3f803f80" % v(T_SWAP))              # bf16 (1, 1): the maxima are done with this register
 
     def stage_a(g):                                          # x = 2^(s*c - M) for scores 4g..4g+3, in place
         xs = [sc + 4 * g + k for k in range(4)]
@@ -100,6 +103,9 @@ def softmax_ops(sc):
             add("v_add_f32 %s, %s, %s" % (v(PS1), v(PS1), v(xs[3])))
         add("v_cvt_pk_bf16_f32 %s, %s, %s" % (v(P + 2 * g), v(xs[0]), v(xs[1])), need)
         add("v_cvt_pk_bf16_f32 %s, %s, %s" % (v(P + 2 * g + 1), v(xs[2]), v(xs[3])), need)
+        # second row sum, of the rounded values: what the PV product really weighs V with
+        add("v_dot2_f32_bf16 %s, %s, %s, %s" % (v(TM_A), v(P + 2 * g), v(T_SWAP), "0" if g == 0 else v(TM_A)), need)
+        add("v_dot2_f32_bf16 %s, %s, %s, %s" % (v(TM_B), v(P + 2 * g + 1), v(T_SWAP), "0" if g == 0 else v(TM_B)), need)
 
     stage_a(0)
     for g in range(1, 8):
@@ -108,6 +114,9 @@ def softmax_ops(sc):
     stage_b(7)
     add("v_add_f32 %s, %s, %s" % (v(PS0), v(PS0), v(PS1)))
     add("v_fma_f32 %%[l], %%[l], %%[al], %s" % v(PS0))
+    add("s_nop 1")                                           # a dot result needs 3 wait states before another VALU reads it
+    add("v_add_f32 %s, %s, %s" % (v(TM_A), v(TM_A), v(TM_B)))
+    add("v_fma_f32 %%[l2], %%[l2], %%[al], %s" % v(TM_A))
     return ops
 
 
@@ -182,8 +191,8 @@ def block(name, cur, has_pv, has_s, has_sm):
         ins += ['[sva] "s"(sva)']
         sig += ["uint32_t sva"]
     if has_sm:
-        outs += ['[m] "+v"(m)', '[l] "+v"(l)', '[al] "=&v"(alpha)']
-        sig += ["float &m", "float &l", "float &alpha"]
+        outs += ['[m] "+v"(m)', '[l] "+v"(l)', '[l2] "+v"(l2)', '[al] "=&v"(alpha)']
+        sig += ["float &m", "float &l", "float &l2", "float &alpha"]
         ins += ['[c] "s"(c)']
         sig += ["float c"]
     if has_s:
@@ -192,54 +201,106 @@ def block(name, cur, has_pv, has_s, has_sm):
     return emit(name, sig, lines, outs, ins, ['"memory"', '"vcc"'])
 
 
-def fast_block(name, cur):
-    """Full block (PV, S, softmax) that also issues the cache loads of tile i+3 and re-lays V(i) out in place.
+# Scalar registers of the fast loop (clobbers): constants copied from the operands once, and temporaries.
+S_KG, S_VG = 60, 62                     # s[60:61], s[62:63]: cache base of this KV head (K, V)
+S_KSP, S_VSP, S_KSS, S_VSS = 64, 65, 66, 67      # page and slot strides in bytes
+S_PSHIFT, S_PMASK, S_PCADJ, S_C = 68, 69, 70, 71  # page shift/mask, LDS address of the page-id cache, softmax scale
+S_KDST, S_VDST, S_LO, S_HI = 72, 73, 74, 75       # LDS targets of this wave's loads; v_perm selectors
+ST = 80                                 # s80..s85 temporaries, s[86:87] K tile base, s[88:89] V tile base
 
-    All LDS traffic of the block is in one in-order queue, so every consumer waits with the exact count of
-    younger operations that may still be outstanding.
-    """
+
+def sg(n):
+    return "s%d" % n
+
+
+def fast_step_items(cur, label):
+    """One tile of the steady state as a list of instructions (no waits yet): the full block (PV, S, softmax)
+    plus everything else the tile needs -- page lookup and addresses of tile i+3, its four cache loads, the
+    in-place re-layout of V(i), ring bookkeeping, the (rare) rescaling of O, and the closing barrier."""
     sc, sn = (SA, SB) if cur == "A" else (SB, SA)
     steps = mfma_steps(True, True, sn)
     n = len(steps)
-    sm = softmax_ops(sc)
+    sm = [(t.replace("%[c]", sg(S_C)), need) for t, need in softmax_ops(sc)]
     rx = lambda k: RL + 2 * k          # row k, columns 0..1 (dword x)
     ry = lambda k: RL + 2 * k + 1      # row k, columns 2..3 (dword y)
     t0, t1 = RL + 8, RL + 9
-    # auxiliary stream: (text, kind, lds id or None, ids it needs, PV MFMA it must follow)
-    aux = []
-    dma = ["s_mov_b32 m0, %[kdst]", "s_nop 0", "global_load_lds_dwordx4 %[koff0], %[kb]",
-           "s_add_u32 m0, %[kdst], 0x400", "s_nop 0", "global_load_lds_dwordx4 %[koff1], %[kb]",
-           "s_mov_b32 m0, %[vdst]", "s_nop 0", "global_load_lds_dwordx4 %[voff0], %[vb]",
-           "s_add_u32 m0, %[vdst], 0x400", "s_nop 0", "global_load_lds_dwordx4 %[voff1], %[vb]"]
+    page_a = [  # page id of the tile to load: LDS read now, used a few MFMAs later; slot part of the addresses
+        "s_lshr_b32 %s, %%[pos], %s" % (sg(ST), sg(S_PSHIFT)),
+        "s_lshl_b32 %s, %s, 2" % (sg(ST), sg(ST)),
+        "s_add_u32 %s, %s, %s" % (sg(ST), sg(ST), sg(S_PCADJ)),
+        "v_mov_b32 %s, %s" % (v(t0), sg(ST)),
+        ("ds_read_b32 %s, %s" % (v(t1), v(t0)), ("p", 0)),
+        "s_and_b32 %s, %%[pos], %s" % (sg(ST + 1), sg(S_PMASK)),
+        "s_mul_i32 %s, %s, %s" % (sg(ST + 2), sg(ST + 1), sg(S_KSS)),
+        "s_mul_hi_u32 %s, %s, %s" % (sg(ST + 3), sg(ST + 1), sg(S_KSS)),
+        "s_mul_i32 %s, %s, %s" % (sg(ST + 4), sg(ST + 1), sg(S_VSS)),
+        "s_mul_hi_u32 %s, %s, %s" % (sg(ST + 5), sg(ST + 1), sg(S_VSS)),
+    ]
+    page_b = [
+        ("v_readfirstlane_b32 %s, %s" % (sg(ST), v(t1)), None, [("p", 0)]),
+        "s_nop 3",
+        "s_mul_i32 s86, %s, %s" % (sg(ST), sg(S_KSP)), "s_mul_hi_u32 s87, %s, %s" % (sg(ST), sg(S_KSP)),
+        "s_add_u32 s86, s86, %s" % sg(ST + 2), "s_addc_u32 s87, s87, %s" % sg(ST + 3),
+        "s_add_u32 s86, s86, %s" % sg(S_KG), "s_addc_u32 s87, s87, %s" % sg(S_KG + 1),
+        "s_mul_i32 s88, %s, %s" % (sg(ST), sg(S_VSP)), "s_mul_hi_u32 s89, %s, %s" % (sg(ST), sg(S_VSP)),
+        "s_add_u32 s88, s88, %s" % sg(ST + 4), "s_addc_u32 s89, s89, %s" % sg(ST + 5),
+        "s_add_u32 s88, s88, %s" % sg(S_VG), "s_addc_u32 s89, s89, %s" % sg(S_VG + 1),
+    ]
+    dma = [["s_add_u32 m0, %s, %%[ik]" % sg(S_KDST), "s_nop 0", "global_load_lds_dwordx4 %[koff0], s[86:87]"],
+           ["s_add_u32 m0, m0, 0x400", "s_nop 0", "global_load_lds_dwordx4 %[koff1], s[86:87]"],
+           ["s_add_u32 m0, %s, %%[iv]" % sg(S_VDST), "s_nop 0", "global_load_lds_dwordx4 %[voff0], s[88:89]"],
+           ["s_add_u32 m0, m0, 0x400", "s_nop 0", "global_load_lds_dwordx4 %[voff1], s[88:89]"]]
+    def ring(reg, wrap):
+        return ["s_add_u32 %s, %s, 0x4000" % (reg, reg), "s_cmp_eq_u32 %s, 0x%x" % (reg, wrap),
+                "s_cselect_b32 %s, 0, %s" % (reg, reg)]
+    rings = ring("%[ik]", 0xc000) + ring("%[iv]", 0x14000) + ring("%[kn]", 0xc000) + ["s_mov_b32 %[vp], %[vc]"] + \
+            ring("%[vc]", 0x14000) + ["s_add_u32 %[pos], %[pos], 64"]
+
+    def item(x, mf=-1):
+        if isinstance(x, tuple):
+            d = dict(t=x[0], mf=mf)
+            if x[1]:
+                d["lds"] = x[1]
+            if len(x) > 2:
+                d["needs"] = x[2]
+            return d
+        return dict(t=x, mf=mf)
+
+    aux = [item(x) for x in page_a]
     for t, need in sm[:12]:
         aux.append(dict(t=t, mf=need))
-    rl_reads = [dict(t="v_add_u32 %s, %%[srl], %s" % (v(t1), v(RD_BASE))),
-                dict(t="v_add_u32 %s, %%[srl], %s" % (v(WRT), v(WR_BASE)))]
+    aux += [item(x) for x in page_b]
+    rl_reads = [dict(t="v_add_u32 %s, %%[vc], %s" % (v(t1), v(RD_BASE))),
+                dict(t="v_add_u32 %s, %%[vc], %s" % (v(WRT), v(WR_BASE)))]
     for k in range(4):
         rl_reads.append(dict(t="ds_read_b64 %s, %s offset:%d" % (vr(rx(k), 2), v(t1), 256 * k), lds=("r", k)))
+    slo, shi = sg(S_LO), sg(S_HI)
     relay = [
-        dict(t="v_perm_b32 %s, %s, %s, %%[slo]" % (v(t0), v(rx(1)), v(rx(0))), needs=[("r", 0), ("r", 1)]),
-        dict(t="v_perm_b32 %s, %s, %s, %%[slo]" % (v(t1), v(rx(3)), v(rx(2))), needs=[("r", 2), ("r", 3)]),
+        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(t0), v(rx(1)), v(rx(0)), slo), needs=[("r", 0), ("r", 1)]),
+        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(t1), v(rx(3)), v(rx(2)), slo), needs=[("r", 2), ("r", 3)]),
         dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(WRT), v(t0), v(t1)), lds=("w", 0)),
-        dict(t="v_perm_b32 %s, %s, %s, %%[shi]" % (v(rx(0)), v(rx(1)), v(rx(0)))),
-        dict(t="v_perm_b32 %s, %s, %s, %%[shi]" % (v(rx(2)), v(rx(3)), v(rx(2)))),
+        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(rx(0)), v(rx(1)), v(rx(0)), shi)),
+        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(rx(2)), v(rx(3)), v(rx(2)), shi)),
         dict(t="v_xor_b32 %s, 16, %s" % (v(rx(1)), v(WRT))),
         dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(rx(1)), v(rx(0)), v(rx(2))), lds=("w", 1)),
-        dict(t="v_perm_b32 %s, %s, %s, %%[slo]" % (v(t0), v(ry(1)), v(ry(0)))),
-        dict(t="v_perm_b32 %s, %s, %s, %%[slo]" % (v(t1), v(ry(3)), v(ry(2)))),
+        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(t0), v(ry(1)), v(ry(0)), slo)),
+        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(t1), v(ry(3)), v(ry(2)), slo)),
         dict(t="v_xor_b32 %s, 32, %s" % (v(rx(3)), v(WRT))),
         dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(rx(3)), v(t0), v(t1)), lds=("w", 2)),
-        dict(t="v_perm_b32 %s, %s, %s, %%[shi]" % (v(ry(0)), v(ry(1)), v(ry(0)))),
-        dict(t="v_perm_b32 %s, %s, %s, %%[shi]" % (v(ry(2)), v(ry(3)), v(ry(2)))),
+        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(ry(0)), v(ry(1)), v(ry(0)), shi)),
+        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(ry(2)), v(ry(3)), v(ry(2)), shi)),
         dict(t="v_xor_b32 %s, 48, %s" % (v(ry(1)), v(WRT))),
         dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(ry(1)), v(ry(0)), v(ry(2))), lds=("w", 3)),
     ]
     rest = sm[12:]
-    # The re-layout shares v[38:41] with the V fragment addresses, so it starts once the last PV read is out
-    # (MFMA 11 issued); then one of its instructions after every fourth softmax instruction.
-    ri, started = 0, False
+    # Loads of tile i+3: one every 20 softmax instructions from the 10th on.  The re-layout shares v[38:47]
+    # with the V fragment addresses and the page lookup, so it starts once the last PV read is out (MFMA 11).
+    ri, started, di = 0, False, 0
     for j, (t, need) in enumerate(rest):
         aux.append(dict(t=t, mf=need))
+        if j >= 10 and (j - 10) % 20 == 0 and di < 4:
+            aux += [dict(t=x) for x in dma[di]]
+            di += 1
         if j >= 50 and not started:
             for it in rl_reads:
                 aux.append(dict(it, mf=11))
@@ -247,18 +308,20 @@ def fast_block(name, cur):
         elif started and (j - 50) % 4 == 0 and ri < len(relay):
             aux.append(dict(relay[ri], mf=11))
             ri += 1
-    assert started
+    assert started and di == 4
     for it in relay[ri:]:
         aux.append(dict(it, mf=11))
+    aux += [dict(t=x) for x in rings]
 
-    seq = [dict(t="s_nop 7")] + [dict(t=t) for t in address_setup(True, True)]
+    seq = [dict(t="s_nop 3")] + [dict(t=t.replace("%[sva]", "%[vp]").replace("%[ska]", "%[kn]"))
+                                 for t in address_setup(True, True)]
     def put_reads(r):
         for x in steps[r][0]:
             seq.append(dict(t=x.replace("{f}", frag(r)), lds=("f", r) if x.startswith("ds_read") else None))
     for r in range(DIST):
         put_reads(r)
     vi = 0
-    pre = 12
+    pre = 16
     while vi < pre:
         seq.append(aux[vi])
         vi += 1
@@ -266,9 +329,6 @@ def fast_block(name, cur):
         if r + DIST < n:
             put_reads(r + DIST)
         seq.append(dict(t=steps[r][1].replace("{f}", frag(r)), needs=[("f", r)]))
-        if r % 8 == 1:
-            for t in dma[3 * (r // 8):3 * (r // 8) + 3]:
-                seq.append(dict(t=t))
         target = pre + (len(aux) - pre) * (r + 1) // n
         while vi < len(aux) and vi < target:
             need = aux[vi].get("mf", -1)
@@ -277,7 +337,25 @@ def fast_block(name, cur):
             seq.append(aux[vi])
             vi += 1
     seq += aux[vi:]
-    # wait insertion
+    # O still holds sums relative to the old reference when it moved (rare): rescale, then close the tile
+    seq += [dict(t="v_cmp_neq_f32 vcc, 1.0, %[al]"), dict(t="s_cbranch_vccz %df" % label), dict(t="s_nop 15"),
+            dict(t="s_nop 7")]
+    seq += [dict(t="v_mul_f32 %s, %%[al], %s" % (v(O + k), v(O + k))) for k in range(64)]
+    seq += [dict(t="s_nop 3"), dict(t="%d:" % label), dict(t="s_waitcnt vmcnt(4)"),
+            dict(t="s_waitcnt lgkmcnt(0)", flush=True), dict(t="s_barrier")]
+    return seq
+
+
+def fast_loop(name):
+    """`cnt` pairs of steady-state tiles (buffer A current, then buffer B) as one asm statement with its own loop,
+    so that the scalar bookkeeping of a tile is issued in the shadow of its matrix and vector work."""
+    head = ["s_mov_b64 s[%d:%d], %%[kg]" % (S_KG, S_KG + 1), "s_mov_b64 s[%d:%d], %%[vg]" % (S_VG, S_VG + 1),
+            "s_mov_b64 s[%d:%d], %%[sp]" % (S_KSP, S_VSP), "s_mov_b64 s[%d:%d], %%[ss]" % (S_KSS, S_VSS),
+            "s_mov_b64 s[%d:%d], %%[pp]" % (S_PSHIFT, S_PMASK), "s_mov_b64 s[%d:%d], %%[pc]" % (S_PCADJ, S_C),
+            "s_mov_b64 s[%d:%d], %%[dst]" % (S_KDST, S_VDST), "s_mov_b32 %s, 0x05040100" % sg(S_LO),
+            "s_mov_b32 %s, 0x07060302" % sg(S_HI), "1:"]
+    seq = [dict(t=t) for t in head] + fast_step_items("A", 2) + fast_step_items("B", 3)
+    seq += [dict(t="s_sub_u32 %[cnt], %[cnt], 1"), dict(t="s_cmp_lg_u32 %[cnt], 0"), dict(t="s_cbranch_scc1 1b")]
     lines, issued, done = [], [], -1
     for it in seq:
         needs = it.get("needs")
@@ -289,18 +367,21 @@ def fast_block(name, cur):
         lines.append(it["t"])
         if it.get("lds"):
             issued.append(it["lds"])
-    sig = ["uint32_t sva", "float &m", "float &l", "float &alpha", "float c", "uint32_t ska", "const void *kb",
-           "const void *vb", "uint32_t kdst", "uint32_t vdst", "uint32_t koff0", "uint32_t koff1", "uint32_t voff0",
-           "uint32_t voff1", "uint32_t srl"]
-    outs = ['[m] "+v"(m)', '[l] "+v"(l)', '[al] "=&v"(alpha)']
-    ins = ['[sva] "s"(sva)', '[c] "s"(c)', '[ska] "s"(ska)', '[kb] "s"(kb)', '[vb] "s"(vb)',
-           '[kdst] "s"(kdst)', '[vdst] "s"(vdst)', '[koff0] "v"(koff0)', '[koff1] "v"(koff1)', '[voff0] "v"(voff0)',
-           '[voff1] "v"(voff1)', '[srl] "s"(srl)', '[slo] "s"(0x05040100u)', '[shi] "s"(0x07060302u)']
-    return emit(name, sig, lines, outs, ins, ['"memory"', '"vcc"', '"scc"'])
+        if it.get("flush"):
+            issued, done = [], -1
+    sig = ["float &m", "float &l", "float &l2", "uint32_t &ik", "uint32_t &iv", "uint32_t &kn", "uint32_t &vp", "uint32_t &vc",
+           "uint32_t &pos", "uint32_t &cnt", "uint64_t kg", "uint64_t vg", "uint64_t sp", "uint64_t ss", "uint64_t pp",
+           "uint64_t pc", "uint64_t dst", "uint32_t koff0", "uint32_t koff1", "uint32_t voff0", "uint32_t voff1"]
+    outs = ['[m] "+v"(m)', '[l] "+v"(l)', '[l2] "+v"(l2)', '[al] "=&v"(alpha)'] + \
+           ['[%s] "+s"(%s)' % (x, x) for x in ("ik", "iv", "kn", "vp", "vc", "pos", "cnt")]
+    ins = ['[%s] "s"(%s)' % (x, x) for x in ("kg", "vg", "sp", "ss", "pp", "pc", "dst")] + \
+          ['[%s] "v"(%s)' % (x, x) for x in ("koff0", "koff1", "voff0", "voff1")]
+    clob = ['"memory"', '"vcc"', '"scc"'] + ['"s%d"' % i for i in list(range(60, 76)) + list(range(80, 90))]
+    return emit(name, sig, lines, outs, ins, clob, pre="    float alpha;")
 
 
-def emit(name, sig, lines, outs, ins, clob):
-    code = ["__device__ __forceinline__ void %s(%s)" % (name, ", ".join(sig)), "{", "    asm volatile("]
+def emit(name, sig, lines, outs, ins, clob, pre=None):
+    code = ["__device__ __forceinline__ void %s(%s)" % (name, ", ".join(sig)), "{"] + ([pre] if pre else []) + ["    asm volatile("]
     for ln in lines:
         code.append('        "%s\\n\\t"' % ln)
     code.append("        : " + ", ".join(outs))
@@ -358,8 +439,6 @@ if __name__ == "__main__":
     print()
     print(block("sp_pv", "A", True, False, False))               # drain: the last tile's P . V
     print()
-    print(fast_block("sp_fast_A", "A"))
-    print()
-    print(fast_block("sp_fast_B", "B"))
+    print(fast_loop("sp_fast_loop"))
     print()
     print(helpers())

@@ -119,7 +119,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     size_t user_ws_bytes = 0;
     if (opts) {
         if (opts->reserved != 0 || opts->num_splits < 0 || opts->kernel < TA_KERNEL_AUTO ||
-            opts->kernel > TA_KERNEL_MFMA_BASIC + 1)
+            opts->kernel > TA_KERNEL_MFMA_BASIC)
             return TA_ERR_OPTS;
         kernel = opts->kernel;
         num_splits = opts->num_splits;
@@ -143,7 +143,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
                          ((uintptr_t)q->data % 16) == 0 && ((uintptr_t)k->data % 16) == 0 &&
                          ((uintptr_t)v->data % 16) == 0 && k->stride[0] < INT32_MAX && k->stride[2] < INT32_MAX &&
                          v->stride[0] < INT32_MAX && v->stride[2] < INT32_MAX;
-    const int basic = kernel == TA_KERNEL_MFMA_BASIC ? 1 : (kernel == TA_KERNEL_MFMA_BASIC + 1 ? 2 : 0);
+    const int basic = kernel == TA_KERNEL_MFMA_BASIC ? 1 : 0;
     if (basic)
         kernel = TA_KERNEL_MFMA;
     if (kernel == TA_KERNEL_MFMA && !mfma_ok)

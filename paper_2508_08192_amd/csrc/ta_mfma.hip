@@ -444,25 +444,6 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// 256-row variant: 8 waves, two per SIMD, software-pipelined and phase-skewed.
-//
-// Per tile a wave runs a matrix phase M(i) = { O^T += V^T(i-1) . P^T(i-1) ;  S^T(i) = K(i) . Q^T } and a
-// vector phase SM(i) = running-softmax bookkeeping of tile i.  Phases end in workgroup barriers and
-// waves 4..7 run one phase behind waves 0..3, so on every SIMD one wave feeds the matrix pipe while
-// its partner runs the vector ALU.  K and V tiles travel global -> LDS without touching registers
-// (global_load_lds_dwordx4, three raw tiles in the ring); V is then re-laid out token-minor by waves
-// 0..3 (LDS -> registers -> LDS) one phase pair before its use.
-//
-// The matrix phase is written in inline assembly: 32 LDS fragment reads feed 32 MFMAs one to one,
-// each read issued three steps ahead of its MFMA, with explicit lgkmcnt waits.  The cache loads of the
-// loop are issued from assembly too, so their vmcnt bookkeeping is exact: at the end of M(i) exactly
-// the four loads of tile i+2 may still be in flight.
-// ---------------------------------------------------------------------------------------------
-#define PP_RAW 3                                  // raw K|V tiles in LDS (32 KB each)
-#define PP_VT 2                                   // token-minor V tiles (16 KB each)
-#define PP_RAW_BYTES (2 * MF_TILE_BYTES)
-#define PP_VT_OFF (PP_RAW * PP_RAW_BYTES)
 #define PP_PAGES 2048                             // page ids cached in LDS per span of tiles
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -478,308 +459,6 @@ template <int N>
 __device__ __forceinline__ void vm_wait()
 {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-#include "ta_pp_phase.inc"
-
-__device__ __forceinline__ void softmax_tile_pp(const f32x16 (&s)[2], float c, float &m_run, float &l_run,
-                                                f32x16 (&acc_o)[4], u32x4 (&pb)[4])
-{
-    float tmax = fmaxf(s[0][0], s[1][0]);
-#pragma unroll
-    for (int i = 1; i < 16; ++i)
-        tmax = max3(tmax, s[0][i], s[1][i]);
-    tmax = half_swap_max(tmax);
-    const float m_new = fmaxf(m_run, tmax);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-    const float neg_mc = -m_new * c;
-    m_run = m_new;
-    float psum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
-        float e[8];
-#pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-            e[jj] = __builtin_amdgcn_exp2f(fmaf(s[kb >> 1][8 * (kb & 1) + jj], c, neg_mc));
-            psum += e[jj];
-        }
-        pb[kb] = (u32x4){pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3]), pack_bf16(e[4], e[5]), pack_bf16(e[6], e[7])};
-    }
-    l_run = l_run * alpha + psum;
-    if (__any(alpha != 1.0f)) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                acc_o[db][i] *= alpha;
-    }
-}
-
-__global__ __launch_bounds__(512) void ta_mfma_pp_kernel(TAParams p)
-{
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    char *raw = smem;                                                     // [PP_RAW][K raw 16 KB | V raw 16 KB]
-    char *vtr = smem + PP_VT_OFF;                                         // [PP_VT][16 KB]
-    unsigned long long *masks = (unsigned long long *)(vtr + PP_VT * MF_TILE_BYTES);
-    int *flag = (int *)(masks + TA_MAX_TREE);
-    int *par_s = flag + 4;                                                // [TA_MAX_TREE]
-    int *pcache = par_s + TA_MAX_TREE;                                    // [PP_PAGES] page ids of the current span
-    int *cum = pcache + PP_PAGES;
-    const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
-
-    ta_build_schedule(p, cum);
-    const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
-    const int share = ta_share(p, total);
-    const int w = blockIdx.x, rg = blockIdx.y;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int r32 = lane & 31, hf = lane >> 5;
-    const int grp = wave >> 2;                        // 0: leading waves, 1: waves one phase behind
-    int t = w * share;
-    const int t_end = min(total, t + share);
-    const int rows_here = min(p.rows_grp, p.rows - rg * p.rows_grp);
-    const float c = p.scale_log2e;
-    const bool paged = p.page_table != nullptr;
-    // fragment offsets of this lane inside a tile
-    // K fragment of step kk sits at kbase + (ka ^ 32kk): row r32, 16-byte slot (2kk + hf) ^ (r32 & 15)
-    const uint32_t ka = (uint32_t)(r32 * 256 + ((hf ^ (r32 & 15)) << 4));
-    uint32_t kbase, vaddr[4];
-    auto reset_addresses = [&]() {                    // tile 0 of an item: raw buffer 0; "tile -1": V buffer 1
-        kbase = lds0;
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            const int d = db * 32 + r32;
-            vaddr[db] = lds0 + PP_VT_OFF + (PP_VT - 1) * MF_TILE_BYTES + ((hf * 128 + (d ^ ((d >> 4) & 7))) << 4);
-        }
-    };
-    // cache-load role of this lane: rows drow and drow+4 of every tile, 16-byte slot dslot
-    const int drow = wave * 8 + (lane >> 4), dslot = lane & 15;
-    const int kc0 = (dslot ^ (drow & 15)) * 8, kc1 = (dslot ^ ((drow + 4) & 15)) * 8;      // swizzled K chunks
-    // re-layout role (waves 0..3): quad tq, chunk tc of the V tile
-    const int tq = (tid & 255) >> 4, tc = tid & 15;
-
-    while (t < t_end) {
-        // the schedule comes out of LDS, which the compiler treats as lane-varying: pin it to SGPRs
-        const int b = __builtin_amdgcn_readfirstlane(ta_find_request(p, cum, t));
-        const int n_b = __builtin_amdgcn_readfirstlane(cum[b + 1] - cum[b]);
-        const int cum_b = __builtin_amdgcn_readfirstlane(cum[b]);
-        const int g = (t - p.Hkv * cum_b) / n_b;
-        const int seg_start = p.Hkv * cum_b + g * n_b;
-        const int j0 = t - seg_start;
-        const int j1 = min(n_b, t_end - seg_start);
-        const int n = j1 - j0;
-        const int slot = w + b * p.Hkv + g;
-        const int L = __builtin_amdgcn_readfirstlane(p.seq_lens[(int64_t)b * p.sl_s]);
-        bool poison = !ta_request_ok(p, L);
-        if (poison && tid == 0)
-            atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
-        const bool has_tree_tile = (j1 == n_b);
-        if (has_tree_tile && !poison) {
-            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag, par_s)) {
-                poison = true;
-                if (tid == 0)
-                    atomicOr(p.status, TA_STATUS_BAD_PARENT);
-            }
-        }
-        const int row = wave * 32 + r32;
-        const int R = rg * p.rows_grp + row;
-        const bool row_ok = row < rows_here;
-        const int node = row_ok ? R / p.G : 0;
-
-        if (poison) {
-            if (row_ok) {
-                const int64_t wrow = ta_ws_row(p, slot, rg, row);
-                for (int d = hf * 64; d < hf * 64 + 64; d += 4)
-                    *(float4 *)(p.ws_o + wrow * MF_D + d) = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (hf == 0)
-                    p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
-            }
-            __syncthreads();
-            t = seg_start + j1;
-            continue;
-        }
-
-        u32x4 qf[8];
-        if (row_ok) {
-            const uint16_t *qp = (const uint16_t *)p.q + (int64_t)b * p.q_sb + (int64_t)node * p.q_st +
-                                 (int64_t)(g * p.G + R % p.G) * p.q_sh + hf * 8;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                qf[kk] = *(const u32x4 *)(qp + kk * 16);
-        } else {
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                qf[kk] = (u32x4){0u, 0u, 0u, 0u};
-        }
-        // pin the arrival of Q here, before any load the compiler does not see is in flight
-        asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]),
-                     "+v"(qf[7]));
-        const unsigned long long tree_mask = (has_tree_tile && row_ok) ? masks[node] : ~0ull;
-        const uint16_t *kgp = (const uint16_t *)p.k + (int64_t)g * p.k_sh;
-        const uint16_t *vgp = (const uint16_t *)p.v + (int64_t)g * p.v_sh + dslot * 8;
-        const uint32_t ksp = (uint32_t)p.k_sp, kss = (uint32_t)p.k_ss, vsp = (uint32_t)p.v_sp, vss = (uint32_t)p.v_ss;
-
-        // tile ti of this item: first logical position and number of tokens it holds
-        auto tile_pos0 = [&](int ti) { return (j0 + ti == n_b - 1) ? L : (j0 + ti) * TA_TILE; };
-        auto tile_count = [&](int ti) { return (j0 + ti == n_b - 1) ? p.T : min(TA_TILE, L - (j0 + ti) * TA_TILE); };
-        // The item is walked in spans of tiles whose page ids fit the LDS cache (one span unless the pages are
-        // tiny and the share very long); inside a span no page-table load is needed.
-        int span_first_page = 0;
-        const int span_tiles = !paged ? n
-                               : (p.ps_shift >= 6 ? PP_PAGES - 2 : max(1, ((PP_PAGES - 2) << p.ps_shift) / TA_TILE));
-        // Cache loads of tile ti (absolute index in the item) into raw buffer `buf`; rows past the tile's end
-        // re-read its first token.
-        auto issue_dma = [&](int ti, int buf) {
-            const int pos0 = tile_pos0(ti), cnt = tile_count(ti);
-            const int pa = pos0 + (drow < cnt ? drow : 0), pb_ = pos0 + (drow + 4 < cnt ? drow + 4 : 0);
-            uint32_t pg0 = (uint32_t)b, pg1 = (uint32_t)b, sa = (uint32_t)pa, sb = (uint32_t)pb_;
-            if (paged) {
-                pg0 = (uint32_t)pcache[(pa >> p.ps_shift) - span_first_page];
-                pg1 = (uint32_t)pcache[(pb_ >> p.ps_shift) - span_first_page];
-                sa = (uint32_t)(pa & (p.ps - 1));
-                sb = (uint32_t)(pb_ & (p.ps - 1));
-            }
-            const uint32_t kdst = lds0 + buf * PP_RAW_BYTES + wave * 2048;
-            const uint32_t vdst = kdst + MF_TILE_BYTES;
-            dma16(kgp + (uint64_t)pg0 * ksp + sa * kss + kc0, kdst);
-            dma16(kgp + (uint64_t)pg1 * ksp + sb * kss + kc1, kdst + 1024);
-            dma16(vgp + (uint64_t)pg0 * vsp + sa * vss, vdst);
-            dma16(vgp + (uint64_t)pg1 * vsp + sb * vss, vdst + 1024);
-        };
-        // waves 0..3: V tile ti from the raw ring into token-minor form (absent tokens become zeros)
-        auto relayout_v = [&](int ti, int i) {
-            const char *vr = raw + (i % PP_RAW) * PP_RAW_BYTES + MF_TILE_BYTES;
-            const int cnt = tile_count(ti);
-            Unit u;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                u.r[k] = *(const uint4 *)(vr + (tq * 4 + k) * 256 + tc * 16);
-                if (tq * 4 + k >= cnt)
-                    u.r[k] = make_uint4(0, 0, 0, 0);
-            }
-            store_v_unit(vtr + (i % PP_VT) * MF_TILE_BYTES, u, tq, tc);
-        };
-
-        f32x16 acc_o[4], acc_s[2];
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-                acc_o[db][e] = 0.f;
-        float m_run = -INFINITY, l_run = 0.f;
-        u32x4 pb[4];
-        // after M(i): K addresses move to raw buffer (i+1) % PP_RAW, V addresses to buffer i % PP_VT
-        auto advance_addresses = [&](int i) {
-            const int dk = ((i + 1) % PP_RAW == 0) ? -(PP_RAW - 1) * PP_RAW_BYTES : PP_RAW_BYTES;
-            const int dv = (i % PP_VT == 0) ? -(PP_VT - 1) * MF_TILE_BYTES : MF_TILE_BYTES;
-            kbase += dk;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-                vaddr[db] += dv;
-        };
-
-        for (int s0 = 0; s0 < n; s0 += span_tiles) {
-            const int ns = min(span_tiles, n - s0);            // tiles s0 .. s0+ns-1 of the item; i is span-local
-            if (paged) {
-                span_first_page = tile_pos0(s0) >> p.ps_shift;
-                const int last_page = (tile_pos0(s0 + ns - 1) + tile_count(s0 + ns - 1) - 1) >> p.ps_shift;
-                for (int k = tid; k <= last_page - span_first_page; k += 512)
-                    pcache[k] = p.page_table[(int64_t)b * p.pt_sb + span_first_page + k];
-                __syncthreads();
-            }
-            reset_addresses();
-
-            // ---- prologue: tiles 0 and 1 of the span on their way
-            issue_dma(s0, 0);
-            if (ns > 1) {
-                issue_dma(s0 + 1, 1);
-                vm_wait<4>();                                  // tile 0 has landed (tile 1 may still fly)
-            } else {
-                vm_wait<0>();
-            }
-            lds_barrier();
-            if (grp == 1) {
-                if (!TA_OFF(8))
-                    relayout_v(s0, 0);                         // the trailing waves are idle in this slot
-                if (!TA_OFF(16))
-                    lds_barrier();
-            }
-
-            // end of M(i).  Tile i+1 must be in LDS before anyone starts M(i+1): the trailing waves, whose
-            // M(i) ends at that point, wait here for their share of it (nothing younger is in flight).
-            auto m_tail = [&](int i) {
-                advance_addresses(i);
-                if (grp == 1)
-                    vm_wait<0>();
-                lds_barrier();
-            };
-            // SM(i): first the cache loads of tile i+2 (their latency hides behind the softmax and the next
-            // matrix phase), then the running softmax; the trailing waves also re-lay V of tile i+1 out.
-            // The leading waves end SM(i) where the trailing ones end M(i): they wait for tile i+1 here,
-            // leaving only the four loads of tile i+2 in flight.
-            auto sm_phase = [&](int i) {
-                const bool issued = i + 2 < ns && !TA_OFF(4);
-                if (issued)
-                    issue_dma(s0 + i + 2, (i + 2) % PP_RAW);
-                const int j = j0 + s0 + i;
-                const bool tree_tile = (j == n_b - 1);
-                const int rem = L - j * TA_TILE;
-                if (!TA_OFF(1)) {
-                    if (tree_tile || rem < TA_TILE)
-                        mask_scores(acc_s, (tree_tile ? tree_mask : ((1ull << rem) - 1ull)) >> (4 * hf));
-                    softmax_tile_pp(acc_s, c, m_run, l_run, acc_o, pb);
-                }
-                if (grp == 1) {
-                    if (i + 1 < ns && !TA_OFF(8))
-                        relayout_v(s0 + i + 1, i + 1);
-                } else if (issued) {
-                    vm_wait<4>();
-                } else {
-                    vm_wait<0>();
-                }
-                lds_barrier();
-            };
-
-            pp_phase_s(acc_s, qf, ka, kbase);
-            m_tail(0);
-            sm_phase(0);
-#pragma unroll 1
-            for (int i = 1; i < ns; ++i) {
-                if (!TA_OFF(2))
-                    pp_phase_pv_s(acc_o, pb, vaddr, acc_s, qf, ka, kbase);
-                m_tail(i);
-                sm_phase(i);
-            }
-            pp_phase_pv(acc_o, pb, vaddr);
-            lds_barrier();
-            lds_barrier();
-            if (grp == 0 && !TA_OFF(16))
-                lds_barrier();
-        }
-
-        if (row_ok) {
-            const int64_t wrow = ta_ws_row(p, slot, rg, row);
-            const float l_tot = l_run + __shfl_xor(l_run, 32, TA_WAVE);
-            const float inv = 1.f / l_tot;
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    float4 o;
-                    o.x = acc_o[db][4 * i4 + 0] * inv;
-                    o.y = acc_o[db][4 * i4 + 1] * inv;
-                    o.z = acc_o[db][4 * i4 + 2] * inv;
-                    o.w = acc_o[db][4 * i4 + 3] * inv;
-                    *(float4 *)(p.ws_o + wrow * MF_D + db * 32 + 8 * i4 + 4 * hf) = o;
-                }
-            }
-            if (hf == 0)
-                p.ws_lse[wrow] = m_run * c + log2f(l_tot);
-        }
-        __syncthreads();
-        t = seg_start + j1;
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -834,6 +513,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
 
 #ifdef TA_TUNING
     const unsigned long long tun_c0 = __builtin_readcyclecounter(), tun_r0 = __builtin_amdgcn_s_memrealtime();
+    unsigned long long tun_blk = 0, tun_n = 0;
 #endif
     ta_build_schedule(p, cum);
     const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
@@ -947,7 +627,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         const uint16_t *vgp = (const uint16_t *)p.v + (int64_t)g * p.v_sh;
 
         // tile ti of this item: first logical position and number of tokens it holds
-        auto tile_pos0 = [&](int ti) { return TA_OFF(32) ? 0 : ((j0 + ti == n_b - 1) ? L : (j0 + ti) * TA_TILE); };
+        auto tile_pos0 = [&](int ti) { return (j0 + ti == n_b - 1) ? L : (j0 + ti) * TA_TILE; };
         auto tile_count = [&](int ti) { return (j0 + ti == n_b - 1) ? p.T : min(TA_TILE, L - (j0 + ti) * TA_TILE); };
         // bits of the tokens tile ti really holds for this lane's half, or all ones when nothing is to mask
         auto tile_mask = [&](int ti) -> unsigned long long {
@@ -1041,7 +721,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         };
 
         sp_zero_o();
-        float m_run = -INFINITY, l_run = 0.f;
+        float m_run = -INFINITY, l_run = 0.f, l2_run = 0.f;   // l2: sum of the bf16-rounded probabilities
 
         for (int s0 = 0; s0 < n; s0 += span_tiles) {
             const int ns = min(span_tiles, n - s0);            // tiles s0 .. s0+ns-1 of the item; i is span-local
@@ -1050,6 +730,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 const int last_page = (tile_pos0(s0 + ns - 1) + tile_count(s0 + ns - 1) - 1) >> p.ps_shift;
                 for (int k = tid; k <= last_page - span_first_page; k += 512)
                     pcache[k] = p.page_table[(int64_t)b * p.pt_sb + span_first_page + k];
+                __syncthreads();
+            } else {
+                if (tid == 0)
+                    pcache[0] = b;                             // the steady-state loop sees one page: the request's cache
                 __syncthreads();
             }
             // ring positions: next slots to load into, K slot of tile i+1, V slots of tiles i and i-1
@@ -1085,19 +769,19 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 } else if constexpr (A) {
                     if (i == 0) {
                         if (has_next)
-                            sp_head_A(m_run, l_run, alpha, c, ska);
+                            sp_head_A(m_run, l_run, l2_run, alpha, c, ska);
                         else
-                            sp_only_A(m_run, l_run, alpha, c);
+                            sp_only_A(m_run, l_run, l2_run, alpha, c);
                     } else if (has_next) {
-                        sp_full_A(sva, m_run, l_run, alpha, c, ska);
+                        sp_full_A(sva, m_run, l_run, l2_run, alpha, c, ska);
                     } else {
-                        sp_last_A(sva, m_run, l_run, alpha, c);
+                        sp_last_A(sva, m_run, l_run, l2_run, alpha, c);
                     }
                 } else {
                     if (has_next)
-                        sp_full_B(sva, m_run, l_run, alpha, c, ska);
+                        sp_full_B(sva, m_run, l_run, l2_run, alpha, c, ska);
                     else
-                        sp_last_B(sva, m_run, l_run, alpha, c);
+                        sp_last_B(sva, m_run, l_run, l2_run, alpha, c);
                 }
                 if (!TA_OFF(8))
                     relayout_v(vc);
@@ -1119,55 +803,33 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             };
             // Steady state, two tiles per turn: every tile involved is a full prefix tile inside one page, so the
             // block itself issues the loads of tile i+3 and re-lays V(i) out (sp_fast_*); no masks, no choices.
-            // The page id of the tile a fast step loads comes out of the LDS cache one step ahead (pg_ahead holds
-            // the raw value; it has long arrived when the next step reads it).
-            int pg_ahead = 0;
-            bool ahead_valid = false;
-            auto page_of = [&](int pos0) {
-                return pcache[min((pos0 >> p.ps_shift) - span_first_page, PP_PAGES - 1)];
-            };
-            auto fast_step = [&](auto tag, int i) {
-                constexpr bool A = decltype(tag)::value;
-                const int pos0 = TA_OFF(32) ? 0 : (j0 + s0 + i + 3) * TA_TILE;
-                uint32_t pg = (uint32_t)b, sl = (uint32_t)pos0;
-                if (paged) {
-                    pg = (uint32_t)__builtin_amdgcn_readfirstlane(ahead_valid ? pg_ahead : page_of(pos0));
-                    sl = (uint32_t)(pos0 & (p.ps - 1));
-                    pg_ahead = page_of(pos0 + TA_TILE);
-                    ahead_valid = true;
-                }
-                const uint16_t *kb_ = kgp + (uint64_t)pg * ksp + (uint64_t)sl * kss;
-                const uint16_t *vb_ = vgp + (uint64_t)pg * vsp + (uint64_t)sl * vss;
-                const uint32_t kdst = lds0 + ik * MF_TILE_BYTES + wave * 2048;
-                const uint32_t vdst = lds0 + SP_V_OFF + iv * MF_TILE_BYTES + wave * 2048;
-                ik = ik == SP_RK - 1 ? 0 : ik + 1;
-                iv = iv == SP_RV - 1 ? 0 : iv + 1;
-                float alpha;
-                if constexpr (A)
-                    sp_fast_A(vp * MF_TILE_BYTES, m_run, l_run, alpha, c, kn * MF_TILE_BYTES, kb_, vb_, kdst, vdst, koff0,
-                              koff1, voff0, voff1, vc * MF_TILE_BYTES);
-                else
-                    sp_fast_B(vp * MF_TILE_BYTES, m_run, l_run, alpha, c, kn * MF_TILE_BYTES, kb_, vb_, kdst, vdst, koff0,
-                              koff1, voff0, voff1, vc * MF_TILE_BYTES);
-                if (__any(alpha != 1.0f))
-                    sp_scale_o(alpha);
-                if (!TA_OFF(64))
-                    vm_wait<4>();                              // this wave's part of tile i+2 has landed
-                if (!TA_OFF(128))
-                    lds_barrier();
-                kn = kn == SP_RK - 1 ? 0 : kn + 1;
-                vp = vc;
-                vc = vc == SP_RV - 1 ? 0 : vc + 1;
-            };
+            // Steady state: every tile involved is a full prefix tile inside one page (or the contiguous cache), so
+            // whole pairs of tiles run inside sp_fast_loop, which does its own loads, re-layout and bookkeeping.
+            const int n_plain = max(0, min(ns, L / TA_TILE - (j0 + s0)));     // leading full prefix tiles of the span
             int i = 0;
 #pragma unroll 1
             while (i < ns) {
-                if (!(i & 1) && i >= 2 && fast_geom && i + 4 < ns && !tile_ragged(s0 + i + 4)) {
-                    fast_step(SpTag<true>{}, i);
-                    fast_step(SpTag<false>{}, i + 1);
-                    i += 2;
+                if (!(i & 1) && i >= 2 && fast_geom && i + 4 < n_plain && !TA_OFF(256)) {
+                    const uint32_t pairs = (uint32_t)((n_plain - 5 - i) / 2 + 1);
+                    uint32_t cnt = pairs, pos = (uint32_t)((j0 + s0 + i + 3) * TA_TILE);
+                    uint32_t ik_o = ik * MF_TILE_BYTES, iv_o = iv * MF_TILE_BYTES, kn_o = kn * MF_TILE_BYTES;
+                    uint32_t vp_o = vp * MF_TILE_BYTES, vc_o = vc * MF_TILE_BYTES;
+                    const uint32_t pshift = paged ? (uint32_t)p.ps_shift : 31u;
+                    const uint32_t pmask = paged ? (uint32_t)(p.ps - 1) : 0x7fffffffu;
+                    const uint32_t pc_lds = lds0 + (uint32_t)((char *)pcache - smem) - 4u * (uint32_t)span_first_page;
+                    sp_fast_loop(m_run, l_run, l2_run, ik_o, iv_o, kn_o, vp_o, vc_o, pos, cnt, (uint64_t)(uintptr_t)kgp,
+                                 (uint64_t)(uintptr_t)vgp, (uint64_t)(ksp * 2u) | ((uint64_t)(vsp * 2u) << 32),
+                                 (uint64_t)(kss * 2u) | ((uint64_t)(vss * 2u) << 32), (uint64_t)pshift | ((uint64_t)pmask << 32),
+                                 (uint64_t)pc_lds | ((uint64_t)__float_as_uint(c) << 32),
+                                 (uint64_t)(lds0 + wave * 2048) | ((uint64_t)(lds0 + SP_V_OFF + wave * 2048) << 32), koff0,
+                                 koff1, voff0, voff1);
+                    ik = ik_o / MF_TILE_BYTES;
+                    iv = iv_o / MF_TILE_BYTES;
+                    kn = kn_o / MF_TILE_BYTES;
+                    vp = vp_o / MF_TILE_BYTES;
+                    vc = vc_o / MF_TILE_BYTES;
+                    i += 2 * (int)pairs;
                 } else {
-                    ahead_valid = false;
                     if (i & 1)
                         step(SpTag<false>{}, i);
                     else
@@ -1183,9 +845,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             const int x = fresh_tid();
             const int rw = (x >> 6) * 32 + (x & 31), h = (x >> 5) & 1;
             const float l_tot = l_run + __shfl_xor(l_run, 32, TA_WAVE);
+            const float l2_tot = l2_run + __shfl_xor(l2_run, 32, TA_WAVE);
             if (rw < rows_here) {
                 const int64_t wrow = ta_ws_row(p, slot, rg, rw);
-                const float inv = 1.f / l_tot;
+                const float inv = 1.f / l2_tot;
                 float *dst = p.ws_o + wrow * MF_D + 4 * h;
                 float o[16];
                 sp_get_o0(inv, o);
@@ -1219,7 +882,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         dbg[0] = tun_r0;
         dbg[1] = __builtin_amdgcn_s_memrealtime();
         dbg[2] = __builtin_readcyclecounter() - tun_c0;
-        dbg[3] = xcc;
+        dbg[3] = (unsigned long long)xcc | (tun_n << 8) | (tun_blk << 24);
     }
 #endif
 }
@@ -1251,39 +914,22 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
     case 64: return launch_variant<2, 1, 128>(p, stream);
     case 128: return launch_variant<4, 1, 256>(p, stream);
     case 256: {
-        const size_t smem = PP_RAW * PP_RAW_BYTES + PP_VT * MF_TILE_BYTES + sizeof(unsigned long long) * TA_MAX_TREE +
-                            16 + sizeof(int) * TA_MAX_TREE + sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
-        if (p.basic == 1 || smem > 160 * 1024 - 512)
+        const size_t smem = SP_AUX_OFF + sizeof(unsigned long long) * TA_MAX_TREE + 16 + sizeof(int) * TA_MAX_TREE +
+                            sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
+        if (p.basic || smem > 160 * 1024 - 512)
             return launch_variant<8, 1, 512>(p, stream);
-        if (p.basic == 2) {
-            static bool sp_attr_set[64] = {};
-            int d2 = 0;
-            if (hipGetDevice(&d2) != hipSuccess || d2 < 0 || d2 >= 64)
-                return hipErrorInvalidDevice;
-            if (!sp_attr_set[d2]) {
-                hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_sp_kernel,
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-                if (e != hipSuccess)
-                    return e;
-                sp_attr_set[d2] = true;
-            }
-            const size_t sm2 = SP_AUX_OFF + sizeof(unsigned long long) * TA_MAX_TREE + 16 + sizeof(int) * TA_MAX_TREE +
-                               sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
-            hipLaunchKernelGGL(ta_mfma_sp_kernel, dim3(p.n_wg, p.n_rg), dim3(512), sm2, stream, p);
-            return hipGetLastError();
-        }
         static bool attr_set[64] = {};
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
             return hipErrorInvalidDevice;
         if (!attr_set[dev]) {
-            hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_pp_kernel,
+            hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_sp_kernel,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
             if (e != hipSuccess)
                 return e;
             attr_set[dev] = true;
         }
-        hipLaunchKernelGGL(ta_mfma_pp_kernel, dim3(p.n_wg, p.n_rg), dim3(512), smem, stream, p);
+        hipLaunchKernelGGL(ta_mfma_sp_kernel, dim3(p.n_wg, p.n_rg), dim3(512), smem, stream, p);
         return hipGetLastError();
     }
     default: return hipErrorInvalidValue;
