@@ -179,8 +179,9 @@ def measure(w, steps, warmup, log, num_splits=0, kernel=0, rotate=0, check=False
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    # the GPU's clock needs about 0.1 s of uninterrupted load to settle: a short warm-up times a clock ramp instead
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0)
@@ -281,7 +282,7 @@ def main():
             if name == args.workload:
                 continue
             wo = W.make_config(idx)
-            mo = measure(wo, 15, 3, log)
+            mo = measure(wo, 100, 100, log)
             others[wo.name] = {"us_per_step": mo["ms_per_step"] * 1e3, "kv_pass_us": mo["kv_us"],
                                "merge_pass_us": mo["merge_us"], "hbm_frac": mo["hbm_frac"],
                                "mfma_frac": mo["mfma_frac"], "algorithmic_bytes": mo["alg_bytes"],

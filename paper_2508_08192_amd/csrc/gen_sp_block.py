@@ -213,14 +213,15 @@ def sg(n):
     return "s%d" % n
 
 
-def fast_step_items(cur, label):
+def fast_step_items(cur, label, helper=False):
     """One tile of the steady state as a list of instructions (no waits yet): the full block (PV, S, softmax)
     plus everything else the tile needs -- page lookup and addresses of tile i+3, its four cache loads, the
-    in-place re-layout of V(i), ring bookkeeping, the (rare) rescaling of O, and the closing barrier."""
+    in-place re-layout of V(i), ring bookkeeping, the (rare) rescaling of O, and the closing barrier.
+    helper=True leaves the block itself out: a wave without query rows still moves its share of the tiles."""
     sc, sn = (SA, SB) if cur == "A" else (SB, SA)
-    steps = mfma_steps(True, True, sn)
+    steps = [] if helper else mfma_steps(True, True, sn)
     n = len(steps)
-    sm = [(t.replace("%[c]", sg(S_C)), need) for t, need in softmax_ops(sc)]
+    sm = [] if helper else [(t.replace("%[c]", sg(S_C)), need) for t, need in softmax_ops(sc)]
     rx = lambda k: RL + 2 * k          # row k, columns 0..1 (dword x)
     ry = lambda k: RL + 2 * k + 1      # row k, columns 2..3 (dword y)
     t0, t1 = RL + 8, RL + 9
@@ -296,6 +297,11 @@ def fast_step_items(cur, label):
     # Loads of tile i+3: one every 20 softmax instructions from the 10th on.  The re-layout shares v[38:47]
     # with the V fragment addresses and the page lookup, so it starts once the last PV read is out (MFMA 11).
     ri, started, di = 0, False, 0
+    if helper:
+        for x in dma:
+            aux += [dict(t=y) for y in x]
+        aux += rl_reads
+        started, di = True, 4
     for j, (t, need) in enumerate(rest):
         aux.append(dict(t=t, mf=need))
         if j >= 10 and (j - 10) % 20 == 0 and di < 4:
@@ -313,15 +319,15 @@ def fast_step_items(cur, label):
         aux.append(dict(it, mf=11))
     aux += [dict(t=x) for x in rings]
 
-    seq = [dict(t="s_nop 3")] + [dict(t=t.replace("%[sva]", "%[vp]").replace("%[ska]", "%[kn]"))
-                                 for t in address_setup(True, True)]
+    seq = [] if helper else [dict(t="s_nop 3")] + [dict(t=t.replace("%[sva]", "%[vp]").replace("%[ska]", "%[kn]"))
+                                                   for t in address_setup(True, True)]
     def put_reads(r):
         for x in steps[r][0]:
             seq.append(dict(t=x.replace("{f}", frag(r)), lds=("f", r) if x.startswith("ds_read") else None))
-    for r in range(DIST):
+    for r in range(min(DIST, n)):
         put_reads(r)
     vi = 0
-    pre = 16
+    pre = min(16, len(aux))
     while vi < pre:
         seq.append(aux[vi])
         vi += 1
@@ -337,16 +343,17 @@ def fast_step_items(cur, label):
             seq.append(aux[vi])
             vi += 1
     seq += aux[vi:]
-    # O still holds sums relative to the old reference when it moved (rare): rescale, then close the tile
-    seq += [dict(t="v_cmp_neq_f32 vcc, 1.0, %[al]"), dict(t="s_cbranch_vccz %df" % label), dict(t="s_nop 15"),
-            dict(t="s_nop 7")]
-    seq += [dict(t="v_mul_f32 %s, %%[al], %s" % (v(O + k), v(O + k))) for k in range(64)]
-    seq += [dict(t="s_nop 3"), dict(t="%d:" % label), dict(t="s_waitcnt vmcnt(4)"),
-            dict(t="s_waitcnt lgkmcnt(0)", flush=True), dict(t="s_barrier")]
+    if not helper:
+        # O still holds sums relative to the old reference when it moved (rare): rescale, then close the tile
+        seq += [dict(t="v_cmp_neq_f32 vcc, 1.0, %[al]"), dict(t="s_cbranch_vccz %df" % label), dict(t="s_nop 15"),
+                dict(t="s_nop 7")]
+        seq += [dict(t="v_mul_f32 %s, %%[al], %s" % (v(O + k), v(O + k))) for k in range(64)]
+        seq += [dict(t="s_nop 3"), dict(t="%d:" % label)]
+    seq += [dict(t="s_waitcnt vmcnt(4)"), dict(t="s_waitcnt lgkmcnt(0)", flush=True), dict(t="s_barrier")]
     return seq
 
 
-def fast_loop(name):
+def fast_loop(name, helper=False):
     """`cnt` pairs of steady-state tiles (buffer A current, then buffer B) as one asm statement with its own loop,
     so that the scalar bookkeeping of a tile is issued in the shadow of its matrix and vector work."""
     head = ["s_mov_b64 s[%d:%d], %%[kg]" % (S_KG, S_KG + 1), "s_mov_b64 s[%d:%d], %%[vg]" % (S_VG, S_VG + 1),
@@ -354,7 +361,7 @@ def fast_loop(name):
             "s_mov_b64 s[%d:%d], %%[pp]" % (S_PSHIFT, S_PMASK), "s_mov_b64 s[%d:%d], %%[pc]" % (S_PCADJ, S_C),
             "s_mov_b64 s[%d:%d], %%[dst]" % (S_KDST, S_VDST), "s_mov_b32 %s, 0x05040100" % sg(S_LO),
             "s_mov_b32 %s, 0x07060302" % sg(S_HI), "1:"]
-    seq = [dict(t=t) for t in head] + fast_step_items("A", 2) + fast_step_items("B", 3)
+    seq = [dict(t=t) for t in head] + fast_step_items("A", 2, helper) + fast_step_items("B", 3, helper)
     seq += [dict(t="s_sub_u32 %[cnt], %[cnt], 1"), dict(t="s_cmp_lg_u32 %[cnt], 0"), dict(t="s_cbranch_scc1 1b")]
     lines, issued, done = [], [], -1
     for it in seq:
@@ -369,15 +376,15 @@ def fast_loop(name):
             issued.append(it["lds"])
         if it.get("flush"):
             issued, done = [], -1
-    sig = ["float &m", "float &l", "float &l2", "uint32_t &ik", "uint32_t &iv", "uint32_t &kn", "uint32_t &vp", "uint32_t &vc",
+    sig = ([] if helper else ["float &m", "float &l", "float &l2"]) + ["uint32_t &ik", "uint32_t &iv", "uint32_t &kn", "uint32_t &vp", "uint32_t &vc",
            "uint32_t &pos", "uint32_t &cnt", "uint64_t kg", "uint64_t vg", "uint64_t sp", "uint64_t ss", "uint64_t pp",
            "uint64_t pc", "uint64_t dst", "uint32_t koff0", "uint32_t koff1", "uint32_t voff0", "uint32_t voff1"]
-    outs = ['[m] "+v"(m)', '[l] "+v"(l)', '[l2] "+v"(l2)', '[al] "=&v"(alpha)'] + \
+    outs = ([] if helper else ['[m] "+v"(m)', '[l] "+v"(l)', '[l2] "+v"(l2)', '[al] "=&v"(alpha)']) + \
            ['[%s] "+s"(%s)' % (x, x) for x in ("ik", "iv", "kn", "vp", "vc", "pos", "cnt")]
     ins = ['[%s] "s"(%s)' % (x, x) for x in ("kg", "vg", "sp", "ss", "pp", "pc", "dst")] + \
           ['[%s] "v"(%s)' % (x, x) for x in ("koff0", "koff1", "voff0", "voff1")]
     clob = ['"memory"', '"vcc"', '"scc"'] + ['"s%d"' % i for i in list(range(60, 76)) + list(range(80, 90))]
-    return emit(name, sig, lines, outs, ins, clob, pre="    float alpha;")
+    return emit(name, sig, lines, outs, ins, clob, pre=None if helper else "    float alpha;")
 
 
 def emit(name, sig, lines, outs, ins, clob, pre=None):
@@ -440,5 +447,7 @@ if __name__ == "__main__":
     print(block("sp_pv", "A", True, False, False))               # drain: the last tile's P . V
     print()
     print(fast_loop("sp_fast_loop"))
+    print()
+    print(fast_loop("sp_fast_loop_helper", helper=True))
     print()
     print(helpers())

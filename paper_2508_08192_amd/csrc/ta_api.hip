@@ -180,17 +180,16 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
         return TA_ERR_SHAPE;
     if (kernel == TA_KERNEL_MFMA) {
         pl.rows_grp = mfma_rows_group(p.rows);
-        pl.threads = pl.rows_grp <= 64 ? 128 : (pl.rows_grp == 128 ? 256 : 512);
+        pl.threads = 512;                                   // always eight waves; one workgroup per CU
         pl.n_rg = (p.rows + pl.rows_grp - 1) / pl.rows_grp;
         // A workgroup's partial result costs rows*D*4 bytes written and read again; a tile of keys and
-        // values costs TA_TILE*D*4 bytes.  Keep a share at least as long as the rows are many, so the
-        // partials stay a small fraction of the cache traffic.
-        const int per_cu = pl.threads >= 512 ? 1 : (pl.threads >= 256 ? 2 : 4);
-        int64_t want = (int64_t)num_cus * per_cu / pl.n_rg;
+        // values costs TA_TILE*D*4 bytes.  Keep a share at least a few tiles long, so the partials stay a
+        // small fraction of the cache traffic.
+        int64_t want = (int64_t)num_cus / pl.n_rg;
         if (want < 1)
             want = 1;
         pl.n_wg = (int)(num_splits > 0 ? num_splits : want);
-        pl.min_q = num_splits > 0 ? 1 : (pl.rows_grp >= 128 ? 4 : 2);
+        pl.min_q = num_splits > 0 ? 1 : 4;
     } else {
         pl.rows_grp = p.rows < TA_ROW_GROUP ? p.rows : TA_ROW_GROUP;
         pl.threads = 256;

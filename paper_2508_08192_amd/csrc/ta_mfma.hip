@@ -586,6 +586,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         }
         const int row = wave * 32 + r32;
         const bool row_ok = row < rows_here;
+        // A wave whose 32 rows all lie beyond the row group (T*G < 256) computes nothing; it still loads and
+        // re-lays out its share of every tile and takes part in every barrier.
+        const bool active = wave * 32 < rows_here;
 
         if (poison) {
             if (row_ok) {
@@ -745,8 +748,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             }
             wait_loads(issued - 1);                            // tile 0 has landed
             lds_barrier();
-            sp_s_first(0u);
-            if (tile_ragged(s0)) {
+            if (active)
+                sp_s_first(0u);
+            if (active && tile_ragged(s0)) {
                 const unsigned long long vm = tile_mask(s0);
                 sp_mask_A((uint32_t)vm, (uint32_t)(vm >> 32));
             }
@@ -765,7 +769,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 const bool has_next = i + 1 < ns;
                 const uint32_t ska = kn * MF_TILE_BYTES, sva = vp * MF_TILE_BYTES;
                 float alpha = 1.f;
-                if (TA_OFF(1)) {
+                if (TA_OFF(1) || !active) {
                 } else if constexpr (A) {
                     if (i == 0) {
                         if (has_next)
@@ -787,7 +791,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     relayout_v(vc);
                 if (__any(alpha != 1.0f))
                     sp_scale_o(alpha);             // O still holds sums relative to the old reference
-                if (has_next && tile_ragged(s0 + i + 1)) {
+                if (active && has_next && tile_ragged(s0 + i + 1)) {
                     const unsigned long long vm = tile_mask(s0 + i + 1);
                     if constexpr (A)
                         sp_mask_B((uint32_t)vm, (uint32_t)(vm >> 32));
@@ -817,12 +821,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     const uint32_t pshift = paged ? (uint32_t)p.ps_shift : 31u;
                     const uint32_t pmask = paged ? (uint32_t)(p.ps - 1) : 0x7fffffffu;
                     const uint32_t pc_lds = lds0 + (uint32_t)((char *)pcache - smem) - 4u * (uint32_t)span_first_page;
-                    sp_fast_loop(m_run, l_run, l2_run, ik_o, iv_o, kn_o, vp_o, vc_o, pos, cnt, (uint64_t)(uintptr_t)kgp,
-                                 (uint64_t)(uintptr_t)vgp, (uint64_t)(ksp * 2u) | ((uint64_t)(vsp * 2u) << 32),
-                                 (uint64_t)(kss * 2u) | ((uint64_t)(vss * 2u) << 32), (uint64_t)pshift | ((uint64_t)pmask << 32),
-                                 (uint64_t)pc_lds | ((uint64_t)__float_as_uint(c) << 32),
-                                 (uint64_t)(lds0 + wave * 2048) | ((uint64_t)(lds0 + SP_V_OFF + wave * 2048) << 32), koff0,
-                                 koff1, voff0, voff1);
+                    const uint64_t c_kg = (uint64_t)(uintptr_t)kgp, c_vg = (uint64_t)(uintptr_t)vgp;
+                    const uint64_t c_sp = (uint64_t)(ksp * 2u) | ((uint64_t)(vsp * 2u) << 32);
+                    const uint64_t c_ss = (uint64_t)(kss * 2u) | ((uint64_t)(vss * 2u) << 32);
+                    const uint64_t c_pp = (uint64_t)pshift | ((uint64_t)pmask << 32);
+                    const uint64_t c_pc = (uint64_t)pc_lds | ((uint64_t)__float_as_uint(c) << 32);
+                    const uint64_t c_dst = (uint64_t)(lds0 + wave * 2048) | ((uint64_t)(lds0 + SP_V_OFF + wave * 2048) << 32);
+                    if (active)
+                        sp_fast_loop(m_run, l_run, l2_run, ik_o, iv_o, kn_o, vp_o, vc_o, pos, cnt, c_kg, c_vg, c_sp, c_ss, c_pp,
+                                     c_pc, c_dst, koff0, koff1, voff0, voff1);
+                    else
+                        sp_fast_loop_helper(ik_o, iv_o, kn_o, vp_o, vc_o, pos, cnt, c_kg, c_vg, c_sp, c_ss, c_pp, c_pc, c_dst,
+                                            koff0, koff1, voff0, voff1);
                     ik = ik_o / MF_TILE_BYTES;
                     iv = iv_o / MF_TILE_BYTES;
                     kn = kn_o / MF_TILE_BYTES;
@@ -837,7 +847,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     ++i;
                 }
             }
-            sp_pv(vp * MF_TILE_BYTES);
+            if (active)
+                sp_pv(vp * MF_TILE_BYTES);
             lds_barrier();                                     // the rings are free for the next span or item
         }
 
@@ -909,29 +920,24 @@ static hipError_t launch_variant(const TAParams &p, hipStream_t stream)
 
 hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
 {
-    switch (p.rows_grp) {
-    case 32: return launch_variant<1, 1, 128>(p, stream);
-    case 64: return launch_variant<2, 1, 128>(p, stream);
-    case 128: return launch_variant<4, 1, 256>(p, stream);
-    case 256: {
-        const size_t smem = SP_AUX_OFF + sizeof(unsigned long long) * TA_MAX_TREE + 16 + sizeof(int) * TA_MAX_TREE +
-                            sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
-        if (p.basic || smem > 160 * 1024 - 512)
-            return launch_variant<8, 1, 512>(p, stream);
-        static bool attr_set[64] = {};
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
-            return hipErrorInvalidDevice;
-        if (!attr_set[dev]) {
-            hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_sp_kernel,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-            if (e != hipSuccess)
-                return e;
-            attr_set[dev] = true;
-        }
-        hipLaunchKernelGGL(ta_mfma_sp_kernel, dim3(p.n_wg, p.n_rg), dim3(512), smem, stream, p);
-        return hipGetLastError();
+    if (p.rows_grp != 32 && p.rows_grp != 64 && p.rows_grp != 128 && p.rows_grp != 256)
+        return hipErrorInvalidValue;
+    // One kernel for every row group: with fewer than 256 rows some of its eight waves only move tiles.
+    const size_t smem = SP_AUX_OFF + sizeof(unsigned long long) * TA_MAX_TREE + 16 + sizeof(int) * TA_MAX_TREE +
+                        sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
+    if (p.basic || smem > 160 * 1024 - 512)
+        return launch_variant<8, 1, 512>(p, stream);       // register-staged kernel: very large batches, or on request
+    static bool attr_set[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
+        hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_sp_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           160 * 1024 - 512);
+        if (e != hipSuccess)
+            return e;
+        attr_set[dev] = true;
     }
-    default: return hipErrorInvalidValue;
-    }
+    hipLaunchKernelGGL(ta_mfma_sp_kernel, dim3(p.n_wg, p.n_rg), dim3(512), smem, stream, p);
+    return hipGetLastError();
 }

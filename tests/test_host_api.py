@@ -104,7 +104,7 @@ def test_plan_picks_kernel_family_and_sizes():
     assert p["threads"] == 512 and p["tile"] == 64
     assert p["partial_slots"] == p["kv_workgroups"] + 8
     p = _plan(_good(B=32, T=16, Hq=32, Hkv=8, max_pages=129))
-    assert p["kernel"] == ta.TA_KERNEL_MFMA and p["rows_per_group"] == 64 and p["threads"] == 128
+    assert p["kernel"] == ta.TA_KERNEL_MFMA and p["rows_per_group"] == 64 and p["threads"] == 512
     p = _plan(_good(B=1, T=64, Hq=64, Hkv=8, max_pages=65))       # 512 rows -> two row groups
     assert p["row_groups"] == 2 and p["rows_per_group"] == 256
     p = _plan(_good(B=1, T=7, Hq=4, Hkv=1, D=64, dtype=ta.TA_F32))
