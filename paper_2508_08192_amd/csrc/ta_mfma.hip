@@ -513,9 +513,13 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
 
 #ifdef TA_TUNING
     const unsigned long long tun_c0 = __builtin_readcyclecounter(), tun_r0 = __builtin_amdgcn_s_memrealtime();
-    unsigned long long tun_blk = 0, tun_n = 0;
+    unsigned long long tun_mark[8] = {};
+#define TUN_MARK(i) do { if (tun_mark[i] == 0) tun_mark[i] = __builtin_amdgcn_s_memrealtime() - tun_r0; } while (0)
+#else
+#define TUN_MARK(i) do { } while (0)
 #endif
     ta_build_schedule(p, cum);
+    TUN_MARK(0);
     const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
     const int share = ta_share(p, total);
     const int w = blockIdx.x, rg = blockIdx.y;
@@ -723,6 +727,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 vm_wait<0>();
         };
 
+        TUN_MARK(1);
         sp_zero_o();
         float m_run = -INFINITY, l_run = 0.f, l2_run = 0.f;   // l2: sum of the bf16-rounded probabilities
 
@@ -739,6 +744,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     pcache[0] = b;                             // the steady-state loop sees one page: the request's cache
                 __syncthreads();
             }
+            TUN_MARK(2);
             // ring positions: next slots to load into, K slot of tile i+1, V slots of tiles i and i-1
             int ik = 0, iv = 0, issued = 0;
             for (; issued < min(ns, 3); ++issued) {
@@ -746,8 +752,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 ik = ik == SP_RK - 1 ? 0 : ik + 1;
                 iv = iv == SP_RV - 1 ? 0 : iv + 1;
             }
+            TUN_MARK(3);
             wait_loads(issued - 1);                            // tile 0 has landed
             lds_barrier();
+            TUN_MARK(4);
             if (active)
                 sp_s_first(0u);
             if (active && tile_ragged(s0)) {
@@ -809,6 +817,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             // block itself issues the loads of tile i+3 and re-lays V(i) out (sp_fast_*); no masks, no choices.
             // Steady state: every tile involved is a full prefix tile inside one page (or the contiguous cache), so
             // whole pairs of tiles run inside sp_fast_loop, which does its own loads, re-layout and bookkeeping.
+            TUN_MARK(5);
             const int n_plain = max(0, min(ns, L / TA_TILE - (j0 + s0)));     // leading full prefix tiles of the span
             int i = 0;
 #pragma unroll 1
@@ -847,39 +856,55 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     ++i;
                 }
             }
+            TUN_MARK(6);
             if (active)
                 sp_pv(vp * MF_TILE_BYTES);
             lds_barrier();                                     // the rings are free for the next span or item
         }
 
         {
+            // Partial result of this (workgroup, list) overlap.  A lane holds 16-byte pieces of one row, 32 bytes
+            // apart; written like that, every store would touch 64 cache lines.  So each wave first turns its
+            // 32 x 128 block into row-major order in its 16 KB of the (now idle) K/V rings -- 16-byte chunk j of
+            // row r sits at chunk j ^ r, which keeps both directions free of bank conflicts -- and then stores
+            // whole 512-byte rows.
+            TUN_MARK(7);
             const int x = fresh_tid();
-            const int rw = (x >> 6) * 32 + (x & 31), h = (x >> 5) & 1;
+            const int ln = x & 63, wv = x >> 6;
+            const int r32_ = ln & 31, h = ln >> 5;
             const float l_tot = l_run + __shfl_xor(l_run, 32, TA_WAVE);
             const float l2_tot = l2_run + __shfl_xor(l2_run, 32, TA_WAVE);
-            if (rw < rows_here) {
-                const int64_t wrow = ta_ws_row(p, slot, rg, rw);
+            if (active) {
                 const float inv = 1.f / l2_tot;
-                float *dst = p.ws_o + wrow * MF_D + 4 * h;
+                char *stage = smem + wv * 16384;
                 float o[16];
+                auto put = [&](int db) {
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        const int chunk = 8 * db + 2 * i4 + h;
+                        *(float4 *)(stage + r32_ * 512 + ((chunk ^ r32_) << 4)) =
+                            make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
+                    }
+                };
                 sp_get_o0(inv, o);
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4)
-                    *(float4 *)(dst + 8 * i4) = make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
+                put(0);
                 sp_get_o1(inv, o);
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4)
-                    *(float4 *)(dst + 32 + 8 * i4) = make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
+                put(1);
                 sp_get_o2(inv, o);
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4)
-                    *(float4 *)(dst + 64 + 8 * i4) = make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
+                put(2);
                 sp_get_o3(inv, o);
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4)
-                    *(float4 *)(dst + 96 + 8 * i4) = make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
-                if (h == 0)
-                    p.ws_lse[wrow] = m_run + log2f(l_tot);
+                put(3);
+                __builtin_amdgcn_wave_barrier();
+                const int rw0 = wv * 32;
+#pragma unroll 4
+                for (int it = 0; it < 16; ++it) {
+                    const int rr = 2 * it + h;                         // row of the wave's block, chunk r32_
+                    const float4 val = *(const float4 *)(stage + rr * 512 + ((r32_ ^ rr) << 4));
+                    if (rw0 + rr < rows_here)
+                        *(float4 *)(p.ws_o + ta_ws_row(p, slot, rg, rw0 + rr) * MF_D + 4 * r32_) = val;
+                }
+                if (h == 0 && rw0 + r32_ < rows_here)
+                    p.ws_lse[ta_ws_row(p, slot, rg, rw0 + r32_)] = m_run + log2f(l_tot);
             }
         }
         __syncthreads();
@@ -893,7 +918,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         dbg[0] = tun_r0;
         dbg[1] = __builtin_amdgcn_s_memrealtime();
         dbg[2] = __builtin_readcyclecounter() - tun_c0;
-        dbg[3] = (unsigned long long)xcc | (tun_n << 8) | (tun_blk << 24);
+        dbg[3] = xcc;
+        if (blockIdx.x == 0) {
+            unsigned long long *d2 = (unsigned long long *)(p.status + 16) + 4 * 1024;
+            for (int i = 0; i < 8; ++i) d2[i] = tun_mark[i];
+            d2[8] = __builtin_amdgcn_s_memrealtime() - tun_r0;
+        }
     }
 #endif
 }
