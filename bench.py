@@ -240,8 +240,7 @@ def main():
     else:
         roof = {"bound": "mfma", "achieved": flops / (kv_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": m["mfma_frac"], "traffic": traffic}
-    roof.update({"kernel": "ta_generic_kv_kernel" if plan["kernel"] != 2 else
-                 ("ta_mfma_pp_kernel" if plan["rows_per_group"] == 256 else "ta_mfma_kv_kernel"),
+    roof.update({"kernel": "ta_generic_kv_kernel" if plan["kernel"] != 2 else "ta_mfma_sp_kernel",
                  "avg_launch_us": kv_us, "algorithmic_bytes_per_launch": kv_alg,
                  "useful_flops_per_launch": flops, "hbm_frac": m["hbm_frac"], "mfma_frac": m["mfma_frac"]})
 
