@@ -78,12 +78,16 @@ __device__ __forceinline__ int ta_request_tiles(const TAParams &p, int b)
 }
 
 // cum[0..B]: exclusive prefix sums of the per-request tile counts.  Needs blockDim.x >= 64; ends
-// with a barrier.
-__device__ __forceinline__ void ta_build_schedule(const TAParams &p, int *cum)
+// with a barrier.  If `lens` is given, it also receives the B prefix lengths as they were read.
+__device__ __forceinline__ void ta_build_schedule(const TAParams &p, int *cum, int *lens = nullptr)
 {
     const int tid = threadIdx.x;
-    for (int b = tid; b < p.B; b += blockDim.x)
-        cum[b + 1] = ta_request_tiles(p, b);
+    for (int b = tid; b < p.B; b += blockDim.x) {
+        const int L = p.seq_lens[(int64_t)b * p.sl_s];
+        cum[b + 1] = ta_request_ok(p, L) ? (L + TA_TILE - 1) / TA_TILE + 1 : 1;
+        if (lens)
+            lens[b] = L;
+    }
     if (tid == 0)
         cum[0] = 0;
     __syncthreads();
@@ -159,6 +163,37 @@ __device__ __forceinline__ bool ta_encode_tree(const int32_t *parent, int T, uns
         *flag = 0;
     if (tid < T)
         par_s[tid] = parent[tid];
+    __syncthreads();
+    if (tid < T) {
+        unsigned long long m = 0;
+        int cur = tid, steps = 0;
+        bool bad = false;
+        while (cur >= 0) {
+            if (cur >= T || steps >= T) {
+                bad = true;
+                break;
+            }
+            m |= 1ull << cur;
+            cur = par_s[cur];
+            ++steps;
+        }
+        masks[tid] = bad ? 0ull : m;
+        if (bad)
+            atomicOr(flag, 1);
+    }
+    __syncthreads();
+    return *flag == 0;
+}
+
+// Same, for a caller that has already loaded the parent id of node threadIdx.x (any value for threads >= T).
+__device__ __forceinline__ bool ta_encode_tree_from(int parent_of_tid, int T, unsigned long long *masks, int *flag,
+                                                    int *par_s)
+{
+    const int tid = threadIdx.x;
+    if (tid == 0)
+        *flag = 0;
+    if (tid < T)
+        par_s[tid] = parent_of_tid;
     __syncthreads();
     if (tid < T) {
         unsigned long long m = 0;

@@ -508,7 +508,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
     int *flag = (int *)(masks + TA_MAX_TREE);
     int *par_s = flag + 4;                                                // [TA_MAX_TREE]
     int *pcache = par_s + TA_MAX_TREE;                                    // [PP_PAGES] page ids of the current span
-    int *cum = pcache + PP_PAGES;
+    int *cum = pcache + PP_PAGES;                                         // [B + 1] schedule, then [B] prefix lengths
+    int *lens = cum + p.B + 1;
     const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
 
 #ifdef TA_TUNING
@@ -518,7 +519,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
 #else
 #define TUN_MARK(i) do { } while (0)
 #endif
-    ta_build_schedule(p, cum);
+    ta_build_schedule(p, cum, lens);
     TUN_MARK(0);
     const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
     const int share = ta_share(p, total);
@@ -576,16 +577,30 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         const int j1 = min(n_b, t_end - seg_start);
         const int n = j1 - j0;
         const int slot = w + b * p.Hkv + g;
-        const int L = __builtin_amdgcn_readfirstlane(p.seq_lens[(int64_t)b * p.sl_s]);
+        const int L = __builtin_amdgcn_readfirstlane(lens[b]);
         bool poison = !ta_request_ok(p, L);
         if (poison && tid == 0)
             atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
-        if (has_tree_tile && !poison) {
-            if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag, par_s)) {
-                poison = true;
-                if (tid == 0)
-                    atomicOr(p.status, TA_STATUS_BAD_PARENT);
+        // tile ti of this item: first logical position and number of tokens it holds
+        auto tile_pos0 = [&](int ti) { return (j0 + ti == n_b - 1) ? L : (j0 + ti) * TA_TILE; };
+        auto tile_count = [&](int ti) { return (j0 + ti == n_b - 1) ? p.T : min(TA_TILE, L - (j0 + ti) * TA_TILE); };
+        // The item is walked in spans of tiles whose page ids fit the LDS cache (one span unless the pages are
+        // tiny and the share very long).
+        const int span_tiles = !paged ? n
+                               : (p.ps_shift >= 6 ? PP_PAGES - 2 : max(1, ((PP_PAGES - 2) << p.ps_shift) / TA_TILE));
+        // Loads that do not depend on each other go out together: this thread's parent id (for the ancestor
+        // masks), its page id of the first span, and below the row's Q; one round trip instead of three.
+        int par_v = -1, pg_v = 0, page0 = 0, pages0 = 0;
+        if (!poison) {
+            if (has_tree_tile && tid < p.T)
+                par_v = p.parent[(int64_t)b * p.par_sb + tid];
+            if (paged) {
+                const int ns0 = min(span_tiles, n);
+                page0 = tile_pos0(0) >> p.ps_shift;
+                pages0 = ((tile_pos0(ns0 - 1) + tile_count(ns0 - 1) - 1) >> p.ps_shift) - page0 + 1;
+                if (tid < pages0)
+                    pg_v = p.page_table[(int64_t)b * p.pt_sb + page0 + tid];
             }
         }
         const int row = wave * 32 + r32;
@@ -594,7 +609,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         // re-lays out its share of every tile and takes part in every barrier.
         const bool active = wave * 32 < rows_here;
 
-        if (poison) {
+        auto write_poison = [&]() {                        // a NaN log-sum-exp poisons the rows in the merge
             if (row_ok) {
                 const int64_t wrow = ta_ws_row(p, slot, rg, row);
                 for (int d = hf * 64; d < hf * 64 + 64; d += 4)
@@ -602,6 +617,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 if (hf == 0)
                     p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
             }
+        };
+        if (poison) {
+            write_poison();
             __syncthreads();
             t = seg_start + j1;
             continue;
@@ -630,12 +648,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     sp_set_q_hi(x);
             }
         }
+        if (has_tree_tile && !ta_encode_tree_from(par_v, p.T, masks, flag, par_s)) {
+            if (tid == 0)
+                atomicOr(p.status, TA_STATUS_BAD_PARENT);
+            write_poison();
+            __syncthreads();
+            t = seg_start + j1;
+            continue;
+        }
         const uint16_t *kgp = (const uint16_t *)p.k + (int64_t)g * p.k_sh;
         const uint16_t *vgp = (const uint16_t *)p.v + (int64_t)g * p.v_sh;
 
-        // tile ti of this item: first logical position and number of tokens it holds
-        auto tile_pos0 = [&](int ti) { return (j0 + ti == n_b - 1) ? L : (j0 + ti) * TA_TILE; };
-        auto tile_count = [&](int ti) { return (j0 + ti == n_b - 1) ? p.T : min(TA_TILE, L - (j0 + ti) * TA_TILE); };
         // bits of the tokens tile ti really holds for this lane's half, or all ones when nothing is to mask
         auto tile_mask = [&](int ti) -> unsigned long long {
             const int x = fresh_tid();
@@ -648,8 +671,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         };
         auto tile_ragged = [&](int ti) { return j0 + ti == n_b - 1 || L - (j0 + ti) * TA_TILE < TA_TILE; };
         int span_first_page = 0;
-        const int span_tiles = !paged ? n
-                               : (p.ps_shift >= 6 ? PP_PAGES - 2 : max(1, ((PP_PAGES - 2) << p.ps_shift) / TA_TILE));
         // Cache loads of tile ti into K slot ks and V slot vs: four 16-byte loads per lane.  Rows past the tile's
         // end re-read its first token (their probabilities are exactly zero).
         auto issue_tile = [&](int ti, int ks, int vs) {
@@ -736,7 +757,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             if (paged) {
                 span_first_page = tile_pos0(s0) >> p.ps_shift;
                 const int last_page = (tile_pos0(s0 + ns - 1) + tile_count(s0 + ns - 1) - 1) >> p.ps_shift;
-                for (int k = tid; k <= last_page - span_first_page; k += 512)
+                if (s0 == 0 && tid < pages0)
+                    pcache[tid] = pg_v;                        // loaded ahead, together with Q
+                for (int k = tid + (s0 == 0 ? 512 : 0); k <= last_page - span_first_page; k += 512)
                     pcache[k] = p.page_table[(int64_t)b * p.pt_sb + span_first_page + k];
                 __syncthreads();
             } else {
@@ -907,7 +930,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     p.ws_lse[ta_ws_row(p, slot, rg, rw0 + r32_)] = m_run + log2f(l_tot);
             }
         }
-        __syncthreads();
+        lds_barrier();                 // the staging area is ring space again; the stores themselves may still fly
         t = seg_start + j1;
     }
 #ifdef TA_TUNING
@@ -954,7 +977,7 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
         return hipErrorInvalidValue;
     // One kernel for every row group: with fewer than 256 rows some of its eight waves only move tiles.
     const size_t smem = SP_AUX_OFF + sizeof(unsigned long long) * TA_MAX_TREE + 16 + sizeof(int) * TA_MAX_TREE +
-                        sizeof(int) * PP_PAGES + sizeof(int) * (p.B + 2);
+                        sizeof(int) * PP_PAGES + sizeof(int) * (2 * p.B + 2);
     if (p.basic || smem > 160 * 1024 - 512)
         return launch_variant<8, 1, 512>(p, stream);       // register-staged kernel: very large batches, or on request
     static bool attr_set[64] = {};
