@@ -70,6 +70,32 @@ def test_bf16_row_shapes(kernel, shape):
     _check(w, "rows %r kernel=%d" % (shape, kernel), kernel=kernel)
 
 
+@pytest.mark.parametrize("shape", [
+    dict(T=1, Hq=4, Hkv=1),          # 4 rows: one wave computes, seven only move tiles
+    dict(T=3, Hq=8, Hkv=1),          # 24 rows
+    dict(T=12, Hq=10, Hkv=2),        # 60 rows: two waves, the second ragged
+    dict(T=12, Hq=8, Hkv=1),         # 96 rows
+    dict(T=33, Hq=7, Hkv=1),         # 231 rows: the eighth wave has 7 rows
+])
+@pytest.mark.parametrize("ps,splits", [(64, 1), (128, 0), (0, 2)])
+def test_steady_state_loop_with_idle_waves(shape, ps, splits):
+    """Prefixes long enough for the asm steady-state loop, row counts that leave waves without rows."""
+    rng = np.random.default_rng(100 + shape["T"])
+    T = shape["T"]
+    trees = np.stack([W.random_tree(T, 6, rng) for _ in range(2)])
+    w = W.make_workload("steady", B=2, T=T, D=128, seq_lens=[1500, 2117], trees=trees, page_size=ps, dtype="bf16",
+                        seed=450 + T, paged=ps > 0, **{k: v for k, v in shape.items() if k != "T"})
+    _check(w, "steady %r ps=%d splits=%d" % (shape, ps, splits), kernel=MFMA, num_splits=splits)
+
+
+def test_steady_state_loop_over_two_page_id_spans():
+    """One share longer than the page-id cache (2046 pages of 64 tokens): the loop restarts on a second span."""
+    T = 16
+    w = W.make_workload("two_spans", B=1, T=T, Hq=4, Hkv=1, D=128, seq_lens=[133000], trees=W.bfs_tree(T, [3, 2], 5),
+                        page_size=64, dtype="bf16", seed=460)
+    _check(w, kernel=MFMA, num_splits=1)
+
+
 @pytest.mark.parametrize("kernel", [GENERIC, MFMA])
 def test_contiguous_layout_and_chain_tree(kernel):
     w = W.make_workload("contig", B=3, T=24, Hq=4, Hkv=2, D=128, seq_lens=[90, 0, 301], trees=W.chain_tree(24),
