@@ -16,18 +16,26 @@ __device__ __forceinline__ float load_elem(const void *base, int64_t idx)
     return ((const float *)base)[idx];
 }
 
-// KV pass, one wave per query row at a time: lanes are the 64 tokens of a tile for the scores
-// (section 3.1: prefix tiles are mask-free, the tree tile keeps only the row's ancestors), then lanes
-// are head-dim columns for the weighted sum of V.  Running max / sum per row (base-2 domain).
+#define GEN_RB 4                                  // query rows a wave carries at a time
+#define GEN_TB 8                                  // tokens a wave stages per round trip
+
+// KV pass for any shape.  A workgroup walks its share of a (request, KV head) tile list once per block of
+// GEN_WAVES * GEN_RB query rows: every tile (64 tokens; section 3.1: prefix tiles are mask-free, the tree tile
+// keeps only a row's ancestors) is staged in LDS as fp32, rows of tokens read coalesced, and then each wave
+// updates its rows -- lanes are the tile's tokens for the scores, then head-dim columns for the weighted sum
+// of V.  Running max / sum per row (base-2 domain).  Tokens that do not exist are staged as zeros.
 template <bool BF16>
 __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
 {
     extern __shared__ int smem_i[];
     int *cum = smem_i;                                                   // [B + 1]
     unsigned long long *masks = (unsigned long long *)(cum + ((p.B + 2) & ~1));   // [64]
-    float *qrow = (float *)(masks + TA_MAX_TREE);                        // [GEN_WAVES][TA_MAX_HEAD_DIM]
-    int *flag = (int *)(qrow + GEN_WAVES * TA_MAX_HEAD_DIM);             // flag[4], then par_s[TA_MAX_TREE]
+    int *flag = (int *)(masks + TA_MAX_TREE);                            // flag[4], then par_s[TA_MAX_TREE]
     int *par_s = flag + 4;
+    float *qrow = (float *)(par_s + TA_MAX_TREE);                        // [GEN_WAVES * GEN_RB][D]
+    float *kt = qrow + GEN_WAVES * GEN_RB * p.D;                         // [64][D + 1]: a lane reads its token's row
+    float *vt = kt + TA_TILE * (p.D + 1);                                // [64][D]
+    const int ldk = p.D + 1;
 
     ta_build_schedule(p, cum);
     const int total = p.Hkv * cum[p.B];
@@ -58,91 +66,168 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                     atomicOr(p.status, TA_STATUS_BAD_PARENT);
             }
         }
-        for (int r = wave; r < rows_here; r += GEN_WAVES) {
-            const int R = rg * p.rows_grp + r;
-            const int node = R / p.G, h = g * p.G + R % p.G;
-            const int64_t wrow = ta_ws_row(p, slot, rg, r);
-            if (poison) {
-                for (int d = lane; d < p.D; d += TA_WAVE)
-                    p.ws_o[wrow * p.D + d] = 0.f;
-                if (lane == 0)
-                    p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
-                continue;
-            }
-            float *qs = qrow + wave * TA_MAX_HEAD_DIM;
-            const int64_t qoff = (int64_t)b * p.q_sb + (int64_t)node * p.q_st + (int64_t)h * p.q_sh;
-            for (int d = lane; d < p.D; d += TA_WAVE)
-                qs[d] = load_elem<BF16>(p.q, qoff + d);
-            __builtin_amdgcn_wave_barrier();
-            const unsigned long long mask = has_tree_tile ? masks[node] : 0ull;
-            float m = -INFINITY, l = 0.f;
-            float acc[GEN_DCHUNKS];
+        for (int r0 = 0; r0 < rows_here; r0 += GEN_WAVES * GEN_RB) {
+            int rr[GEN_RB];
+            bool rok[GEN_RB];
+            unsigned long long mask[GEN_RB];
+            float m[GEN_RB], l[GEN_RB], acc[GEN_RB][GEN_DCHUNKS];
 #pragma unroll
-            for (int c = 0; c < GEN_DCHUNKS; ++c)
-                acc[c] = 0.f;
-            for (int j = j0; j < j1; ++j) {
-                const bool tree_tile = (j == n_b - 1);
-                bool valid;
-                int pos;
-                if (tree_tile) {
-                    valid = lane < p.T && ((mask >> lane) & 1ull);
-                    pos = L + lane;
-                } else {
-                    pos = j * TA_TILE + lane;
-                    valid = pos < L;
-                }
-                float s = -INFINITY;
-                int64_t voff = 0;
-                if (valid) {
-                    const int64_t koff = ta_cache_offset(p, b, g, pos, p.k_sp, p.k_sh, p.k_ss);
-                    voff = ta_cache_offset(p, b, g, pos, p.v_sp, p.v_sh, p.v_ss);
-                    float dot = 0.f;
-                    for (int d = 0; d < p.D; ++d)
-                        dot = fmaf(qs[d], load_elem<BF16>(p.k, koff + d), dot);
-                    s = dot * p.scale_log2e;
-                }
-                const float m_new = fmaxf(m, ta_wave_max(s));       // finite: every tile has a valid token
-                const float alpha = exp2f(m - m_new);
-                const float pr = valid ? exp2f(s - m_new) : 0.f;
-                l = l * alpha + ta_wave_sum(pr);
-                m = m_new;
+            for (int i = 0; i < GEN_RB; ++i) {
+                rr[i] = r0 + wave * GEN_RB + i;
+                rok[i] = rr[i] < rows_here;
+                m[i] = -INFINITY;
+                l[i] = 0.f;
 #pragma unroll
                 for (int c = 0; c < GEN_DCHUNKS; ++c)
-                    acc[c] *= alpha;
-                for (int jj = 0; jj < TA_TILE; ++jj) {
-                    const float pj = __shfl(pr, jj, TA_WAVE);
-                    if (pj == 0.f)
+                    acc[i][c] = 0.f;
+                mask[i] = 0ull;
+            }
+            if (poison) {
+#pragma unroll
+                for (int i = 0; i < GEN_RB; ++i) {
+                    if (!rok[i])
+                        continue;
+                    const int64_t wrow = ta_ws_row(p, slot, rg, rr[i]);
+                    for (int d = lane; d < p.D; d += TA_WAVE)
+                        p.ws_o[wrow * p.D + d] = 0.f;
+                    if (lane == 0)
+                        p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
+                }
+                continue;
+            }
+#pragma unroll
+            for (int i = 0; i < GEN_RB; ++i) {
+                if (!rok[i])
+                    continue;
+                const int R = rg * p.rows_grp + rr[i];
+                const int node = R / p.G, h = g * p.G + R % p.G;
+                const int64_t qoff = (int64_t)b * p.q_sb + (int64_t)node * p.q_st + (int64_t)h * p.q_sh;
+                float *qs = qrow + (wave * GEN_RB + i) * p.D;
+                for (int d = lane; d < p.D; d += TA_WAVE)
+                    qs[d] = load_elem<BF16>(p.q, qoff + d);
+                mask[i] = has_tree_tile ? masks[node] : 0ull;
+            }
+            for (int j = j0; j < j1; ++j) {
+                const bool tree_tile = (j == n_b - 1);
+                __syncthreads();                                     // the previous tile has been consumed
+                // wave w stages tokens 16w .. 16w+15, GEN_TB at a time with all their loads in flight together
+                for (int tk0 = wave * (TA_TILE / GEN_WAVES); tk0 < (wave + 1) * (TA_TILE / GEN_WAVES); tk0 += GEN_TB) {
+                    float kvv[GEN_TB][GEN_DCHUNKS], vvv[GEN_TB][GEN_DCHUNKS];
+#pragma unroll
+                    for (int u = 0; u < GEN_TB; ++u) {
+                        const int tk = tk0 + u;
+                        const int pos = tree_tile ? L + tk : j * TA_TILE + tk;
+                        const bool exists = tree_tile ? tk < p.T : pos < L;
+                        const int64_t koff = exists ? ta_cache_offset(p, b, g, pos, p.k_sp, p.k_sh, p.k_ss) : 0;
+                        const int64_t voff = exists ? ta_cache_offset(p, b, g, pos, p.v_sp, p.v_sh, p.v_ss) : 0;
+#pragma unroll
+                        for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                            const int d = lane + c * TA_WAVE;
+                            const bool ld = exists && d < p.D;
+                            kvv[u][c] = ld ? load_elem<BF16>(p.k, koff + d) : 0.f;
+                            vvv[u][c] = ld ? load_elem<BF16>(p.v, voff + d) : 0.f;
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < GEN_TB; ++u)
+#pragma unroll
+                        for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                            const int d = lane + c * TA_WAVE;
+                            if (d < p.D) {
+                                kt[(tk0 + u) * ldk + d] = kvv[u][c];
+                                vt[(tk0 + u) * p.D + d] = vvv[u][c];
+                            }
+                        }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < GEN_RB; ++i) {
+                    if (!rok[i])
                         continue;                                    // wave-uniform
-                    const int64_t vj = ((int64_t)__shfl((int)(voff >> 32), jj, TA_WAVE) << 32) |
-                                       (uint32_t)__shfl((int)(voff & 0xffffffff), jj, TA_WAVE);
+                    const float *qs = qrow + (wave * GEN_RB + i) * p.D;
+                    const bool valid = tree_tile ? (lane < p.T && ((mask[i] >> lane) & 1ull)) : (j * TA_TILE + lane < L);
+                    // q[d] comes out of the lane that holds it (scalar operand), K from the lane's token row in LDS
+                    float qreg[GEN_DCHUNKS];
+#pragma unroll
+                    for (int c = 0; c < GEN_DCHUNKS; ++c)
+                        qreg[c] = lane + c * TA_WAVE < p.D ? qs[lane + c * TA_WAVE] : 0.f;
+                    float dot4[4] = {0.f, 0.f, 0.f, 0.f};
+                    const float *kr = kt + lane * ldk;
 #pragma unroll
                     for (int c = 0; c < GEN_DCHUNKS; ++c) {
-                        const int d = lane + c * TA_WAVE;
-                        if (d < p.D)
-                            acc[c] = fmaf(pj, load_elem<BF16>(p.v, vj + d), acc[c]);
+                        const int dn = min(TA_WAVE, p.D - c * TA_WAVE);          // columns of this chunk
+                        int dd = 0;
+                        for (; dd + 4 <= dn; dd += 4) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                dot4[e] = fmaf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(qreg[c]), dd + e)),
+                                               kr[c * TA_WAVE + dd + e], dot4[e]);
+                        }
+                        for (; dd < dn; ++dd)
+                            dot4[0] = fmaf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(qreg[c]), dd)),
+                                           kr[c * TA_WAVE + dd], dot4[0]);
+                    }
+                    const float dot = (dot4[0] + dot4[1]) + (dot4[2] + dot4[3]);
+                    const float s = valid ? dot * p.scale_log2e : -INFINITY;
+                    const float m_new = fmaxf(m[i], ta_wave_max(s));  // finite: every tile has a valid token
+                    const float alpha = exp2f(m[i] - m_new);
+                    const float pr = valid ? exp2f(s - m_new) : 0.f;
+                    l[i] = l[i] * alpha + ta_wave_sum(pr);
+                    m[i] = m_new;
+#pragma unroll
+                    for (int c = 0; c < GEN_DCHUNKS; ++c)
+                        acc[i][c] *= alpha;
+#pragma unroll 4
+                    for (int jj = 0; jj < TA_TILE; ++jj) {
+                        const float pj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), jj));   // scalar
+#pragma unroll
+                        for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                            const int d = lane + c * TA_WAVE;
+                            if (d < p.D)
+                                acc[i][c] = fmaf(pj, vt[jj * p.D + d], acc[i][c]);
+                        }
                     }
                 }
             }
-            const float inv = 1.f / l;
 #pragma unroll
-            for (int c = 0; c < GEN_DCHUNKS; ++c) {
-                const int d = lane + c * TA_WAVE;
-                if (d < p.D)
-                    p.ws_o[wrow * p.D + d] = acc[c] * inv;
+            for (int i = 0; i < GEN_RB; ++i) {
+                if (!rok[i])
+                    continue;
+                const int64_t wrow = ta_ws_row(p, slot, rg, rr[i]);
+                const float inv = 1.f / l[i];
+#pragma unroll
+                for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                    const int d = lane + c * TA_WAVE;
+                    if (d < p.D)
+                        p.ws_o[wrow * p.D + d] = acc[i][c] * inv;
+                }
+                if (lane == 0)
+                    p.ws_lse[wrow] = m[i] + log2f(l[i]);
             }
-            if (lane == 0)
-                p.ws_lse[wrow] = m + log2f(l);
-            __builtin_amdgcn_wave_barrier();
         }
-        __syncthreads();               // masks / flag are reused by the next item
+        __syncthreads();               // masks / flag and the tiles are reused by the next item
         t = seg_start + j1;
     }
 }
 
 hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream)
 {
-    const size_t smem = sizeof(int) * ((p.B + 2) & ~1) + sizeof(unsigned long long) * TA_MAX_TREE +
-                        sizeof(float) * GEN_WAVES * TA_MAX_HEAD_DIM + 16 + sizeof(int) * TA_MAX_TREE;
+    const size_t smem = sizeof(int) * ((p.B + 2) & ~1) + sizeof(unsigned long long) * TA_MAX_TREE + 16 +
+                        sizeof(int) * TA_MAX_TREE +
+                        sizeof(float) * ((size_t)GEN_WAVES * GEN_RB * p.D + (size_t)TA_TILE * (2 * p.D + 1));
+    if (smem > 160 * 1024 - 512)
+        return hipErrorInvalidValue;
+    static bool attr_set[64][2] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return hipErrorInvalidDevice;
+    const void *fn = p.is_bf16 ? (const void *)ta_generic_kv_kernel<true> : (const void *)ta_generic_kv_kernel<false>;
+    if (!attr_set[dev][p.is_bf16 ? 1 : 0]) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+        if (e != hipSuccess)
+            return e;
+        attr_set[dev][p.is_bf16 ? 1 : 0] = true;
+    }
     dim3 grid(p.n_wg, p.n_rg);
     if (p.is_bf16)
         hipLaunchKernelGGL(ta_generic_kv_kernel<true>, grid, dim3(GEN_THREADS), smem, stream, p);
