@@ -140,52 +140,58 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                         }
                 }
                 __syncthreads();
+                // Scores of the wave's rows against the lane's token: one LDS read of K serves all rows; q[d]
+                // comes out of the lane that holds it as a scalar operand.
+                float qreg[GEN_RB][GEN_DCHUNKS], dot[GEN_RB];
 #pragma unroll
                 for (int i = 0; i < GEN_RB; ++i) {
-                    if (!rok[i])
-                        continue;                                    // wave-uniform
                     const float *qs = qrow + (wave * GEN_RB + i) * p.D;
-                    const bool valid = tree_tile ? (lane < p.T && ((mask[i] >> lane) & 1ull)) : (j * TA_TILE + lane < L);
-                    // q[d] comes out of the lane that holds it (scalar operand), K from the lane's token row in LDS
-                    float qreg[GEN_DCHUNKS];
+                    dot[i] = 0.f;
 #pragma unroll
                     for (int c = 0; c < GEN_DCHUNKS; ++c)
-                        qreg[c] = lane + c * TA_WAVE < p.D ? qs[lane + c * TA_WAVE] : 0.f;
-                    float dot4[4] = {0.f, 0.f, 0.f, 0.f};
-                    const float *kr = kt + lane * ldk;
+                        qreg[i][c] = (rok[i] && lane + c * TA_WAVE < p.D) ? qs[lane + c * TA_WAVE] : 0.f;
+                }
+                const float *kr = kt + lane * ldk;
 #pragma unroll
-                    for (int c = 0; c < GEN_DCHUNKS; ++c) {
-                        const int dn = min(TA_WAVE, p.D - c * TA_WAVE);          // columns of this chunk
-                        int dd = 0;
-                        for (; dd + 4 <= dn; dd += 4) {
+                for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                    const int dn = min(TA_WAVE, p.D - c * TA_WAVE);              // columns of this chunk (<= 0: none)
+#pragma unroll 4
+                    for (int dd = 0; dd < dn; ++dd) {
+                        const float kd = kr[c * TA_WAVE + dd];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                dot4[e] = fmaf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(qreg[c]), dd + e)),
-                                               kr[c * TA_WAVE + dd + e], dot4[e]);
-                        }
-                        for (; dd < dn; ++dd)
-                            dot4[0] = fmaf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(qreg[c]), dd)),
-                                           kr[c * TA_WAVE + dd], dot4[0]);
+                        for (int i = 0; i < GEN_RB; ++i)
+                            dot[i] = fmaf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(qreg[i][c]), dd)), kd,
+                                          dot[i]);
                     }
-                    const float dot = (dot4[0] + dot4[1]) + (dot4[2] + dot4[3]);
-                    const float s = valid ? dot * p.scale_log2e : -INFINITY;
-                    const float m_new = fmaxf(m[i], ta_wave_max(s));  // finite: every tile has a valid token
-                    const float alpha = exp2f(m[i] - m_new);
-                    const float pr = valid ? exp2f(s - m_new) : 0.f;
-                    l[i] = l[i] * alpha + ta_wave_sum(pr);
+                }
+                float pr[GEN_RB];
+#pragma unroll
+                for (int i = 0; i < GEN_RB; ++i) {
+                    const bool valid = rok[i] && (tree_tile ? (lane < p.T && ((mask[i] >> lane) & 1ull))
+                                                            : (j * TA_TILE + lane < L));
+                    const float s = valid ? dot[i] * p.scale_log2e : -INFINITY;
+                    // rows that exist always see a valid token in a tile; padding rows keep m = -inf, pr = 0
+                    const float m_new = fmaxf(m[i], ta_wave_max(s));
+                    const float alpha = rok[i] ? exp2f(m[i] - m_new) : 1.f;
+                    pr[i] = valid ? exp2f(s - m_new) : 0.f;
+                    l[i] = l[i] * alpha + ta_wave_sum(pr[i]);
                     m[i] = m_new;
 #pragma unroll
                     for (int c = 0; c < GEN_DCHUNKS; ++c)
                         acc[i][c] *= alpha;
+                }
 #pragma unroll 4
-                    for (int jj = 0; jj < TA_TILE; ++jj) {
-                        const float pj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), jj));   // scalar
+                for (int jj = 0; jj < TA_TILE; ++jj) {
+                    float vj[GEN_DCHUNKS];
 #pragma unroll
-                        for (int c = 0; c < GEN_DCHUNKS; ++c) {
-                            const int d = lane + c * TA_WAVE;
-                            if (d < p.D)
-                                acc[i][c] = fmaf(pj, vt[jj * p.D + d], acc[i][c]);
-                        }
+                    for (int c = 0; c < GEN_DCHUNKS; ++c)
+                        vj[c] = lane + c * TA_WAVE < p.D ? vt[jj * p.D + lane + c * TA_WAVE] : 0.f;
+#pragma unroll
+                    for (int i = 0; i < GEN_RB; ++i) {
+                        const float pj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr[i]), jj));  // scalar
+#pragma unroll
+                        for (int c = 0; c < GEN_DCHUNKS; ++c)
+                            acc[i][c] = fmaf(pj, vj[c], acc[i][c]);
                     }
                 }
             }
