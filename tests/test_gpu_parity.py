@@ -325,3 +325,44 @@ def test_empty_batch_and_no_lse():
     e = {k: (v[:0] if v is not None and k != "k_cache" and k != "v_cache" else v) for k, v in dev.items()}
     assert ta.tree_attn_fwd(e["q"], e["k_cache"], e["v_cache"], e["page_table"], e["seq_lens"], e["tree_parent"],
                             e["out"], e["lse"]) == 0
+
+
+def test_side_stream_and_graph_replay_follow_device_side_lengths():
+    """The call neither synchronises nor allocates once the workspace is reserved, and every length it needs is read
+    on the device: captured in a HIP graph on a side stream, replays must track seq_lens rewritten between them."""
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+    rng = np.random.default_rng(77)
+    T = 32
+    trees = np.stack([W.random_tree(T, 6, rng), W.bfs_tree(T, [4, 2], 5)])
+    lens = [[900, 2500], [64, 1], [1777, 640]]
+    big = W.make_workload("graph_big", B=2, T=T, Hq=8, Hkv=1, D=128, seq_lens=[2500, 2500], trees=trees, page_size=64,
+                          dtype="bf16", seed=4242)
+    dev = to_device(big)
+    ta.tree_attn_reserve(ta.tree_attn_workspace_bytes(big.B, big.T, big.Hq, big.Hkv, big.D, ta.TA_BF16))
+    side = torch.cuda.Stream()
+    args = (dev["q"], dev["k_cache"], dev["v_cache"], dev["page_table"], dev["seq_lens"], dev["tree_parent"], dev["out"],
+            dev["lse"])
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ta.tree_attn_fwd(*args, stream=side)               # warm-up on the side stream (sets kernel attributes)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ta.tree_attn_fwd(*args, stream=torch.cuda.current_stream())
+    for rep in range(2):
+        for L in lens:
+            # same caches and page table (capacity 2500 + T each), new prefix lengths: the oracle sees the same thing
+            w = W.make_workload("graph_case", B=2, T=T, Hq=8, Hkv=1, D=128, seq_lens=[2500, 2500], trees=trees,
+                                page_size=64, dtype="bf16", seed=4242)
+            w.seq_lens[:] = np.asarray(L, dtype=w.seq_lens.dtype)
+            ref, ref_lse = run_oracle(w)
+            dev["seq_lens"].copy_(torch.from_numpy(w.seq_lens))
+            dev["out"].fill_(float("nan"))
+            dev["lse"].fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = dev["out"].float().cpu().numpy().astype(np.float64)
+            got_lse = dev["lse"].cpu().numpy().astype(np.float64)
+            assert_parity(got, got_lse, ref, ref_lse, "bf16", "graph replay %d L=%r" % (rep, L))
