@@ -85,9 +85,9 @@ typedef struct {
 #define TA_KERNEL_AUTO 0
 #define TA_KERNEL_GENERIC 1   /* scalar fp32-accumulating kernel: any dtype, head_dim, page size */
 #define TA_KERNEL_MFMA 2      /* bf16 matrix-core kernel: head_dim 128, power-of-two page size (or contiguous) */
-#define TA_KERNEL_MFMA_BASIC 3 /* as MFMA, but 256-row groups also take the register-staged kernel that the
-                                 smaller row groups use (the library falls back to it by itself when the
-                                 pipelined 256-row kernel's LDS need exceeds one CU's, i.e. for B above ~5000) */
+#define TA_KERNEL_MFMA_BASIC 3 /* as MFMA, but with the plain register-staged matrix-core kernel instead of the
+                                 software-pipelined one (the library falls back to it by itself when the batch
+                                 is so large, B above ~2500, that its schedule does not fit beside the tiles in LDS) */
 
 typedef struct {
     float scale;              /* softmax scale; <= 0 or NaN selects 1/sqrt(head_dim) */

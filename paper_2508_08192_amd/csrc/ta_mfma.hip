@@ -8,7 +8,11 @@
 // one workgroup are merged on the fly by the running softmax, which is the same log-sum-exp merge the
 // merge pass applies across workgroups.
 //
-// Each wave owns one or two blocks of 32 rows.  Both contractions are issued in transposed form so that
+// Two kernels share this scheme: ta_mfma_sp_kernel (the one that normally runs: per-tile instruction streams
+// written in assembly, tiles loaded straight into LDS) and ta_mfma_kv_kernel (plain, compiler-scheduled,
+// register-staged tiles; the fallback).
+//
+// Each wave owns a block of 32 rows.  Both contractions are issued in transposed form so that
 // a lane owns one query row per block throughout (row statistics never leave the lane):
 //     S^T[token, row] = K[token, :] . Q[row, :]      A = K fragment (LDS),  B = Q fragment (registers)
 //     O^T[d, row]    += V^T[d, token] . P^T[token, row]   A = V^T fragment (LDS), B = P (registers)
