@@ -296,7 +296,7 @@ def fast_step_items(cur, label, helper=False):
     rest = sm[12:]
     # Loads of tile i+3: one every 20 softmax instructions from the 10th on.  The re-layout shares v[38:47]
     # with the V fragment addresses and the page lookup, so it starts once the last PV read is out (MFMA 11).
-    ri, started, di = 0, False, 0
+    ri, started, di, ring_at = 0, False, 0, 0
     if helper:
         for x in dma:
             aux += [dict(t=y) for y in x]
@@ -311,13 +311,26 @@ def fast_step_items(cur, label, helper=False):
             for it in rl_reads:
                 aux.append(dict(it, mf=11))
             started = True
+            ring_at = len(aux) + 24                # ring bookkeeping: after the last use of every ring position
         elif started and (j - 50) % 4 == 0 and ri < len(relay):
             aux.append(dict(relay[ri], mf=11))
             ri += 1
     assert started and di == 4
     for it in relay[ri:]:
         aux.append(dict(it, mf=11))
-    aux += [dict(t=x) for x in rings]
+    if helper:
+        aux += [dict(t=x) for x in rings]
+    else:
+        # spread through the second half of the block, one scalar instruction after every fourth other one
+        # (a compare and the select that reads its SCC stay neighbours: other scalar work writes SCC too)
+        k, i = ring_at, 0
+        while i < len(rings):
+            grp = rings[i:i + 2] if rings[i].startswith("s_cmp") else rings[i:i + 1]
+            at = min(k, len(aux))
+            for x in reversed(grp):
+                aux.insert(at, dict(t=x))
+            i += len(grp)
+            k += 4 + len(grp)
 
     seq = [] if helper else [dict(t="s_nop 3")] + [dict(t=t.replace("%[sva]", "%[vp]").replace("%[ska]", "%[kn]"))
                                                    for t in address_setup(True, True)]
