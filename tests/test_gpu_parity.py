@@ -366,3 +366,23 @@ def test_side_stream_and_graph_replay_follow_device_side_lengths():
             got = dev["out"].float().cpu().numpy().astype(np.float64)
             got_lse = dev["lse"].cpu().numpy().astype(np.float64)
             assert_parity(got, got_lse, ref, ref_lse, "bf16", "graph replay %d L=%r" % (rep, L))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_against_oracle(seed):
+    """Seeded random geometry: tree size, GQA group, page size, prefix lengths around tile and page edges, splits."""
+    rng = np.random.default_rng(9000 + seed)
+    T = int(rng.choice([1, 2, 5, 8, 16, 27, 32, 64]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hkv = int(rng.choice([1, 2]))
+    B = int(rng.integers(1, 4))
+    ps = int(rng.choice([0, 16, 64, 128, 256]))
+    edges = [0, 1, 63, 64, 65, 127, 128, 129, 191, 192, 193, 255, 256, 257, 320, 447, 448, 449, 511, 512, 513, 640,
+             700, 1023, 1024, 1025, 1500]
+    seq_lens = [int(rng.choice(edges)) for _ in range(B)]
+    trees = np.stack([W.random_tree(T, int(rng.integers(2, 8)), rng) for _ in range(B)])
+    splits = int(rng.choice([0, 0, 1, 2, 3, 5]))
+    w = W.make_workload("rand%d" % seed, B=B, T=T, Hq=G * Hkv, Hkv=Hkv, D=128, seq_lens=seq_lens, trees=trees,
+                        page_size=ps, dtype="bf16", seed=9100 + seed, paged=ps > 0)
+    _check(w, "random seed=%d T=%d G=%d Hkv=%d B=%d ps=%d L=%r splits=%d" % (seed, T, G, Hkv, B, ps, seq_lens, splits),
+           kernel=MFMA, num_splits=splits)
