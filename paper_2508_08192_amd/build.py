@@ -37,8 +37,49 @@ def build_library(verbose=False, extra_flags=()):
         raise RuntimeError("hipcc failed:\n" + log)
     if verbose and log.strip():
         print(log)
+    try:
+        verify_register_partition(verbose)
+    except Exception:
+        os.remove(tmp)
+        raise
     os.replace(tmp, LIB)
     return LIB
+
+
+def verify_register_partition(verbose=False):
+    """ta_mfma_sp_kernel keeps its large operands in v32..v255, which only its asm blocks may touch: the compiler
+    is confined to v0..v31 by amdgpu_num_vgpr.  That contract is checked here on the generated ISA rather than
+    trusted: outside the asm blocks no VGPR above v31 may appear, and the kernel must be sized for 256 VGPRs."""
+    import re
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in FLAGS if f not in ("-fPIC", "-shared")]
+    if os.environ.get("TREEATTN_TUNING"):
+        flags.append("-DTA_TUNING")
+    cmd = [hipcc] + flags + ["-S", "--cuda-device-only", "-o", "-", os.path.join(CSRC, "ta_mfma.hip")]
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc -S failed for ta_mfma.hip")
+    lines = proc.stdout.split("\n")
+    try:
+        start = next(i for i, l in enumerate(lines) if l.startswith("_Z17ta_mfma_sp_kernel"))
+    except StopIteration:
+        raise RuntimeError("ta_mfma_sp_kernel not found in the ISA")
+    end = next(i for i in range(start, len(lines)) if ".end_amdhsa_kernel" in lines[i])
+    in_asm, worst = False, -1
+    for l in lines[start:end]:
+        if "#ASMSTART" in l:
+            in_asm = True
+        elif "#ASMEND" in l:
+            in_asm = False
+        elif not in_asm and not l.lstrip().startswith((";", ".")):
+            for m in re.finditer(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]", l):
+                worst = max(worst, int(m.group(1) or m.group(3)))
+    sized = any(".amdhsa_next_free_vgpr 256" in l for l in lines[start:end])
+    if worst > 31 or not sized:
+        raise RuntimeError("register partition of ta_mfma_sp_kernel broken: compiler code uses v%d (limit v31), "
+                           "kernel sized for 256 VGPRs: %s" % (worst, sized))
+    if verbose:
+        print("ta_mfma_sp_kernel: compiler code stays in v0..v%d; kernel sized for 256 VGPRs" % worst)
 
 
 if __name__ == "__main__":
