@@ -436,11 +436,16 @@ def helpers():
                 lines.append("v_cndmask_b32 %s, %s, %s, vcc" % (v(base + 16 * tb + i), v(base + 16 * tb + i), v(TMP)))
         out.append(emit("sp_mask_" + cur, ["uint32_t lo", "uint32_t hi"], lines, [], ['[lo] "v"(lo)', '[hi] "v"(hi)'],
                         ['"memory"', '"vcc"']))
-    for db in range(4):
-        lines = (["s_nop 15", "s_nop 7"] if db == 0 else []) + \
-                ["v_mul_f32 %%%d, %%[inv], %s" % (k, v(O + 16 * db + k)) for k in range(16)]
-        out.append(emit("sp_get_o%d" % db, ["float inv", "float (&o)[16]"], lines, ['"=&v"(o[%d])' % k for k in range(16)],
-                        ['[inv] "v"(inv)'], ['"memory"']))
+    # Epilogue: O *= inv in place, then each lane's sixteen 16-byte pieces go to the row-major staging block in LDS;
+    # piece c of the lane lives at byte address a0 ^ (c << 5) (the caller folds the row, the lane half and the
+    # chunk swizzle into a0).
+    lines = ["s_nop 15", "s_nop 7"] + ["v_mul_f32 %s, %%[inv], %s" % (v(O + k), v(O + k)) for k in range(64)]
+    for c in range(16):
+        t = v(TMP + (c & 3))
+        lines.append("v_xor_b32 %s, 0x%x, %%[a0]" % (t, c << 5))
+        lines.append("ds_write_b128 %s, v[%d:%d]" % (t, O + 4 * c, O + 4 * c + 3))
+    lines.append("s_waitcnt lgkmcnt(0)")
+    out.append(emit("sp_put_o", ["float inv", "uint32_t a0"], lines, [], ['[inv] "v"(inv)', '[a0] "v"(a0)'], ['"memory"']))
     return "\n\n".join(out)
 
 

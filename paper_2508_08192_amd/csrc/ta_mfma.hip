@@ -598,7 +598,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         int par_v = -1, pg_v = 0, page0 = 0, pages0 = 0;
         if (!poison) {
             if (has_tree_tile && tid < p.T)
-                par_v = p.parent[(int64_t)b * p.par_sb + tid];
+                par_v = p.parent[(int64_t)b * p.par_sb + fresh_tid()];
             if (paged) {
                 const int ns0 = min(span_tiles, n);
                 page0 = tile_pos0(0) >> p.ps_shift;
@@ -607,7 +607,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     pg_v = p.page_table[(int64_t)b * p.pt_sb + page0 + tid];
             }
         }
-        const int row = wave * 32 + r32;
+        // (lane roles inside an item come from fresh_tid(): nothing lane-dependent is carried from item to item)
+        const int xl = fresh_tid();
+        const int row = (xl >> 6) * 32 + (xl & 31), hfl = (xl >> 5) & 1;
         const bool row_ok = row < rows_here;
         // A wave whose 32 rows all lie beyond the row group (T*G < 256) computes nothing; it still loads and
         // re-lays out its share of every tile and takes part in every barrier.
@@ -616,9 +618,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         auto write_poison = [&]() {                        // a NaN log-sum-exp poisons the rows in the merge
             if (row_ok) {
                 const int64_t wrow = ta_ws_row(p, slot, rg, row);
-                for (int d = hf * 64; d < hf * 64 + 64; d += 4)
+                for (int d = hfl * 64; d < hfl * 64 + 64; d += 4)
                     *(float4 *)(p.ws_o + wrow * MF_D + d) = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (hf == 0)
+                if (hfl == 0)
                     p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
             }
         };
@@ -633,7 +635,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             // Q fragments of this lane's row into their fixed registers, 16 dwords at a time
             const int R = rg * p.rows_grp + row;
             const uint16_t *qp = (const uint16_t *)p.q + (int64_t)b * p.q_sb + (int64_t)(R / p.G) * p.q_st +
-                                 (int64_t)(g * p.G + R % p.G) * p.q_sh + hf * 8;
+                                 (int64_t)(g * p.G + R % p.G) * p.q_sh + hfl * 8;
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 uint32_t x[16];
@@ -904,23 +906,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             if (active) {
                 const float inv = 1.f / l2_tot;
                 char *stage = smem + wv * 16384;
-                float o[16];
-                auto put = [&](int db) {
-#pragma unroll
-                    for (int i4 = 0; i4 < 4; ++i4) {
-                        const int chunk = 8 * db + 2 * i4 + h;
-                        *(float4 *)(stage + r32_ * 512 + ((chunk ^ r32_) << 4)) =
-                            make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
-                    }
-                };
-                sp_get_o0(inv, o);
-                put(0);
-                sp_get_o1(inv, o);
-                put(1);
-                sp_get_o2(inv, o);
-                put(2);
-                sp_get_o3(inv, o);
-                put(3);
+                // chunk (2 c + h) ^ r32_ of row r32_:  the c-dependent part is an XOR on address bits 5..8
+                sp_put_o(inv, lds0 + (uint32_t)(wv * 16384 + r32_ * 512 + ((h ^ r32_) << 4)));
                 __builtin_amdgcn_wave_barrier();
                 const int rw0 = wv * 32;
 #pragma unroll 4
