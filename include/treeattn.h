@@ -93,7 +93,10 @@ typedef struct {
     float scale;              /* softmax scale; <= 0 or NaN selects 1/sqrt(head_dim) */
     int32_t num_splits;       /* 0 = automatic; n > 0 = cut the batch's KV work into at most n workgroup shares */
     int32_t kernel;           /* TA_KERNEL_* */
-    int32_t reserved;         /* must be 0 */
+    int32_t item_cost;        /* 0 = automatic.  n > 0: when the KV work is cut into workgroup shares, every
+                                 (request, KV head) list counts n - 1 tiles more than it holds, which stands for
+                                 the fixed work a workgroup spends per list it touches (1 = none).  Results do
+                                 not depend on it beyond the order of the fp32 merge. */
     void *workspace;          /* device scratch, 256-byte aligned, or NULL = library-owned per-device buffer */
     size_t workspace_bytes;   /* size of `workspace` */
     void *events[3];          /* optional hipEvent_t handles (HOST values) recorded on `stream`: [0] before the

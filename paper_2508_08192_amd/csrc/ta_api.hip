@@ -113,16 +113,17 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
             (pt && !pt->data) || (lse && !lse->data))
             return TA_ERR_NULL;
     }
-    int kernel = TA_KERNEL_AUTO, num_splits = 0;
+    int kernel = TA_KERNEL_AUTO, num_splits = 0, item_cost = 0;
     float scale = 0.f;
     void *user_ws = nullptr;
     size_t user_ws_bytes = 0;
     if (opts) {
-        if (opts->reserved != 0 || opts->num_splits < 0 || opts->kernel < TA_KERNEL_AUTO ||
+        if (opts->item_cost < 0 || opts->item_cost > 4096 || opts->num_splits < 0 || opts->kernel < TA_KERNEL_AUTO ||
             opts->kernel > TA_KERNEL_MFMA_BASIC)
             return TA_ERR_OPTS;
         kernel = opts->kernel;
         num_splits = opts->num_splits;
+        item_cost = opts->item_cost;
         scale = opts->scale;
         user_ws = opts->workspace;
         user_ws_bytes = opts->workspace_bytes;
@@ -175,8 +176,13 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
 
     Plan &pl = pr->plan;
     pl.kernel = kernel;
+    // Fixed work per (workgroup, list) overlap, in tiles' worth of time: finding the list, the tree masks, Q, the
+    // first loads' round trip, and writing the partial result.  Measured on the pipelined kernel at about 15 us
+    // against 1.3 to 2.3 us per tile; the register-staged and the scalar kernel have less to set up.
+    const int pad = item_cost > 0 ? item_cost - 1 : (kernel == TA_KERNEL_MFMA ? (basic ? 2 : 8) : 0);
+    p.pad = pad;
     const int64_t tiles_cap = (int64_t)B * Hkv * ((capacity - T + TA_TILE - 1) / TA_TILE + 1);
-    if (tiles_cap > INT32_MAX)
+    if (tiles_cap + (int64_t)B * Hkv * pad > INT32_MAX)     // schedule units are counted in 32 bits
         return TA_ERR_SHAPE;
     if (kernel == TA_KERNEL_MFMA) {
         pl.rows_grp = mfma_rows_group(p.rows);

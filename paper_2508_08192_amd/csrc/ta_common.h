@@ -36,6 +36,7 @@ struct TAParams {
     int32_t n_rg;              // row groups
     int32_t n_wg;              // workgroups of the KV pass along x
     int32_t min_q;             // smallest share of tiles a workgroup takes
+    int32_t pad;               // schedule units a list counts on top of its tiles (fixed cost per list)
     int32_t is_bf16;
     float scale_log2e;         // softmax scale * log2(e): scores are kept in the base-2 domain
     float *ws_o;               // partial outputs  [slot][rg][rows_grp][D], normalised, fp32
@@ -77,14 +78,19 @@ __device__ __forceinline__ int ta_request_tiles(const TAParams &p, int b)
     return ta_request_ok(p, L) ? (L + TA_TILE - 1) / TA_TILE + 1 : 1;
 }
 
-// cum[0..B]: exclusive prefix sums of the per-request tile counts.  Needs blockDim.x >= 64; ends
+// The KV work of the batch is one line of schedule units: request after request, KV head after KV head, and
+// per (request, KV head) list first p.pad units that stand for the list's fixed cost, then one unit per tile
+// (prefix tiles, then the tree tile).  Workgroup w takes units [w * share, (w + 1) * share); a workgroup
+// whose range touches only the padding of a list has no work in it and writes no partial result.
+//
+// cum[0..B]: exclusive prefix sums of the per-request unit counts (per KV head).  Needs blockDim.x >= 64; ends
 // with a barrier.  If `lens` is given, it also receives the B prefix lengths as they were read.
 __device__ __forceinline__ void ta_build_schedule(const TAParams &p, int *cum, int *lens = nullptr)
 {
     const int tid = threadIdx.x;
     for (int b = tid; b < p.B; b += blockDim.x) {
         const int L = p.seq_lens[(int64_t)b * p.sl_s];
-        cum[b + 1] = ta_request_ok(p, L) ? (L + TA_TILE - 1) / TA_TILE + 1 : 1;
+        cum[b + 1] = (ta_request_ok(p, L) ? (L + TA_TILE - 1) / TA_TILE + 1 : 1) + p.pad;
         if (lens)
             lens[b] = L;
     }

@@ -48,11 +48,14 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
 
     while (t < t_end) {
         const int b = ta_find_request(p, cum, t);
-        const int n_b = cum[b + 1] - cum[b];
-        const int g = (t - p.Hkv * cum[b]) / n_b;
-        const int seg_start = p.Hkv * cum[b] + g * n_b;
-        const int j0 = t - seg_start;
+        const int n_u = cum[b + 1] - cum[b];                       // schedule units of one list of request b
+        const int g = (t - p.Hkv * cum[b]) / n_u;
+        const int seg_start = p.Hkv * cum[b] + g * n_u + p.pad;    // unit of the list's tile 0
+        const int n_b = n_u - p.pad;
+        const int j0 = max(0, t - seg_start);
         const int j1 = min(n_b, t_end - seg_start);
+        if (j1 <= j0)
+            break;                                                 // the share ends inside the list's padding
         const int slot = w + b * p.Hkv + g;
         const int L = p.seq_lens[(int64_t)b * p.sl_s];
         bool poison = !ta_request_ok(p, L);
@@ -256,8 +259,9 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
     const int seg = blockIdx.x;
     const int b = seg / p.Hkv, g = seg % p.Hkv;
     const int lane = threadIdx.x % TA_WAVE, wave = threadIdx.x / TA_WAVE;
-    const int n_b = cum[b + 1] - cum[b];
-    const int seg_start = p.Hkv * cum[b] + g * n_b;
+    const int n_u = cum[b + 1] - cum[b];
+    const int seg_start = p.Hkv * cum[b] + g * n_u + p.pad;
+    const int n_b = n_u - p.pad;
     const int w_first = seg_start / share;
     const int n_parts = (seg_start + n_b - 1) / share - w_first + 1;
     const float LN2 = 0.6931471805599453f;

@@ -241,12 +241,15 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
     while (t < t_end) {
         // the schedule comes out of LDS, which the compiler treats as lane-varying: pin it to SGPRs
         const int b = __builtin_amdgcn_readfirstlane(ta_find_request(p, cum, t));
-        const int n_b = __builtin_amdgcn_readfirstlane(cum[b + 1] - cum[b]);
+        const int n_u = __builtin_amdgcn_readfirstlane(cum[b + 1] - cum[b]);   // schedule units of one list
         const int cum_b = __builtin_amdgcn_readfirstlane(cum[b]);
-        const int g = (t - p.Hkv * cum_b) / n_b;
-        const int seg_start = p.Hkv * cum_b + g * n_b;
-        const int j0 = t - seg_start;
+        const int g = (t - p.Hkv * cum_b) / n_u;
+        const int seg_start = p.Hkv * cum_b + g * n_u + p.pad;                 // unit of the list's tile 0
+        const int n_b = n_u - p.pad;
+        const int j0 = max(0, t - seg_start);
         const int j1 = min(n_b, t_end - seg_start);
+        if (j1 <= j0)
+            break;                                                             // the share ends inside the padding
         const int slot = w + b * p.Hkv + g;
         const int L = __builtin_amdgcn_readfirstlane(p.seq_lens[(int64_t)b * p.sl_s]);
         bool poison = !ta_request_ok(p, L);
@@ -573,12 +576,15 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
 
     while (t < t_end) {
         const int b = __builtin_amdgcn_readfirstlane(ta_find_request(p, cum, t));
-        const int n_b = __builtin_amdgcn_readfirstlane(cum[b + 1] - cum[b]);
+        const int n_u = __builtin_amdgcn_readfirstlane(cum[b + 1] - cum[b]);   // schedule units of one list
         const int cum_b = __builtin_amdgcn_readfirstlane(cum[b]);
-        const int g = (t - p.Hkv * cum_b) / n_b;
-        const int seg_start = p.Hkv * cum_b + g * n_b;
-        const int j0 = t - seg_start;
+        const int g = (t - p.Hkv * cum_b) / n_u;
+        const int seg_start = p.Hkv * cum_b + g * n_u + p.pad;                 // unit of the list's tile 0
+        const int n_b = n_u - p.pad;
+        const int j0 = max(0, t - seg_start);
         const int j1 = min(n_b, t_end - seg_start);
+        if (j1 <= j0)
+            break;                                                             // the share ends inside the padding
         const int n = j1 - j0;
         const int slot = w + b * p.Hkv + g;
         const int L = __builtin_amdgcn_readfirstlane(lens[b]);

@@ -41,7 +41,7 @@ class ta_opts(ctypes.Structure):
         ("scale", ctypes.c_float),
         ("num_splits", ctypes.c_int32),
         ("kernel", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("item_cost", ctypes.c_int32),
         ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t),
         ("events", ctypes.c_void_p * 3),
@@ -146,12 +146,12 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def _opts(scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None):
+def _opts(scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None, item_cost=0):
     o = ta_opts()
     o.scale = 0.0 if scale is None else float(scale)
     o.num_splits = int(num_splits)
     o.kernel = int(kernel)
-    o.reserved = 0
+    o.item_cost = int(item_cost)
     if workspace is not None:
         o.workspace = workspace.data_ptr()
         o.workspace_bytes = workspace.numel() * workspace.element_size()
@@ -179,10 +179,11 @@ def tree_attn_fwd(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, l
 
 
 def tree_attn_fwd_ex(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse=None, stream=None,
-                     scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None, check=True):
+                     scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None, check=True,
+                     item_cost=0):
     """include/treeattn.h: tree_attn_fwd_ex.  `events`: up to three hipEvent_t handles (ctypes.c_void_p)."""
     ds = [_desc(x) for x in (q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse)]
-    o = _opts(scale, num_splits, kernel, workspace, events)
+    o = _opts(scale, num_splits, kernel, workspace, events, item_cost)
     rc = load_library().tree_attn_fwd_ex(*[_ref(d) for d in ds], _stream_ptr(stream) if stream != 0 else None,
                                          ctypes.byref(o))
     if check and rc != TA_OK:

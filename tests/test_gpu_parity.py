@@ -161,6 +161,23 @@ def test_result_does_not_depend_on_the_split(kernel):
         assert_parity(got, got_lse, ref, ref_lse, "bf16", "num_splits=%d" % n)
 
 
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA, MFMA_BASIC])
+def test_result_does_not_depend_on_the_per_list_cost_of_the_schedule(kernel):
+    """Shares are cut over tiles plus a fixed number of units per list; shares that end inside a list's padding,
+    lists shorter than the padding and shares longer than several lists all have to give the same result."""
+    rng = np.random.default_rng(17)
+    T = 12
+    trees = np.stack([W.random_tree(T, 4, rng) for _ in range(6)])
+    w = W.make_workload("item_cost", B=6, T=T, Hq=8, Hkv=2, D=128, seq_lens=[900, 0, 64, 2100, 5, 130], trees=trees,
+                        page_size=64, dtype="bf16", seed=1701)
+    ref, ref_lse = run_oracle(w)
+    dev = to_device(w)
+    for cost, n in [(1, 0), (2, 5), (4, 0), (9, 7), (9, 0), (40, 3), (40, 0), (300, 11), (4096, 0)]:
+        _announce("item_cost=%d num_splits=%d kernel=%d" % (cost, n, kernel))
+        got, got_lse = run_hip(w, dev, kernel=kernel, num_splits=n, item_cost=cost)
+        assert_parity(got, got_lse, ref, ref_lse, "bf16", "item_cost=%d num_splits=%d" % (cost, n))
+
+
 @pytest.mark.parametrize("kernel", [GENERIC, MFMA])
 def test_non_topological_node_numbering_and_forest(kernel):
     rng = np.random.default_rng(8)
