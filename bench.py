@@ -93,7 +93,7 @@ def cpu_baseline(w, budget_s, log):
                       "scaled by %d/%d" % (n, total, dt, total, n)}
 
 
-def measure(w, steps, warmup, log, num_splits=0, kernel=0, rotate=0, check=False):
+def measure(w, steps, warmup, log, num_splits=0, kernel=0, rotate=0, check=False, item_cost=0):
     """Times `steps` verify steps of workload w (after `warmup` untimed ones).  Returns a dict with the step
     time, per-kernel times from HIP events recorded inside the timed region, and roofline figures."""
     import numpy as np
@@ -130,7 +130,7 @@ def measure(w, steps, warmup, log, num_splits=0, kernel=0, rotate=0, check=False
         k, v = pools[i % n_pools]
         ta.tree_attn_fwd_ex(dev["q"], k, v, dev["page_table"], dev["seq_lens"], dev["tree_parent"], dev["out"],
                             dev["lse"], stream=stream, scale=w.scale, num_splits=num_splits, kernel=kernel,
-                            events=events)
+                            events=events, item_cost=item_cost)
 
     if check:
         import oracle
@@ -185,6 +185,7 @@ def main():
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0)
+    ap.add_argument("--item-cost", type=int, default=0, help="ta_opts.item_cost (0 = the library's choice)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="wall-time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--rotate", type=int, default=0,
                     help="distinct KV pools to cycle through (0 = enough to exceed the 256 MB last-level cache)")
@@ -223,7 +224,8 @@ def main():
     t0 = time.time()
     w = W.make_config(WORKLOADS[args.workload])
     log("workload %s generated in %.1f s" % (w.name, time.time() - t0))
-    m = measure(w, args.steps, args.warmup, log, args.num_splits, args.kernel, args.rotate, args.check)
+    m = measure(w, args.steps, args.warmup, log, args.num_splits, args.kernel, args.rotate, args.check,
+                args.item_cost)
     ms_per_step, kv_us, plan = m["ms_per_step"], m["kv_us"], m["plan"]
     alg_bytes, kv_alg, flops = m["alg_bytes"], m["kv_alg"], m["flops"]
 

@@ -20,8 +20,8 @@ softmax addresses single registers of the score and probability tuples, which as
   v[32:35] lane constants: LDS offsets of the lane's V fragments, K fragments, re-layout reads and writes
   v[36:37] K fragment address and re-layout write address of the current block
 
-Small helpers move values between the two worlds: sp_zero_o, sp_set_q_lo/hi, sp_set_bases, sp_get_rl, sp_scale_o,
-sp_mask_A/B, sp_get_o0..3.
+Small helpers move values between the two worlds: sp_zero_o, sp_load_q, sp_set_bases, sp_get_rl, sp_scale_o,
+sp_mask_A/B, sp_put_o.
 
 S^T(i) and S^T(i+1) alternate between buffers A and B, so every block exists in an "A current" and a "B current"
 flavour.  P has one buffer: the PV MFMAs, which read P(i-1), come first in program order and the conversion that
@@ -415,9 +415,10 @@ def helpers():
     out = []
     # O = 0.  Naming v255 as clobbered makes the compiler size the kernel's register file for all 256 VGPRs.
     out.append(emit("sp_zero_o", [], ["v_mov_b32 %s, 0" % v(O + k) for k in range(64)], [], [], ['"memory"', '"v255"']))
-    for half, name in ((0, "sp_set_q_lo"), (1, "sp_set_q_hi")):
-        lines = ["v_mov_b32 %s, %%%d" % (v(Q + 16 * half + k), k) for k in range(16)]
-        out.append(emit(name, ["const uint32_t (&x)[16]"], lines, [], ['"v"(x[%d])' % k for k in range(16)], ['"memory"']))
+    # Q of the lane's row straight from global memory into its registers: eight 16-byte pieces, 32 bytes apart.
+    # Nothing waits here; the caller's next wait on the vector-memory counter covers these loads.
+    lines = ["global_load_dwordx4 %s, %%[qp], off offset:%d" % (vr(Q + 4 * k, 4), 32 * k) for k in range(8)]
+    out.append(emit("sp_load_q", ["const void *qp"], lines, [], ['[qp] "v"(qp)'], ['"memory"']))
     out.append(emit("sp_set_bases", ["uint32_t va", "uint32_t ka", "uint32_t rd", "uint32_t wr"],
                     ["v_mov_b32 %s, %%%d" % (v(r), k) for k, r in enumerate((VA_BASE, KA_BASE, RD_BASE, WR_BASE))], [],
                     ['"v"(va)', '"v"(ka)', '"v"(rd)', '"v"(wr)'], ['"memory"']))

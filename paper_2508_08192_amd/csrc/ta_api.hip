@@ -143,7 +143,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
                          v->stride[0] % 8 == 0 && v->stride[1] % 8 == 0 && v->stride[2] % 8 == 0 &&
                          ((uintptr_t)q->data % 16) == 0 && ((uintptr_t)k->data % 16) == 0 &&
                          ((uintptr_t)v->data % 16) == 0 && k->stride[0] < INT32_MAX && k->stride[2] < INT32_MAX &&
-                         v->stride[0] < INT32_MAX && v->stride[2] < INT32_MAX;
+                         v->stride[0] < INT32_MAX && v->stride[2] < INT32_MAX && Hq / Hkv <= 256;
     const int basic = kernel == TA_KERNEL_MFMA_BASIC ? 1 : 0;
     if (basic)
         kernel = TA_KERNEL_MFMA;
@@ -171,6 +171,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     p.B = (int)B; p.T = (int)T; p.Hq = (int)Hq; p.Hkv = (int)Hkv; p.G = (int)(Hq / Hkv); p.D = (int)D;
     p.ps = (int)ps; p.ps_shift = ps_shift; p.capacity = (int)capacity;
     p.rows = p.T * p.G;
+    p.g_magic = (1u << 24) / (uint32_t)p.G + 1u;
     p.is_bf16 = q->dtype == TA_BF16;
     p.scale_log2e = scale * 1.4426950408889634f;
 

@@ -37,6 +37,7 @@ struct TAParams {
     int32_t n_wg;              // workgroups of the KV pass along x
     int32_t min_q;             // smallest share of tiles a workgroup takes
     int32_t pad;               // schedule units a list counts on top of its tiles (fixed cost per list)
+    uint32_t g_magic;          // 2^24 / G + 1: R / G == mulhi(R << 8, g_magic) for R * G < 2^24 (matrix-core kernels)
     int32_t is_bf16;
     float scale_log2e;         // softmax scale * log2(e): scores are kept in the base-2 domain
     float *ws_o;               // partial outputs  [slot][rg][rows_grp][D], normalised, fp32
@@ -191,16 +192,11 @@ __device__ __forceinline__ bool ta_encode_tree(const int32_t *parent, int T, uns
     return *flag == 0;
 }
 
-// Same, for a caller that has already loaded the parent id of node threadIdx.x (any value for threads >= T).
-__device__ __forceinline__ bool ta_encode_tree_from(int parent_of_tid, int T, unsigned long long *masks, int *flag,
-                                                    int *par_s)
+// The walk itself: par_s[0..T) and *flag = 0 are already in LDS and visible to the workgroup.  Ends with a barrier.
+// tid: threadIdx.x (a parameter so that a caller short of registers can keep the compiler from hoisting its uses).
+__device__ __forceinline__ bool ta_encode_tree_lds(int tid, int T, unsigned long long *masks, int *flag,
+                                                   const int *par_s)
 {
-    const int tid = threadIdx.x;
-    if (tid == 0)
-        *flag = 0;
-    if (tid < T)
-        par_s[tid] = parent_of_tid;
-    __syncthreads();
     if (tid < T) {
         unsigned long long m = 0;
         int cur = tid, steps = 0;
@@ -220,6 +216,19 @@ __device__ __forceinline__ bool ta_encode_tree_from(int parent_of_tid, int T, un
     }
     __syncthreads();
     return *flag == 0;
+}
+
+// Same, for a caller that has already loaded the parent id of node threadIdx.x (any value for threads >= T).
+__device__ __forceinline__ bool ta_encode_tree_from(int parent_of_tid, int T, unsigned long long *masks, int *flag,
+                                                    int *par_s)
+{
+    const int tid = threadIdx.x;
+    if (tid == 0)
+        *flag = 0;
+    if (tid < T)
+        par_s[tid] = parent_of_tid;
+    __syncthreads();
+    return ta_encode_tree_lds(tid, T, masks, flag, par_s);
 }
 
 __device__ __forceinline__ float ta_wave_max(float x)

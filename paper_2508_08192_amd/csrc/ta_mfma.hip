@@ -523,11 +523,19 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
     const unsigned long long tun_c0 = __builtin_readcyclecounter(), tun_r0 = __builtin_amdgcn_s_memrealtime();
     unsigned long long tun_mark[8] = {};
 #define TUN_MARK(i) do { if (tun_mark[i] == 0) tun_mark[i] = __builtin_amdgcn_s_memrealtime() - tun_r0; } while (0)
+    // time per phase, summed over the workgroup's items: 0 schedule, 1 item set-up, 2 first loads to S(0),
+    // 3 generic steps, 4 steady-state loop, 5 drain and partial result; 6 items, 7 generic steps (counts)
+    unsigned long long tun_acc[16] = {}, tun_last = tun_r0;
+#define TUN_ACC(k) do { const unsigned long long now_ = __builtin_amdgcn_s_memrealtime(); tun_acc[k] += now_ - tun_last; tun_last = now_; } while (0)
+#define TUN_CNT(k) do { tun_acc[k] += 1; } while (0)
 #else
 #define TUN_MARK(i) do { } while (0)
+#define TUN_ACC(k) do { } while (0)
+#define TUN_CNT(k) do { } while (0)
 #endif
     ta_build_schedule(p, cum, lens);
     TUN_MARK(0);
+    TUN_ACC(0);
     const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
     const int share = ta_share(p, total);
     const int w = blockIdx.x, rg = blockIdx.y;
@@ -562,15 +570,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         asm volatile("" : "+v"(x));
         return x;
     };
-    uint32_t koff0, koff1, voff0, voff1;
-    {
-        const int drow = wave * 8 + (lane >> 4), dslot = lane & 15;
-        const int tv0 = 16 * (wave >> 1) + 4 * (wave & 1) + (lane >> 4);
+    // (recomputed where needed rather than kept: a value that lives across the whole walk would be spilled, and a
+    // reload from scratch memory waits for every cache load in flight)
+    auto lane_offsets = [&](uint32_t &koff0, uint32_t &koff1, uint32_t &voff0, uint32_t &voff1) {
+        const int x = fresh_tid();
+        const int wv = x >> 6, ln = x & 63;
+        const int drow = wv * 8 + (ln >> 4), dslot = ln & 15;
+        const int tv0 = 16 * (wv >> 1) + 4 * (wv & 1) + (ln >> 4);
         koff0 = (uint32_t)(drow * kss + (dslot ^ (drow & 15)) * 8) * 2u;
         koff1 = (uint32_t)((drow + 4) * kss + (dslot ^ ((drow + 4) & 15)) * 8) * 2u;
         voff0 = (uint32_t)(tv0 * vss + dslot * 8) * 2u;
         voff1 = (uint32_t)((tv0 + 8) * vss + dslot * 8) * 2u;
-    }
+    };
     // one page (or the contiguous cache) holds a whole aligned tile, and lane offsets fit 32 bits
     const bool fast_geom = (!paged || p.ps_shift >= 6) && kss < (1u << 22) && vss < (1u << 22);
 
@@ -592,6 +603,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         if (poison && tid == 0)
             atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
+        TUN_ACC(8);
         // tile ti of this item: first logical position and number of tokens it holds
         auto tile_pos0 = [&](int ti) { return (j0 + ti == n_b - 1) ? L : (j0 + ti) * TA_TILE; };
         auto tile_count = [&](int ti) { return (j0 + ti == n_b - 1) ? p.T : min(TA_TILE, L - (j0 + ti) * TA_TILE); };
@@ -599,34 +611,19 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         // tiny and the share very long).
         const int span_tiles = !paged ? n
                                : (p.ps_shift >= 6 ? PP_PAGES - 2 : max(1, ((PP_PAGES - 2) << p.ps_shift) / TA_TILE));
-        // Loads that do not depend on each other go out together: this thread's parent id (for the ancestor
-        // masks), its page id of the first span, and below the row's Q; one round trip instead of three.
-        int par_v = -1, pg_v = 0, page0 = 0, pages0 = 0;
-        if (!poison) {
-            if (has_tree_tile && tid < p.T)
-                par_v = p.parent[(int64_t)b * p.par_sb + fresh_tid()];
-            if (paged) {
-                const int ns0 = min(span_tiles, n);
-                page0 = tile_pos0(0) >> p.ps_shift;
-                pages0 = ((tile_pos0(ns0 - 1) + tile_count(ns0 - 1) - 1) >> p.ps_shift) - page0 + 1;
-                if (tid < pages0)
-                    pg_v = p.page_table[(int64_t)b * p.pt_sb + page0 + tid];
-            }
-        }
         // (lane roles inside an item come from fresh_tid(): nothing lane-dependent is carried from item to item)
-        const int xl = fresh_tid();
-        const int row = (xl >> 6) * 32 + (xl & 31), hfl = (xl >> 5) & 1;
-        const bool row_ok = row < rows_here;
         // A wave whose 32 rows all lie beyond the row group (T*G < 256) computes nothing; it still loads and
         // re-lays out its share of every tile and takes part in every barrier.
         const bool active = wave * 32 < rows_here;
 
         auto write_poison = [&]() {                        // a NaN log-sum-exp poisons the rows in the merge
-            if (row_ok) {
-                const int64_t wrow = ta_ws_row(p, slot, rg, row);
-                for (int d = hfl * 64; d < hfl * 64 + 64; d += 4)
+            const int x = fresh_tid();
+            const int prow = (x >> 6) * 32 + (x & 31), ph = (x >> 5) & 1;
+            if (prow < rows_here) {
+                const int64_t wrow = ta_ws_row(p, slot, rg, prow);
+                for (int d = ph * 64; d < ph * 64 + 64; d += 4)
                     *(float4 *)(p.ws_o + wrow * MF_D + d) = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (hfl == 0)
+                if (ph == 0)
                     p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
             }
         };
@@ -637,36 +634,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             continue;
         }
 
-        {
-            // Q fragments of this lane's row into their fixed registers, 16 dwords at a time
-            const int R = rg * p.rows_grp + row;
-            const uint16_t *qp = (const uint16_t *)p.q + (int64_t)b * p.q_sb + (int64_t)(R / p.G) * p.q_st +
-                                 (int64_t)(g * p.G + R % p.G) * p.q_sh + hfl * 8;
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                uint32_t x[16];
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    u32x4 f = (u32x4){0u, 0u, 0u, 0u};
-                    if (row_ok)
-                        f = *(const u32x4 *)(qp + (4 * half + kk) * 16);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        x[4 * kk + e] = f[e];
-                }
-                if (half == 0)
-                    sp_set_q_lo(x);
-                else
-                    sp_set_q_hi(x);
-            }
-        }
-        if (has_tree_tile && !ta_encode_tree_from(par_v, p.T, masks, flag, par_s)) {
-            if (tid == 0)
-                atomicOr(p.status, TA_STATUS_BAD_PARENT);
-            write_poison();
-            __syncthreads();
-            t = seg_start + j1;
-            continue;
+        TUN_ACC(9);
+        if (active) {
+            // Q of this lane's row goes straight into its fixed registers; it is first read after the wait for the
+            // first tile, which these loads precede.  Rows past the group's end read the group's first row (their
+            // results are never stored).
+            const int xl = fresh_tid();
+            const int row = (xl >> 6) * 32 + (xl & 31), hfl = (xl >> 5) & 1;
+            const int R = rg * p.rows_grp + (row < rows_here ? row : 0);
+            const int node = (int)__umulhi((uint32_t)R << 8, p.g_magic);                 // R / G
+            sp_load_q((const uint16_t *)p.q + (int64_t)b * p.q_sb + (int64_t)node * p.q_st +
+                      (int64_t)(g * p.G + R - node * p.G) * p.q_sh + hfl * 8);
         }
         const uint16_t *kgp = (const uint16_t *)p.k + (int64_t)g * p.k_sh;
         const uint16_t *vgp = (const uint16_t *)p.v + (int64_t)g * p.v_sh;
@@ -677,7 +655,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             const int rw = (x >> 6) * 32 + (x & 31), h = (x >> 5) & 1;
             const int j = j0 + ti;
             if (j == n_b - 1)
-                return (rw < rows_here ? masks[(rg * p.rows_grp + rw) / p.G] : ~0ull) >> (4 * h);
+                return (rw < rows_here ? masks[__umulhi((uint32_t)(rg * p.rows_grp + rw) << 8, p.g_magic)] : ~0ull) >> (4 * h);
             const int rem = L - j * TA_TILE;
             return (rem < TA_TILE ? ((1ull << rem) - 1ull) : ~0ull) >> (4 * h);
         };
@@ -697,6 +675,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 }
                 const uint16_t *kb_ = kgp + (uint64_t)pg * ksp + (uint64_t)sl * kss;
                 const uint16_t *vb_ = vgp + (uint64_t)pg * vsp + (uint64_t)sl * vss;
+                uint32_t koff0, koff1, voff0, voff1;
+                lane_offsets(koff0, koff1, voff0, voff1);
                 dma16s(kb_, koff0, kdst);
                 dma16s(kb_, koff1, kdst + 1024);
                 dma16s(vb_, voff0, vdst);
@@ -761,24 +741,34 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         };
 
         TUN_MARK(1);
-        sp_zero_o();
+        TUN_ACC(1);
+        TUN_CNT(6);
+        bool bad_tree = false;
         float m_run = -INFINITY, l_run = 0.f, l2_run = 0.f;   // l2: sum of the bf16-rounded probabilities
 
         for (int s0 = 0; s0 < n; s0 += span_tiles) {
             const int ns = min(span_tiles, n - s0);            // tiles s0 .. s0+ns-1 of the item; i is span-local
-            if (paged) {
-                span_first_page = tile_pos0(s0) >> p.ps_shift;
-                const int last_page = (tile_pos0(s0 + ns - 1) + tile_count(s0 + ns - 1) - 1) >> p.ps_shift;
-                if (s0 == 0 && tid < pages0)
-                    pcache[tid] = pg_v;                        // loaded ahead, together with Q
-                for (int k = tid + (s0 == 0 ? 512 : 0); k <= last_page - span_first_page; k += 512)
-                    pcache[k] = p.page_table[(int64_t)b * p.pt_sb + span_first_page + k];
-                __syncthreads();
-            } else {
-                if (tid == 0)
+            // Page ids of the span and (first span) the parent ids, global memory -> LDS.  Q is on its way meanwhile;
+            // everything here is used at once, so nothing lane-dependent has to be kept across the item.
+            {
+                const int x = fresh_tid();
+                if (paged) {
+                    span_first_page = tile_pos0(s0) >> p.ps_shift;
+                    const int last_page = (tile_pos0(s0 + ns - 1) + tile_count(s0 + ns - 1) - 1) >> p.ps_shift;
+                    for (int k = x; k <= last_page - span_first_page; k += 512)
+                        pcache[k] = p.page_table[(int64_t)b * p.pt_sb + span_first_page + k];
+                } else if (x == 0) {
                     pcache[0] = b;                             // the steady-state loop sees one page: the request's cache
-                __syncthreads();
+                }
+                if (s0 == 0 && has_tree_tile) {
+                    if (x == 0)
+                        *flag = 0;
+                    if (x < p.T)
+                        par_s[x] = p.parent[(int64_t)b * p.par_sb + x];
+                }
             }
+            __syncthreads();
+            TUN_ACC(10);
             TUN_MARK(2);
             // ring positions: next slots to load into, K slot of tile i+1, V slots of tiles i and i-1
             int ik = 0, iv = 0, issued = 0;
@@ -788,8 +778,20 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 iv = iv == SP_RV - 1 ? 0 : iv + 1;
             }
             TUN_MARK(3);
-            wait_loads(issued - 1);                            // tile 0 has landed
+            TUN_ACC(11);
+            if (s0 == 0) {
+                // while the first tiles are on their way: O = 0 and the ancestor masks
+                sp_zero_o();
+                if (has_tree_tile && !ta_encode_tree_lds(fresh_tid(), p.T, masks, flag, par_s)) {
+                    bad_tree = true;
+                    vm_wait<0>();                              // nothing may still land in the rings after this item
+                    break;
+                }
+            }
+            TUN_ACC(12);
+            wait_loads(issued - 1);                            // tile 0 and Q have landed
             lds_barrier();
+            TUN_ACC(13);
             TUN_MARK(4);
             if (active)
                 sp_s_first(0u);
@@ -853,11 +855,13 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             // Steady state: every tile involved is a full prefix tile inside one page (or the contiguous cache), so
             // whole pairs of tiles run inside sp_fast_loop, which does its own loads, re-layout and bookkeeping.
             TUN_MARK(5);
+            TUN_ACC(2);
             const int n_plain = max(0, min(ns, L / TA_TILE - (j0 + s0)));     // leading full prefix tiles of the span
             int i = 0;
 #pragma unroll 1
             while (i < ns) {
                 if (!(i & 1) && i >= 2 && fast_geom && i + 4 < n_plain && !TA_OFF(256)) {
+                    TUN_ACC(3);
                     const uint32_t pairs = (uint32_t)((n_plain - 5 - i) / 2 + 1);
                     uint32_t cnt = pairs, pos = (uint32_t)((j0 + s0 + i + 3) * TA_TILE);
                     uint32_t ik_o = ik * MF_TILE_BYTES, iv_o = iv * MF_TILE_BYTES, kn_o = kn * MF_TILE_BYTES;
@@ -871,6 +875,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     const uint64_t c_pp = (uint64_t)pshift | ((uint64_t)pmask << 32);
                     const uint64_t c_pc = (uint64_t)pc_lds | ((uint64_t)__float_as_uint(c) << 32);
                     const uint64_t c_dst = (uint64_t)(lds0 + wave * 2048) | ((uint64_t)(lds0 + SP_V_OFF + wave * 2048) << 32);
+                    uint32_t koff0, koff1, voff0, voff1;
+                    lane_offsets(koff0, koff1, voff0, voff1);
                     if (active)
                         sp_fast_loop(m_run, l_run, l2_run, ik_o, iv_o, kn_o, vp_o, vc_o, pos, cnt, c_kg, c_vg, c_sp, c_ss, c_pp,
                                      c_pc, c_dst, koff0, koff1, voff0, voff1);
@@ -883,7 +889,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     vp = vp_o / MF_TILE_BYTES;
                     vc = vc_o / MF_TILE_BYTES;
                     i += 2 * (int)pairs;
+                    TUN_ACC(4);
                 } else {
+                    TUN_CNT(7);
                     if (i & 1)
                         step(SpTag<false>{}, i);
                     else
@@ -892,9 +900,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 }
             }
             TUN_MARK(6);
+            TUN_ACC(3);
             if (active)
                 sp_pv(vp * MF_TILE_BYTES);
             lds_barrier();                                     // the rings are free for the next span or item
+        }
+        if (bad_tree) {
+            if (tid == 0)
+                atomicOr(p.status, TA_STATUS_BAD_PARENT);
+            write_poison();
+            __syncthreads();
+            t = seg_start + j1;
+            continue;
         }
 
         {
@@ -928,6 +945,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             }
         }
         lds_barrier();                 // the staging area is ring space again; the stores themselves may still fly
+        TUN_ACC(5);
         t = seg_start + j1;
     }
 #ifdef TA_TUNING
@@ -939,6 +957,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         dbg[1] = __builtin_amdgcn_s_memrealtime();
         dbg[2] = __builtin_readcyclecounter() - tun_c0;
         dbg[3] = xcc;
+        if (blockIdx.x < 240) {                     // 8 + 4112 + 16 * 240 words of 8 bytes fit TA_STATUS_BYTES
+            unsigned long long *d3 = (unsigned long long *)(p.status + 16) + 4096 + 16 + 16 * blockIdx.x;
+            for (int i = 0; i < 16; ++i) d3[i] = tun_acc[i];
+        }
         if (blockIdx.x == 0) {
             unsigned long long *d2 = (unsigned long long *)(p.status + 16) + 4 * 1024;
             for (int i = 0; i < 8; ++i) d2[i] = tun_mark[i];
