@@ -264,5 +264,6 @@ __device__ __forceinline__ uint16_t ta_f32_to_bf16(float f)
 hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream);
 hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream);
 hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream);
+int ta_merge_rows(const TAParams &p);            // output rows one workgroup of the merge pass handles
 hipError_t ta_launch_encode(const int32_t *parent, int64_t par_sb, int B, int T, unsigned long long *masks,
                             int32_t *status, hipStream_t stream);

@@ -363,11 +363,158 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
         p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + (int64_t)node * p.lse_st] = lse2 * LN2;
 }
 
+// The same merge for head_dim 128 and 16-byte aligned outputs: half a wave per output row, so that a lane holds four
+// neighbouring columns (one 16-byte load per partial and lane) and a workgroup of four waves merges eight rows.
+#define MG_ROWS 8
+
+__device__ __forceinline__ float ta_half_max(float x)          // over the 32 lanes of this lane's half-wave
+{
+    for (int off = 16; off > 0; off >>= 1)
+        x = fmaxf(x, __shfl_xor(x, off, TA_WAVE));
+    return x;
+}
+
+__device__ __forceinline__ float ta_half_sum(float x)
+{
+    for (int off = 16; off > 0; off >>= 1)
+        x += __shfl_xor(x, off, TA_WAVE);
+    return x;
+}
+
+__global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
+{
+    extern __shared__ int smem_i[];
+    int *cum = smem_i;
+    ta_build_schedule(p, cum);
+    const int total = p.Hkv * cum[p.B];
+    const int share = ta_share(p, total);
+    const int seg = blockIdx.x;
+    const int b = seg / p.Hkv, g = seg % p.Hkv;
+    const int lane = threadIdx.x % TA_WAVE, wave = threadIdx.x / TA_WAVE;
+    const int hl = lane & 31, half = lane >> 5;
+    const int n_u = cum[b + 1] - cum[b];
+    const int seg_start = p.Hkv * cum[b] + g * n_u + p.pad;
+    const int n_b = n_u - p.pad;
+    const int w_first = seg_start / share;
+    const int n_parts = (seg_start + n_b - 1) / share - w_first + 1;
+    const float LN2 = 0.6931471805599453f;
+    const float QNAN = __uint_as_float(0x7fc00000u);
+
+    const int R_raw = blockIdx.y * MG_ROWS + wave * 2 + half;
+    if (R_raw - half >= p.rows)
+        return;                                            // the whole wave is past the last row
+    const bool live = R_raw < p.rows;
+    const int R = live ? R_raw : p.rows - 1;               // an odd last row: its idle partner half repeats it
+    const int rg = R / p.rows_grp, r = R % p.rows_grp;
+    const int node = R / p.G, h = g * p.G + R % p.G;
+    const int64_t row0 = ta_ws_row(p, w_first + seg, rg, r);              // partial k of this row: row0 + k*pstride
+    const int64_t pstride = (int64_t)p.n_rg * p.rows_grp;
+    const float *o0 = p.ws_o + row0 * 128 + 4 * hl;
+    const int64_t ostride = pstride * 128;
+
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float lse2;
+    if (n_parts <= 32) {
+        // lane k of the half owns partial k
+        const float lk = hl < n_parts ? p.ws_lse[row0 + hl * pstride] : -INFINITY;
+        const bool nan_seen = ta_half_max(lk != lk ? 1.f : 0.f) > 0.f;
+        const float mx = ta_half_max(lk);
+        const float ek = exp2f(lk - mx);                                  // 0 for the idle lanes
+        const float den = ta_half_sum(ek);
+        lse2 = nan_seen ? QNAN : mx + log2f(den);
+        const float wk = nan_seen ? QNAN : ek / den;
+        const int src0 = lane & 32;
+        int k = 0;
+        for (; k + 4 <= n_parts; k += 4) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[u] = *(const float4 *)(o0 + (k + u) * ostride);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float wgt = __shfl(wk, src0 + k + u, TA_WAVE);
+                acc.x = fmaf(wgt, v[u].x, acc.x);
+                acc.y = fmaf(wgt, v[u].y, acc.y);
+                acc.z = fmaf(wgt, v[u].z, acc.z);
+                acc.w = fmaf(wgt, v[u].w, acc.w);
+            }
+        }
+        // The tail's loads go out together as well.  (Both halves of a wave merge rows of the same list, so
+        // n_parts and with it every branch here is uniform over the wave.)
+        float4 v[3];
+#pragma unroll
+        for (int u = 0; u < 3; ++u)
+            if (k + u < n_parts)
+                v[u] = *(const float4 *)(o0 + (k + u) * ostride);
+#pragma unroll
+        for (int u = 0; u < 3; ++u)
+            if (k + u < n_parts) {
+                const float wgt = __shfl(wk, src0 + k + u, TA_WAVE);
+                acc.x = fmaf(wgt, v[u].x, acc.x);
+                acc.y = fmaf(wgt, v[u].y, acc.y);
+                acc.z = fmaf(wgt, v[u].z, acc.z);
+                acc.w = fmaf(wgt, v[u].w, acc.w);
+            }
+    } else {
+        // more partials than lanes in a half: two sweeps over the log-sum-exps, then one over the outputs
+        float mx = -INFINITY, bad = 0.f;
+        for (int q0 = 0; q0 < n_parts; q0 += 32) {
+            const int k = q0 + hl;
+            if (k < n_parts) {
+                const float v = p.ws_lse[row0 + k * pstride];
+                bad = v != v ? 1.f : bad;
+                mx = fmaxf(mx, v);
+            }
+        }
+        mx = ta_half_max(mx);
+        const bool nan_seen = ta_half_max(bad) > 0.f;
+        float den = 0.f;
+        for (int q0 = 0; q0 < n_parts; q0 += 32) {
+            const int k = q0 + hl;
+            if (k < n_parts)
+                den += exp2f(p.ws_lse[row0 + k * pstride] - mx);
+        }
+        den = ta_half_sum(den);
+        lse2 = nan_seen ? QNAN : mx + log2f(den);
+        for (int k = 0; k < n_parts; ++k) {
+            const float wgt = exp2f(p.ws_lse[row0 + k * pstride] - lse2);  // same address in every lane of the half
+            const float4 v = *(const float4 *)(o0 + k * ostride);
+            acc.x = fmaf(wgt, v.x, acc.x);
+            acc.y = fmaf(wgt, v.y, acc.y);
+            acc.z = fmaf(wgt, v.z, acc.z);
+            acc.w = fmaf(wgt, v.w, acc.w);
+        }
+    }
+    if (!live)
+        return;
+    const int64_t ooff = (int64_t)b * p.o_sb + (int64_t)node * p.o_st + (int64_t)h * p.o_sh + 4 * hl;
+    if (p.is_bf16) {
+        uint2 o;
+        o.x = (uint32_t)ta_f32_to_bf16(acc.x) | ((uint32_t)ta_f32_to_bf16(acc.y) << 16);
+        o.y = (uint32_t)ta_f32_to_bf16(acc.z) | ((uint32_t)ta_f32_to_bf16(acc.w) << 16);
+        *(uint2 *)((uint16_t *)p.out + ooff) = o;
+    } else {
+        *(float4 *)((float *)p.out + ooff) = acc;
+    }
+    if (p.lse && hl == 0)
+        p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + (int64_t)node * p.lse_st] = lse2 * LN2;
+}
+
+int ta_merge_rows(const TAParams &p)
+{
+    const bool aligned = ((uintptr_t)p.out % 16) == 0 && p.o_sb % 4 == 0 && p.o_st % 4 == 0 && p.o_sh % 4 == 0;
+    return p.D == 128 && aligned ? MG_ROWS : TA_MERGE_ROWS;
+}
+
 hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream)
 {
     const size_t smem = sizeof(int) * (p.B + 2);
-    dim3 grid(p.B * p.Hkv, (p.rows + TA_MERGE_ROWS - 1) / TA_MERGE_ROWS);
-    hipLaunchKernelGGL(ta_merge_kernel, grid, dim3(GEN_THREADS), smem, stream, p);
+    const int rows_wg = ta_merge_rows(p);
+    dim3 grid(p.B * p.Hkv, (p.rows + rows_wg - 1) / rows_wg);
+    if (rows_wg == MG_ROWS)
+        hipLaunchKernelGGL(ta_merge128_kernel, grid, dim3(256), smem, stream, p);
+    else
+        hipLaunchKernelGGL(ta_merge_kernel, grid, dim3(GEN_THREADS), smem, stream, p);
     return hipGetLastError();
 }
 

@@ -585,8 +585,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
     // one page (or the contiguous cache) holds a whole aligned tile, and lane offsets fit 32 bits
     const bool fast_geom = (!paged || p.ps_shift >= 6) && kss < (1u << 22) && vss < (1u << 22);
 
+    int b_next = -1;                                   // request of the previous item
     while (t < t_end) {
-        const int b = __builtin_amdgcn_readfirstlane(ta_find_request(p, cum, t));
+        // Items after the first start where the previous list ended: the same request's next KV head or the next
+        // request, so only the first one needs the search.
+        int b = b_next;
+        if (b < 0)
+            b = ta_find_request(p, cum, t);
+        else if ((int64_t)p.Hkv * cum[b + 1] <= t)
+            ++b;
+        b = __builtin_amdgcn_readfirstlane(b);
+        b_next = b;
         const int n_u = __builtin_amdgcn_readfirstlane(cum[b + 1] - cum[b]);   // schedule units of one list
         const int cum_b = __builtin_amdgcn_readfirstlane(cum[b]);
         const int g = (t - p.Hkv * cum_b) / n_u;

@@ -267,6 +267,30 @@ def _strided_case(w):
         assert_parity(got, got_lse, ref, ref_lse, "bf16", "strided kernel=%d" % kernel)
 
 
+def test_merge_pass_variants():
+    """More partial results than half a wave holds, an odd number of rows, and an output view whose rows are not
+    16-byte aligned (which takes the general merge kernel) all have to agree with the oracle."""
+    import torch
+    rng = np.random.default_rng(23)
+    T = 5
+    w = W.make_workload("merge", B=2, T=T, Hq=3, Hkv=1, D=128, seq_lens=[4000, 90], trees=W.random_tree(T, 3, rng),
+                        page_size=64, dtype="bf16", seed=2301)                      # 15 rows
+    ref, ref_lse = run_oracle(w)
+    dev = to_device(w)
+    for kernel, n, cost in [(MFMA, 64, 1), (GENERIC, 64, 1), (MFMA, 0, 0), (MFMA, 7, 3)]:
+        _announce("merge kernel=%d num_splits=%d item_cost=%d" % (kernel, n, cost))
+        got, got_lse = run_hip(w, dev, kernel=kernel, num_splits=n, item_cost=cost)
+        assert_parity(got, got_lse, ref, ref_lse, "bf16", "merge num_splits=%d" % n)
+    wide = torch.zeros((2, T, 3, 130), dtype=torch.bfloat16, device="cuda:0")
+    dev["out"] = wide[..., 1:129]                                                  # rows start 2 bytes off
+    _announce("merge into an unaligned output view")
+    got, got_lse = run_hip(w, dev, kernel=MFMA, num_splits=64, item_cost=1)
+    assert_parity(got, got_lse, ref, ref_lse, "bf16", "unaligned out")
+    wf = W.make_workload("merge32", B=1, T=T, Hq=3, Hkv=1, D=128, seq_lens=[3000], trees=W.random_tree(T, 3, rng),
+                         page_size=64, dtype="f32", seed=2302)
+    _check(wf, "merge fp32 many partials", num_splits=48, item_cost=1)
+
+
 @pytest.mark.parametrize("idx,div", [(2, 16), (3, 16), (1, 1)])
 def test_repeat_calls_are_bit_identical(idx, div):
     w = W.make_config(idx, length_div=div)
