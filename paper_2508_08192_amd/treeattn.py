@@ -220,10 +220,10 @@ def tree_attn_last_status(stream=None):
 
 
 def tree_attn_plan(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse=None, num_cus=256,
-                   scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, check=True):
+                   scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, check=True, item_cost=0):
     """Host-only launch plan; returns a dict (or the negative status if check is False and it failed)."""
     ds = [_desc(x) for x in (q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse)]
-    o = _opts(scale, num_splits, kernel, None)
+    o = _opts(scale, num_splits, kernel, None, None, item_cost)
     plan = (ctypes.c_int64 * 8)()
     rc = load_library().tree_attn_plan(*[_ref(d) for d in ds], ctypes.byref(o), num_cus, plan)
     if rc != TA_OK:

@@ -92,6 +92,11 @@ def test_option_errors():
     a = _good()
     assert _plan(a, kernel=7, check=False) == ta.TA_ERR_OPTS
     assert _plan(a, num_splits=-1, check=False) == ta.TA_ERR_OPTS
+    assert _plan(a, item_cost=-1, check=False) == ta.TA_ERR_OPTS
+    assert _plan(a, item_cost=4097, check=False) == ta.TA_ERR_OPTS
+    assert _plan(a, item_cost=4096)["kernel"] == ta.TA_KERNEL_MFMA
+    # more than 256 query heads per KV head: outside the matrix-core kernels' row arithmetic
+    assert _plan(_good(Hq=514, Hkv=2))["kernel"] == ta.TA_KERNEL_GENERIC
     # the matrix-core kernel is bf16, head_dim 128, power-of-two pages only
     assert _plan(_good(dtype=ta.TA_F32), kernel=ta.TA_KERNEL_MFMA, check=False) == ta.TA_ERR_OPTS
     assert _plan(_good(D=64), kernel=ta.TA_KERNEL_MFMA, check=False) == ta.TA_ERR_OPTS
