@@ -80,9 +80,11 @@ __device__ __forceinline__ int ta_request_tiles(const TAParams &p, int b)
 }
 
 // The KV work of the batch is one line of schedule units: request after request, KV head after KV head, and
-// per (request, KV head) list first p.pad units that stand for the list's fixed cost, then one unit per tile
-// (prefix tiles, then the tree tile).  Workgroup w takes units [w * share, (w + 1) * share); a workgroup
-// whose range touches only the padding of a list has no work in it and writes no partial result.
+// per (request, KV head) list one unit per tile (prefix tiles, then the tree tile) followed by p.pad units of
+// padding.  Workgroup w takes units [w * share, (w + 1) * share).  The padding stands for the fixed cost of starting
+// on a list: every workgroup pays that once for the list it begins in, whether at its first tile or in its middle,
+// and once more per list boundary inside its range -- which is exactly where it meets a padding.  A workgroup whose
+// range touches only the padding of a list has no work in it and writes no partial result.
 //
 // cum[0..B]: exclusive prefix sums of the per-request unit counts (per KV head).  Needs blockDim.x >= 64; ends
 // with a barrier.  If `lens` is given, it also receives the B prefix lengths as they were read.

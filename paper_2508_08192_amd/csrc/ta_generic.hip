@@ -50,12 +50,14 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
         const int b = ta_find_request(p, cum, t);
         const int n_u = cum[b + 1] - cum[b];                       // schedule units of one list of request b
         const int g = (t - p.Hkv * cum[b]) / n_u;
-        const int seg_start = p.Hkv * cum[b] + g * n_u + p.pad;    // unit of the list's tile 0
+        const int seg_start = p.Hkv * cum[b] + g * n_u;            // unit of the list's tile 0
         const int n_b = n_u - p.pad;
-        const int j0 = max(0, t - seg_start);
+        const int j0 = t - seg_start;
         const int j1 = min(n_b, t_end - seg_start);
-        if (j1 <= j0)
-            break;                                                 // the share ends inside the list's padding
+        if (j1 <= j0) {
+            t = seg_start + n_u;                              // t lies in the list's trailing padding
+            continue;
+        }
         const int slot = w + b * p.Hkv + g;
         const int L = p.seq_lens[(int64_t)b * p.sl_s];
         bool poison = !ta_request_ok(p, L);
@@ -215,7 +217,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
             }
         }
         __syncthreads();               // masks / flag and the tiles are reused by the next item
-        t = seg_start + j1;
+        t = seg_start + (j1 == n_b ? n_u : j1);
     }
 }
 
@@ -260,7 +262,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
     const int b = seg / p.Hkv, g = seg % p.Hkv;
     const int lane = threadIdx.x % TA_WAVE, wave = threadIdx.x / TA_WAVE;
     const int n_u = cum[b + 1] - cum[b];
-    const int seg_start = p.Hkv * cum[b] + g * n_u + p.pad;
+    const int seg_start = p.Hkv * cum[b] + g * n_u;
     const int n_b = n_u - p.pad;
     const int w_first = seg_start / share;
     const int n_parts = (seg_start + n_b - 1) / share - w_first + 1;
@@ -393,7 +395,7 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
     const int lane = threadIdx.x % TA_WAVE, wave = threadIdx.x / TA_WAVE;
     const int hl = lane & 31, half = lane >> 5;
     const int n_u = cum[b + 1] - cum[b];
-    const int seg_start = p.Hkv * cum[b] + g * n_u + p.pad;
+    const int seg_start = p.Hkv * cum[b] + g * n_u;
     const int n_b = n_u - p.pad;
     const int w_first = seg_start / share;
     const int n_parts = (seg_start + n_b - 1) / share - w_first + 1;

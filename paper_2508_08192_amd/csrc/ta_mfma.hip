@@ -244,12 +244,14 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
         const int n_u = __builtin_amdgcn_readfirstlane(cum[b + 1] - cum[b]);   // schedule units of one list
         const int cum_b = __builtin_amdgcn_readfirstlane(cum[b]);
         const int g = (t - p.Hkv * cum_b) / n_u;
-        const int seg_start = p.Hkv * cum_b + g * n_u + p.pad;                 // unit of the list's tile 0
+        const int seg_start = p.Hkv * cum_b + g * n_u;                         // unit of the list's tile 0
         const int n_b = n_u - p.pad;
-        const int j0 = max(0, t - seg_start);
+        const int j0 = t - seg_start;
         const int j1 = min(n_b, t_end - seg_start);
-        if (j1 <= j0)
-            break;                                                             // the share ends inside the padding
+        if (j1 <= j0) {
+            t = seg_start + n_u;                              // t lies in the list's trailing padding
+            continue;
+        }
         const int slot = w + b * p.Hkv + g;
         const int L = __builtin_amdgcn_readfirstlane(p.seq_lens[(int64_t)b * p.sl_s]);
         bool poison = !ta_request_ok(p, L);
@@ -279,7 +281,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                 }
             }
             __syncthreads();
-            t = seg_start + j1;
+            t = seg_start + (j1 == n_b ? n_u : j1);
             continue;
         }
 
@@ -447,7 +449,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
             }
         }
         __syncthreads();                                       // masks and tiles are reused by the next item
-        t = seg_start + j1;
+        t = seg_start + (j1 == n_b ? n_u : j1);
     }
 }
 
@@ -599,12 +601,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         const int n_u = __builtin_amdgcn_readfirstlane(cum[b + 1] - cum[b]);   // schedule units of one list
         const int cum_b = __builtin_amdgcn_readfirstlane(cum[b]);
         const int g = (t - p.Hkv * cum_b) / n_u;
-        const int seg_start = p.Hkv * cum_b + g * n_u + p.pad;                 // unit of the list's tile 0
+        const int seg_start = p.Hkv * cum_b + g * n_u;                         // unit of the list's tile 0
         const int n_b = n_u - p.pad;
-        const int j0 = max(0, t - seg_start);
+        const int j0 = t - seg_start;
         const int j1 = min(n_b, t_end - seg_start);
-        if (j1 <= j0)
-            break;                                                             // the share ends inside the padding
+        if (j1 <= j0) {
+            t = seg_start + n_u;                              // t lies in the list's trailing padding
+            continue;
+        }
         const int n = j1 - j0;
         const int slot = w + b * p.Hkv + g;
         const int L = __builtin_amdgcn_readfirstlane(lens[b]);
@@ -639,7 +643,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         if (poison) {
             write_poison();
             __syncthreads();
-            t = seg_start + j1;
+            t = seg_start + (j1 == n_b ? n_u : j1);
             continue;
         }
 
@@ -919,7 +923,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 atomicOr(p.status, TA_STATUS_BAD_PARENT);
             write_poison();
             __syncthreads();
-            t = seg_start + j1;
+            t = seg_start + (j1 == n_b ? n_u : j1);
             continue;
         }
 
@@ -955,7 +959,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         }
         lds_barrier();                 // the staging area is ring space again; the stores themselves may still fly
         TUN_ACC(5);
-        t = seg_start + j1;
+        t = seg_start + (j1 == n_b ? n_u : j1);
     }
 #ifdef TA_TUNING
     if (blockIdx.y == 0 && threadIdx.x == 0 && blockIdx.x < 1024) {
