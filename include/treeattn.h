@@ -103,6 +103,12 @@ typedef struct {
     void *events[3];          /* optional hipEvent_t handles (HOST values) recorded on `stream`: [0] before the
                                  KV pass, [1] between KV pass and merge pass, [2] after the merge pass; NULL
                                  entries are skipped.  For measurement harnesses. */
+    const void *tree_masks;   /* optional DEVICE pointer to the ancestor masks tree_attn_encode wrote for these
+                                 trees (64-bit words, node i of request b at [b * tree_masks_stride + i]); the
+                                 call then reads them instead of walking tree_parent again -- for static trees
+                                 (section 3.4, pre-computed static trees) that are encoded once and used for many
+                                 steps.  Bits of nodes >= T are ignored.  tree_parent is still required (shape). */
+    int64_t tree_masks_stride;/* words between the masks of consecutive requests; 0 = one tree for the batch */
 } ta_opts;
 
 /*

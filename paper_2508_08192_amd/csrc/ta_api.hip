@@ -124,6 +124,8 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
         kernel = opts->kernel;
         num_splits = opts->num_splits;
         item_cost = opts->item_cost;
+        if (opts->tree_masks && (((uintptr_t)opts->tree_masks % 8) != 0 || opts->tree_masks_stride < 0))
+            return TA_ERR_OPTS;
         scale = opts->scale;
         user_ws = opts->workspace;
         user_ws_bytes = opts->workspace_bytes;
@@ -172,6 +174,8 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     p.ps = (int)ps; p.ps_shift = ps_shift; p.capacity = (int)capacity;
     p.rows = p.T * p.G;
     p.g_magic = (1u << 24) / (uint32_t)p.G + 1u;
+    p.masks_in = opts ? (const unsigned long long *)opts->tree_masks : nullptr;
+    p.masks_sb = opts ? opts->tree_masks_stride : 0;
     p.is_bf16 = q->dtype == TA_BF16;
     p.scale_log2e = scale * 1.4426950408889634f;
 

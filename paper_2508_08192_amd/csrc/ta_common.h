@@ -38,6 +38,8 @@ struct TAParams {
     int32_t min_q;             // smallest share of tiles a workgroup takes
     int32_t pad;               // schedule units a list counts on top of its tiles (fixed cost per list)
     uint32_t g_magic;          // 2^24 / G + 1: R / G == mulhi(R << 8, g_magic) for R * G < 2^24 (matrix-core kernels)
+    const unsigned long long *masks_in;   // ancestor masks encoded earlier (or null: walk the parents in the call)
+    int64_t masks_sb;          // words between the masks of consecutive requests
     int32_t is_bf16;
     float scale_log2e;         // softmax scale * log2(e): scores are kept in the base-2 domain
     float *ws_o;               // partial outputs  [slot][rg][rows_grp][D], normalised, fp32
@@ -192,6 +194,13 @@ __device__ __forceinline__ bool ta_encode_tree(const int32_t *parent, int T, uns
     }
     __syncthreads();
     return *flag == 0;
+}
+
+// Masks that were encoded before the call: node tid's word of request b, bits of nodes >= T dropped.
+__device__ __forceinline__ unsigned long long ta_given_mask(const TAParams &p, int b, int tid)
+{
+    const unsigned long long m = p.masks_in[(int64_t)b * p.masks_sb + tid];
+    return p.T >= 64 ? m : m & ((1ull << p.T) - 1ull);
 }
 
 // The walk itself: par_s[0..T) and *flag = 0 are already in LDS and visible to the workgroup.  Ends with a barrier.

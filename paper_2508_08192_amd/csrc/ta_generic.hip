@@ -64,7 +64,11 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
         if (poison && threadIdx.x == 0)
             atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
-        if (has_tree_tile && !poison) {
+        if (has_tree_tile && !poison && p.masks_in) {
+            if ((int)threadIdx.x < p.T)
+                masks[threadIdx.x] = ta_given_mask(p, b, threadIdx.x);
+            __syncthreads();
+        } else if (has_tree_tile && !poison) {
             if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag, par_s)) {
                 poison = true;
                 if (threadIdx.x == 0)

@@ -258,7 +258,11 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
         if (poison && tid == 0)
             atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
-        if (has_tree_tile && !poison) {
+        if (has_tree_tile && !poison && p.masks_in) {
+            if ((int)threadIdx.x < p.T)
+                masks[threadIdx.x] = ta_given_mask(p, b, threadIdx.x);
+            __syncthreads();
+        } else if (has_tree_tile && !poison) {
             if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag, par_s)) {
                 poison = true;
                 if (tid == 0)
@@ -773,7 +777,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 } else if (x == 0) {
                     pcache[0] = b;                             // the steady-state loop sees one page: the request's cache
                 }
-                if (s0 == 0 && has_tree_tile) {
+                if (s0 == 0 && has_tree_tile && p.masks_in) {
+                    if (x < p.T)
+                        masks[x] = ta_given_mask(p, b, x);         // encoded before the call
+                } else if (s0 == 0 && has_tree_tile) {
                     if (x == 0)
                         *flag = 0;
                     if (x < p.T)
@@ -795,7 +802,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             if (s0 == 0) {
                 // while the first tiles are on their way: O = 0 and the ancestor masks
                 sp_zero_o();
-                if (has_tree_tile && !ta_encode_tree_lds(fresh_tid(), p.T, masks, flag, par_s)) {
+                if (has_tree_tile && !p.masks_in && !ta_encode_tree_lds(fresh_tid(), p.T, masks, flag, par_s)) {
                     bad_tree = true;
                     vm_wait<0>();                              // nothing may still land in the rings after this item
                     break;

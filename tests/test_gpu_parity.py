@@ -351,6 +351,39 @@ def test_encoder_masks():
     assert np.array_equal(one.cpu().numpy().view(np.uint64), got[1])
 
 
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA, MFMA_BASIC])
+def test_masks_encoded_once_replace_the_walk_over_parents(kernel):
+    """Static trees: tree_attn_encode runs once, later calls take its masks (ta_opts.tree_masks).  The parents passed
+    along are deliberately different trees (all roots), so the call only agrees with the oracle if it reads the masks."""
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+    rng = np.random.default_rng(31)
+    T = 24
+    trees = np.stack([W.random_tree(T, 6, rng) for _ in range(3)])
+    w = W.make_workload("masks", B=3, T=T, Hq=8, Hkv=2, D=128, seq_lens=[700, 0, 130], trees=trees, page_size=64,
+                        dtype="bf16", seed=3101)
+    ref, ref_lse = run_oracle(w)
+    dev = to_device(w)
+    masks = torch.zeros((3, T), dtype=torch.int64, device="cuda")
+    ta.tree_attn_encode(dev["tree_parent"], masks)
+    masks |= (-1 << T)                                             # bits of nodes that do not exist are ignored
+    dev["tree_parent"] = torch.full_like(dev["tree_parent"], -1)
+    _announce("given masks, kernel=%d" % kernel)
+    got, got_lse = run_hip(w, dev, kernel=kernel, tree_masks=masks)
+    assert_parity(got, got_lse, ref, ref_lse, "bf16", "given masks")
+    # one tree for the whole batch: masks [T], stride 0
+    w1 = W.make_workload("masks1", B=3, T=T, Hq=8, Hkv=2, D=128, seq_lens=[64, 333, 1000], trees=trees[2], page_size=64,
+                         dtype="bf16", seed=3102)
+    ref, ref_lse = run_oracle(w1)
+    dev = to_device(w1)
+    one = torch.zeros((T,), dtype=torch.int64, device="cuda")
+    ta.tree_attn_encode(torch.from_numpy(trees[2]).cuda(), one)
+    dev["tree_parent"] = torch.full_like(dev["tree_parent"], -1)
+    _announce("one mask set for the batch, kernel=%d" % kernel)
+    got, got_lse = run_hip(w1, dev, kernel=kernel, tree_masks=one, num_splits=5)
+    assert_parity(got, got_lse, ref, ref_lse, "bf16", "given masks, shared tree")
+
+
 def test_empty_batch_and_no_lse():
     import torch
     from paper_2508_08192_amd import treeattn as ta
