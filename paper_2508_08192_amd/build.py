@@ -18,8 +18,24 @@ FLAGS = [
 ]
 
 
+def generate_blocks(verbose=False):
+    """ta_sp_block.inc is written by csrc/gen_sp_block.py; keep the file in step with its generator."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("gen_sp_block", os.path.join(CSRC, "gen_sp_block.py"))
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    text = gen.generate()
+    path = os.path.join(CSRC, "ta_sp_block.inc")
+    if not os.path.exists(path) or open(path).read() != text:
+        with open(path, "w") as f:
+            f.write(text)
+        if verbose:
+            print("regenerated " + path)
+
+
 def build_library(verbose=False, extra_flags=()):
     """Compile every HIP source for gfx950 and link the C-ABI shared library; returns its path."""
+    generate_blocks(verbose)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp%d" % os.getpid()
     if os.environ.get("TREEATTN_TUNING"):      # ablation switches of the 256-row kernel (see TA_OFF)

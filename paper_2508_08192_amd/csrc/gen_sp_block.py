@@ -450,23 +450,35 @@ def helpers():
     return "\n\n".join(out)
 
 
+def generate():
+    """The whole text of ta_sp_block.inc."""
+    import contextlib
+    import io
+    buf = io.StringIO()
+    with contextlib.redirect_stdout(buf):
+        print("// Generated by gen_sp_block.py -- do not edit.")
+        print(block("sp_s_first", "B", False, True, False))          # S^T(0) into buffer A ("current" B is unused)
+        for cur in "AB":
+            print()
+            print(block("sp_full_" + cur, cur, True, True, True))
+            print()
+            print(block("sp_last_" + cur, cur, True, False, True))    # no tile after this one
+        print()
+        print(block("sp_head_A", "A", False, True, True))            # tile 0 when a tile 1 follows
+        print()
+        print(block("sp_only_A", "A", False, False, True))           # tile 0 of a one-tile walk
+        print()
+        print(block("sp_pv", "A", True, False, False))               # drain: the last tile's P . V
+        print()
+        print(fast_loop("sp_fast_loop"))
+        print()
+        print(fast_loop("sp_fast_loop_helper", helper=True))
+        print()
+        print(helpers())
+
+    return buf.getvalue()
+
+
 if __name__ == "__main__":
-    print("// Generated by gen_sp_block.py -- do not edit.")
-    print(block("sp_s_first", "B", False, True, False))          # S^T(0) into buffer A ("current" B is unused)
-    for cur in "AB":
-        print()
-        print(block("sp_full_" + cur, cur, True, True, True))
-        print()
-        print(block("sp_last_" + cur, cur, True, False, True))    # no tile after this one
-    print()
-    print(block("sp_head_A", "A", False, True, True))            # tile 0 when a tile 1 follows
-    print()
-    print(block("sp_only_A", "A", False, False, True))           # tile 0 of a one-tile walk
-    print()
-    print(block("sp_pv", "A", True, False, False))               # drain: the last tile's P . V
-    print()
-    print(fast_loop("sp_fast_loop"))
-    print()
-    print(fast_loop("sp_fast_loop_helper", helper=True))
-    print()
-    print(helpers())
+    import sys
+    sys.stdout.write(generate())

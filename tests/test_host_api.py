@@ -135,3 +135,14 @@ def test_workspace_bound_covers_every_plan():
             need = p["partial_slots"] * p["row_groups"] * p["rows_per_group"] * (D + 1) * 4
             assert need <= bound
     assert ta.tree_attn_workspace_bytes(1, 65, 8, 8, 128, ta.TA_BF16, 256) == 0
+
+
+def test_generated_asm_blocks_match_their_generator():
+    """csrc/ta_sp_block.inc is committed next to the script that writes it; the two must not drift apart."""
+    import importlib.util
+    import os
+    csrc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2508_08192_amd", "csrc")
+    spec = importlib.util.spec_from_file_location("gen_sp_block", os.path.join(csrc, "gen_sp_block.py"))
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    assert open(os.path.join(csrc, "ta_sp_block.inc")).read() == gen.generate()
