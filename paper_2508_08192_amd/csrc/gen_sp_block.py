@@ -294,9 +294,11 @@ def fast_step_items(cur, label, helper=False):
         dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(ry(1)), v(ry(0)), v(ry(2))), lds=("w", 3)),
     ]
     rest = sm[12:]
-    # Loads of tile i+3: one every 20 softmax instructions from the 10th on.  The re-layout shares v[38:47]
-    # with the V fragment addresses and the page lookup, so it starts once the last PV read is out (MFMA 11).
-    ri, started, di, ring_at = 0, False, 0, 0
+    # Loads of tile i+3: late in the block, one every 10 softmax instructions from the 90th on (they are not needed
+    # before the end of the next block; issued early they cost the 256-row shapes 1.4 %, spread evenly 1 %).  The
+    # re-layout shares v[38:47] with the V fragment addresses and the page lookup, so it starts once the last PV read
+    # is out (MFMA 11).
+    ri, started, di, ring_at, dma_end = 0, False, 0, 0, 0
     if helper:
         for x in dma:
             aux += [dict(t=y) for y in x]
@@ -304,9 +306,10 @@ def fast_step_items(cur, label, helper=False):
         started, di = True, 4
     for j, (t, need) in enumerate(rest):
         aux.append(dict(t=t, mf=need))
-        if j >= 10 and (j - 10) % 20 == 0 and di < 4:
+        if j >= 90 and (j - 90) % 10 == 0 and di < 4:
             aux += [dict(t=x) for x in dma[di]]
             di += 1
+            dma_end = len(aux)                     # the loads read the ring positions ik and iv
         if j >= 50 and not started:
             for it in rl_reads:
                 aux.append(dict(it, mf=11))
@@ -323,7 +326,7 @@ def fast_step_items(cur, label, helper=False):
     else:
         # spread through the second half of the block, one scalar instruction after every fourth other one
         # (a compare and the select that reads its SCC stay neighbours: other scalar work writes SCC too)
-        k, i = ring_at, 0
+        k, i = max(ring_at, dma_end), 0
         while i < len(rings):
             grp = rings[i:i + 2] if rings[i].startswith("s_cmp") else rings[i:i + 1]
             at = min(k, len(aux))
