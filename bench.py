@@ -93,6 +93,9 @@ def cpu_baseline(w, budget_s, log):
                       "scaled by %d/%d" % (n, total, dt, total, n)}
 
 
+EVENT_EVERY = 8
+
+
 def measure(w, steps, warmup, log, num_splits=0, kernel=0, rotate=0, check=False, item_cost=0):
     """Times `steps` verify steps of workload w (after `warmup` untimed ones).  Returns a dict with the step
     time, per-kernel times from HIP events recorded inside the timed region, and roofline figures."""
@@ -147,12 +150,15 @@ def measure(w, steps, warmup, log, num_splits=0, kernel=0, rotate=0, check=False
         step(i)
     torch.cuda.synchronize()
 
+    # Per-kernel durations come from HIP events the library records on the launch stream inside the timed region.
+    # Recording costs 2-3 us per event, which would inflate the step time of the small workloads by a quarter, so
+    # only every EVENT_EVERY-th step of the timed region carries events.
     hev = HipEvents()
-    evs = [[hev.create() for _ in range(3)] for _ in range(steps)]
+    evs = [[hev.create() for _ in range(3)] for _ in range((steps + EVENT_EVERY - 1) // EVENT_EVERY)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        step(warmup + i, evs[i])
+        step(warmup + i, evs[i // EVENT_EVERY] if i % EVENT_EVERY == 0 else None)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / steps * 1e3
