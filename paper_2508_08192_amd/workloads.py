@@ -294,3 +294,32 @@ def make_config(idx, seed=None, length_div=1):
         return make_workload(name, B=4, T=64, Hq=32, Hkv=8, D=128, seq_lens=131072 // length_div, trees=tree,
                              page_size=128, seed=seed, kv_std=0.5)
     raise IndexError(idx)
+
+
+# Shapes of the regime the paper deploys (section 3.4: static pre-computed trees, a small tree at batch size 1 and a
+# short chain above; N8 for the 70B model, N12 for Scout; one GPU's tensor-parallel share of the heads).  The paper
+# does not print the topology of its pruned trees: these are plausible stand-ins of the same sizes.
+PRODUCTION_NAMES = ("p1_70b_share_n8", "p2_70b_share_chain3", "p3_scout_share_n12", "p4_8b_n8_bs128")
+TREE_N8 = np.asarray([-1, 0, 0, 0, 1, 1, 2, 4], dtype=np.int32)                       # 8 nodes, 4 levels
+TREE_N12 = np.asarray([-1, 0, 0, 0, 1, 1, 1, 2, 2, 4, 4, 9], dtype=np.int32)          # 12 nodes, 5 levels
+
+
+def make_production(idx, seed=None, length_div=1):
+    """Memory-bound shapes with few query rows per KV head (idx 0..3); synthetic like the five configurations.
+    length_div > 1 divides every prefix length, for tests that compare all outputs with the oracle."""
+    seed = 2000 + idx if seed is None else seed
+    rng = np.random.default_rng(seed)
+    name = PRODUCTION_NAMES[idx] + ("" if length_div == 1 else "_div%d" % length_div)
+    if idx == 0:        # 70B-shaped, 8 of 64 query heads and 1 of 8 KV heads per GPU, batch 32, 8-node tree
+        return make_workload(name, B=32, T=8, Hq=8, Hkv=1, D=128, seq_lens=rng.integers(1024, 16384 + 1, size=32) // length_div,
+                             trees=TREE_N8, page_size=64, seed=seed)
+    if idx == 1:        # the same share at batch 64 with a chain of 3 draft tokens behind the root
+        return make_workload(name, B=64, T=4, Hq=8, Hkv=1, D=128, seq_lens=rng.integers(1024, 16384 + 1, size=64) // length_div,
+                             trees=chain_tree(4), page_size=64, seed=seed)
+    if idx == 2:        # Scout-shaped (40 query heads, 8 KV heads), one GPU of eight: 5 query heads on 1 KV head
+        return make_workload(name, B=16, T=12, Hq=5, Hkv=1, D=128, seq_lens=rng.integers(8192, 65536 + 1, size=16) // length_div,
+                             trees=TREE_N12, page_size=128, seed=seed)
+    if idx == 3:        # 8B-shaped on one GPU, batch 128, short prefixes, 8-node tree
+        return make_workload(name, B=128, T=8, Hq=32, Hkv=8, D=128, seq_lens=rng.integers(256, 4096 + 1, size=128) // length_div,
+                             trees=TREE_N8, page_size=64, seed=seed)
+    raise IndexError(idx)

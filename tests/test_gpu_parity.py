@@ -216,6 +216,14 @@ def test_benchmark_configs_reduced_lengths_all_outputs(idx, div):
     _check(w)
 
 
+@pytest.mark.parametrize("idx,div", [(0, 16), (1, 32), (2, 64), (3, 16)])
+def test_production_shapes_reduced_lengths_all_outputs(idx, div):
+    """Small static trees on one GPU's share of the heads (8 and 12 nodes, a chain of 3 behind the root; 5 or 8 query
+    heads per KV head): every output against the oracle at reduced prefix lengths."""
+    w = W.make_production(idx, length_div=div)
+    _check(w)
+
+
 @pytest.mark.parametrize("idx", [2, 3, 4])
 def test_full_size_configs_sampled_outputs(idx):
     """The benchmark configurations at full size, in the launch configuration the bench times: sampled
