@@ -31,7 +31,7 @@ struct Plan {
 struct Problem {
     TAParams p;
     Plan plan;
-    size_t ws_o_bytes, ws_bytes;
+    size_t ws_o_bytes, ws_lse_bytes, ws_bytes;
 };
 
 bool strides_ok(const ta_tensor *t)
@@ -216,12 +216,14 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
 
     const size_t rows_total = (size_t)pl.n_slots * pl.n_rg * pl.rows_grp;
     pr->ws_o_bytes = align_up(rows_total * D * sizeof(float), 256);
-    pr->ws_bytes = pr->ws_o_bytes + align_up(rows_total * sizeof(float), 256);
+    pr->ws_lse_bytes = align_up(rows_total * sizeof(float), 256);
+    pr->ws_bytes = pr->ws_o_bytes + pr->ws_lse_bytes + align_up((size_t)(B * Hkv) * 2 * sizeof(int32_t), 256);
     if (user_ws) {
         if (user_ws_bytes < pr->ws_bytes)
             return TA_ERR_WORKSPACE;
         p.ws_o = (float *)user_ws;
         p.ws_lse = (float *)((char *)user_ws + pr->ws_o_bytes);
+        p.ws_parts = (int32_t *)((char *)user_ws + pr->ws_o_bytes + pr->ws_lse_bytes);
     }
     return TA_OK;
 }
@@ -342,7 +344,8 @@ size_t tree_attn_workspace_bytes(int32_t B, int32_t T, int32_t Hq, int32_t Hkv, 
     const size_t n_rg = (rows + rows_grp - 1) / rows_grp;
     const size_t slots = (size_t)num_cus * 4 + (size_t)B * Hkv;
     const size_t rows_total = slots * n_rg * rows_grp;
-    return align_up(rows_total * D * sizeof(float), 256) + align_up(rows_total * sizeof(float), 256);
+    return align_up(rows_total * D * sizeof(float), 256) + align_up(rows_total * sizeof(float), 256) +
+           align_up((size_t)B * Hkv * 2 * sizeof(int32_t), 256);
 }
 
 int tree_attn_reserve(size_t bytes)
@@ -381,6 +384,7 @@ int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tens
                 return rc;
             pr.p.ws_o = (float *)s->ws;
             pr.p.ws_lse = (float *)((char *)s->ws + pr.ws_o_bytes);
+            pr.p.ws_parts = (int32_t *)((char *)s->ws + pr.ws_o_bytes + pr.ws_lse_bytes);
         }
     }
     pr.p.status = s->status;

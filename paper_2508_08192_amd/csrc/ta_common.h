@@ -44,6 +44,8 @@ struct TAParams {
     float scale_log2e;         // softmax scale * log2(e): scores are kept in the base-2 domain
     float *ws_o;               // partial outputs  [slot][rg][rows_grp][D], normalised, fp32
     float *ws_lse;             // partial log2-sum-exp2 [slot][rg][rows_grp]
+    int32_t *ws_parts;         // [B * Hkv][2]: first and last workgroup that hold partial results of a list; written
+                               // by the KV pass (the owners of the list's first and last tile), read by the merge
     int32_t *status;           // sticky status word
     int32_t basic;             // 256-row groups: use the register-staged MFMA kernel, not the pipelined one
 #ifdef TA_TUNING
@@ -138,6 +140,22 @@ __device__ __forceinline__ int ta_find_request(const TAParams &p, const int *cum
             hi = mid;
     }
     return lo;
+}
+
+// The KV pass tells the merge pass which workgroups hold partial results of list (b, g): the owner of the list's
+// first tile and the owner of its last one say so (row group 0 speaks for all).  Saves the merge pass rebuilding
+// the schedule from the prefix lengths in each of its many small workgroups.
+__device__ __forceinline__ void ta_note_owner(const TAParams &p, int b, int g, int w, int j0, int j1, int n_b)
+{
+    if (threadIdx.x == 0 && blockIdx.y == 0) {
+        int wv = w;
+        asm volatile("" : "+s"(wv));              // made where it is stored: a copy kept in a vector register across
+                                                  // the caller's item loop would be spilled there
+        if (j0 == 0)
+            p.ws_parts[2 * (b * p.Hkv + g)] = wv;
+        if (j1 == n_b)
+            p.ws_parts[2 * (b * p.Hkv + g) + 1] = wv;
+    }
 }
 
 __device__ __forceinline__ int64_t ta_ws_row(const TAParams &p, int slot, int rg, int r)

@@ -59,6 +59,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
             continue;
         }
         const int slot = w + b * p.Hkv + g;
+        ta_note_owner(p, b, g, w, j0, j1, n_b);
         const int L = p.seq_lens[(int64_t)b * p.sl_s];
         bool poison = !ta_request_ok(p, L);
         if (poison && threadIdx.x == 0)
@@ -257,19 +258,11 @@ hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream)
 // head-dim columns, with the loads of several partials in flight at once.
 __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
 {
-    extern __shared__ int smem_i[];
-    int *cum = smem_i;
-    ta_build_schedule(p, cum);
-    const int total = p.Hkv * cum[p.B];
-    const int share = ta_share(p, total);
     const int seg = blockIdx.x;
     const int b = seg / p.Hkv, g = seg % p.Hkv;
     const int lane = threadIdx.x % TA_WAVE, wave = threadIdx.x / TA_WAVE;
-    const int n_u = cum[b + 1] - cum[b];
-    const int seg_start = p.Hkv * cum[b] + g * n_u;
-    const int n_b = n_u - p.pad;
-    const int w_first = seg_start / share;
-    const int n_parts = (seg_start + n_b - 1) / share - w_first + 1;
+    const int w_first = p.ws_parts[2 * seg];                             // left by the KV pass
+    const int n_parts = p.ws_parts[2 * seg + 1] - w_first + 1;
     const float LN2 = 0.6931471805599453f;
     const float QNAN = __uint_as_float(0x7fc00000u);
 
@@ -389,20 +382,12 @@ __device__ __forceinline__ float ta_half_sum(float x)
 
 __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
 {
-    extern __shared__ int smem_i[];
-    int *cum = smem_i;
-    ta_build_schedule(p, cum);
-    const int total = p.Hkv * cum[p.B];
-    const int share = ta_share(p, total);
     const int seg = blockIdx.x;
     const int b = seg / p.Hkv, g = seg % p.Hkv;
     const int lane = threadIdx.x % TA_WAVE, wave = threadIdx.x / TA_WAVE;
     const int hl = lane & 31, half = lane >> 5;
-    const int n_u = cum[b + 1] - cum[b];
-    const int seg_start = p.Hkv * cum[b] + g * n_u;
-    const int n_b = n_u - p.pad;
-    const int w_first = seg_start / share;
-    const int n_parts = (seg_start + n_b - 1) / share - w_first + 1;
+    const int w_first = p.ws_parts[2 * seg];                             // left by the KV pass
+    const int n_parts = p.ws_parts[2 * seg + 1] - w_first + 1;
     const float LN2 = 0.6931471805599453f;
     const float QNAN = __uint_as_float(0x7fc00000u);
 
@@ -514,7 +499,7 @@ int ta_merge_rows(const TAParams &p)
 
 hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream)
 {
-    const size_t smem = sizeof(int) * (p.B + 2);
+    const size_t smem = 0;
     const int rows_wg = ta_merge_rows(p);
     dim3 grid(p.B * p.Hkv, (p.rows + rows_wg - 1) / rows_wg);
     if (rows_wg == MG_ROWS)

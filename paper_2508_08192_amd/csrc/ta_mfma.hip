@@ -253,6 +253,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
             continue;
         }
         const int slot = w + b * p.Hkv + g;
+        ta_note_owner(p, b, g, w, j0, j1, n_b);
         const int L = __builtin_amdgcn_readfirstlane(p.seq_lens[(int64_t)b * p.sl_s]);
         bool poison = !ta_request_ok(p, L);
         if (poison && tid == 0)
@@ -615,6 +616,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         }
         const int n = j1 - j0;
         const int slot = w + b * p.Hkv + g;
+        ta_note_owner(p, b, g, w, j0, j1, n_b);
         const int L = __builtin_amdgcn_readfirstlane(lens[b]);
         bool poison = !ta_request_ok(p, L);
         if (poison && tid == 0)
