@@ -66,6 +66,8 @@ typedef struct {
     const int32_t *tree_parent;
     int64_t parent_stride_b;  /* T, or 0 when one tree serves the whole batch */
     double scale;
+    const int32_t *kv_start;  /* [B] or NULL: first prefix position a request's nodes still attend to (section 5,
+                                 local attention: the prefix is restricted to the current sub-sequence); NULL = 0 */
 } oracle_problem;
 
 static double widen(const void *base, int dtype, int64_t idx)
@@ -115,6 +117,8 @@ static int request_is_valid(const oracle_problem *p, int b)
     int64_t cap = (int64_t)p->max_pages * p->page_size;
     if (L < 0 || L + p->T > cap)
         return 0;
+    if (p->kv_start && (p->kv_start[b] < 0 || p->kv_start[b] > L))
+        return 0;
     const int32_t *par = p->tree_parent + b * p->parent_stride_b;
     int32_t path[64];
     for (int i = 0; i < p->T; ++i)
@@ -133,12 +137,14 @@ static void attend_one(const oracle_problem *p, int b, int i, int h,
     const int32_t *par = p->tree_parent + b * p->parent_stride_b;
     int32_t path[64];
     const int plen = root_path(par, p->T, i, path);
-    const int64_t nkeys = L + plen;
+    const int64_t S = p->kv_start ? p->kv_start[b] : 0;   /* keys: prefix positions S..L-1, then the path */
+    const int64_t W = L - S;
+    const int64_t nkeys = W + plen;
     const int64_t qoff = b * p->q_stride[0] + i * p->q_stride[1] + h * p->q_stride[2];
 
     double smax = -INFINITY;
     for (int64_t t = 0; t < nkeys; ++t) {
-        int64_t pos = t < L ? t : L + path[t - L];
+        int64_t pos = t < W ? S + t : L + path[t - W];
         int64_t ko = cache_offset(p, p->k_stride, b, g, pos);
         double dot = 0.0;
         for (int d = 0; d < D; ++d)
@@ -155,7 +161,7 @@ static void attend_one(const oracle_problem *p, int b, int i, int h,
     for (int d = 0; d < D; ++d)
         out_row[d] = 0.0;
     for (int64_t t = 0; t < nkeys; ++t) {
-        int64_t pos = t < L ? t : L + path[t - L];
+        int64_t pos = t < W ? S + t : L + path[t - W];
         int64_t vo = cache_offset(p, p->v_stride, b, g, pos);
         double w = scores[t] / denom;
         for (int d = 0; d < D; ++d)

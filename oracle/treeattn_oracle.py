@@ -40,6 +40,7 @@ class _Problem(ctypes.Structure):
         ("tree_parent", ctypes.c_void_p),
         ("parent_stride_b", ctypes.c_int64),
         ("scale", ctypes.c_double),
+        ("kv_start", ctypes.c_void_p),
     ]
 
 
@@ -79,7 +80,7 @@ def _elem_strides(a, n):
     return [s // a.itemsize for s in a.strides[:n]]
 
 
-def _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale):
+def _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_start=None):
     if q.dtype == np.float32:
         dtype = 0
     elif q.dtype == np.uint16:
@@ -125,12 +126,19 @@ def _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale):
     p.tree_parent = tree_parent.ctypes.data
     p.parent_stride_b = pstride
     p.scale = (1.0 / math.sqrt(D)) if scale is None else float(scale)
+    if kv_start is None:
+        p.kv_start = None
+    else:
+        kv_start = np.ascontiguousarray(kv_start, dtype=np.int32)
+        assert kv_start.shape == (B,)
+        keep.append(kv_start)
+        p.kv_start = kv_start.ctypes.data
     return p, keep
 
 
-def tree_attn_oracle(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale=None):
-    """All outputs in fp64: out [B,T,Hq,D], lse [B,Hq,T]."""
-    p, keep = _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale)
+def tree_attn_oracle(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale=None, kv_start=None):
+    """All outputs in fp64: out [B,T,Hq,D], lse [B,Hq,T].  kv_start [B]: first prefix position still attended to."""
+    p, keep = _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_start)
     out = np.empty((p.B, p.T, p.Hq, p.D), dtype=np.float64)
     lse = np.empty((p.B, p.Hq, p.T), dtype=np.float64)
     rc = _load().tree_attn_oracle(ctypes.byref(p), out.ctypes.data, lse.ctypes.data)
@@ -140,9 +148,10 @@ def tree_attn_oracle(q, k_cache, v_cache, page_table, seq_lens, tree_parent, sca
     return out, lse
 
 
-def tree_attn_oracle_sample(q, k_cache, v_cache, page_table, seq_lens, tree_parent, triples, scale=None):
+def tree_attn_oracle_sample(q, k_cache, v_cache, page_table, seq_lens, tree_parent, triples, scale=None,
+                            kv_start=None):
     """Selected outputs: triples [n,3] of (request, node, head) -> out [n,D], lse [n] in fp64."""
-    p, keep = _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale)
+    p, keep = _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_start)
     triples = np.ascontiguousarray(triples, dtype=np.int32).reshape(-1, 3)
     n = triples.shape[0]
     out = np.empty((n, p.D), dtype=np.float64)

@@ -16,9 +16,9 @@ MUTATIONS = [
     ("node does not attend to itself", "    int n = 0, cur = i;\n", "    int n = 0, cur = parent[i];\n"),
     ("siblings visible (flattened-order causal mask)", "        cur = parent[cur];\n", "        cur = cur - 1;\n"),
     ("query head h reads KV head h mod Hkv", "const int g = h / (p->Hq / p->Hkv);", "const int g = h % p->Hkv;"),
-    ("tree token at the wrong cache position", "int64_t pos = t < L ? t : L + path[t - L];\n        int64_t ko",
+    ("tree token at the wrong cache position", "int64_t pos = t < W ? S + t : L + path[t - W];\n        int64_t ko",
      "int64_t pos = t < L ? t : L + (path[t - L] + 1) % p->T;\n        int64_t ko"),
-    ("value row of another key", "int64_t pos = t < L ? t : L + path[t - L];\n        int64_t vo",
+    ("value row of another key", "int64_t pos = t < W ? S + t : L + path[t - W];\n        int64_t vo",
      "int64_t pos = t < L ? (L - 1 - t) : L + path[t - L];\n        int64_t vo"),
     ("scale dropped", "scores[t] = p->scale * dot;", "scores[t] = dot;"),
     ("page table ignored", "page = p->page_table[(int64_t)b * p->max_pages + pos / p->page_size];",
@@ -27,6 +27,8 @@ MUTATIONS = [
     ("log-sum-exp without the subtracted maximum", "*lse_out = smax + log(denom);", "*lse_out = log(denom);"),
     ("last prefix token dropped", "        scores[t] = p->scale * dot;\n",
      "        scores[t] = (t == L - 1) ? -INFINITY : p->scale * dot;\n"),
+    ("window start ignored", "const int64_t S = p->kv_start ? p->kv_start[b] : 0;", "const int64_t S = 0;"),
+    ("window off by one", "const int64_t W = L - S;", "const int64_t W = L - S + (S > 0);"),
 ]
 
 
@@ -45,7 +47,9 @@ def _battery():
              (pins.test_page_permutation_and_layout_do_not_matter, {}),
              (pins.test_query_head_reads_kv_head_h_div_g, {}),
              (pins.test_constant_values_and_no_garbage_leak, {}),
-             (pins.test_scale_is_applied_to_scores, {})]
+             (pins.test_scale_is_applied_to_scores, {}),
+             (pins.test_window_start_equals_a_cache_that_begins_there, {}),
+             (pins.test_window_start_zero_query_counts_keys_and_hides_what_lies_before, {})]
     failed = []
     for fn, kw in calls:
         try:

@@ -349,3 +349,75 @@ def test_merging_partials_over_disjoint_key_chunks_is_full_attention():
     merged = sum(math.exp(l - lse) * o for l, o in zip(ls_, os_))
     np.testing.assert_allclose(merged, full, atol=1e-14)
     assert abs(lse - full_lse) < 1e-14
+
+
+# ------------------------------------------------------------------ prefix restricted to the current sub-sequence
+# (section 5, "iRoPE": with local attention the prefix a node attends to starts at the current chunk, kv_start)
+
+def _window_case(seed=21):
+    rng = np.random.default_rng(seed)
+    B, T = 4, 9
+    trees = np.stack([W.random_tree(T, 4, rng) for _ in range(B)])
+    w = W.make_workload("win", B=B, T=T, Hq=4, Hkv=2, D=16, seq_lens=[40, 0, 17, 64], trees=trees, page_size=8,
+                        dtype="bf16", seed=seed)
+    return w, np.asarray([13, 0, 17, 1], dtype=np.int32)
+
+
+def test_window_start_equals_a_cache_that_begins_there():
+    """Attending to positions kv_start.. of a cache is attending to all of a cache whose first kv_start tokens
+    were cut off: the second is the already pinned computation on other inputs."""
+    w, start = _window_case()
+    out, lse = run_oracle(w, kv_start=start)
+    B, T, ps = w.B, w.T, 128
+    kc = np.zeros((B, w.Hkv, ps, w.D), dtype=w.k_cache.dtype)
+    vc = np.zeros_like(kc)
+    for b in range(B):
+        Lb, S = int(w.seq_lens[b]), int(start[b])
+        for pos in range(S, Lb + T):
+            page, slot = int(w.page_table[b, pos // w.page_size]), pos % w.page_size
+            kc[b, :, pos - S, :] = w.k_cache[page, :, slot, :]
+            vc[b, :, pos - S, :] = w.v_cache[page, :, slot, :]
+    ref, ref_lse = oracle.tree_attn_oracle(w.q, kc, vc, None, w.seq_lens - start, w.tree_parent, scale=w.scale)
+    np.testing.assert_array_equal(out, ref)
+    np.testing.assert_array_equal(lse, ref_lse)
+
+
+def test_window_start_zero_query_counts_keys_and_hides_what_lies_before():
+    """q = 0: lse = ln(L - kv_start + level); a key before kv_start is never seen, however well it matches q."""
+    w, start = _window_case(22)
+    wq = w.q.copy()
+    w.q[...] = 0
+    out, lse = run_oracle(w, kv_start=start)
+    for b in range(w.B):
+        lv = W.node_levels(w.parents_2d()[b])
+        for i in range(w.T):
+            np.testing.assert_allclose(lse[b, :, i], math.log(int(w.seq_lens[b]) - int(start[b]) + lv[i]),
+                                       rtol=0, atol=1e-13)
+    w.q[...] = wq
+    base, base_lse = run_oracle(w, kv_start=start)
+    # overwrite everything before the window with huge keys and values: nothing may change
+    big = np.uint16(0x4680)                                      # bf16 16384.0
+    for b in range(w.B):
+        for pos in range(int(start[b])):
+            page, slot = int(w.page_table[b, pos // w.page_size]), pos % w.page_size
+            w.k_cache[page, :, slot, :] = big
+            w.v_cache[page, :, slot, :] = big
+    again, again_lse = run_oracle(w, kv_start=start)
+    np.testing.assert_array_equal(base, again)
+    np.testing.assert_array_equal(base_lse, again_lse)
+
+
+def test_window_start_edge_values():
+    w, start = _window_case(23)
+    full, full_lse = run_oracle(w)
+    zero, zero_lse = run_oracle(w, kv_start=np.zeros(w.B, dtype=np.int32))
+    np.testing.assert_array_equal(full, zero)
+    np.testing.assert_array_equal(full_lse, zero_lse)
+    # kv_start beyond the prefix or negative poisons that request alone
+    bad = start.copy()
+    bad[0] = int(w.seq_lens[0]) + 1
+    bad[2] = -1
+    out, lse = run_oracle(w, kv_start=bad)
+    ok, ok_lse = run_oracle(w, kv_start=start)
+    assert np.isnan(out[0]).all() and np.isnan(out[2]).all() and np.isnan(lse[0]).all()
+    np.testing.assert_array_equal(out[[1, 3]], ok[[1, 3]])
