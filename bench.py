@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 WORKLOADS = {"c1": 0, "c2": 1, "c3": 2, "c4": 3, "c5": 4}
 # shapes of the regime the paper deploys (few query rows per KV head, memory-bound): workloads.make_production
-PRODUCTION = {"p1": 0, "p2": 1, "p3": 2, "p4": 3}
+PRODUCTION = {"p1": 0, "p2": 1, "p3": 2, "p4": 3, "p5": 4}
 
 
 def make(name):
@@ -71,6 +71,7 @@ def upload(w, torch):
              seq_lens=up(w.seq_lens), tree_parent=up(w.tree_parent))
     d["out"] = torch.empty_like(d["q"])
     d["lse"] = torch.empty((w.B, w.Hq, w.T), dtype=torch.float32, device="cuda")
+    d["kv_start"] = up(w.kv_start)
     return d
 
 
@@ -86,7 +87,7 @@ def cpu_baseline(w, budget_s, log):
         tri = np.stack([rng.integers(0, w.B, n), rng.integers(0, w.T, n), rng.integers(0, w.Hq, n)], axis=1)
         t0 = time.perf_counter()
         oracle.tree_attn_oracle_sample(w.q, w.k_cache, w.v_cache, w.page_table, w.seq_lens, w.tree_parent, tri,
-                                       scale=w.scale)
+                                       scale=w.scale, kv_start=w.kv_start)
         return time.perf_counter() - t0
 
     probe_n = min(total, 4 * threads)
@@ -140,7 +141,7 @@ def measure(w, steps, warmup, log, num_splits=0, kernel=0, rotate=0, check=False
         k, v = pools[i % n_pools]
         ta.tree_attn_fwd_ex(dev["q"], k, v, dev["page_table"], dev["seq_lens"], dev["tree_parent"], dev["out"],
                             dev["lse"], stream=stream, scale=w.scale, num_splits=num_splits, kernel=kernel,
-                            events=events, item_cost=item_cost)
+                            events=events, item_cost=item_cost, kv_start=dev["kv_start"])
 
     if check:
         import oracle
@@ -149,7 +150,7 @@ def measure(w, steps, warmup, log, num_splits=0, kernel=0, rotate=0, check=False
         rng = np.random.default_rng(7)
         tri = np.stack([rng.integers(0, w.B, 64), rng.integers(0, w.T, 64), rng.integers(0, w.Hq, 64)], axis=1)
         ref, ref_lse = oracle.tree_attn_oracle_sample(w.q, w.k_cache, w.v_cache, w.page_table, w.seq_lens,
-                                                      w.tree_parent, tri, scale=w.scale)
+                                                      w.tree_parent, tri, scale=w.scale, kv_start=w.kv_start)
         got = dev["out"].float().cpu().numpy()[tri[:, 0], tri[:, 1], tri[:, 2]]
         log("check: max-abs err %.3g (oracle max %.3g)" % (np.abs(got - ref).max(), np.abs(ref).max()))
 

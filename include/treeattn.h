@@ -109,6 +109,10 @@ typedef struct {
                                  (section 3.4, pre-computed static trees) that are encoded once and used for many
                                  steps.  Bits of nodes >= T are ignored.  tree_parent is still required (shape). */
     int64_t tree_masks_stride;/* words between the masks of consecutive requests; 0 = one tree for the batch */
+    const void *kv_start;     /* optional DEVICE pointer to int32 [B]: request b's nodes attend to prefix positions
+                                 kv_start[b] .. L_b - 1 only (section 3.4, iRoPE for Llama4: on local-attention layers the prefix is the
+                                 current sub-sequence), plus their tree path as always.  0 <= kv_start[b] <= L_b,
+                                 else the request is NaN-filled and TA_STATUS_BAD_SEQLEN is set.  NULL = 0. */
 } ta_opts;
 
 /*

@@ -66,8 +66,8 @@ typedef struct {
     const int32_t *tree_parent;
     int64_t parent_stride_b;  /* T, or 0 when one tree serves the whole batch */
     double scale;
-    const int32_t *kv_start;  /* [B] or NULL: first prefix position a request's nodes still attend to (section 5,
-                                 local attention: the prefix is restricted to the current sub-sequence); NULL = 0 */
+    const int32_t *kv_start;  /* [B] or NULL: first prefix position a request's nodes still attend to (section 3.4,
+                                 iRoPE for Llama4: the prefix is restricted to the current sub-sequence); NULL = 0 */
 } oracle_problem;
 
 static double widen(const void *base, int dtype, int64_t idx)

@@ -126,6 +126,8 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
         item_cost = opts->item_cost;
         if (opts->tree_masks && (((uintptr_t)opts->tree_masks % 8) != 0 || opts->tree_masks_stride < 0))
             return TA_ERR_OPTS;
+        if (opts->kv_start && ((uintptr_t)opts->kv_start % 4) != 0)
+            return TA_ERR_OPTS;
         scale = opts->scale;
         user_ws = opts->workspace;
         user_ws_bytes = opts->workspace_bytes;
@@ -176,6 +178,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     p.g_magic = (1u << 24) / (uint32_t)p.G + 1u;
     p.masks_in = opts ? (const unsigned long long *)opts->tree_masks : nullptr;
     p.masks_sb = opts ? opts->tree_masks_stride : 0;
+    p.kv_start = opts ? (const int32_t *)opts->kv_start : nullptr;
     p.is_bf16 = q->dtype == TA_BF16;
     p.scale_log2e = scale * 1.4426950408889634f;
 

@@ -38,6 +38,7 @@ struct TAParams {
     int32_t min_q;             // smallest share of tiles a workgroup takes
     int32_t pad;               // schedule units a list counts on top of its tiles (fixed cost per list)
     uint32_t g_magic;          // 2^24 / G + 1: R / G == mulhi(R << 8, g_magic) for R * G < 2^24 (matrix-core kernels)
+    const int32_t *kv_start;   // [B] window starts, or null
     const unsigned long long *masks_in;   // ancestor masks encoded earlier (or null: walk the parents in the call)
     int64_t masks_sb;          // words between the masks of consecutive requests
     int32_t is_bf16;
@@ -72,15 +73,25 @@ struct TAParams {
 // The prefix lengths live on the device, so every workgroup derives the schedule itself.
 // ---------------------------------------------------------------------------------------------
 
-__device__ __forceinline__ bool ta_request_ok(const TAParams &p, int L)
+// S: first prefix position the request's nodes still attend to (section 3.4, iRoPE for Llama4: the prefix is the current
+// sub-sequence only); 0 unless the caller gave kv_start.
+__device__ __forceinline__ int ta_kv_start(const TAParams &p, int b)
 {
-    return L >= 0 && (int64_t)L + p.T <= (int64_t)p.capacity;
+    return p.kv_start ? p.kv_start[b] : 0;
 }
 
-__device__ __forceinline__ int ta_request_tiles(const TAParams &p, int b)
+__device__ __forceinline__ bool ta_request_ok(const TAParams &p, int L, int S)
 {
-    int L = p.seq_lens[(int64_t)b * p.sl_s];
-    return ta_request_ok(p, L) ? (L + TA_TILE - 1) / TA_TILE + 1 : 1;
+    return L >= 0 && (int64_t)L + p.T <= (int64_t)p.capacity && S >= 0 && S <= L;
+}
+
+// Tiles of one list: the 64-token tiles that hold prefix positions S..L-1 (tile S/64 is the first), then the tree
+// tile.  A malformed request owns one tile.
+__device__ __forceinline__ int ta_list_tiles(const TAParams &p, int L, int S)
+{
+    if (!ta_request_ok(p, L, S))
+        return 1;
+    return (S < L ? (L + TA_TILE - 1) / TA_TILE - S / TA_TILE : 0) + 1;
 }
 
 // The KV work of the batch is one line of schedule units: request after request, KV head after KV head, and
@@ -91,15 +102,20 @@ __device__ __forceinline__ int ta_request_tiles(const TAParams &p, int b)
 // range touches only the padding of a list has no work in it and writes no partial result.
 //
 // cum[0..B]: exclusive prefix sums of the per-request unit counts (per KV head).  Needs blockDim.x >= 64; ends
-// with a barrier.  If `lens` is given, it also receives the B prefix lengths as they were read.
-__device__ __forceinline__ void ta_build_schedule(const TAParams &p, int *cum, int *lens = nullptr)
+// with a barrier.  If `lens` is given, it also receives the B prefix lengths as they were read, and `starts` the B
+// window starts.
+__device__ __forceinline__ void ta_build_schedule(const TAParams &p, int *cum, int *lens = nullptr,
+                                                  int *starts = nullptr)
 {
     const int tid = threadIdx.x;
     for (int b = tid; b < p.B; b += blockDim.x) {
         const int L = p.seq_lens[(int64_t)b * p.sl_s];
-        cum[b + 1] = (ta_request_ok(p, L) ? (L + TA_TILE - 1) / TA_TILE + 1 : 1) + p.pad;
+        const int S = ta_kv_start(p, b);
+        cum[b + 1] = ta_list_tiles(p, L, S) + p.pad;
         if (lens)
             lens[b] = L;
+        if (starts)
+            starts[b] = S;
     }
     if (tid == 0)
         cum[0] = 0;
@@ -156,6 +172,16 @@ __device__ __forceinline__ void ta_note_owner(const TAParams &p, int b, int g, i
         if (j1 == n_b)
             p.ws_parts[2 * (b * p.Hkv + g) + 1] = wv;
     }
+}
+
+// Bit k set: token k of the prefix tile that starts at position pos0 lies inside [S, L).
+__device__ __forceinline__ unsigned long long ta_prefix_tile_mask(int pos0, int L, int S)
+{
+    const int rem = L - pos0, lo = S - pos0;
+    unsigned long long m = rem < TA_TILE ? (1ull << rem) - 1ull : ~0ull;
+    if (lo > 0)
+        m &= ~((1ull << lo) - 1ull);
+    return m;
 }
 
 __device__ __forceinline__ int64_t ta_ws_row(const TAParams &p, int slot, int rg, int r)

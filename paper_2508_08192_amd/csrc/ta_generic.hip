@@ -61,7 +61,9 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
         const int slot = w + b * p.Hkv + g;
         ta_note_owner(p, b, g, w, j0, j1, n_b);
         const int L = p.seq_lens[(int64_t)b * p.sl_s];
-        bool poison = !ta_request_ok(p, L);
+        const int S = ta_kv_start(p, b);
+        bool poison = !ta_request_ok(p, L, S);
+        const int tile0 = poison ? 0 : S / TA_TILE;               // absolute index of the list's first prefix tile
         if (poison && threadIdx.x == 0)
             atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
@@ -126,8 +128,8 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
 #pragma unroll
                     for (int u = 0; u < GEN_TB; ++u) {
                         const int tk = tk0 + u;
-                        const int pos = tree_tile ? L + tk : j * TA_TILE + tk;
-                        const bool exists = tree_tile ? tk < p.T : pos < L;
+                        const int pos = tree_tile ? L + tk : (tile0 + j) * TA_TILE + tk;
+                        const bool exists = tree_tile ? tk < p.T : (pos >= S && pos < L);
                         const int64_t koff = exists ? ta_cache_offset(p, b, g, pos, p.k_sp, p.k_sh, p.k_ss) : 0;
                         const int64_t voff = exists ? ta_cache_offset(p, b, g, pos, p.v_sp, p.v_sh, p.v_ss) : 0;
 #pragma unroll
@@ -177,8 +179,9 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                 float pr[GEN_RB];
 #pragma unroll
                 for (int i = 0; i < GEN_RB; ++i) {
+                    const int pos_l = (tile0 + j) * TA_TILE + lane;
                     const bool valid = rok[i] && (tree_tile ? (lane < p.T && ((mask[i] >> lane) & 1ull))
-                                                            : (j * TA_TILE + lane < L));
+                                                            : (pos_l >= S && pos_l < L));
                     const float s = valid ? dot[i] * p.scale_log2e : -INFINITY;
                     // rows that exist always see a valid token in a tile; padding rows keep m = -inf, pr = 0
                     const float m_new = fmaxf(m[i], ta_wave_max(s));

@@ -255,7 +255,9 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
         const int slot = w + b * p.Hkv + g;
         ta_note_owner(p, b, g, w, j0, j1, n_b);
         const int L = __builtin_amdgcn_readfirstlane(p.seq_lens[(int64_t)b * p.sl_s]);
-        bool poison = !ta_request_ok(p, L);
+        const int S = __builtin_amdgcn_readfirstlane(ta_kv_start(p, b));
+        bool poison = !ta_request_ok(p, L, S);
+        const int tile0 = poison ? 0 : S / TA_TILE;                // absolute index of the list's first prefix tile
         if (poison && tid == 0)
             atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
@@ -331,7 +333,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
         Unit stage[UPT];
         auto load_tile = [&](int j) {
             const bool tree_tile = (j == n_b - 1);
-            const int tile_pos0 = tree_tile ? L : j * TA_TILE;
+            const int tile_pos0 = tree_tile ? L : (tile0 + j) * TA_TILE;
             const int limit = tree_tile ? L + p.T : L;
 #pragma unroll
             for (int s = 0; s < UPT; ++s) {
@@ -398,12 +400,13 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                 }
                 // ---- which of this lane's 32 tokens count, then the running softmax per row block
                 const bool tree_tile = (j == n_b - 1);
-                const int rem = L - j * TA_TILE;                   // tokens of a prefix tile that exist
+                const int pos0 = (tile0 + j) * TA_TILE;            // a prefix tile holds positions pos0 .. pos0+63,
+                const bool partial = L - pos0 < TA_TILE || pos0 < S;   // of which those in [S, L) count
                 uint4 pb[RB][4];
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) {
-                    if (tree_tile || rem < TA_TILE)
-                        mask_scores(acc_s[rb], (tree_tile ? tree_mask[rb] : ((1ull << rem) - 1ull)) >> (4 * hf));
+                    if (tree_tile || partial)
+                        mask_scores(acc_s[rb], (tree_tile ? tree_mask[rb] : ta_prefix_tile_mask(pos0, L, S)) >> (4 * hf));
                     softmax_tile(acc_s[rb], c, m_run[rb], l_run[rb], acc_o[rb], pb[rb]);
                 }
                 // ---- O^T += V^T . P^T, each V fragment feeding RB blocks
@@ -524,6 +527,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
     int *pcache = par_s + TA_MAX_TREE;                                    // [PP_PAGES] page ids of the current span
     int *cum = pcache + PP_PAGES;                                         // [B + 1] schedule, then [B] prefix lengths
     int *lens = cum + p.B + 1;
+    int *starts = lens + p.B;                                             // [B] window starts
     const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
 
 #ifdef TA_TUNING
@@ -540,7 +544,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
 #define TUN_ACC(k) do { } while (0)
 #define TUN_CNT(k) do { } while (0)
 #endif
-    ta_build_schedule(p, cum, lens);
+    ta_build_schedule(p, cum, lens, starts);
     TUN_MARK(0);
     TUN_ACC(0);
     const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
@@ -618,14 +622,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         const int slot = w + b * p.Hkv + g;
         ta_note_owner(p, b, g, w, j0, j1, n_b);
         const int L = __builtin_amdgcn_readfirstlane(lens[b]);
-        bool poison = !ta_request_ok(p, L);
+        const int S = __builtin_amdgcn_readfirstlane(starts[b]);
+        bool poison = !ta_request_ok(p, L, S);
+        const int tile0 = poison ? 0 : S / TA_TILE;                // absolute index of the list's first prefix tile
         if (poison && tid == 0)
             atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
         TUN_ACC(8);
         // tile ti of this item: first logical position and number of tokens it holds
-        auto tile_pos0 = [&](int ti) { return (j0 + ti == n_b - 1) ? L : (j0 + ti) * TA_TILE; };
-        auto tile_count = [&](int ti) { return (j0 + ti == n_b - 1) ? p.T : min(TA_TILE, L - (j0 + ti) * TA_TILE); };
+        auto tile_pos0 = [&](int ti) { return (j0 + ti == n_b - 1) ? L : (tile0 + j0 + ti) * TA_TILE; };
+        auto tile_count = [&](int ti) {
+            return (j0 + ti == n_b - 1) ? p.T : min(TA_TILE, L - (tile0 + j0 + ti) * TA_TILE);
+        };
         // The item is walked in spans of tiles whose page ids fit the LDS cache (one span unless the pages are
         // tiny and the share very long).
         const int span_tiles = !paged ? n
@@ -675,10 +683,13 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             const int j = j0 + ti;
             if (j == n_b - 1)
                 return (rw < rows_here ? masks[__umulhi((uint32_t)(rg * p.rows_grp + rw) << 8, p.g_magic)] : ~0ull) >> (4 * h);
-            const int rem = L - j * TA_TILE;
-            return (rem < TA_TILE ? ((1ull << rem) - 1ull) : ~0ull) >> (4 * h);
+            return ta_prefix_tile_mask((tile0 + j) * TA_TILE, L, S) >> (4 * h);
         };
-        auto tile_ragged = [&](int ti) { return j0 + ti == n_b - 1 || L - (j0 + ti) * TA_TILE < TA_TILE; };
+        // tiles that need a mask: the tree tile, a last prefix tile that is not full, a first one that begins before S
+        auto tile_ragged = [&](int ti) {
+            const int pos0 = (tile0 + j0 + ti) * TA_TILE;
+            return j0 + ti == n_b - 1 || L - pos0 < TA_TILE || pos0 < S;
+        };
         int span_first_page = 0;
         // Cache loads of tile ti into K slot ks and V slot vs: four 16-byte loads per lane.  Rows past the tile's
         // end re-read its first token (their probabilities are exactly zero).
@@ -878,14 +889,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             // whole pairs of tiles run inside sp_fast_loop, which does its own loads, re-layout and bookkeeping.
             TUN_MARK(5);
             TUN_ACC(2);
-            const int n_plain = max(0, min(ns, L / TA_TILE - (j0 + s0)));     // leading full prefix tiles of the span
+            const int n_plain = max(0, min(ns, L / TA_TILE - (tile0 + j0 + s0)));     // leading full prefix tiles of the span
             int i = 0;
 #pragma unroll 1
             while (i < ns) {
                 if (!(i & 1) && i >= 2 && fast_geom && i + 4 < n_plain && !TA_OFF(256)) {
                     TUN_ACC(3);
                     const uint32_t pairs = (uint32_t)((n_plain - 5 - i) / 2 + 1);
-                    uint32_t cnt = pairs, pos = (uint32_t)((j0 + s0 + i + 3) * TA_TILE);
+                    uint32_t cnt = pairs, pos = (uint32_t)((tile0 + j0 + s0 + i + 3) * TA_TILE);
                     uint32_t ik_o = ik * MF_TILE_BYTES, iv_o = iv * MF_TILE_BYTES, kn_o = kn * MF_TILE_BYTES;
                     uint32_t vp_o = vp * MF_TILE_BYTES, vc_o = vc * MF_TILE_BYTES;
                     const uint32_t pshift = paged ? (uint32_t)p.ps_shift : 31u;
@@ -1018,7 +1029,7 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
         return hipErrorInvalidValue;
     // One kernel for every row group: with fewer than 256 rows some of its eight waves only move tiles.
     const size_t smem = SP_AUX_OFF + sizeof(unsigned long long) * TA_MAX_TREE + 16 + sizeof(int) * TA_MAX_TREE +
-                        sizeof(int) * PP_PAGES + sizeof(int) * (2 * p.B + 2);
+                        sizeof(int) * PP_PAGES + sizeof(int) * (3 * p.B + 2);
     if (p.basic || smem > 160 * 1024 - 512)
         return launch_variant<8, 1, 512>(p, stream);       // register-staged kernel: very large batches, or on request
     static bool attr_set[64] = {};

@@ -129,6 +129,12 @@ class Workload:
     tree_parent: np.ndarray
     scale: float
     meta: dict = field(default_factory=dict)
+    kv_start: Optional[np.ndarray] = None     # int32 [B]: first prefix position still attended to (None: all of it)
+
+    def window_lens(self):
+        """Prefix tokens each request attends to."""
+        L = self.seq_lens.astype(np.int64)
+        return L if self.kv_start is None else L - self.kv_start.astype(np.int64)
 
     @property
     def B(self):
@@ -163,7 +169,7 @@ class Workload:
         """Bytes the method itself must move for one verify step: every prefix and tree K and V
         element once, q in, out, lse, the page ids touched, lengths and parents."""
         es = 4 if self.dtype == "f32" else 2
-        L = self.seq_lens.astype(np.int64)
+        L = self.window_lens()
         kv = int((L + self.T).sum()) * self.Hkv * self.D * 2 * es
         qo = 2 * self.B * self.T * self.Hq * self.D * es
         lse = 4 * self.B * self.T * self.Hq
@@ -173,7 +179,7 @@ class Workload:
 
     def useful_flops(self):
         """2 flops per multiply-add of the two contractions over every attended (query, key) pair."""
-        L = self.seq_lens.astype(np.int64)
+        L = self.window_lens()
         par = self.parents_2d()
         pairs = 0
         for b in range(self.B):
@@ -299,7 +305,8 @@ def make_config(idx, seed=None, length_div=1):
 # Shapes of the regime the paper deploys (section 3.4: static pre-computed trees, a small tree at batch size 1 and a
 # short chain above; N8 for the 70B model, N12 for Scout; one GPU's tensor-parallel share of the heads).  The paper
 # does not print the topology of its pruned trees: these are plausible stand-ins of the same sizes.
-PRODUCTION_NAMES = ("p1_70b_share_n8", "p2_70b_share_chain3", "p3_scout_share_n12", "p4_8b_n8_bs128")
+PRODUCTION_NAMES = ("p1_70b_share_n8", "p2_70b_share_chain3", "p3_scout_share_n12", "p4_8b_n8_bs128",
+                    "p5_scout_share_local")
 TREE_N8 = np.asarray([-1, 0, 0, 0, 1, 1, 2, 4], dtype=np.int32)                       # 8 nodes, 4 levels
 TREE_N12 = np.asarray([-1, 0, 0, 0, 1, 1, 1, 2, 2, 4, 4, 9], dtype=np.int32)          # 12 nodes, 5 levels
 
@@ -322,4 +329,11 @@ def make_production(idx, seed=None, length_div=1):
     if idx == 3:        # 8B-shaped on one GPU, batch 128, short prefixes, 8-node tree
         return make_workload(name, B=128, T=8, Hq=32, Hkv=8, D=128, seq_lens=rng.integers(256, 4096 + 1, size=128) // length_div,
                              trees=TREE_N8, page_size=64, seed=seed)
+    if idx == 4:        # p3's shape on a local-attention layer (section 3.4, iRoPE for Llama4): the prefix is the current 8192-token chunk
+        w = make_workload(name, B=16, T=12, Hq=5, Hkv=1, D=128,
+                          seq_lens=rng.integers(8192, 65536 + 1, size=16) // length_div,
+                          trees=TREE_N12, page_size=128, seed=seed)
+        chunk = max(8192 // length_div, 1)
+        w.kv_start = (w.seq_lens // chunk * chunk).astype(np.int32)
+        return w
     raise IndexError(idx)

@@ -38,6 +38,8 @@ def ancestors_inclusive(parent, i):
 
 def run_oracle(w, **kw):
     import oracle
+    if w.kv_start is not None:
+        kw.setdefault("kv_start", w.kv_start)
     return oracle.tree_attn_oracle(w.q, w.k_cache, w.v_cache, w.page_table, w.seq_lens, w.tree_parent,
                                    scale=w.scale, **kw)
 
@@ -70,6 +72,8 @@ def run_hip(w, dev=None, **opts):
     d["out"].fill_(float("nan"))
     d["lse"].fill_(float("nan"))
     args = (d["q"], d["k_cache"], d["v_cache"], d["page_table"], d["seq_lens"], d["tree_parent"], d["out"], d["lse"])
+    if w.kv_start is not None and "kv_start" not in opts:
+        opts = dict(opts, kv_start=torch.from_numpy(w.kv_start).cuda())
     if opts or w.scale != float(1.0 / np.sqrt(w.D)):
         ta.tree_attn_fwd_ex(*args, scale=w.scale, **opts)
     else:

@@ -216,7 +216,7 @@ def test_benchmark_configs_reduced_lengths_all_outputs(idx, div):
     _check(w)
 
 
-@pytest.mark.parametrize("idx,div", [(0, 16), (1, 32), (2, 64), (3, 16)])
+@pytest.mark.parametrize("idx,div", [(0, 16), (1, 32), (2, 64), (3, 16), (4, 16)])
 def test_production_shapes_reduced_lengths_all_outputs(idx, div):
     """Small static trees on one GPU's share of the heads (8 and 12 nodes, a chain of 3 behind the root; 5 or 8 query
     heads per KV head): every output against the oracle at reduced prefix lengths."""
@@ -390,6 +390,46 @@ def test_masks_encoded_once_replace_the_walk_over_parents(kernel):
     _announce("one mask set for the batch, kernel=%d" % kernel)
     got, got_lse = run_hip(w1, dev, kernel=kernel, tree_masks=one, num_splits=5)
     assert_parity(got, got_lse, ref, ref_lse, "bf16", "given masks, shared tree")
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA, MFMA_BASIC])
+@pytest.mark.parametrize("T,Hq,Hkv", [(8, 8, 2), (64, 8, 2)])
+def test_window_start_restricts_the_prefix(kernel, T, Hq, Hkv):
+    """ta_opts.kv_start: windows that begin on and off tile and page edges, an empty window, one that leaves a
+    single token, and long ones that run through the steady-state loop."""
+    import torch
+    rng = np.random.default_rng(41)
+    lens = [700, 64, 130, 0, 1500, 9000, 9000, 3000, 65]
+    start = [0, 64, 70, 0, 1000, 8192, 3001, 2999, 1]
+    B = len(lens)
+    trees = np.stack([W.random_tree(T, 5, rng) for _ in range(B)])
+    w = W.make_workload("window", B=B, T=T, Hq=Hq, Hkv=Hkv, D=128, seq_lens=lens, trees=trees, page_size=64,
+                        dtype="bf16", seed=4100 + T)
+    ks = np.asarray(start, dtype=np.int32)
+    ref, ref_lse = run_oracle(w, kv_start=ks)
+    dev = to_device(w)
+    dks = torch.from_numpy(ks).cuda()
+    for n in (0, 3):
+        _announce("kv_start kernel=%d T=%d num_splits=%d" % (kernel, T, n))
+        got, got_lse = run_hip(w, dev, kernel=kernel, kv_start=dks, num_splits=n)
+        assert_parity(got, got_lse, ref, ref_lse, "bf16", "kv_start num_splits=%d" % n)
+
+
+def test_window_start_out_of_range_poisons_the_request():
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+    rng = np.random.default_rng(42)
+    T = 8
+    w = W.make_workload("window_bad", B=3, T=T, Hq=4, Hkv=1, D=128, seq_lens=[100, 200, 300],
+                        trees=W.random_tree(T, 3, rng), page_size=64, dtype="bf16", seed=4201)
+    ks = np.asarray([101, 5, -1], dtype=np.int32)
+    ref, ref_lse = run_oracle(w, kv_start=ks)
+    ta.tree_attn_last_status()
+    got, got_lse = run_hip(w, kernel=MFMA, kv_start=torch.from_numpy(ks).cuda())
+    assert np.isnan(got[0]).all() and np.isnan(got[2]).all() and np.isnan(got_lse[0]).all()
+    assert np.isnan(ref[0]).all() and np.isnan(ref[2]).all()
+    assert np.abs(got[1] - ref[1]).max() <= 1e-2
+    assert ta.tree_attn_last_status() & ta.TA_STATUS_BAD_SEQLEN
 
 
 def test_empty_batch_and_no_lse():

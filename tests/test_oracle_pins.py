@@ -352,7 +352,7 @@ def test_merging_partials_over_disjoint_key_chunks_is_full_attention():
 
 
 # ------------------------------------------------------------------ prefix restricted to the current sub-sequence
-# (section 5, "iRoPE": with local attention the prefix a node attends to starts at the current chunk, kv_start)
+# (section 3.4, "iRoPE for Llama4": with local attention the prefix a node attends to starts at the current chunk, kv_start)
 
 def _window_case(seed=21):
     rng = np.random.default_rng(seed)
