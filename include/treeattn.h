@@ -167,6 +167,17 @@ int tree_attn_reserve(size_t bytes);
  */
 int tree_attn_encode(const ta_tensor *tree_parent, ta_tensor *masks, void *stream);
 
+/*
+ * Write-back of the tree tokens' keys and values (section 3.4, paged KV with tree attention: the keys and values
+ * computed in this step are written back to the cache, behind the prefix, where tree_attn_fwd reads them):
+ * k_new, v_new [B, T, Hkv, D] (dtype of the cache, unit D stride) go to logical positions L_b .. L_b+T-1 of request b
+ * in k_cache / v_cache, addressed through page_table exactly as in tree_attn_fwd (NULL = contiguous).  A request
+ * with L_b < 0 or L_b + T beyond what its page-table row can address is skipped and TA_STATUS_BAD_SEQLEN is set.
+ * One launch on `stream`, no allocation, no synchronisation.
+ */
+int tree_attn_append(const ta_tensor *k_new, const ta_tensor *v_new, ta_tensor *k_cache, ta_tensor *v_cache,
+                     const ta_tensor *page_table, const ta_tensor *seq_lens, void *stream);
+
 /* Read and clear the sticky status word of the current device.  Synchronises `stream`.
  * *host_status receives an OR of TA_STATUS_* bits (HOST pointer). */
 int tree_attn_last_status(int32_t *host_status, void *stream);

@@ -456,6 +456,68 @@ int tree_attn_encode(const ta_tensor *tree_parent, ta_tensor *masks, void *strea
     return e == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
 
+int tree_attn_append(const ta_tensor *k_new, const ta_tensor *v_new, ta_tensor *k_cache, ta_tensor *v_cache,
+                     const ta_tensor *page_table, const ta_tensor *seq_lens, void *stream)
+{
+    const ta_tensor *kn = k_new, *vn = v_new, *k = k_cache, *v = v_cache, *pt = page_table, *sl = seq_lens;
+    if (!kn || !vn || !k || !v || !sl)
+        return TA_ERR_NULL;
+    if ((kn->dtype != TA_BF16 && kn->dtype != TA_F32) || vn->dtype != kn->dtype || k->dtype != kn->dtype ||
+        v->dtype != kn->dtype || sl->dtype != TA_I32 || (pt && pt->dtype != TA_I32))
+        return TA_ERR_DTYPE;
+    if (kn->ndim != 4 || vn->ndim != 4 || k->ndim != 4 || v->ndim != 4 || sl->ndim != 1 || (pt && pt->ndim != 2))
+        return TA_ERR_RANK;
+    const int64_t B = kn->shape[0], T = kn->shape[1], Hkv = kn->shape[2], D = kn->shape[3], ps = k->shape[2];
+    if (B < 0 || B > TA_MAX_BATCH)
+        return TA_ERR_BATCH;
+    if (T < 1 || T > TA_MAX_TREE)
+        return TA_ERR_TREE_SIZE;
+    if (D < 1 || D > TA_MAX_HEAD_DIM)
+        return TA_ERR_HEAD_DIM;
+    for (int i = 0; i < 4; ++i)
+        if (vn->shape[i] != kn->shape[i] || v->shape[i] != k->shape[i])
+            return TA_ERR_SHAPE;
+    if (Hkv < 1 || k->shape[1] != Hkv || k->shape[3] != D || ps < 1 || sl->shape[0] != B)
+        return TA_ERR_SHAPE;
+    if (pt ? (pt->shape[0] != B || pt->shape[1] < 1) : k->shape[0] < B)
+        return TA_ERR_PAGE_TABLE;
+    if (!strides_ok(kn) || !strides_ok(vn) || !strides_ok(k) || !strides_ok(v) || !strides_ok(sl) ||
+        (pt && !strides_ok(pt)) || kn->stride[3] != 1 || vn->stride[3] != 1 || k->stride[3] != 1 || v->stride[3] != 1 ||
+        (pt && pt->stride[1] != 1))
+        return TA_ERR_STRIDE;
+    const int64_t capacity = pt ? pt->shape[1] * ps : ps;
+    if (capacity < T)
+        return TA_ERR_PAGE_TABLE;
+    if (capacity > INT32_MAX)
+        return TA_ERR_SHAPE;
+    if (B == 0)
+        return TA_OK;
+    if (!kn->data || !vn->data || !k->data || !v->data || !sl->data || (pt && !pt->data))
+        return TA_ERR_NULL;
+    DeviceState *s = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        int rc = device_state(&s);
+        if (rc != TA_OK)
+            return rc;
+    }
+    TAAppend a;
+    memset(&a, 0, sizeof a);
+    a.k_new = kn->data; a.v_new = vn->data; a.k = k->data; a.v = v->data;
+    a.page_table = pt ? (const int32_t *)pt->data : nullptr;
+    a.seq_lens = (const int32_t *)sl->data;
+    a.kn_sb = kn->stride[0]; a.kn_st = kn->stride[1]; a.kn_sh = kn->stride[2];
+    a.vn_sb = vn->stride[0]; a.vn_st = vn->stride[1]; a.vn_sh = vn->stride[2];
+    a.k_sp = k->stride[0]; a.k_sh = k->stride[1]; a.k_ss = k->stride[2];
+    a.v_sp = v->stride[0]; a.v_sh = v->stride[1]; a.v_ss = v->stride[2];
+    a.pt_sb = pt ? pt->stride[0] : 0;
+    a.sl_s = sl->stride[0];
+    a.B = (int)B; a.T = (int)T; a.Hkv = (int)Hkv; a.D = (int)D; a.ps = (int)ps; a.capacity = (int)capacity;
+    a.elem_bytes = kn->dtype == TA_BF16 ? 2 : 4;
+    a.status = s->status;
+    return ta_launch_append(a, (hipStream_t)stream) == hipSuccess ? TA_OK : TA_ERR_HIP;
+}
+
 int tree_attn_last_status(int32_t *host_status, void *stream)
 {
     if (!host_status)

@@ -320,5 +320,15 @@ hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream);
 hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream);
 hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream);
 int ta_merge_rows(const TAParams &p);            // output rows one workgroup of the merge pass handles
+struct TAAppend {
+    const void *k_new, *v_new;         // [B, T, Hkv, D]
+    void *k, *v;                       // caches
+    const int32_t *page_table, *seq_lens;
+    int64_t kn_sb, kn_st, kn_sh, vn_sb, vn_st, vn_sh;
+    int64_t k_sp, k_sh, k_ss, v_sp, v_sh, v_ss, pt_sb, sl_s;
+    int32_t B, T, Hkv, D, ps, capacity, elem_bytes;
+    int32_t *status;
+};
+hipError_t ta_launch_append(const TAAppend &a, hipStream_t stream);
 hipError_t ta_launch_encode(const int32_t *parent, int64_t par_sb, int B, int T, unsigned long long *masks,
                             int32_t *status, hipStream_t stream);

@@ -533,3 +533,39 @@ hipError_t ta_launch_encode(const int32_t *parent, int64_t par_sb, int B, int T,
     hipLaunchKernelGGL(ta_encode_kernel, dim3(B), dim3(TA_WAVE), 0, stream, parent, par_sb, T, masks, status);
     return hipGetLastError();
 }
+
+// Write-back of the tree tokens' K and V rows (section 3.4, paged KV with tree attention): one workgroup per
+// (request, node), threads over (KV head, head-dim element).
+template <typename E>
+__global__ __launch_bounds__(256) void ta_append_kernel(TAAppend a)
+{
+    const int b = blockIdx.x, i = blockIdx.y;
+    const int L = a.seq_lens[(int64_t)b * a.sl_s];
+    if (L < 0 || (int64_t)L + a.T > (int64_t)a.capacity) {
+        if (threadIdx.x == 0 && i == 0)
+            atomicOr(a.status, TA_STATUS_BAD_SEQLEN);
+        return;
+    }
+    const int pos = L + i;
+    int64_t page = b, slot = pos;
+    if (a.page_table) {
+        page = a.page_table[(int64_t)b * a.pt_sb + pos / a.ps];
+        slot = pos % a.ps;
+    }
+    for (int x = threadIdx.x; x < a.Hkv * a.D; x += blockDim.x) {
+        const int g = x / a.D, d = x % a.D;
+        ((E *)a.k)[page * a.k_sp + g * a.k_sh + slot * a.k_ss + d] =
+            ((const E *)a.k_new)[b * a.kn_sb + i * a.kn_st + g * a.kn_sh + d];
+        ((E *)a.v)[page * a.v_sp + g * a.v_sh + slot * a.v_ss + d] =
+            ((const E *)a.v_new)[b * a.vn_sb + i * a.vn_st + g * a.vn_sh + d];
+    }
+}
+
+hipError_t ta_launch_append(const TAAppend &a, hipStream_t stream)
+{
+    if (a.elem_bytes == 2)
+        hipLaunchKernelGGL(ta_append_kernel<uint16_t>, dim3(a.B, a.T), dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL(ta_append_kernel<uint32_t>, dim3(a.B, a.T), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}

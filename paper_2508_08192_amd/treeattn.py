@@ -22,6 +22,7 @@ TA_ERR_BATCH, TA_ERR_OPTS = -12, -13
 
 EXPORTS = (
     "tree_attn_fwd", "tree_attn_fwd_ex", "tree_attn_workspace_bytes", "tree_attn_reserve", "tree_attn_encode",
+    "tree_attn_append",
     "tree_attn_last_status", "tree_attn_plan", "tree_attn_strerror", "tree_attn_version",
 )
 
@@ -96,6 +97,8 @@ def load_library():
         lib.tree_attn_reserve.argtypes = [ctypes.c_size_t]
         lib.tree_attn_encode.restype = ctypes.c_int
         lib.tree_attn_encode.argtypes = [T, T, ctypes.c_void_p]
+        lib.tree_attn_append.restype = ctypes.c_int
+        lib.tree_attn_append.argtypes = [T, T, T, T, T, T, ctypes.c_void_p]
         lib.tree_attn_last_status.restype = ctypes.c_int
         lib.tree_attn_last_status.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
         lib.tree_attn_plan.restype = ctypes.c_int
@@ -216,6 +219,15 @@ def tree_attn_encode(tree_parent, masks, stream=None, check=True):
     rc = load_library().tree_attn_encode(_ref(a), _ref(b), _stream_ptr(stream) if stream != 0 else None)
     if check and rc != TA_OK:
         raise TreeAttnError(rc, "tree_attn_encode")
+    return rc
+
+
+def tree_attn_append(k_new, v_new, k_cache, v_cache, page_table, seq_lens, stream=None, check=True):
+    """include/treeattn.h: tree_attn_append (write-back of the tree tokens' keys and values)."""
+    ds = [_desc(x) for x in (k_new, v_new, k_cache, v_cache, page_table, seq_lens)]
+    rc = load_library().tree_attn_append(*[_ref(d) for d in ds], _stream_ptr(stream) if stream != 0 else None)
+    if check and rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_append")
     return rc
 
 

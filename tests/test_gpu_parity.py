@@ -432,6 +432,41 @@ def test_window_start_out_of_range_poisons_the_request():
     assert ta.tree_attn_last_status() & ta.TA_STATUS_BAD_SEQLEN
 
 
+@pytest.mark.parametrize("dtype,ps", [("bf16", 64), ("bf16", 0), ("f32", 16)])
+def test_write_back_of_tree_keys_and_values(dtype, ps):
+    """tree_attn_append puts k_new/v_new at positions L_b .. L_b+T-1, bit for bit, and touches nothing else; the
+    attention over the cache it completed agrees with the oracle."""
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+    rng = np.random.default_rng(51)
+    T, Hkv, D = 9, 2, 128 if dtype == "bf16" else 64
+    w = W.make_workload("append", B=3, T=T, Hq=4, Hkv=Hkv, D=D, seq_lens=[130, 0, 63], trees=W.random_tree(T, 4, rng),
+                        page_size=ps, dtype=dtype, seed=5100 + ps, paged=ps > 0)
+    ref, ref_lse = run_oracle(w)
+    dev = to_device(w)
+    # pull the tree tokens out of the cache into dense tensors, then wipe them in the cache
+    k_new = torch.empty((w.B, T, Hkv, D), dtype=dev["k_cache"].dtype, device="cuda")
+    v_new = torch.empty_like(k_new)
+    kc, vc = dev["k_cache"].clone(), dev["v_cache"].clone()
+    for b in range(w.B):
+        for i in range(T):
+            pos = int(w.seq_lens[b]) + i
+            page, slot = (b, pos) if w.page_table is None else (int(w.page_table[b, pos // ps]), pos % ps)
+            k_new[b, i] = kc[page, :, slot, :]
+            v_new[b, i] = vc[page, :, slot, :]
+            dev["k_cache"][page, :, slot, :] = 7.0
+            dev["v_cache"][page, :, slot, :] = 7.0
+    _announce("append %s ps=%d" % (dtype, ps))
+    ta.tree_attn_append(k_new, v_new, dev["k_cache"], dev["v_cache"], dev["page_table"], dev["seq_lens"])
+    torch.cuda.synchronize()
+    assert torch.equal(dev["k_cache"].view(torch.int16 if dtype == "bf16" else torch.int32),
+                       kc.view(torch.int16 if dtype == "bf16" else torch.int32))
+    assert torch.equal(dev["v_cache"].view(torch.int16 if dtype == "bf16" else torch.int32),
+                       vc.view(torch.int16 if dtype == "bf16" else torch.int32))
+    got, got_lse = run_hip(w, dev)
+    assert_parity(got, got_lse, ref, ref_lse, dtype, "after write-back")
+
+
 def test_empty_batch_and_no_lse():
     import torch
     from paper_2508_08192_amd import treeattn as ta

@@ -146,3 +146,23 @@ def test_generated_asm_blocks_match_their_generator():
     gen = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(gen)
     assert open(os.path.join(csrc, "ta_sp_block.inc")).read() == gen.generate()
+
+
+def test_append_rejects_bad_arguments_before_any_launch():
+    a = _good()
+    kn = Desc((2, 8, 2, 128), ta.TA_BF16)
+    ok = dict(k_new=kn, v_new=kn, k_cache=a["k_cache"], v_cache=a["v_cache"], page_table=a["page_table"],
+              seq_lens=a["seq_lens"])
+
+    def rc(**over):
+        d = dict(ok)
+        d.update(over)
+        return ta.tree_attn_append(d["k_new"], d["v_new"], d["k_cache"], d["v_cache"], d["page_table"], d["seq_lens"],
+                                   stream=0, check=False)
+    assert rc(k_new=None) == ta.TA_ERR_NULL
+    assert rc(v_new=Desc((2, 8, 2, 128), ta.TA_F32)) == ta.TA_ERR_DTYPE
+    assert rc(v_new=Desc((2, 8, 2, 64), ta.TA_BF16)) == ta.TA_ERR_SHAPE
+    assert rc(k_new=Desc((2, 8, 3, 128), ta.TA_BF16), v_new=Desc((2, 8, 3, 128), ta.TA_BF16)) == ta.TA_ERR_SHAPE
+    assert rc(k_new=Desc((2, 65, 2, 128), ta.TA_BF16), v_new=Desc((2, 65, 2, 128), ta.TA_BF16)) == ta.TA_ERR_TREE_SIZE
+    assert rc(seq_lens=Desc((3,), ta.TA_I32)) == ta.TA_ERR_SHAPE
+    assert rc(page_table=Desc((3, 5), ta.TA_I32)) == ta.TA_ERR_PAGE_TABLE
