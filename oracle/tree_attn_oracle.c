@@ -66,6 +66,9 @@ typedef struct {
     const int32_t *tree_parent;
     int64_t parent_stride_b;  /* T, or 0 when one tree serves the whole batch */
     double scale;
+    int32_t Tq, q_off;        /* q, out and lse hold the Tq nodes q_off .. q_off+Tq-1 of the T-node tree (section 3.1:
+                                 the same attention serves the drafting stage, where only the newest nodes are
+                                 queries and all nodes so far are keys); Tq = 0 means all T nodes */
     const int32_t *kv_start;  /* [B] or NULL: first prefix position a request's nodes still attend to (section 3.4,
                                  iRoPE for Llama4: the prefix is restricted to the current sub-sequence); NULL = 0 */
 } oracle_problem;
@@ -136,7 +139,7 @@ static void attend_one(const oracle_problem *p, int b, int i, int h,
     const int64_t L = p->seq_lens[b];
     const int32_t *par = p->tree_parent + b * p->parent_stride_b;
     int32_t path[64];
-    const int plen = root_path(par, p->T, i, path);
+    const int plen = root_path(par, p->T, p->q_off + i, path);   /* query i is tree node q_off + i */
     const int64_t S = p->kv_start ? p->kv_start[b] : 0;   /* keys: prefix positions S..L-1, then the path */
     const int64_t W = L - S;
     const int64_t nkeys = W + plen;
@@ -180,6 +183,8 @@ static int check_shapes(const oracle_problem *p)
         return -1;
     if (p->dtype != ORACLE_F32 && p->dtype != ORACLE_BF16)
         return -1;
+    if (p->Tq < 0 || p->q_off < 0 || (p->Tq ? p->Tq : p->T) + p->q_off > p->T)
+        return -1;
     return 0;
 }
 
@@ -202,7 +207,8 @@ int tree_attn_oracle_sample(const oracle_problem *p, const int32_t *triples, int
         for (int64_t s = 0; s < n; ++s) {
             int b = triples[3 * s], i = triples[3 * s + 1], h = triples[3 * s + 2];
             double *row = out + s * p->D;
-            if (b < 0 || b >= p->B || i < 0 || i >= p->T || h < 0 || h >= p->Hq || !request_is_valid(p, b)) {
+            if (b < 0 || b >= p->B || i < 0 || i >= (p->Tq ? p->Tq : p->T) || h < 0 || h >= p->Hq ||
+                !request_is_valid(p, b)) {
                 for (int d = 0; d < p->D; ++d)
                     row[d] = NAN;
                 lse[s] = NAN;
@@ -216,7 +222,7 @@ int tree_attn_oracle_sample(const oracle_problem *p, const int32_t *triples, int
     return poisoned;
 }
 
-/* Every output: out[B,T,Hq,D], lse[B,Hq,T] (both dense, fp64).
+/* Every output: out[B,Tq,Hq,D], lse[B,Hq,Tq] (both dense, fp64).
  * Returns the number of poisoned requests, or -1 on bad arguments. */
 int tree_attn_oracle(const oracle_problem *p, double *out, double *lse)
 {
@@ -230,7 +236,8 @@ int tree_attn_oracle(const oracle_problem *p, double *out, double *lse)
         if (!request_is_valid(p, b))
             poisoned += 1;
     }
-    const int64_t per_b = (int64_t)p->Hq * p->T;
+    const int Tq = p->Tq ? p->Tq : p->T;                 /* rows of q, out and lse per request */
+    const int64_t per_b = (int64_t)p->Hq * Tq;
     const int64_t total = per_b * p->B;
 #pragma omp parallel
     {
@@ -238,10 +245,10 @@ int tree_attn_oracle(const oracle_problem *p, double *out, double *lse)
 #pragma omp for schedule(dynamic, 1)
         for (int64_t w = 0; w < total; ++w) {
             int b = (int)(w / per_b);
-            int h = (int)((w % per_b) / p->T);
-            int i = (int)(w % p->T);
-            double *row = out + (((int64_t)b * p->T + i) * p->Hq + h) * p->D;
-            double *l = lse + ((int64_t)b * p->Hq + h) * p->T + i;
+            int h = (int)((w % per_b) / Tq);
+            int i = (int)(w % Tq);
+            double *row = out + (((int64_t)b * Tq + i) * p->Hq + h) * p->D;
+            double *l = lse + ((int64_t)b * p->Hq + h) * Tq + i;
             if (!request_is_valid(p, b)) {
                 for (int d = 0; d < p->D; ++d)
                     row[d] = NAN;

@@ -40,6 +40,8 @@ class _Problem(ctypes.Structure):
         ("tree_parent", ctypes.c_void_p),
         ("parent_stride_b", ctypes.c_int64),
         ("scale", ctypes.c_double),
+        ("Tq", ctypes.c_int32),
+        ("q_off", ctypes.c_int32),
         ("kv_start", ctypes.c_void_p),
     ]
 
@@ -80,7 +82,7 @@ def _elem_strides(a, n):
     return [s // a.itemsize for s in a.strides[:n]]
 
 
-def _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_start=None):
+def _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_start=None, q_node_offset=None):
     if q.dtype == np.float32:
         dtype = 0
     elif q.dtype == np.uint16:
@@ -91,12 +93,17 @@ def _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_s
         raise TypeError("q, k_cache and v_cache must share a dtype")
     if q.ndim != 4 or k_cache.ndim != 4 or v_cache.ndim != 4:
         raise ValueError("q is [B,T,Hq,D]; caches are [num_pages,Hkv,page_size,D]")
-    B, T, Hq, D = q.shape
+    B, Tq, Hq, D = q.shape
+    tree_parent = np.ascontiguousarray(tree_parent, dtype=np.int32)
+    T = tree_parent.shape[-1]                  # nodes of the tree (keys); q holds Tq of them from q_node_offset on
+    if q_node_offset is None:
+        if Tq != T:
+            raise ValueError("q has %d nodes, the tree %d: pass q_node_offset" % (Tq, T))
+        q_node_offset = 0
     _, Hkv, ps, Dk = k_cache.shape
     if Dk != D or v_cache.shape != k_cache.shape:
         raise ValueError("cache shapes disagree with q")
     seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
-    tree_parent = np.ascontiguousarray(tree_parent, dtype=np.int32)
     if tree_parent.ndim == 1:
         pstride = 0
     else:
@@ -126,6 +133,7 @@ def _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_s
     p.tree_parent = tree_parent.ctypes.data
     p.parent_stride_b = pstride
     p.scale = (1.0 / math.sqrt(D)) if scale is None else float(scale)
+    p.Tq, p.q_off = Tq, int(q_node_offset)
     if kv_start is None:
         p.kv_start = None
     else:
@@ -136,11 +144,13 @@ def _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_s
     return p, keep
 
 
-def tree_attn_oracle(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale=None, kv_start=None):
-    """All outputs in fp64: out [B,T,Hq,D], lse [B,Hq,T].  kv_start [B]: first prefix position still attended to."""
-    p, keep = _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_start)
-    out = np.empty((p.B, p.T, p.Hq, p.D), dtype=np.float64)
-    lse = np.empty((p.B, p.Hq, p.T), dtype=np.float64)
+def tree_attn_oracle(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale=None, kv_start=None,
+                     q_node_offset=None):
+    """All outputs in fp64: out [B,Tq,Hq,D], lse [B,Hq,Tq].  kv_start [B]: first prefix position still attended to.
+    q_node_offset: q holds the nodes q_node_offset .. q_node_offset+Tq-1 of the tree (default: all of them)."""
+    p, keep = _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_start, q_node_offset)
+    out = np.empty((p.B, p.Tq, p.Hq, p.D), dtype=np.float64)
+    lse = np.empty((p.B, p.Hq, p.Tq), dtype=np.float64)
     rc = _load().tree_attn_oracle(ctypes.byref(p), out.ctypes.data, lse.ctypes.data)
     if rc < 0:
         raise ValueError("oracle rejected the arguments")
@@ -149,9 +159,9 @@ def tree_attn_oracle(q, k_cache, v_cache, page_table, seq_lens, tree_parent, sca
 
 
 def tree_attn_oracle_sample(q, k_cache, v_cache, page_table, seq_lens, tree_parent, triples, scale=None,
-                            kv_start=None):
-    """Selected outputs: triples [n,3] of (request, node, head) -> out [n,D], lse [n] in fp64."""
-    p, keep = _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_start)
+                            kv_start=None, q_node_offset=None):
+    """Selected outputs: triples [n,3] of (request, row of q, head) -> out [n,D], lse [n] in fp64."""
+    p, keep = _marshal(q, k_cache, v_cache, page_table, seq_lens, tree_parent, scale, kv_start, q_node_offset)
     triples = np.ascontiguousarray(triples, dtype=np.int32).reshape(-1, 3)
     n = triples.shape[0]
     out = np.empty((n, p.D), dtype=np.float64)

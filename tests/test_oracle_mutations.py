@@ -29,6 +29,8 @@ MUTATIONS = [
      "        scores[t] = (t == L - 1) ? -INFINITY : p->scale * dot;\n"),
     ("window start ignored", "const int64_t S = p->kv_start ? p->kv_start[b] : 0;", "const int64_t S = 0;"),
     ("window off by one", "const int64_t W = L - S;", "const int64_t W = L - S + (S > 0);"),
+    ("query range starts at node 0 whatever the offset", "root_path(par, p->T, p->q_off + i, path);",
+     "root_path(par, p->T, i, path);"),
 ]
 
 
@@ -49,7 +51,8 @@ def _battery():
              (pins.test_constant_values_and_no_garbage_leak, {}),
              (pins.test_scale_is_applied_to_scores, {}),
              (pins.test_window_start_equals_a_cache_that_begins_there, {}),
-             (pins.test_window_start_zero_query_counts_keys_and_hides_what_lies_before, {})]
+             (pins.test_window_start_zero_query_counts_keys_and_hides_what_lies_before, {}),
+             (pins.test_query_subset_equals_those_rows_of_the_whole_tree, {})]
     failed = []
     for fn, kw in calls:
         try:

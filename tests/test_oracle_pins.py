@@ -421,3 +421,34 @@ def test_window_start_edge_values():
     ok, ok_lse = run_oracle(w, kv_start=start)
     assert np.isnan(out[0]).all() and np.isnan(out[2]).all() and np.isnan(lse[0]).all()
     np.testing.assert_array_equal(out[[1, 3]], ok[[1, 3]])
+
+
+# ------------------------------------------------------------------ queries are a range of the tree's nodes
+# (section 3.1: the same attention is used in the drafting stage, where the newest nodes ask and every node so far,
+# behind the prefix, is a key)
+
+def test_query_subset_equals_those_rows_of_the_whole_tree():
+    rng = np.random.default_rng(31)
+    B, T = 3, 11
+    trees = np.stack([W.random_tree(T, 5, rng) for _ in range(B)])
+    w = W.make_workload("sub", B=B, T=T, Hq=4, Hkv=2, D=16, seq_lens=[29, 0, 64], trees=trees, page_size=8,
+                        dtype="bf16", seed=31)
+    full, full_lse = run_oracle(w)
+    for off, tq in [(0, 11), (7, 4), (3, 1), (0, 5), (10, 1)]:
+        q = np.ascontiguousarray(w.q[:, off:off + tq])
+        out, lse = oracle.tree_attn_oracle(q, w.k_cache, w.v_cache, w.page_table, w.seq_lens, w.tree_parent,
+                                           scale=w.scale, q_node_offset=off)
+        assert out.shape == (B, tq, 4, 16) and lse.shape == (B, 4, tq)
+        np.testing.assert_array_equal(out, full[:, off:off + tq])
+        np.testing.assert_array_equal(lse, full_lse[:, :, off:off + tq])
+    # the same through the sampled entry point
+    tri = np.asarray([[0, 1, 3], [2, 3, 0], [1, 0, 2]], dtype=np.int32)
+    q = np.ascontiguousarray(w.q[:, 6:10])
+    so, sl = oracle.tree_attn_oracle_sample(q, w.k_cache, w.v_cache, w.page_table, w.seq_lens, w.tree_parent, tri,
+                                            scale=w.scale, q_node_offset=6)
+    for k, (b, i, h) in enumerate(tri):
+        np.testing.assert_array_equal(so[k], full[b, 6 + i, h])
+        assert sl[k] == full_lse[b, h, 6 + i]
+    with pytest.raises(ValueError):
+        oracle.tree_attn_oracle(q, w.k_cache, w.v_cache, w.page_table, w.seq_lens, w.tree_parent, scale=w.scale,
+                                q_node_offset=8)                 # 8 + 4 nodes do not fit a tree of 11
