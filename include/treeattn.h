@@ -109,6 +109,11 @@ typedef struct {
                                  (section 3.4, pre-computed static trees) that are encoded once and used for many
                                  steps.  Bits of nodes >= T are ignored.  tree_parent is still required (shape). */
     int64_t tree_masks_stride;/* words between the masks of consecutive requests; 0 = one tree for the batch */
+    int32_t q_node_offset;    /* q, out and lse may hold fewer nodes than tree_parent describes: their row i is tree
+                                 node q_node_offset + i, while all T nodes of the tree are keys (section 3.1: the
+                                 same attention serves the drafting stage, where only the newest nodes ask).
+                                 0 <= q_node_offset, q_node_offset + q.shape[1] <= T.  Default 0. */
+    int32_t reserved;         /* must be 0 */
     const void *kv_start;     /* optional DEVICE pointer to int32 [B]: request b's nodes attend to prefix positions
                                  kv_start[b] .. L_b - 1 only (section 3.4, iRoPE for Llama4: on local-attention layers the prefix is the
                                  current sub-sequence), plus their tree path as always.  0 <= kv_start[b] <= L_b,
@@ -118,7 +123,8 @@ typedef struct {
 /*
  * Tree attention forward (section 3.1; cache addressing per section 3.4).
  *
- *   q           [B, T, Hq, D]  TA_BF16 or TA_F32; node i of request b, query head h
+ *   q           [B, T, Hq, D]  TA_BF16 or TA_F32; node i of request b, query head h (fewer nodes than the tree has:
+ *               see ta_opts.q_node_offset)
  *   k_cache     [num_pages, Hkv, page_size, D] -- any 4-D strided view with unit D stride, dtype of q.
  *               Token at logical position t of request b, KV head g lives in page page_table[b][t / page_size],
  *               slot t % page_size.  Logical positions 0..L_b-1 are the prefix, L_b+i is tree node i.

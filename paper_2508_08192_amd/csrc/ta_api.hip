@@ -67,12 +67,18 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     if (q->ndim != 4 || k->ndim != 4 || v->ndim != 4 || out->ndim != 4 || sl->ndim != 1 ||
         (par->ndim != 1 && par->ndim != 2) || (pt && pt->ndim != 2) || (lse && lse->ndim != 3))
         return TA_ERR_RANK;
-    const int64_t B = q->shape[0], T = q->shape[1], Hq = q->shape[2], D = q->shape[3];
+    // T: nodes of the tree, all of them keys; Tq: the nodes that ask, q_off .. q_off+Tq-1 (all of them by default)
+    const int64_t B = q->shape[0], Tq = q->shape[1], Hq = q->shape[2], D = q->shape[3];
+    const int64_t T = par->shape[par->ndim - 1], q_off = opts ? opts->q_node_offset : 0;
     const int64_t n_pages = k->shape[0], Hkv = k->shape[1], ps = k->shape[2];
     if (B < 0 || B > TA_MAX_BATCH)
         return TA_ERR_BATCH;
-    if (T < 1 || T > TA_MAX_TREE)
+    if (T < 1 || T > TA_MAX_TREE || Tq < 1 || Tq > TA_MAX_TREE)
         return TA_ERR_TREE_SIZE;
+    if (Tq > T)
+        return TA_ERR_SHAPE;                     // more query nodes than the tree has
+    if (q_off < 0 || q_off + Tq > T)
+        return TA_ERR_OPTS;
     if (D < 1 || D > TA_MAX_HEAD_DIM)
         return TA_ERR_HEAD_DIM;
     if (Hq < 1 || Hkv < 1 || Hq % Hkv != 0)
@@ -86,9 +92,9 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
             return TA_ERR_SHAPE;
     if (sl->shape[0] != B)
         return TA_ERR_SHAPE;
-    if (par->ndim == 2 ? (par->shape[0] != B || par->shape[1] != T) : (par->shape[0] != T))
+    if (par->ndim == 2 && par->shape[0] != B)
         return TA_ERR_SHAPE;
-    if (lse && (lse->shape[0] != B || lse->shape[1] != Hq || lse->shape[2] != T))
+    if (lse && (lse->shape[0] != B || lse->shape[1] != Hq || lse->shape[2] != Tq))
         return TA_ERR_SHAPE;
     if (pt && pt->shape[0] != B)
         return TA_ERR_SHAPE;
@@ -118,7 +124,8 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     void *user_ws = nullptr;
     size_t user_ws_bytes = 0;
     if (opts) {
-        if (opts->item_cost < 0 || opts->item_cost > 4096 || opts->num_splits < 0 || opts->kernel < TA_KERNEL_AUTO ||
+        if (opts->item_cost < 0 || opts->item_cost > 4096 || opts->reserved != 0 || opts->num_splits < 0 ||
+            opts->kernel < TA_KERNEL_AUTO ||
             opts->kernel > TA_KERNEL_MFMA_BASIC)
             return TA_ERR_OPTS;
         kernel = opts->kernel;
@@ -174,7 +181,8 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     p.sl_s = sl->stride[0];
     p.B = (int)B; p.T = (int)T; p.Hq = (int)Hq; p.Hkv = (int)Hkv; p.G = (int)(Hq / Hkv); p.D = (int)D;
     p.ps = (int)ps; p.ps_shift = ps_shift; p.capacity = (int)capacity;
-    p.rows = p.T * p.G;
+    p.rows = (int)Tq * p.G;
+    p.q_off = (int)q_off;
     p.g_magic = (1u << 24) / (uint32_t)p.G + 1u;
     p.masks_in = opts ? (const unsigned long long *)opts->tree_masks : nullptr;
     p.masks_sb = opts ? opts->tree_masks_stride : 0;

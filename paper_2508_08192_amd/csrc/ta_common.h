@@ -39,6 +39,7 @@ struct TAParams {
     int32_t pad;               // schedule units a list counts on top of its tiles (fixed cost per list)
     uint32_t g_magic;          // 2^24 / G + 1: R / G == mulhi(R << 8, g_magic) for R * G < 2^24 (matrix-core kernels)
     const int32_t *kv_start;   // [B] window starts, or null
+    int32_t q_off;             // row r of q, out and lse is tree node q_off + r / G (rows = Tq * G)
     const unsigned long long *masks_in;   // ancestor masks encoded earlier (or null: walk the parents in the call)
     int64_t masks_sb;          // words between the masks of consecutive requests
     int32_t is_bf16;

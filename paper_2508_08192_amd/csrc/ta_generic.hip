@@ -117,7 +117,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                 float *qs = qrow + (wave * GEN_RB + i) * p.D;
                 for (int d = lane; d < p.D; d += TA_WAVE)
                     qs[d] = load_elem<BF16>(p.q, qoff + d);
-                mask[i] = has_tree_tile ? masks[node] : 0ull;
+                mask[i] = has_tree_tile ? masks[p.q_off + node] : 0ull;
             }
             for (int j = j0; j < j1; ++j) {
                 const bool tree_tile = (j == n_b - 1);

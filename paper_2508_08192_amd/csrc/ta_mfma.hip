@@ -313,7 +313,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                     qf[rb][kk] = make_uint4(0, 0, 0, 0);
             }
             // Rows of padding keep an all-ones mask so that their (discarded) softmax stays finite.
-            tree_mask[rb] = (has_tree_tile && row_ok) ? masks[node] : ~0ull;
+            tree_mask[rb] = (has_tree_tile && row_ok) ? masks[p.q_off + node] : ~0ull;
         }
 
         f32x16 acc_o[RB][4];
@@ -682,7 +682,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             const int rw = (x >> 6) * 32 + (x & 31), h = (x >> 5) & 1;
             const int j = j0 + ti;
             if (j == n_b - 1)
-                return (rw < rows_here ? masks[__umulhi((uint32_t)(rg * p.rows_grp + rw) << 8, p.g_magic)] : ~0ull) >> (4 * h);
+                return (rw < rows_here ? masks[p.q_off + __umulhi((uint32_t)(rg * p.rows_grp + rw) << 8, p.g_magic)]
+                                       : ~0ull) >> (4 * h);
             return ta_prefix_tile_mask((tile0 + j) * TA_TILE, L, S) >> (4 * h);
         };
         // tiles that need a mask: the tree tile, a last prefix tile that is not full, a first one that begins before S

@@ -48,6 +48,8 @@ class ta_opts(ctypes.Structure):
         ("events", ctypes.c_void_p * 3),
         ("tree_masks", ctypes.c_void_p),
         ("tree_masks_stride", ctypes.c_int64),
+        ("q_node_offset", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
         ("kv_start", ctypes.c_void_p),
     ]
 
@@ -153,7 +155,7 @@ def _stream_ptr(stream):
 
 
 def _opts(scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None, item_cost=0, tree_masks=None,
-          kv_start=None):
+          kv_start=None, q_node_offset=0):
     o = ta_opts()
     o.scale = 0.0 if scale is None else float(scale)
     o.num_splits = int(num_splits)
@@ -170,6 +172,7 @@ def _opts(scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, event
         o.tree_masks_stride = int(tree_masks.stride(0)) if tree_masks.dim() == 2 else 0
     if kv_start is not None:                           # int32 [B], contiguous
         o.kv_start = kv_start.data_ptr()
+    o.q_node_offset = int(q_node_offset)
     return o
 
 
@@ -192,10 +195,10 @@ def tree_attn_fwd(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, l
 
 def tree_attn_fwd_ex(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse=None, stream=None,
                      scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None, check=True,
-                     item_cost=0, tree_masks=None, kv_start=None):
+                     item_cost=0, tree_masks=None, kv_start=None, q_node_offset=0):
     """include/treeattn.h: tree_attn_fwd_ex.  `events`: up to three hipEvent_t handles (ctypes.c_void_p)."""
     ds = [_desc(x) for x in (q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse)]
-    o = _opts(scale, num_splits, kernel, workspace, events, item_cost, tree_masks, kv_start)
+    o = _opts(scale, num_splits, kernel, workspace, events, item_cost, tree_masks, kv_start, q_node_offset)
     rc = load_library().tree_attn_fwd_ex(*[_ref(d) for d in ds], _stream_ptr(stream) if stream != 0 else None,
                                          ctypes.byref(o))
     if check and rc != TA_OK:

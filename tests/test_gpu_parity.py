@@ -467,6 +467,34 @@ def test_write_back_of_tree_keys_and_values(dtype, ps):
     assert_parity(got, got_lse, ref, ref_lse, dtype, "after write-back")
 
 
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA, MFMA_BASIC])
+def test_queries_are_a_range_of_the_tree_nodes(kernel):
+    """Drafting stage: the tree grows level by level; the newest nodes are the queries (ta_opts.q_node_offset), every
+    node so far is a key.  Each level's outputs are the corresponding rows of the whole-tree result."""
+    import torch
+    rng = np.random.default_rng(61)
+    T = 21
+    tree = W.bfs_tree(T, [4, 2, 1], 4)                              # levels of 1, 4, 8, 8 nodes, numbered level by level
+    w = W.make_workload("draft", B=3, T=T, Hq=8, Hkv=2, D=128, seq_lens=[900, 0, 131], trees=tree, page_size=64,
+                        dtype="bf16", seed=6101)
+    ref, ref_lse = run_oracle(w)
+    dev = to_device(w)
+    q_all = dev["q"]
+    for off, tq in [(0, 1), (1, 4), (5, 8), (13, 8), (0, 21), (20, 1)]:
+        dev["q"] = q_all[:, off:off + tq].contiguous()
+        dev["out"] = torch.empty_like(dev["q"])
+        dev["lse"] = torch.empty((w.B, w.Hq, tq), dtype=torch.float32, device="cuda")
+        _announce("query nodes %d..%d kernel=%d" % (off, off + tq - 1, kernel))
+        got, got_lse = run_hip(w, dev, kernel=kernel, q_node_offset=off)
+        assert_parity(got, got_lse, ref[:, off:off + tq], ref_lse[:, :, off:off + tq], "bf16", "nodes from %d" % off)
+    # a view into the full q works as well (strided rows)
+    dev["q"] = q_all[:, 5:13]
+    dev["out"] = torch.empty((w.B, 8, w.Hq, w.D), dtype=q_all.dtype, device="cuda")
+    dev["lse"] = torch.empty((w.B, w.Hq, 8), dtype=torch.float32, device="cuda")
+    got, got_lse = run_hip(w, dev, kernel=kernel, q_node_offset=5)
+    assert_parity(got, got_lse, ref[:, 5:13], ref_lse[:, :, 5:13], "bf16", "q view")
+
+
 def test_empty_batch_and_no_lse():
     import torch
     from paper_2508_08192_amd import treeattn as ta
