@@ -156,7 +156,7 @@ int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tens
  * Upper bound, in bytes, of the scratch a call with these sizes needs (split-KV partial outputs and
  * their log-sum-exps; section 3.1, the partial results that the merge combines).  Host-only.
  * `num_cus` is the compute-unit count of the target device (0 = query the current device, 256 when
- * no device is present).  Returns 0 for invalid sizes.
+ * no device is present).  T counts the query nodes (q.shape[1]).  Returns 0 for invalid sizes.
  */
 size_t tree_attn_workspace_bytes(int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t D,
                                  int32_t dtype, int32_t num_cus);
