@@ -88,7 +88,7 @@ typedef struct {
                                  aligned q/k/v rows, at most 256 query heads per KV head */
 #define TA_KERNEL_MFMA_BASIC 3 /* as MFMA, but with the plain register-staged matrix-core kernel instead of the
                                  software-pipelined one (the library falls back to it by itself when the batch
-                                 is so large, B above ~2500, that its schedule does not fit beside the tiles in LDS) */
+                                 is so large, B above ~1900, that its schedule does not fit beside the tiles in LDS) */
 
 typedef struct {
     float scale;              /* softmax scale; <= 0 or NaN selects 1/sqrt(head_dim) */
@@ -115,9 +115,10 @@ typedef struct {
                                  0 <= q_node_offset, q_node_offset + q.shape[1] <= T.  Default 0. */
     int32_t reserved;         /* must be 0 */
     const void *kv_start;     /* optional DEVICE pointer to int32 [B]: request b's nodes attend to prefix positions
-                                 kv_start[b] .. L_b - 1 only (section 3.4, iRoPE for Llama4: on local-attention layers the prefix is the
-                                 current sub-sequence), plus their tree path as always.  0 <= kv_start[b] <= L_b,
-                                 else the request is NaN-filled and TA_STATUS_BAD_SEQLEN is set.  NULL = 0. */
+                                 kv_start[b] .. L_b - 1 only (section 3.4, iRoPE for Llama4: on local-attention
+                                 layers the prefix is the current sub-sequence), plus their tree path as always.
+                                 0 <= kv_start[b] <= L_b, else the request is NaN-filled and TA_STATUS_BAD_SEQLEN
+                                 is set.  NULL = 0. */
 } ta_opts;
 
 /*
