@@ -495,6 +495,19 @@ def test_queries_are_a_range_of_the_tree_nodes(kernel):
     assert_parity(got, got_lse, ref[:, 5:13], ref_lse[:, :, 5:13], "bf16", "q view")
 
 
+def test_very_large_batch_falls_back_to_the_register_staged_kernel():
+    """With more than about 1900 requests the schedule no longer fits beside the tile rings in LDS and the library
+    takes the register-staged matrix-core kernel by itself (kernel = MFMA is still what the caller asked for)."""
+    rng = np.random.default_rng(71)
+    B, T = 2100, 4
+    lens = rng.integers(0, 200, size=B)
+    w = W.make_workload("big_batch", B=B, T=T, Hq=4, Hkv=1, D=128, seq_lens=lens, trees=W.chain_tree(T), page_size=64,
+                        dtype="bf16", seed=7101)
+    ks = (lens // 3).astype(np.int32)
+    w.kv_start = ks
+    _check(w, "B=2100 with window starts", kernel=MFMA)
+
+
 def test_empty_batch_and_no_lse():
     import torch
     from paper_2508_08192_amd import treeattn as ta
