@@ -415,6 +415,23 @@ def test_window_start_restricts_the_prefix(kernel, T, Hq, Hkv):
         assert_parity(got, got_lse, ref, ref_lse, "bf16", "kv_start num_splits=%d" % n)
 
 
+@pytest.mark.parametrize("ps", [0, 8, 256])
+def test_window_start_other_layouts(ps):
+    """The window start with the contiguous cache, with pages smaller than a tile (several page-id spans) and with
+    pages larger than one."""
+    import torch
+    rng = np.random.default_rng(43)
+    T = 16
+    lens = [20000, 777, 4100]
+    start = [18000 if ps != 8 else 1000, 700, 4096]
+    trees = np.stack([W.random_tree(T, 5, rng) for _ in range(3)])
+    w = W.make_workload("window_ps%d" % ps, B=3, T=T, Hq=16, Hkv=1, D=128, seq_lens=lens, trees=trees, page_size=ps,
+                        dtype="bf16", seed=4300 + ps, paged=ps > 0)
+    w.kv_start = np.asarray(start, dtype=np.int32)
+    _check(w, "window ps=%d one share" % ps, kernel=MFMA, num_splits=1)
+    _check(w, "window ps=%d" % ps, kernel=MFMA)
+
+
 def test_window_start_out_of_range_poisons_the_request():
     import torch
     from paper_2508_08192_amd import treeattn as ta
