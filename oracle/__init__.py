@@ -1,4 +1,4 @@
-"""fp64 CPU oracle for tree attention (test infrastructure only).
+"""CPU oracles: fp64 tree attention and the cache bookkeeping after acceptance (test infrastructure only).
 
 Only tests, the smoke check and the bench's cpu_baseline leg may import this
 package.  It shares no code with the HIP path and never imports it.
@@ -9,3 +9,4 @@ from .treeattn_oracle import (  # noqa: F401
     tree_attn_oracle,
     tree_attn_oracle_sample,
 )
+from .kv_compact_oracle import kv_compact_oracle  # noqa: F401,E402
