@@ -9,4 +9,4 @@ from .treeattn_oracle import (  # noqa: F401
     tree_attn_oracle,
     tree_attn_oracle_sample,
 )
-from .kv_compact_oracle import kv_compact_oracle  # noqa: F401,E402
+from . import kv_compact_oracle  # noqa: F401,E402  (module: kv_compact_oracle.kv_compact_oracle)
