@@ -72,6 +72,7 @@ typedef enum {
 /* Bits of the sticky device status word. */
 #define TA_STATUS_BAD_PARENT 1   /* parent id outside [-1, T) or a parent cycle */
 #define TA_STATUS_BAD_SEQLEN 2   /* L_b < 0 or L_b + T > max_pages * page_size */
+#define TA_STATUS_BAD_PATH 4     /* tree_attn_compact: accepted length outside [0, A] or a node id outside [0, T) */
 
 typedef struct {
     void *data;           /* device pointer */
@@ -184,6 +185,28 @@ int tree_attn_encode(const ta_tensor *tree_parent, ta_tensor *masks, void *strea
  */
 int tree_attn_append(const ta_tensor *k_new, const ta_tensor *v_new, ta_tensor *k_cache, ta_tensor *v_cache,
                      const ta_tensor *page_table, const ta_tensor *seq_lens, void *stream);
+
+/*
+ * Bookkeeping after acceptance (section 3, stage 6: the KV cache is rewound to the position the accepted length
+ * gives; with a tree, node i of request b sits at logical position L_b + i, so the accepted path is first made
+ * contiguous): the K/V rows of nodes accepted[b][0 .. n_b-1] (node ids, path order, root first; n_b =
+ * n_accepted[b]) become logical positions L_b .. L_b+n_b-1 of request b, addressed through page_table exactly as in
+ * tree_attn_fwd (NULL = contiguous).  Every row is read before any is written, so sources and destinations may
+ * overlap; nothing else in the caches changes.
+ *
+ *   accepted      TA_I32 [B, A], 1 <= A <= TA_MAX_TREE, unit inner stride; entries past n_b are not read
+ *   n_accepted    TA_I32 [B]
+ *   tree_size     T: node ids must lie in [0, T); 1 <= T <= TA_MAX_TREE
+ *   seq_lens_out  TA_I32 [B] or NULL: receives L_b + n_b.  May be seq_lens itself (same pointer and stride), must not
+ *                 overlap it otherwise.
+ *
+ * A request with L_b < 0, L_b + T beyond what its page-table row can address (TA_STATUS_BAD_SEQLEN), n_b outside
+ * [0, A] or a node id outside [0, T) (TA_STATUS_BAD_PATH) is left alone and its length is passed through unchanged.
+ * One launch on `stream` (one workgroup per request), no allocation, no synchronisation.
+ */
+int tree_attn_compact(ta_tensor *k_cache, ta_tensor *v_cache, const ta_tensor *page_table, const ta_tensor *seq_lens,
+                      const ta_tensor *accepted, const ta_tensor *n_accepted, int32_t tree_size,
+                      ta_tensor *seq_lens_out, void *stream);
 
 /* Read and clear the sticky status word of the current device.  Synchronises `stream`.
  * *host_status receives an OR of TA_STATUS_* bits (HOST pointer). */

@@ -526,6 +526,82 @@ int tree_attn_append(const ta_tensor *k_new, const ta_tensor *v_new, ta_tensor *
     return ta_launch_append(a, (hipStream_t)stream) == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
 
+int tree_attn_compact(ta_tensor *k_cache, ta_tensor *v_cache, const ta_tensor *page_table, const ta_tensor *seq_lens,
+                      const ta_tensor *accepted, const ta_tensor *n_accepted, int32_t tree_size,
+                      ta_tensor *seq_lens_out, void *stream)
+{
+    const ta_tensor *k = k_cache, *v = v_cache, *pt = page_table, *sl = seq_lens, *ac = accepted, *na = n_accepted;
+    const ta_tensor *so = seq_lens_out;
+    if (!k || !v || !sl || !ac || !na)
+        return TA_ERR_NULL;
+    if ((k->dtype != TA_BF16 && k->dtype != TA_F32) || v->dtype != k->dtype || sl->dtype != TA_I32 ||
+        ac->dtype != TA_I32 || na->dtype != TA_I32 || (pt && pt->dtype != TA_I32) || (so && so->dtype != TA_I32))
+        return TA_ERR_DTYPE;
+    if (k->ndim != 4 || v->ndim != 4 || sl->ndim != 1 || ac->ndim != 2 || na->ndim != 1 || (pt && pt->ndim != 2) ||
+        (so && so->ndim != 1))
+        return TA_ERR_RANK;
+    const int64_t B = ac->shape[0], A = ac->shape[1], Hkv = k->shape[1], D = k->shape[3], ps = k->shape[2];
+    const int64_t T = tree_size;
+    if (B < 0 || B > TA_MAX_BATCH)
+        return TA_ERR_BATCH;
+    if (T < 1 || T > TA_MAX_TREE || A < 1 || A > TA_MAX_TREE)
+        return TA_ERR_TREE_SIZE;
+    if (D < 1 || D > TA_MAX_HEAD_DIM)
+        return TA_ERR_HEAD_DIM;
+    for (int i = 0; i < 4; ++i)
+        if (v->shape[i] != k->shape[i])
+            return TA_ERR_SHAPE;
+    if (Hkv < 1 || ps < 1 || sl->shape[0] != B || na->shape[0] != B || (so && so->shape[0] != B))
+        return TA_ERR_SHAPE;
+    if (pt ? (pt->shape[0] != B || pt->shape[1] < 1) : k->shape[0] < B)
+        return TA_ERR_PAGE_TABLE;
+    if (!strides_ok(k) || !strides_ok(v) || !strides_ok(ac) || (pt && !strides_ok(pt)) || k->stride[3] != 1 ||
+        v->stride[3] != 1 || (pt && pt->stride[1] != 1) || sl->stride[0] < 0 || na->stride[0] < 0 ||
+        (so && so->stride[0] < 0))
+        return TA_ERR_STRIDE;
+    const int64_t capacity = pt ? pt->shape[1] * ps : ps;
+    if (capacity < T)
+        return TA_ERR_PAGE_TABLE;
+    if (capacity > INT32_MAX)
+        return TA_ERR_SHAPE;
+    if (B == 0)
+        return TA_OK;
+    if (!k->data || !v->data || !sl->data || !ac->data || !na->data || (pt && !pt->data) || (so && !so->data))
+        return TA_ERR_NULL;
+    if (so && B > 1) {
+        // the lengths may be updated in place; any other overlap of the two arrays would let one request's new length
+        // be read as another's old one
+        const bool same = so->data == sl->data && so->stride[0] == sl->stride[0];
+        const char *a0 = (const char *)sl->data, *a1 = a0 + ((B - 1) * sl->stride[0] + 1) * 4;
+        const char *b0 = (const char *)so->data, *b1 = b0 + ((B - 1) * so->stride[0] + 1) * 4;
+        if (!same && a0 < b1 && b0 < a1)
+            return TA_ERR_STRIDE;
+    }
+    DeviceState *s = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        int rc = device_state(&s);
+        if (rc != TA_OK)
+            return rc;
+    }
+    TACompact c;
+    memset(&c, 0, sizeof c);
+    c.k = k->data; c.v = v->data;
+    c.page_table = pt ? (const int32_t *)pt->data : nullptr;
+    c.seq_lens = (const int32_t *)sl->data;
+    c.accepted = (const int32_t *)ac->data;
+    c.n_accepted = (const int32_t *)na->data;
+    c.seq_lens_out = so ? (int32_t *)so->data : nullptr;
+    c.k_sp = k->stride[0]; c.k_sh = k->stride[1]; c.k_ss = k->stride[2];
+    c.v_sp = v->stride[0]; c.v_sh = v->stride[1]; c.v_ss = v->stride[2];
+    c.pt_sb = pt ? pt->stride[0] : 0;
+    c.sl_s = sl->stride[0]; c.acc_sb = ac->stride[0]; c.na_s = na->stride[0]; c.slo_s = so ? so->stride[0] : 0;
+    c.B = (int)B; c.T = (int)T; c.A = (int)A; c.Hkv = (int)Hkv; c.D = (int)D; c.ps = (int)ps; c.capacity = (int)capacity;
+    c.elem_bytes = k->dtype == TA_BF16 ? 2 : 4;
+    c.status = s->status;
+    return ta_launch_compact(c, (hipStream_t)stream) == hipSuccess ? TA_OK : TA_ERR_HIP;
+}
+
 int tree_attn_last_status(int32_t *host_status, void *stream)
 {
     if (!host_status)

@@ -331,5 +331,14 @@ struct TAAppend {
     int32_t *status;
 };
 hipError_t ta_launch_append(const TAAppend &a, hipStream_t stream);
+struct TACompact {
+    void *k, *v;                       // caches
+    const int32_t *page_table, *seq_lens, *accepted, *n_accepted;
+    int32_t *seq_lens_out;             // or nullptr
+    int64_t k_sp, k_sh, k_ss, v_sp, v_sh, v_ss, pt_sb, sl_s, acc_sb, na_s, slo_s;
+    int32_t B, T, A, Hkv, D, ps, capacity, elem_bytes;
+    int32_t *status;
+};
+hipError_t ta_launch_compact(const TACompact &c, hipStream_t stream);
 hipError_t ta_launch_encode(const int32_t *parent, int64_t par_sb, int B, int T, unsigned long long *masks,
                             int32_t *status, hipStream_t stream);

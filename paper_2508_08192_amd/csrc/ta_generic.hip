@@ -561,6 +561,99 @@ __global__ __launch_bounds__(256) void ta_append_kernel(TAAppend a)
     }
 }
 
+// Bookkeeping after acceptance (section 3, stage 6): the accepted path's K/V rows move behind the prefix.  One
+// workgroup per request.  The rows of one phase -- as many (KV head, K or V) units of n rows as fit the staging
+// buffer -- are all read into LDS before any of them is written back, and no two phases touch the same bytes, so
+// sources that are also destinations are safe.
+constexpr int CP_STAGE_BYTES = 64 * 1024;
+
+template <typename E>
+__global__ __launch_bounds__(256) void ta_compact_kernel(TACompact c)
+{
+    extern __shared__ __attribute__((aligned(16))) char cp_stage[];
+    __shared__ int ids[TA_MAX_TREE];
+    __shared__ int bad;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int L = c.seq_lens[(int64_t)b * c.sl_s];
+    const int n = c.n_accepted[(int64_t)b * c.na_s];
+    if (tid == 0)
+        bad = 0;
+    __syncthreads();
+    const bool len_ok = L >= 0 && (int64_t)L + c.T <= (int64_t)c.capacity;
+    const bool n_ok = n >= 0 && n <= c.A;
+    if (n_ok && tid < n) {
+        const int id = c.accepted[(int64_t)b * c.acc_sb + tid];
+        ids[tid] = id;
+        if (id < 0 || id >= c.T)
+            atomicOr(&bad, 1);
+    }
+    __syncthreads();
+    const bool path_ok = n_ok && bad == 0;
+    if (!len_ok || !path_ok) {
+        if (tid == 0) {
+            atomicOr(c.status, !len_ok ? TA_STATUS_BAD_SEQLEN : TA_STATUS_BAD_PATH);
+            if (c.seq_lens_out)
+                c.seq_lens_out[(int64_t)b * c.slo_s] = L;
+        }
+        return;
+    }
+    E *stage = (E *)cp_stage;
+    const int unit = n * c.D;                                      // elements of one (KV head, K or V) unit
+    const int units = 2 * c.Hkv;
+    const int per_phase = unit > 0 ? max(1, (int)(CP_STAGE_BYTES / sizeof(E)) / unit) : units;
+    for (int u0 = 0; u0 < units && unit > 0; u0 += per_phase) {
+        const int nu = min(per_phase, units - u0);
+        for (int pass = 0; pass < 2; ++pass) {                     // 0: cache -> LDS (sources), 1: LDS -> cache
+            for (int x = tid; x < nu * unit; x += blockDim.x) {
+                const int u = u0 + x / unit, r = x % unit;
+                const int j = r / c.D, d = r % c.D;
+                const int g = u >> 1;
+                const int pos = L + (pass == 0 ? ids[j] : j);
+                int64_t page = b, slot = pos;
+                if (c.page_table) {
+                    page = c.page_table[(int64_t)b * c.pt_sb + pos / c.ps];
+                    slot = pos % c.ps;
+                }
+                E *row = (u & 1) ? (E *)c.v + page * c.v_sp + g * c.v_sh + slot * c.v_ss
+                                 : (E *)c.k + page * c.k_sp + g * c.k_sh + slot * c.k_ss;
+                if (pass == 0)
+                    stage[x] = row[d];
+                else
+                    row[d] = stage[x];
+            }
+            __syncthreads();
+        }
+    }
+    if (tid == 0 && c.seq_lens_out)
+        c.seq_lens_out[(int64_t)b * c.slo_s] = L + n;
+}
+
+hipError_t ta_launch_compact(const TACompact &c, hipStream_t stream)
+{
+    // staging: one phase holds at most CP_STAGE_BYTES; a single unit (A rows of D elements) never exceeds that
+    const size_t unit_bytes = (size_t)c.A * c.D * c.elem_bytes;
+    if (unit_bytes > (size_t)CP_STAGE_BYTES)
+        return hipErrorInvalidValue;
+    const size_t smem = CP_STAGE_BYTES;                            // with the static part just above the 64 KB default
+    static bool attr_set[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
+        for (const void *fn : {(const void *)ta_compact_kernel<uint16_t>, (const void *)ta_compact_kernel<uint32_t>}) {
+            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess)
+                return e;
+        }
+        attr_set[dev] = true;
+    }
+    if (c.elem_bytes == 2)
+        hipLaunchKernelGGL(ta_compact_kernel<uint16_t>, dim3(c.B), dim3(256), smem, stream, c);
+    else
+        hipLaunchKernelGGL(ta_compact_kernel<uint32_t>, dim3(c.B), dim3(256), smem, stream, c);
+    return hipGetLastError();
+}
+
 hipError_t ta_launch_append(const TAAppend &a, hipStream_t stream)
 {
     if (a.elem_bytes == 2)

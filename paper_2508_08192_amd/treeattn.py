@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libtreeattn.so")
 
 TA_F32, TA_BF16, TA_I32, TA_U64 = 0, 1, 2, 3
 TA_KERNEL_AUTO, TA_KERNEL_GENERIC, TA_KERNEL_MFMA, TA_KERNEL_MFMA_BASIC = 0, 1, 2, 3
-TA_STATUS_BAD_PARENT, TA_STATUS_BAD_SEQLEN = 1, 2
+TA_STATUS_BAD_PARENT, TA_STATUS_BAD_SEQLEN, TA_STATUS_BAD_PATH = 1, 2, 4
 
 TA_OK = 0
 TA_ERR_NULL, TA_ERR_DTYPE, TA_ERR_RANK, TA_ERR_SHAPE, TA_ERR_STRIDE, TA_ERR_HEADS = -1, -2, -3, -4, -5, -6
@@ -23,6 +23,7 @@ TA_ERR_BATCH, TA_ERR_OPTS = -12, -13
 EXPORTS = (
     "tree_attn_fwd", "tree_attn_fwd_ex", "tree_attn_workspace_bytes", "tree_attn_reserve", "tree_attn_encode",
     "tree_attn_append",
+    "tree_attn_compact",
     "tree_attn_last_status", "tree_attn_plan", "tree_attn_strerror", "tree_attn_version",
 )
 
@@ -101,6 +102,8 @@ def load_library():
         lib.tree_attn_encode.argtypes = [T, T, ctypes.c_void_p]
         lib.tree_attn_append.restype = ctypes.c_int
         lib.tree_attn_append.argtypes = [T, T, T, T, T, T, ctypes.c_void_p]
+        lib.tree_attn_compact.restype = ctypes.c_int
+        lib.tree_attn_compact.argtypes = [T, T, T, T, T, T, ctypes.c_int32, T, ctypes.c_void_p]
         lib.tree_attn_last_status.restype = ctypes.c_int
         lib.tree_attn_last_status.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
         lib.tree_attn_plan.restype = ctypes.c_int
@@ -231,6 +234,18 @@ def tree_attn_append(k_new, v_new, k_cache, v_cache, page_table, seq_lens, strea
     rc = load_library().tree_attn_append(*[_ref(d) for d in ds], _stream_ptr(stream) if stream != 0 else None)
     if check and rc != TA_OK:
         raise TreeAttnError(rc, "tree_attn_append")
+    return rc
+
+
+def tree_attn_compact(k_cache, v_cache, page_table, seq_lens, accepted, n_accepted, tree_size, seq_lens_out=None,
+                      stream=None, check=True):
+    """include/treeattn.h: tree_attn_compact (bookkeeping after acceptance: the accepted path moves behind the prefix)."""
+    ds = [_desc(x) for x in (k_cache, v_cache, page_table, seq_lens, accepted, n_accepted)]
+    so = _desc(seq_lens_out)
+    rc = load_library().tree_attn_compact(*[_ref(d) for d in ds], int(tree_size), _ref(so),
+                                          _stream_ptr(stream) if stream != 0 else None)
+    if check and rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_compact")
     return rc
 
 

@@ -4,7 +4,7 @@ import pytest
 
 from paper_2508_08192_amd import workloads as W
 
-from .helpers import assert_parity, run_hip, run_oracle, to_device
+from .helpers import ancestors_inclusive, assert_parity, run_hip, run_oracle, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -482,6 +482,89 @@ def test_write_back_of_tree_keys_and_values(dtype, ps):
                        vc.view(torch.int16 if dtype == "bf16" else torch.int32))
     got, got_lse = run_hip(w, dev)
     assert_parity(got, got_lse, ref, ref_lse, dtype, "after write-back")
+
+
+@pytest.mark.parametrize("dtype,ps,D,Hkv,T", [("bf16", 64, 128, 8, 12), ("bf16", 0, 128, 2, 9), ("f32", 4, 64, 3, 16),
+                                              ("f32", 16, 256, 2, 64)])
+def test_bookkeeping_moves_the_accepted_path_behind_the_prefix(dtype, ps, D, Hkv, T):
+    """tree_attn_compact against the bookkeeping oracle, bit for bit over the whole cache (so nothing else may change),
+    with lengths updated in place; then plain decoding over the rewound cache agrees with the attention oracle.
+    Covers pages smaller than the path, the contiguous layout, sources that are also destinations, a unit larger
+    than one staging phase (T 64, D 256, fp32), zero accepted nodes and the requests that must be left alone."""
+    import torch
+    from oracle import kv_compact_oracle as KC
+    from paper_2508_08192_amd import treeattn as ta
+    rng = np.random.default_rng(81)
+    B = 6
+    tree = W.shuffle_tree(W.random_deep_tree(T, min(T, 7), rng), rng)[0]
+    lens = [130, 0, 63, 17, 5, 40]
+    w = W.make_workload("compact", B=B, T=T, Hq=Hkv * 2, Hkv=Hkv, D=D, seq_lens=lens, trees=tree, page_size=ps if ps else 64,
+                        dtype=dtype, seed=8100 + ps, paged=ps > 0)
+    A = T
+    acc = np.full((B, A), -3, dtype=np.int32)
+    n = np.zeros(B, dtype=np.int32)
+    paths = [max((ancestors_inclusive(tree, i) for i in range(T)), key=len)]
+    paths.append(list(rng.permutation(T)[:A]))                     # not a path at all: a permutation, sources = destinations
+    paths.append([])                                               # nothing accepted
+    paths.append(paths[0][:2])
+    paths.append([0, T])                                           # id out of range: left alone
+    paths.append(paths[0])
+    for b, p in enumerate(paths):
+        acc[b, :len(p)] = p
+        n[b] = len(p)
+    n[5] = A + 1                                                   # accepted length beyond the list: left alone
+    k_ref, v_ref, lens_ref, skipped = KC.kv_compact_oracle(w.k_cache, w.v_cache, w.page_table, w.seq_lens, acc, n, T)
+    assert skipped == [4, 5]
+    dev = to_device(w)
+    _announce("compact %s ps=%d D=%d Hkv=%d T=%d" % (dtype, ps, D, Hkv, T))
+    ta.tree_attn_last_status()
+    ta.tree_attn_compact(dev["k_cache"], dev["v_cache"], dev["page_table"], dev["seq_lens"],
+                         torch.from_numpy(acc).cuda(), torch.from_numpy(n).cuda(), T, seq_lens_out=dev["seq_lens"])
+    torch.cuda.synchronize()
+    bits = torch.int16 if dtype == "bf16" else torch.int32
+    assert np.array_equal(dev["k_cache"].view(bits).cpu().numpy(), k_ref.view(np.int16 if dtype == "bf16" else np.int32))
+    assert np.array_equal(dev["v_cache"].view(bits).cpu().numpy(), v_ref.view(np.int16 if dtype == "bf16" else np.int32))
+    assert np.array_equal(dev["seq_lens"].cpu().numpy(), lens_ref)
+    assert ta.tree_attn_last_status() == ta.TA_STATUS_BAD_PATH
+    # the next step's attention over the rewound cache: the last accepted token is the single tree node
+    keep = [0, 3]
+    w1 = W.Workload(name="after", dtype=dtype, q=np.stack([w.q[b, paths[b][-1]] for b in keep])[:, None],
+                    k_cache=k_ref if w.page_table is not None else k_ref[keep],
+                    v_cache=v_ref if w.page_table is not None else v_ref[keep],
+                    page_table=None if w.page_table is None else w.page_table[keep],
+                    seq_lens=np.int32([lens_ref[b] - 1 for b in keep]), tree_parent=np.int32([-1]), scale=w.scale)
+    ref, ref_lse = run_oracle(w1)
+    full, full_lse = run_oracle(w)
+    for r, b in enumerate(keep):                                    # (the pin of the oracle, repeated on this input)
+        np.testing.assert_allclose(ref[r, 0], full[b, paths[b][-1]], rtol=0, atol=1e-12)
+    got, got_lse = run_hip(w1)
+    assert_parity(got, got_lse, ref, ref_lse, dtype, "decode after bookkeeping")
+
+
+def test_bookkeeping_reports_a_prefix_without_room_and_writes_a_separate_length_array():
+    import torch
+    from oracle import kv_compact_oracle as KC
+    from paper_2508_08192_amd import treeattn as ta
+    T = 8
+    w = W.make_workload("compact2", B=3, T=T, Hq=4, Hkv=2, D=128, seq_lens=[20, 9, 33], trees=W.chain_tree(T),
+                        page_size=16, dtype="bf16", seed=8200)
+    w.seq_lens[1] = w.page_table.shape[1] * 16 - T + 1             # the tree would not fit: left alone
+    acc = np.int32([[0, 1, 2], [0, 1, 2], [0, 1, 2]])
+    n = np.int32([3, 3, 1])
+    k_ref, v_ref, lens_ref, skipped = KC.kv_compact_oracle(w.k_cache, w.v_cache, w.page_table, w.seq_lens, acc, n, T)
+    assert skipped == [1]
+    dev = to_device(w)
+    new_lens = torch.full((3, 2), -1, dtype=torch.int32, device="cuda")
+    _announce("compact: separate strided length array")
+    ta.tree_attn_last_status()
+    ta.tree_attn_compact(dev["k_cache"], dev["v_cache"], dev["page_table"], dev["seq_lens"],
+                         torch.from_numpy(acc).cuda(), torch.from_numpy(n).cuda(), T, seq_lens_out=new_lens[:, 0])
+    torch.cuda.synchronize()
+    assert np.array_equal(dev["k_cache"].view(torch.int16).cpu().numpy(), k_ref.view(np.int16))
+    assert np.array_equal(dev["v_cache"].view(torch.int16).cpu().numpy(), v_ref.view(np.int16))
+    assert np.array_equal(new_lens[:, 0].cpu().numpy(), lens_ref) and (new_lens[:, 1] == -1).all()
+    assert np.array_equal(dev["seq_lens"].cpu().numpy(), w.seq_lens)
+    assert ta.tree_attn_last_status() == ta.TA_STATUS_BAD_SEQLEN
 
 
 @pytest.mark.parametrize("kernel", [GENERIC, MFMA, MFMA_BASIC])

@@ -166,3 +166,32 @@ def test_append_rejects_bad_arguments_before_any_launch():
     assert rc(k_new=Desc((2, 65, 2, 128), ta.TA_BF16), v_new=Desc((2, 65, 2, 128), ta.TA_BF16)) == ta.TA_ERR_TREE_SIZE
     assert rc(seq_lens=Desc((3,), ta.TA_I32)) == ta.TA_ERR_SHAPE
     assert rc(page_table=Desc((3, 5), ta.TA_I32)) == ta.TA_ERR_PAGE_TABLE
+
+
+def test_compact_rejects_bad_arguments_before_any_launch():
+    a = _good()
+    ok = dict(k_cache=a["k_cache"], v_cache=a["v_cache"], page_table=a["page_table"], seq_lens=a["seq_lens"],
+              accepted=Desc((2, 6), ta.TA_I32), n_accepted=Desc((2,), ta.TA_I32), tree_size=8,
+              seq_lens_out=Desc((2,), ta.TA_I32))
+
+    def rc(**over):
+        d = dict(ok)
+        d.update(over)
+        return ta.tree_attn_compact(d["k_cache"], d["v_cache"], d["page_table"], d["seq_lens"], d["accepted"],
+                                    d["n_accepted"], d["tree_size"], d["seq_lens_out"], stream=0, check=False)
+    assert rc(accepted=None) == ta.TA_ERR_NULL
+    assert rc(k_cache=None) == ta.TA_ERR_NULL
+    assert rc(accepted=Desc((2, 6), ta.TA_F32)) == ta.TA_ERR_DTYPE
+    assert rc(v_cache=Desc((16, 2, 64, 128), ta.TA_F32)) == ta.TA_ERR_DTYPE
+    assert rc(accepted=Desc((12,), ta.TA_I32)) == ta.TA_ERR_RANK
+    assert rc(accepted=Desc((2, 65), ta.TA_I32)) == ta.TA_ERR_TREE_SIZE
+    assert rc(tree_size=0) == ta.TA_ERR_TREE_SIZE
+    assert rc(tree_size=65) == ta.TA_ERR_TREE_SIZE
+    assert rc(n_accepted=Desc((3,), ta.TA_I32)) == ta.TA_ERR_SHAPE
+    assert rc(seq_lens_out=Desc((3,), ta.TA_I32)) == ta.TA_ERR_SHAPE
+    assert rc(v_cache=Desc((16, 2, 32, 128), ta.TA_BF16)) == ta.TA_ERR_SHAPE
+    assert rc(page_table=Desc((3, 5), ta.TA_I32)) == ta.TA_ERR_PAGE_TABLE
+    assert rc(accepted=Desc((2, 6), ta.TA_I32, stride=(6, 2))) == ta.TA_ERR_STRIDE
+    # lengths may be updated in place, but a shifted overlap of the two arrays is refused
+    sl = ok["seq_lens"]
+    assert rc(seq_lens_out=Desc((2,), ta.TA_I32, ptr=sl.ptr + 4)) == ta.TA_ERR_STRIDE
