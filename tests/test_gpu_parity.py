@@ -666,6 +666,88 @@ def test_side_stream_and_graph_replay_follow_device_side_lengths():
             assert_parity(got, got_lse, ref, ref_lse, "bf16", "graph replay %d L=%r" % (rep, L))
 
 
+def test_verify_loop_in_a_graph_write_back_attention_bookkeeping():
+    """Stages 4 and 6 of section 3 as the serving loop runs them: per step the tree tokens' K/V are written back,
+    the tree is verified, and the accepted path is moved behind the prefix with the lengths advanced on the device.
+    The three calls are captured once in a HIP graph; each replay is checked against the oracles run on a host mirror
+    of the cache, and after the last step the caches agree bit for bit.  (Which nodes are accepted is the sampler's
+    business and outside this library: seeded root-to-node paths stand in.)"""
+    import torch
+    from oracle import kv_compact_oracle as KC
+    from paper_2508_08192_amd import treeattn as ta
+    rng = np.random.default_rng(91)
+    tree, T, B, Hq, Hkv, D, ps, steps = W.TREE_N8, 8, 3, 8, 2, 128, 16, 5
+    lens0 = np.int32([40, 0, 250])
+    w = W.make_workload("loop", B=B, T=T, Hq=Hq, Hkv=Hkv, D=D, seq_lens=list(lens0 + steps * 4), trees=tree, page_size=ps,
+                        dtype="bf16", seed=9100)
+    w.seq_lens[:] = lens0
+    k_np, v_np, L = w.k_cache.copy(), w.v_cache.copy(), lens0.copy()
+    dev = to_device(w)
+    k_new = torch.zeros((B, T, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    v_new = torch.zeros_like(k_new)
+    acc = torch.zeros((B, T), dtype=torch.int32, device="cuda")
+    n_acc = torch.zeros((B,), dtype=torch.int32, device="cuda")
+    ta.tree_attn_reserve(ta.tree_attn_workspace_bytes(B, T, Hq, Hkv, D, ta.TA_BF16))
+
+    def step(kc, vc, sl, stream):
+        ta.tree_attn_append(k_new, v_new, kc, vc, dev["page_table"], sl, stream=stream)
+        ta.tree_attn_fwd(dev["q"], kc, vc, dev["page_table"], sl, dev["tree_parent"], dev["out"], dev["lse"], stream=stream)
+        ta.tree_attn_compact(kc, vc, dev["page_table"], sl, acc, n_acc, T, seq_lens_out=sl, stream=stream)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                  # warm-up on copies: kernel attributes get set
+        step(dev["k_cache"].clone(), dev["v_cache"].clone(), dev["seq_lens"].clone(), side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(dev["k_cache"], dev["v_cache"], dev["seq_lens"], torch.cuda.current_stream())
+    ta.tree_attn_last_status()
+
+    def bits(x):
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+
+    for s in range(steps):
+        q_s = W.to_bf16_bits(rng.standard_normal((B, T, Hq, D)).astype(np.float32))
+        kn_s = W.to_bf16_bits(rng.standard_normal((B, T, Hkv, D)).astype(np.float32))
+        vn_s = W.to_bf16_bits(rng.standard_normal((B, T, Hkv, D)).astype(np.float32))
+        paths = [ancestors_inclusive(tree, int(rng.integers(0, T))) for _ in range(B)]
+        acc_s = np.zeros((B, T), dtype=np.int32)
+        n_s = np.int32([len(p) for p in paths])
+        for b, p in enumerate(paths):
+            acc_s[b, :len(p)] = p
+        # host mirror: write-back, attention oracle, bookkeeping oracle
+        for b in range(B):
+            for i in range(T):
+                pos = int(L[b]) + i
+                page, slot = int(w.page_table[b, pos // ps]), pos % ps
+                k_np[page, :, slot, :] = kn_s[b, i]
+                v_np[page, :, slot, :] = vn_s[b, i]
+        import oracle
+        ref, ref_lse = oracle.tree_attn_oracle(q_s, k_np, v_np, w.page_table, L, tree, scale=w.scale)
+        k_np, v_np, L, skipped = KC.kv_compact_oracle(k_np, v_np, w.page_table, L, acc_s, n_s, T)
+        assert skipped == []
+        # device: new inputs into the captured buffers, one replay
+        dev["q"].copy_(bits(q_s))
+        k_new.copy_(bits(kn_s))
+        v_new.copy_(bits(vn_s))
+        acc.copy_(torch.from_numpy(acc_s))
+        n_acc.copy_(torch.from_numpy(n_s))
+        dev["out"].fill_(float("nan"))
+        dev["lse"].fill_(float("nan"))
+        torch.cuda.synchronize()
+        _announce("verify loop step %d lens %r accepted %r" % (s, list(L - n_s), list(n_s)))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = dev["out"].float().cpu().numpy().astype(np.float64)
+        got_lse = dev["lse"].cpu().numpy().astype(np.float64)
+        assert_parity(got, got_lse, ref, ref_lse, "bf16", "verify loop step %d" % s)
+        assert np.array_equal(dev["seq_lens"].cpu().numpy(), L)
+    assert np.array_equal(dev["k_cache"].view(torch.int16).cpu().numpy(), k_np.view(np.int16))
+    assert np.array_equal(dev["v_cache"].view(torch.int16).cpu().numpy(), v_np.view(np.int16))
+    assert ta.tree_attn_last_status() == 0
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_shapes_against_oracle(seed):
     """Seeded random geometry: tree size, GQA group, page size, prefix lengths around tile and page edges, splits."""
