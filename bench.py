@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 WORKLOADS = {"c1": 0, "c2": 1, "c3": 2, "c4": 3, "c5": 4}
 # shapes of the regime the paper deploys (few query rows per KV head, memory-bound): workloads.make_production
-PRODUCTION = {"p1": 0, "p2": 1, "p3": 2, "p4": 3, "p5": 4}
+PRODUCTION = {"p1": 0, "p2": 1, "p3": 2, "p4": 3, "p5": 4, "p6": 5, "p7": 6}
 
 
 def make(name):

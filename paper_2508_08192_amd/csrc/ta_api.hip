@@ -222,8 +222,8 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     if (pl.n_wg > tiles_cap)
         pl.n_wg = (int)(tiles_cap > 0 ? tiles_cap : 1);
     pl.n_slots = pl.n_wg + (int)(B * Hkv);
-    pl.merge_wgs = (int)(B * Hkv) * ((p.rows + ta_merge_rows(p) - 1) / ta_merge_rows(p));
     p.rows_grp = pl.rows_grp; p.n_rg = pl.n_rg; p.n_wg = pl.n_wg; p.min_q = pl.min_q;
+    pl.merge_wgs = (int)(B * Hkv) * ((p.rows + ta_merge_rows(p) - 1) / ta_merge_rows(p));
 
     const size_t rows_total = (size_t)pl.n_slots * pl.n_rg * pl.rows_grp;
     pr->ws_o_bytes = align_up(rows_total * D * sizeof(float), 256);

@@ -494,10 +494,138 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
         p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + (int64_t)node * p.lse_st] = lse2 * LN2;
 }
 
+// Many partials per list (few lists cut over the whole chip: the batch-size-one regime): one workgroup per output row,
+// its eight half-waves take every eighth partial each, up to MW_FLIGHT loads in flight per lane, and their sums meet
+// in LDS.  The loads of the first round are issued before the log-sum-exps are reduced, so the two latencies overlap.
+// (With the kernel above a half-wave walks all partials of its row alone: 256 partials took 38 us, now about 7.)
+constexpr int MW_HALVES = 8, MW_FLIGHT = 8;
+
+__global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
+{
+    __shared__ float red[8];
+    __shared__ float4 part[MW_HALVES][32];
+    const int seg = blockIdx.x, R = blockIdx.y;
+    const int b = seg / p.Hkv, g = seg % p.Hkv;
+    const int tid = threadIdx.x, hw = tid >> 5, hl = tid & 31, wave = tid >> 6;
+    const int w_first = p.ws_parts[2 * seg];                             // left by the KV pass
+    const int n_parts = p.ws_parts[2 * seg + 1] - w_first + 1;
+    const float LN2 = 0.6931471805599453f;
+    const float QNAN = __uint_as_float(0x7fc00000u);
+    const int rg = R / p.rows_grp, r = R % p.rows_grp;
+    const int node = R / p.G, h = g * p.G + R % p.G;
+    const int64_t row0 = ta_ws_row(p, w_first + seg, rg, r);              // partial k of this row: row0 + k*pstride
+    const int64_t pstride = (int64_t)p.n_rg * p.rows_grp;
+    const float *o0 = p.ws_o + row0 * 128 + 4 * hl;
+    const int64_t ostride = pstride * 128;
+
+    // first round of this half-wave's partials (hw, hw + 8, ...): outputs and their log-sum-exps
+    float4 v[MW_FLIGHT];
+    float lk[MW_FLIGHT];
+#pragma unroll
+    for (int u = 0; u < MW_FLIGHT; ++u) {
+        const int k = hw + MW_HALVES * u;
+        if (k < n_parts) {
+            v[u] = *(const float4 *)(o0 + k * ostride);
+            lk[u] = p.ws_lse[row0 + k * pstride];
+        }
+    }
+    // log-sum-exp of the row over all partials
+    float mx = -INFINITY, bad = 0.f;
+    for (int k = tid; k < n_parts; k += 256) {
+        const float x = p.ws_lse[row0 + k * pstride];
+        bad = x != x ? 1.f : bad;
+        mx = fmaxf(mx, x);
+    }
+    mx = ta_wave_max(mx);
+    bad = ta_wave_max(bad);
+    if ((tid & 63) == 0) {
+        red[wave] = mx;
+        red[4 + wave] = bad;
+    }
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const bool nan_seen = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7])) > 0.f;
+    __syncthreads();
+    float den = 0.f;
+    for (int k = tid; k < n_parts; k += 256)
+        den += exp2f(p.ws_lse[row0 + k * pstride] - mx);
+    den = ta_wave_sum(den);
+    if ((tid & 63) == 0)
+        red[wave] = den;
+    __syncthreads();
+    den = (red[0] + red[1]) + (red[2] + red[3]);
+    const float lse2 = nan_seen ? QNAN : mx + log2f(den);
+
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int k0 = hw; k0 < n_parts; k0 += MW_HALVES * MW_FLIGHT) {
+        if (k0 != hw) {
+#pragma unroll
+            for (int u = 0; u < MW_FLIGHT; ++u) {
+                const int k = k0 + MW_HALVES * u;
+                if (k < n_parts) {
+                    v[u] = *(const float4 *)(o0 + k * ostride);
+                    lk[u] = p.ws_lse[row0 + k * pstride];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < MW_FLIGHT; ++u) {
+            if (k0 + MW_HALVES * u < n_parts) {
+                const float wgt = nan_seen ? QNAN : exp2f(lk[u] - lse2);
+                acc.x = fmaf(wgt, v[u].x, acc.x);
+                acc.y = fmaf(wgt, v[u].y, acc.y);
+                acc.z = fmaf(wgt, v[u].z, acc.z);
+                acc.w = fmaf(wgt, v[u].w, acc.w);
+            }
+        }
+    }
+    part[hw][hl] = acc;
+    __syncthreads();
+    if (tid >= 32)
+        return;
+    acc = part[0][hl];
+#pragma unroll
+    for (int k = 1; k < MW_HALVES; ++k) {
+        const float4 x = part[k][hl];
+        acc.x += x.x;
+        acc.y += x.y;
+        acc.z += x.z;
+        acc.w += x.w;
+    }
+    const int64_t ooff = (int64_t)b * p.o_sb + (int64_t)node * p.o_st + (int64_t)h * p.o_sh + 4 * hl;
+    if (p.is_bf16) {
+        uint2 o;
+        o.x = (uint32_t)ta_f32_to_bf16(acc.x) | ((uint32_t)ta_f32_to_bf16(acc.y) << 16);
+        o.y = (uint32_t)ta_f32_to_bf16(acc.z) | ((uint32_t)ta_f32_to_bf16(acc.w) << 16);
+        *(uint2 *)((uint16_t *)p.out + ooff) = o;
+    } else {
+        *(float4 *)((float *)p.out + ooff) = acc;
+    }
+    if (p.lse && hl == 0)
+        p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + (int64_t)node * p.lse_st] = lse2 * LN2;
+}
+
+// Partials per list the schedule produces on average: the KV pass's workgroups spread over the lists, plus the one
+// boundary each list shares with its neighbour.
+static int merge_parts_estimate(const TAParams &p)
+{
+    const int lists = p.B * p.Hkv > 0 ? p.B * p.Hkv : 1;
+    return (p.n_wg + lists - 1) / lists + 1;
+}
+
+// The row-per-workgroup merge is taken from 13 partials per list on, as long as it stays a latency problem: with
+// more than 1024 output rows (four workgroups per CU) the eight-rows-per-workgroup kernel is the faster one again
+// (measured: 8 lists x 256 rows x 33 partials 9.3 against 11.2 us; 1 list x 64 rows x 256 partials 38 against 9 us).
+constexpr int MW_FROM_PARTS = 13, MW_MAX_ROWS = 1024;
+
 int ta_merge_rows(const TAParams &p)
 {
     const bool aligned = ((uintptr_t)p.out % 16) == 0 && p.o_sb % 4 == 0 && p.o_st % 4 == 0 && p.o_sh % 4 == 0;
-    return p.D == 128 && aligned ? MG_ROWS : TA_MERGE_ROWS;
+    if (p.D == 128 && aligned) {
+        const bool wide = merge_parts_estimate(p) >= MW_FROM_PARTS && (int64_t)p.B * p.Hkv * p.rows <= MW_MAX_ROWS;
+        return wide ? 1 : MG_ROWS;
+    }
+    return TA_MERGE_ROWS;
 }
 
 hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream)
@@ -505,7 +633,9 @@ hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream)
     const size_t smem = 0;
     const int rows_wg = ta_merge_rows(p);
     dim3 grid(p.B * p.Hkv, (p.rows + rows_wg - 1) / rows_wg);
-    if (rows_wg == MG_ROWS)
+    if (rows_wg == 1)
+        hipLaunchKernelGGL(ta_merge128_wide_kernel, grid, dim3(256), smem, stream, p);
+    else if (rows_wg == MG_ROWS)
         hipLaunchKernelGGL(ta_merge128_kernel, grid, dim3(256), smem, stream, p);
     else
         hipLaunchKernelGGL(ta_merge_kernel, grid, dim3(GEN_THREADS), smem, stream, p);

@@ -216,10 +216,11 @@ def test_benchmark_configs_reduced_lengths_all_outputs(idx, div):
     _check(w)
 
 
-@pytest.mark.parametrize("idx,div", [(0, 16), (1, 32), (2, 64), (3, 16), (4, 16)])
+@pytest.mark.parametrize("idx,div", [(0, 16), (1, 32), (2, 64), (3, 16), (4, 16), (5, 1), (6, 1)])
 def test_production_shapes_reduced_lengths_all_outputs(idx, div):
     """Small static trees on one GPU's share of the heads (8 and 12 nodes, a chain of 3 behind the root; 5 or 8 query
-    heads per KV head): every output against the oracle at reduced prefix lengths."""
+    heads per KV head): every output against the oracle at reduced prefix lengths (the two batch-size-one shapes at
+    full length)."""
     w = W.make_production(idx, length_div=div)
     _check(w)
 
@@ -664,6 +665,31 @@ def test_side_stream_and_graph_replay_follow_device_side_lengths():
             got = dev["out"].float().cpu().numpy().astype(np.float64)
             got_lse = dev["lse"].cpu().numpy().astype(np.float64)
             assert_parity(got, got_lse, ref, ref_lse, "bf16", "graph replay %d L=%r" % (rep, L))
+
+
+@pytest.mark.parametrize("splits", [0, 100, 300])
+def test_one_long_list_cut_over_the_whole_chip(splits):
+    """Batch size one (the paper's latency regime: one request, one GPU's share of the heads, a small static tree):
+    the single list is cut into up to a few hundred shares, and the merge takes one workgroup per output row with its
+    half-waves sharing the partials.  The second request of the second case is poisoned: its rows must be NaN, the
+    other's untouched."""
+    from paper_2508_08192_amd import treeattn as ta
+    w = W.make_workload("b1", B=1, T=8, Hq=8, Hkv=1, D=128, seq_lens=[20000], trees=W.TREE_N8, page_size=64,
+                        dtype="bf16", seed=9300)
+    dev = to_device(w)
+    plan = ta.tree_attn_plan(dev["q"], dev["k_cache"], dev["v_cache"], dev["page_table"], dev["seq_lens"],
+                             dev["tree_parent"], dev["out"], dev["lse"], num_splits=splits)
+    assert plan["merge_workgroups"] == 64                          # one per output row
+    _check(w, "one list, %d splits" % splits, num_splits=splits)
+    w2 = W.make_workload("b2", B=2, T=12, Hq=5, Hkv=1, D=128, seq_lens=[9000, 700], trees=W.TREE_N12, page_size=128,
+                         dtype="bf16", seed=9301)
+    w2.seq_lens[1] = -5
+    ref, ref_lse = run_oracle(w2)
+    _announce("two lists, one poisoned, %d splits" % splits)
+    got, got_lse = run_hip(w2, num_splits=splits)
+    assert np.isnan(got[1]).all() and np.isnan(got_lse[1]).all() and np.isnan(ref[1]).all()
+    assert_parity(got[:1], got_lse[:1], ref[:1], ref_lse[:1], "bf16", "beside a poisoned request")
+    assert ta.tree_attn_last_status() & ta.TA_STATUS_BAD_SEQLEN
 
 
 def test_verify_loop_in_a_graph_write_back_attention_bookkeeping():
