@@ -206,12 +206,13 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
         pl.n_rg = (p.rows + pl.rows_grp - 1) / pl.rows_grp;
         // A workgroup's partial result costs rows*D*4 bytes written and read again; a tile of keys and
         // values costs TA_TILE*D*4 bytes.  Keep a share at least a few tiles long, so the partials stay a
-        // small fraction of the cache traffic.
+        // small fraction of the cache traffic: four tiles for 256 rows, one for 64 rows and fewer (batch size one
+        // with a small tree: the shorter the shares, the shorter the step).
         int64_t want = (int64_t)num_cus / pl.n_rg;
         if (want < 1)
             want = 1;
         pl.n_wg = (int)(num_splits > 0 ? num_splits : want);
-        pl.min_q = num_splits > 0 ? 1 : 4;
+        pl.min_q = num_splits > 0 ? 1 : (pl.rows_grp >= 256 ? 4 : pl.rows_grp >= 128 ? 2 : 1);
     } else {
         pl.rows_grp = p.rows < TA_ROW_GROUP ? p.rows : TA_ROW_GROUP;
         pl.threads = 256;
