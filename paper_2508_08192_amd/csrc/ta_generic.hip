@@ -529,9 +529,11 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
             lk[u] = p.ws_lse[row0 + k * pstride];
         }
     }
-    // log-sum-exp of the row over all partials
-    float mx = -INFINITY, bad = 0.f;
-    for (int k = tid; k < n_parts; k += 256) {
+    // log-sum-exp of the row over all partials (thread t keeps partial t's value for the second sweep; only with
+    // more than 256 partials is anything read twice)
+    const float x_own = tid < n_parts ? p.ws_lse[row0 + tid * pstride] : -INFINITY;
+    float mx = x_own, bad = x_own != x_own ? 1.f : 0.f;
+    for (int k = tid + 256; k < n_parts; k += 256) {
         const float x = p.ws_lse[row0 + k * pstride];
         bad = x != x ? 1.f : bad;
         mx = fmaxf(mx, x);
@@ -546,8 +548,8 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
     mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     const bool nan_seen = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7])) > 0.f;
     __syncthreads();
-    float den = 0.f;
-    for (int k = tid; k < n_parts; k += 256)
+    float den = tid < n_parts ? exp2f(x_own - mx) : 0.f;
+    for (int k = tid + 256; k < n_parts; k += 256)
         den += exp2f(p.ws_lse[row0 + k * pstride] - mx);
     den = ta_wave_sum(den);
     if ((tid & 63) == 0)
