@@ -120,6 +120,16 @@ typedef struct {
                                  layers the prefix is the current sub-sequence), plus their tree path as always.
                                  0 <= kv_start[b] <= L_b, else the request is NaN-filled and TA_STATUS_BAD_SEQLEN
                                  is set.  NULL = 0. */
+    const ta_tensor *k_new;   /* optional, with v_new (HOST descriptors, DEVICE data): the step's keys and values of the T
+                                 tree tokens, [B, T, Hkv, D], dtype of the cache, unit D stride -- the write-back folded
+                                 into the call (section 3.4, paged KV with tree attention: the step's keys and values
+                                 are written back rather than fetched).  The call then takes the tree tokens' K/V from
+                                 these tensors, never from the cache, and also stores them at logical positions
+                                 L_b .. L_b+T-1 of k_cache / v_cache (which it therefore writes), exactly as
+                                 tree_attn_append would have before the call; out and lse are bit for bit those of
+                                 append followed by the plain call.  A request that is NaN-filled for a bad length
+                                 is not written.  Both NULL = the tree tokens are already in the cache. */
+    const ta_tensor *v_new;
 } ta_opts;
 
 /*

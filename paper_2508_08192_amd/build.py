@@ -76,26 +76,27 @@ def verify_register_partition(verbose=False):
     if proc.returncode != 0:
         raise RuntimeError("hipcc -S failed for ta_mfma.hip")
     lines = proc.stdout.split("\n")
-    try:
-        start = next(i for i, l in enumerate(lines) if l.startswith("_Z17ta_mfma_sp_kernel"))
-    except StopIteration:
-        raise RuntimeError("ta_mfma_sp_kernel not found in the ISA")
-    end = next(i for i in range(start, len(lines)) if ".end_amdhsa_kernel" in lines[i])
-    in_asm, worst = False, -1
-    for l in lines[start:end]:
-        if "#ASMSTART" in l:
-            in_asm = True
-        elif "#ASMEND" in l:
-            in_asm = False
-        elif not in_asm and not l.lstrip().startswith((";", ".")):
-            for m in re.finditer(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]", l):
-                worst = max(worst, int(m.group(1) or m.group(3)))
-    sized = any(".amdhsa_next_free_vgpr 256" in l for l in lines[start:end])
-    if worst > 31 or not sized:
-        raise RuntimeError("register partition of ta_mfma_sp_kernel broken: compiler code uses v%d (limit v31), "
-                           "kernel sized for 256 VGPRs: %s" % (worst, sized))
-    if verbose:
-        print("ta_mfma_sp_kernel: compiler code stays in v0..v%d; kernel sized for 256 VGPRs" % worst)
+    starts = [i for i, l in enumerate(lines) if re.match(r"_Z17ta_mfma_sp_kernel\w*:", l)]
+    if len(starts) != 2:
+        raise RuntimeError("expected both instances of ta_mfma_sp_kernel in the ISA, found %d" % len(starts))
+    for start in starts:
+        name = lines[start].split(":")[0]
+        end = next(i for i in range(start, len(lines)) if ".end_amdhsa_kernel" in lines[i])
+        in_asm, worst = False, -1
+        for l in lines[start:end]:
+            if "#ASMSTART" in l:
+                in_asm = True
+            elif "#ASMEND" in l:
+                in_asm = False
+            elif not in_asm and not l.lstrip().startswith((";", ".")):
+                for mm in re.finditer(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]", l):
+                    worst = max(worst, int(mm.group(1) or mm.group(3)))
+        sized = any(".amdhsa_next_free_vgpr 256" in l for l in lines[start:end])
+        if worst > 31 or not sized:
+            raise RuntimeError("register partition of %s broken: compiler code uses v%d (limit v31), "
+                               "kernel sized for 256 VGPRs: %s" % (name, worst, sized))
+        if verbose:
+            print("%s: compiler code stays in v0..v%d; kernel sized for 256 VGPRs" % (name, worst))
 
 
 if __name__ == "__main__":

@@ -42,6 +42,13 @@ bool strides_ok(const ta_tensor *t)
     return t->stride[t->ndim - 1] == 1 || t->shape[t->ndim - 1] <= 1;
 }
 
+// rows of a dense K/V tensor as the matrix-core kernels load them: 16-byte aligned, strides within 32 bits
+bool new_rows_aligned(const ta_tensor *n)
+{
+    return ((uintptr_t)n->data % 16) == 0 && n->stride[0] % 8 == 0 && n->stride[1] % 8 == 0 && n->stride[2] % 8 == 0 &&
+           n->stride[0] < INT32_MAX && n->stride[1] < INT32_MAX;
+}
+
 int mfma_rows_group(int rows)
 {
     // 32 rows per wave; workgroups of 1, 2, 4 or 8 such waves, at most TA_ROW_GROUP rows.
@@ -120,6 +127,7 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
             return TA_ERR_NULL;
     }
     int kernel = TA_KERNEL_AUTO, num_splits = 0, item_cost = 0;
+    const ta_tensor *kn = nullptr, *vn = nullptr;
     float scale = 0.f;
     void *user_ws = nullptr;
     size_t user_ws_bytes = 0;
@@ -135,6 +143,25 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
             return TA_ERR_OPTS;
         if (opts->kv_start && ((uintptr_t)opts->kv_start % 4) != 0)
             return TA_ERR_OPTS;
+        if ((opts->k_new != nullptr) != (opts->v_new != nullptr))
+            return TA_ERR_OPTS;
+        if (opts->k_new) {
+            // the tree tokens' K/V of this step, dense: [B, T, Hkv, D] in the cache's dtype, rows contiguous
+            for (const ta_tensor *n : {opts->k_new, opts->v_new}) {
+                if (n->dtype != k->dtype)
+                    return TA_ERR_DTYPE;
+                if (n->ndim != 4)
+                    return TA_ERR_RANK;
+                if (n->shape[0] != B || n->shape[1] != T || n->shape[2] != Hkv || n->shape[3] != D)
+                    return TA_ERR_SHAPE;
+                if (!strides_ok(n) || n->stride[3] != 1)
+                    return TA_ERR_STRIDE;
+                if (B > 0 && !n->data)
+                    return TA_ERR_NULL;
+            }
+            kn = opts->k_new;
+            vn = opts->v_new;
+        }
         scale = opts->scale;
         user_ws = opts->workspace;
         user_ws_bytes = opts->workspace_bytes;
@@ -154,7 +181,8 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
                          v->stride[0] % 8 == 0 && v->stride[1] % 8 == 0 && v->stride[2] % 8 == 0 &&
                          ((uintptr_t)q->data % 16) == 0 && ((uintptr_t)k->data % 16) == 0 &&
                          ((uintptr_t)v->data % 16) == 0 && k->stride[0] < INT32_MAX && k->stride[2] < INT32_MAX &&
-                         v->stride[0] < INT32_MAX && v->stride[2] < INT32_MAX && Hq / Hkv <= 256;
+                         v->stride[0] < INT32_MAX && v->stride[2] < INT32_MAX && Hq / Hkv <= 256 &&
+                         (!kn || (new_rows_aligned(kn) && new_rows_aligned(vn)));
     const int basic = kernel == TA_KERNEL_MFMA_BASIC ? 1 : 0;
     if (basic)
         kernel = TA_KERNEL_MFMA;
@@ -188,6 +216,20 @@ int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, co
     p.masks_sb = opts ? opts->tree_masks_stride : 0;
     p.kv_start = opts ? (const int32_t *)opts->kv_start : nullptr;
     p.is_bf16 = q->dtype == TA_BF16;
+    if (kn) {
+        p.kn = kn->data; p.vn = vn->data;
+        p.kn_sb = kn->stride[0]; p.kn_st = kn->stride[1]; p.kn_sh = kn->stride[2];
+        p.vn_sb = vn->stride[0]; p.vn_st = vn->stride[1]; p.vn_sh = vn->stride[2];
+        const int es = p.is_bf16 ? 2 : 4;
+        const int per16 = 16 / es;
+        auto vec_ok = [&](const void *ptr, int64_t a, int64_t b2, int64_t c) {
+            return ((uintptr_t)ptr % 16) == 0 && a % per16 == 0 && b2 % per16 == 0 && c % per16 == 0;
+        };
+        p.kn_vec = D % per16 == 0 && vec_ok(kn->data, kn->stride[0], kn->stride[1], kn->stride[2]) &&
+                   vec_ok(vn->data, vn->stride[0], vn->stride[1], vn->stride[2]) &&
+                   vec_ok(k->data, k->stride[0], k->stride[1], k->stride[2]) &&
+                   vec_ok(v->data, v->stride[0], v->stride[1], v->stride[2]);
+    }
     p.scale_log2e = scale * 1.4426950408889634f;
 
     Plan &pl = pr->plan;

@@ -50,6 +50,11 @@ struct TAParams {
                                // by the KV pass (the owners of the list's first and last tile), read by the merge
     int32_t *status;           // sticky status word
     int32_t basic;             // 256-row groups: use the register-staged MFMA kernel, not the pipelined one
+    // write-back folded into the call: the tree tokens' K/V come from these dense tensors [B, T, Hkv, D] (element
+    // strides), the KV pass reads them there and the merge pass copies them behind the prefix in the caches
+    const void *kn, *vn;
+    int64_t kn_sb, kn_st, kn_sh, vn_sb, vn_st, vn_sh;
+    int32_t kn_vec;            // rows can be copied in 16-byte pieces
 #ifdef TA_TUNING
     int32_t dbg;               // bit flags that switch parts of a kernel off (results become wrong)
 #endif
@@ -314,6 +319,79 @@ __device__ __forceinline__ uint16_t ta_f32_to_bf16(float f)
         return (uint16_t)((u >> 16) | 0x40u);
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+
+// The write-back of ta_opts.k_new / v_new for one (request, KV head) list: its T rows go to logical positions
+// L_b .. L_b+T-1 of the caches.  Every workgroup of the merge pass takes part (workgroup `part` of the `parts` that
+// serve the list moves the tokens part, part + parts, ...); nothing in the same call reads those cache positions (the
+// KV pass takes the tree tokens from the dense tensors).  The work comes in three steps so that a merge kernel can
+// hide it behind its own loads: ta_scatter_load issues the loads that depend on nothing (the request's length and
+// this thread's first 16-byte piece), ta_scatter_locate looks the destination up in the page table once the length
+// is there, ta_scatter_store writes -- and moves what the first piece per thread does not cover (more pieces than
+// threads, or rows that are not 16-byte aligned) in a plain loop.
+struct TAScatter {
+    uint4 v;                   // this thread's first piece
+    int64_t dst;               // its byte offset in the cache
+    int L, S, i, c, mine, per_row;
+    bool is_v, live, ok;
+};
+
+__device__ __forceinline__ void ta_scatter_load(const TAParams &p, int b, int g, int part, int parts, TAScatter &s)
+{
+    s.L = p.seq_lens[(int64_t)b * p.sl_s];
+    s.S = ta_kv_start(p, b);
+    s.live = false;
+    s.ok = false;
+    s.mine = part < p.T ? (p.T - part + parts - 1) / parts : 0;            // tokens of this workgroup
+    const int es = p.is_bf16 ? 2 : 4;
+    s.per_row = p.kn_vec ? p.D * es / 16 : p.D;                           // pieces of a row
+    const int x = threadIdx.x;
+    if (p.kn_vec && x < 2 * s.mine * s.per_row) {
+        s.is_v = x >= s.mine * s.per_row;
+        const int y = s.is_v ? x - s.mine * s.per_row : x;
+        s.i = part + (y / s.per_row) * parts;
+        s.c = y % s.per_row;
+        const int64_t src = s.is_v ? (int64_t)b * p.vn_sb + (int64_t)s.i * p.vn_st + (int64_t)g * p.vn_sh
+                                   : (int64_t)b * p.kn_sb + (int64_t)s.i * p.kn_st + (int64_t)g * p.kn_sh;
+        s.v = *(const uint4 *)((const char *)(s.is_v ? p.vn : p.kn) + src * es + 16 * s.c);
+        s.live = true;
+    }
+}
+
+__device__ __forceinline__ void ta_scatter_locate(const TAParams &p, int b, int g, TAScatter &s)
+{
+    s.ok = s.mine > 0 && ta_request_ok(p, s.L, s.S);
+    if (s.ok && s.live) {
+        const int es = p.is_bf16 ? 2 : 4;
+        s.dst = (s.is_v ? ta_cache_offset(p, b, g, s.L + s.i, p.v_sp, p.v_sh, p.v_ss)
+                        : ta_cache_offset(p, b, g, s.L + s.i, p.k_sp, p.k_sh, p.k_ss)) * es + 16 * s.c;
+    }
+}
+
+__device__ __forceinline__ void ta_scatter_store(const TAParams &p, int b, int g, int part, int parts, const TAScatter &s)
+{
+    if (!s.ok)
+        return;
+    if (s.live)
+        *(uint4 *)((char *)(s.is_v ? p.v : p.k) + s.dst) = s.v;
+    const int es = p.is_bf16 ? 2 : 4;
+    for (int x = threadIdx.x + (p.kn_vec ? blockDim.x : 0); x < 2 * s.mine * s.per_row; x += blockDim.x) {
+        const int is_v = x >= s.mine * s.per_row;
+        const int y = is_v ? x - s.mine * s.per_row : x;
+        const int i = part + (y / s.per_row) * parts, c = y % s.per_row;
+        const int64_t src = is_v ? (int64_t)b * p.vn_sb + (int64_t)i * p.vn_st + (int64_t)g * p.vn_sh
+                                 : (int64_t)b * p.kn_sb + (int64_t)i * p.kn_st + (int64_t)g * p.kn_sh;
+        const int64_t dst = is_v ? ta_cache_offset(p, b, g, s.L + i, p.v_sp, p.v_sh, p.v_ss)
+                                 : ta_cache_offset(p, b, g, s.L + i, p.k_sp, p.k_sh, p.k_ss);
+        const char *sp = (const char *)(is_v ? p.vn : p.kn) + src * es;
+        char *dp = (char *)(is_v ? p.v : p.k) + dst * es;
+        if (p.kn_vec)
+            *(uint4 *)(dp + 16 * c) = *(const uint4 *)(sp + 16 * c);
+        else if (p.is_bf16)
+            *(uint16_t *)(dp + 2 * c) = *(const uint16_t *)(sp + 2 * c);
+        else
+            *(uint32_t *)(dp + 4 * c) = *(const uint32_t *)(sp + 4 * c);
+    }
 }
 
 // Launchers implemented next to their kernels.

@@ -130,14 +130,23 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                         const int tk = tk0 + u;
                         const int pos = tree_tile ? L + tk : (tile0 + j) * TA_TILE + tk;
                         const bool exists = tree_tile ? tk < p.T : (pos >= S && pos < L);
-                        const int64_t koff = exists ? ta_cache_offset(p, b, g, pos, p.k_sp, p.k_sh, p.k_ss) : 0;
-                        const int64_t voff = exists ? ta_cache_offset(p, b, g, pos, p.v_sp, p.v_sh, p.v_ss) : 0;
+                        // with the write-back folded in, the tree tokens come from the dense tensors of this step
+                        const bool from_new = tree_tile && p.kn != nullptr;
+                        const void *kb = from_new ? p.kn : p.k, *vb = from_new ? p.vn : p.v;
+                        int64_t koff = 0, voff = 0;
+                        if (exists && from_new) {
+                            koff = (int64_t)b * p.kn_sb + (int64_t)tk * p.kn_st + (int64_t)g * p.kn_sh;
+                            voff = (int64_t)b * p.vn_sb + (int64_t)tk * p.vn_st + (int64_t)g * p.vn_sh;
+                        } else if (exists) {
+                            koff = ta_cache_offset(p, b, g, pos, p.k_sp, p.k_sh, p.k_ss);
+                            voff = ta_cache_offset(p, b, g, pos, p.v_sp, p.v_sh, p.v_ss);
+                        }
 #pragma unroll
                         for (int c = 0; c < GEN_DCHUNKS; ++c) {
                             const int d = lane + c * TA_WAVE;
                             const bool ld = exists && d < p.D;
-                            kvv[u][c] = ld ? load_elem<BF16>(p.k, koff + d) : 0.f;
-                            vvv[u][c] = ld ? load_elem<BF16>(p.v, voff + d) : 0.f;
+                            kvv[u][c] = ld ? load_elem<BF16>(kb, koff + d) : 0.f;
+                            vvv[u][c] = ld ? load_elem<BF16>(vb, voff + d) : 0.f;
                         }
                     }
 #pragma unroll
@@ -259,6 +268,7 @@ hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream)
 // through their log-sum-exps).  One wave per output row: lanes first span the partials of the row
 // (wave-wide max and sum of the partial log-sum-exps give every partial its weight), then span
 // head-dim columns, with the loads of several partials in flight at once.
+template <bool NEW>
 __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
 {
     const int seg = blockIdx.x;
@@ -269,6 +279,12 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
     const float LN2 = 0.6931471805599453f;
     const float QNAN = __uint_as_float(0x7fc00000u);
 
+    if constexpr (NEW) {
+        TAScatter sc;
+        ta_scatter_load(p, b, g, blockIdx.y, gridDim.y, sc);
+        ta_scatter_locate(p, b, g, sc);
+        ta_scatter_store(p, b, g, blockIdx.y, gridDim.y, sc);
+    }
     const int R = blockIdx.y * TA_MERGE_ROWS + wave;
     if (R >= p.rows)
         return;
@@ -383,6 +399,7 @@ __device__ __forceinline__ float ta_half_sum(float x)
     return x;
 }
 
+template <bool NEW>
 __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
 {
     const int seg = blockIdx.x;
@@ -394,9 +411,17 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
     const float LN2 = 0.6931471805599453f;
     const float QNAN = __uint_as_float(0x7fc00000u);
 
+    TAScatter sc;                                          // write-back folded into the call: see ta_scatter_load
+    if constexpr (NEW)
+        ta_scatter_load(p, b, g, blockIdx.y, gridDim.y, sc);
     const int R_raw = blockIdx.y * MG_ROWS + wave * 2 + half;
-    if (R_raw - half >= p.rows)
-        return;                                            // the whole wave is past the last row
+    if (R_raw - half >= p.rows) {                          // the whole wave is past the last row
+        if constexpr (NEW) {
+            ta_scatter_locate(p, b, g, sc);
+            ta_scatter_store(p, b, g, blockIdx.y, gridDim.y, sc);
+        }
+        return;
+    }
     const bool live = R_raw < p.rows;
     const int R = live ? R_raw : p.rows - 1;               // an odd last row: its idle partner half repeats it
     const int rg = R / p.rows_grp, r = R % p.rows_grp;
@@ -411,6 +436,8 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
     if (n_parts <= 32) {
         // lane k of the half owns partial k
         const float lk = hl < n_parts ? p.ws_lse[row0 + hl * pstride] : -INFINITY;
+        if constexpr (NEW)
+            ta_scatter_locate(p, b, g, sc);
         const bool nan_seen = ta_half_max(lk != lk ? 1.f : 0.f) > 0.f;
         const float mx = ta_half_max(lk);
         const float ek = exp2f(lk - mx);                                  // 0 for the idle lanes
@@ -450,6 +477,8 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
                 acc.w = fmaf(wgt, v[u].w, acc.w);
             }
     } else {
+        if constexpr (NEW)
+            ta_scatter_locate(p, b, g, sc);
         // more partials than lanes in a half: two sweeps over the log-sum-exps, then one over the outputs
         float mx = -INFINITY, bad = 0.f;
         for (int q0 = 0; q0 < n_parts; q0 += 32) {
@@ -479,6 +508,8 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
             acc.w = fmaf(wgt, v.w, acc.w);
         }
     }
+    if constexpr (NEW)
+        ta_scatter_store(p, b, g, blockIdx.y, gridDim.y, sc);
     if (!live)
         return;
     const int64_t ooff = (int64_t)b * p.o_sb + (int64_t)node * p.o_st + (int64_t)h * p.o_sh + 4 * hl;
@@ -500,6 +531,7 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
 // (With the kernel above a half-wave walks all partials of its row alone: 256 partials took 38 us, now about 7.)
 constexpr int MW_HALVES = 8, MW_FLIGHT = 8;
 
+template <bool NEW>
 __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
 {
     __shared__ float red[8];
@@ -511,6 +543,9 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
     const int n_parts = p.ws_parts[2 * seg + 1] - w_first + 1;
     const float LN2 = 0.6931471805599453f;
     const float QNAN = __uint_as_float(0x7fc00000u);
+    TAScatter sc;                                          // write-back folded into the call: see ta_scatter_load
+    if constexpr (NEW)
+        ta_scatter_load(p, b, g, blockIdx.y, gridDim.y, sc);
     const int rg = R / p.rows_grp, r = R % p.rows_grp;
     const int node = R / p.G, h = g * p.G + R % p.G;
     const int64_t row0 = ta_ws_row(p, w_first + seg, rg, r);              // partial k of this row: row0 + k*pstride
@@ -529,6 +564,8 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
             lk[u] = p.ws_lse[row0 + k * pstride];
         }
     }
+    if constexpr (NEW)
+        ta_scatter_locate(p, b, g, sc);
     // log-sum-exp of the row over all partials (thread t keeps partial t's value for the second sweep; only with
     // more than 256 partials is anything read twice)
     const float x_own = tid < n_parts ? p.ws_lse[row0 + tid * pstride] : -INFINITY;
@@ -582,6 +619,8 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
         }
     }
     part[hw][hl] = acc;
+    if constexpr (NEW)
+        ta_scatter_store(p, b, g, blockIdx.y, gridDim.y, sc);
     __syncthreads();
     if (tid >= 32)
         return;
@@ -635,12 +674,23 @@ hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream)
     const size_t smem = 0;
     const int rows_wg = ta_merge_rows(p);
     dim3 grid(p.B * p.Hkv, (p.rows + rows_wg - 1) / rows_wg);
-    if (rows_wg == 1)
-        hipLaunchKernelGGL(ta_merge128_wide_kernel, grid, dim3(256), smem, stream, p);
-    else if (rows_wg == MG_ROWS)
-        hipLaunchKernelGGL(ta_merge128_kernel, grid, dim3(256), smem, stream, p);
-    else
-        hipLaunchKernelGGL(ta_merge_kernel, grid, dim3(GEN_THREADS), smem, stream, p);
+    // (the instances with the write-back folded in also copy the tree tokens' K/V into the caches)
+    if (rows_wg == 1) {
+        if (p.kn)
+            hipLaunchKernelGGL(ta_merge128_wide_kernel<true>, grid, dim3(256), smem, stream, p);
+        else
+            hipLaunchKernelGGL(ta_merge128_wide_kernel<false>, grid, dim3(256), smem, stream, p);
+    } else if (rows_wg == MG_ROWS) {
+        if (p.kn)
+            hipLaunchKernelGGL(ta_merge128_kernel<true>, grid, dim3(256), smem, stream, p);
+        else
+            hipLaunchKernelGGL(ta_merge128_kernel<false>, grid, dim3(256), smem, stream, p);
+    } else {
+        if (p.kn)
+            hipLaunchKernelGGL(ta_merge_kernel<true>, grid, dim3(GEN_THREADS), smem, stream, p);
+        else
+            hipLaunchKernelGGL(ta_merge_kernel<false>, grid, dim3(GEN_THREADS), smem, stream, p);
+    }
     return hipGetLastError();
 }
 

@@ -58,11 +58,11 @@ struct Unit {
 // staged as zeros, so stale cache contents -- NaN included -- never reach a product).  Page and slot
 // strides fit 32 bits (checked on the host), which keeps the address arithmetic to a few instructions.
 __device__ __forceinline__ void load_unit(const TAParams &p, Unit &u, const uint16_t *tbase, uint32_t sp, uint32_t ss,
-                                          int b, int pos0, int n_valid)
+                                          int b, int pos0, int n_valid, bool contiguous)
 {
     const uint16_t *ptr[4];
     if (n_valid > 0) {
-        if (!p.page_table) {
+        if (contiguous) {
             const uint16_t *p0 = tbase + (uint64_t)(uint32_t)b * sp + (uint64_t)(uint32_t)pos0 * ss;
 #pragma unroll
             for (int k = 0; k < 4; ++k)
@@ -341,12 +341,22 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                 const int uu = u & 255, quad = uu >> 4, chunk = uu & 15;
                 const int pos0 = tile_pos0 + quad * 4;
                 const int n_valid = max(0, min(4, limit - pos0));
-                if (u < 256)
+                if (tree_tile && p.kn) {
+                    // write-back folded into the call: the tree tokens sit in the dense tensors of this step, which
+                    // are addressed like a contiguous cache -- request stride for the page, token stride for the slot
+                    if (u < 256)
+                        load_unit(p, stage[s], (const uint16_t *)p.kn + (int64_t)g * p.kn_sh + chunk * 8,
+                                  (uint32_t)p.kn_sb, (uint32_t)p.kn_st, b, pos0 - L, n_valid, true);
+                    else
+                        load_unit(p, stage[s], (const uint16_t *)p.vn + (int64_t)g * p.vn_sh + chunk * 8,
+                                  (uint32_t)p.vn_sb, (uint32_t)p.vn_st, b, pos0 - L, n_valid, true);
+                } else if (u < 256) {
                     load_unit(p, stage[s], (const uint16_t *)p.k + (int64_t)g * p.k_sh + chunk * 8, (uint32_t)p.k_sp,
-                              (uint32_t)p.k_ss, b, pos0, n_valid);
-                else
+                              (uint32_t)p.k_ss, b, pos0, n_valid, !p.page_table);
+                } else {
                     load_unit(p, stage[s], (const uint16_t *)p.v + (int64_t)g * p.v_sh + chunk * 8, (uint32_t)p.v_sp,
-                              (uint32_t)p.v_ss, b, pos0, n_valid);
+                              (uint32_t)p.v_ss, b, pos0, n_valid, !p.page_table);
+                }
             }
         };
         auto store_tile = [&](int buf) {
@@ -518,6 +528,9 @@ struct SpTag {
 };
 
 // amdgpu_num_vgpr(16): the register allocator stays in v0..v31; v32..v255 belong to the asm blocks (see gen_sp_block.py)
+// NEW: the tree tokens' K/V come from the dense tensors of ta_opts.k_new / v_new (an instance of its own, so that the
+// ordinary call carries none of that addressing).
+template <bool NEW>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_mfma_sp_kernel(TAParams p)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -718,23 +731,35 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 const int tv0 = 16 * (x >> 7) + 4 * ((x >> 6) & 1) + ((x & 63) >> 4);
                 const int pk[2] = {pos0 + (drow < cnt ? drow : 0), pos0 + (drow + 4 < cnt ? drow + 4 : 0)};
                 const int pv[2] = {pos0 + (tv0 < cnt ? tv0 : 0), pos0 + (tv0 + 8 < cnt ? tv0 + 8 : 0)};
+                // With the write-back folded into the call the tree tokens come from the dense tensors of this step:
+                // addressed like a contiguous cache, request stride for the page, token stride for the slot.
+                bool from_new = false;
+                if constexpr (NEW)
+                    from_new = j0 + ti == n_b - 1;
+                const uint16_t *kb0 = from_new ? (const uint16_t *)p.kn + (int64_t)g * p.kn_sh : kgp;
+                const uint16_t *vb0 = from_new ? (const uint16_t *)p.vn + (int64_t)g * p.vn_sh : vgp;
+                const uint64_t ksp_ = from_new ? (uint64_t)p.kn_sb : ksp, kss_ = from_new ? (uint64_t)p.kn_st : kss;
+                const uint64_t vsp_ = from_new ? (uint64_t)p.vn_sb : vsp, vss_ = from_new ? (uint64_t)p.vn_st : vss;
                 uint64_t ke[2], ve[2];
 #pragma unroll
                 for (int k = 0; k < 2; ++k) {
                     uint32_t pgk = (uint32_t)b, slk = (uint32_t)pk[k], pgv = (uint32_t)b, slv = (uint32_t)pv[k];
-                    if (paged) {
+                    if (from_new) {
+                        slk -= (uint32_t)L;
+                        slv -= (uint32_t)L;
+                    } else if (paged) {
                         pgk = (uint32_t)pcache[(pk[k] >> p.ps_shift) - span_first_page];
                         pgv = (uint32_t)pcache[(pv[k] >> p.ps_shift) - span_first_page];
                         slk = (uint32_t)(pk[k] & (p.ps - 1));
                         slv = (uint32_t)(pv[k] & (p.ps - 1));
                     }
-                    ke[k] = (uint64_t)pgk * ksp + (uint64_t)slk * kss + (dslot ^ ((drow + 4 * k) & 15)) * 8;
-                    ve[k] = (uint64_t)pgv * vsp + (uint64_t)slv * vss + dslot * 8;
+                    ke[k] = (uint64_t)pgk * ksp_ + (uint64_t)slk * kss_ + (dslot ^ ((drow + 4 * k) & 15)) * 8;
+                    ve[k] = (uint64_t)pgv * vsp_ + (uint64_t)slv * vss_ + dslot * 8;
                 }
-                dma16(kgp + ke[0], kdst);
-                dma16(kgp + ke[1], kdst + 1024);
-                dma16(vgp + ve[0], vdst);
-                dma16(vgp + ve[1], vdst + 1024);
+                dma16(kb0 + ke[0], kdst);
+                dma16(kb0 + ke[1], kdst + 1024);
+                dma16(vb0 + ve[0], vdst);
+                dma16(vb0 + ve[1], vdst + 1024);
             }
         };
         // this wave's 8-token group of the V tile in slot vs: raw rows -> token-minor, in place
@@ -1038,12 +1063,16 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
     if (!attr_set[dev]) {
-        hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_sp_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           160 * 1024 - 512);
-        if (e != hipSuccess)
-            return e;
+        for (const void *fn : {(const void *)ta_mfma_sp_kernel<false>, (const void *)ta_mfma_sp_kernel<true>}) {
+            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+            if (e != hipSuccess)
+                return e;
+        }
         attr_set[dev] = true;
     }
-    hipLaunchKernelGGL(ta_mfma_sp_kernel, dim3(p.n_wg, p.n_rg), dim3(512), smem, stream, p);
+    if (p.kn)
+        hipLaunchKernelGGL(ta_mfma_sp_kernel<true>, dim3(p.n_wg, p.n_rg), dim3(512), smem, stream, p);
+    else
+        hipLaunchKernelGGL(ta_mfma_sp_kernel<false>, dim3(p.n_wg, p.n_rg), dim3(512), smem, stream, p);
     return hipGetLastError();
 }

@@ -52,6 +52,8 @@ class ta_opts(ctypes.Structure):
         ("q_node_offset", ctypes.c_int32),
         ("reserved", ctypes.c_int32),
         ("kv_start", ctypes.c_void_p),
+        ("k_new", ctypes.POINTER(ta_tensor)),
+        ("v_new", ctypes.POINTER(ta_tensor)),
     ]
 
 
@@ -158,8 +160,13 @@ def _stream_ptr(stream):
 
 
 def _opts(scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None, item_cost=0, tree_masks=None,
-          kv_start=None, q_node_offset=0):
+          kv_start=None, q_node_offset=0, k_new=None, v_new=None):
     o = ta_opts()
+    o._keep = [_desc(k_new), _desc(v_new)]             # the descriptors must outlive the call
+    if o._keep[0] is not None:
+        o.k_new = ctypes.pointer(o._keep[0])
+    if o._keep[1] is not None:
+        o.v_new = ctypes.pointer(o._keep[1])
     o.scale = 0.0 if scale is None else float(scale)
     o.num_splits = int(num_splits)
     o.kernel = int(kernel)
@@ -198,10 +205,10 @@ def tree_attn_fwd(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, l
 
 def tree_attn_fwd_ex(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse=None, stream=None,
                      scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None, check=True,
-                     item_cost=0, tree_masks=None, kv_start=None, q_node_offset=0):
+                     item_cost=0, tree_masks=None, kv_start=None, q_node_offset=0, k_new=None, v_new=None):
     """include/treeattn.h: tree_attn_fwd_ex.  `events`: up to three hipEvent_t handles (ctypes.c_void_p)."""
     ds = [_desc(x) for x in (q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse)]
-    o = _opts(scale, num_splits, kernel, workspace, events, item_cost, tree_masks, kv_start, q_node_offset)
+    o = _opts(scale, num_splits, kernel, workspace, events, item_cost, tree_masks, kv_start, q_node_offset, k_new, v_new)
     rc = load_library().tree_attn_fwd_ex(*[_ref(d) for d in ds], _stream_ptr(stream) if stream != 0 else None,
                                          ctypes.byref(o))
     if check and rc != TA_OK:

@@ -568,6 +568,81 @@ def test_bookkeeping_reports_a_prefix_without_room_and_writes_a_separate_length_
     assert ta.tree_attn_last_status() == ta.TA_STATUS_BAD_SEQLEN
 
 
+@pytest.mark.parametrize("kernel,dtype,ps,T", [(MFMA, "bf16", 64, 9), (MFMA, "bf16", 0, 64), (MFMA_BASIC, "bf16", 16, 33),
+                                                (GENERIC, "bf16", 128, 12), (GENERIC, "f32", 16, 7), (MFMA, "bf16", 16, 64)])
+def test_write_back_folded_into_the_call(kernel, dtype, ps, T):
+    """ta_opts.k_new / v_new: the call takes the tree tokens' K/V from the dense tensors and stores them behind the
+    prefix itself.  Its out and lse are bit for bit those of tree_attn_append followed by the plain call, the caches
+    end up bit for bit the same, the oracle agrees, and a request with a bad length is neither computed nor written."""
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+    rng = np.random.default_rng(52)
+    Hkv, D = 2, 128 if dtype == "bf16" else 64
+    lens = [130, 0, 63, 900]
+    w = W.make_workload("fused", B=4, T=T, Hq=8, Hkv=Hkv, D=D, seq_lens=lens, trees=W.random_tree(T, 5, rng),
+                        page_size=ps if ps else 64, dtype=dtype, seed=5200 + ps + T, paged=ps > 0)
+    ref, ref_lse = run_oracle(w)
+    dev = to_device(w)
+    bits = torch.int16 if dtype == "bf16" else torch.int32
+    k_new = torch.empty((w.B, T, Hkv, D), dtype=dev["k_cache"].dtype, device="cuda")
+    v_new = torch.empty_like(k_new)
+    full_k, full_v = dev["k_cache"].clone(), dev["v_cache"].clone()
+    for b in range(w.B):                                           # tree tokens out of the cache, garbage in their place
+        for i in range(T):
+            pos = int(w.seq_lens[b]) + i
+            page, slot = (b, pos) if w.page_table is None else (int(w.page_table[b, pos // ps]), pos % ps)
+            k_new[b, i] = full_k[page, :, slot, :]
+            v_new[b, i] = full_v[page, :, slot, :]
+            dev["k_cache"][page, :, slot, :] = 7.0
+            dev["v_cache"][page, :, slot, :] = 7.0
+    wiped_k, wiped_v = dev["k_cache"].clone(), dev["v_cache"].clone()
+    _announce("folded write-back kernel=%d %s ps=%d T=%d" % (kernel, dtype, ps, T))
+    got, got_lse = run_hip(w, dev, kernel=kernel, k_new=k_new, v_new=v_new)
+    assert_parity(got, got_lse, ref, ref_lse, dtype, "folded write-back")
+    assert torch.equal(dev["k_cache"].view(bits), full_k.view(bits))
+    assert torch.equal(dev["v_cache"].view(bits), full_v.view(bits))
+    out_fused, lse_fused = dev["out"].clone(), dev["lse"].clone()
+    # the two-call form on the wiped cache
+    dev["k_cache"].copy_(wiped_k)
+    dev["v_cache"].copy_(wiped_v)
+    ta.tree_attn_append(k_new, v_new, dev["k_cache"], dev["v_cache"], dev["page_table"], dev["seq_lens"])
+    run_hip(w, dev, kernel=kernel)
+    assert torch.equal(dev["out"].view(bits), out_fused.view(bits)) and torch.equal(dev["lse"], lse_fused)
+    # strided views of larger tensors serve as well; a request with a bad length is left alone
+    big_k = torch.zeros((w.B, T + 3, Hkv + 1, D + 8), dtype=k_new.dtype, device="cuda")
+    big_v = torch.zeros_like(big_k)
+    big_k[:, 1:T + 1, 1:, :D] = k_new
+    big_v[:, 1:T + 1, 1:, :D] = v_new
+    dev["k_cache"].copy_(wiped_k)
+    dev["v_cache"].copy_(wiped_v)
+    dev["seq_lens"][2] = -1
+    ta.tree_attn_last_status()
+    got, got_lse = run_hip(w, dev, kernel=kernel, k_new=big_k[:, 1:T + 1, 1:, :D], v_new=big_v[:, 1:T + 1, 1:, :D])
+    assert ta.tree_attn_last_status() & ta.TA_STATUS_BAD_SEQLEN
+    keep = [0, 1, 3]                    # (the shares are cut differently now, so only the tolerance holds, not the bits)
+    assert_parity(got[keep], got_lse[keep], ref[keep], ref_lse[keep], dtype, "beside a request with a bad length")
+    assert np.isnan(got[2]).all() and np.isnan(got_lse[2]).all()
+    exp_k, exp_v = full_k.clone(), full_v.clone()
+    for i in range(T):                                             # request 2's tree positions keep the garbage
+        pos = int(w.seq_lens[2]) + i
+        page, slot = (2, pos) if w.page_table is None else (int(w.page_table[2, pos // ps]), pos % ps)
+        exp_k[page, :, slot, :] = 7.0
+        exp_v[page, :, slot, :] = 7.0
+    assert torch.equal(dev["k_cache"].view(bits), exp_k.view(bits)) and torch.equal(dev["v_cache"].view(bits), exp_v.view(bits))
+    if kernel == GENERIC:
+        # rows that are not 16-byte aligned: element-wise copy, scalar kernel only
+        odd_k = torch.zeros((w.B, T, Hkv, D + 3), dtype=k_new.dtype, device="cuda")
+        odd_v = torch.zeros_like(odd_k)
+        odd_k[..., 1:D + 1] = k_new
+        odd_v[..., 1:D + 1] = v_new
+        dev["k_cache"].copy_(wiped_k)
+        dev["v_cache"].copy_(wiped_v)
+        dev["seq_lens"][2] = int(w.seq_lens[2])
+        run_hip(w, dev, kernel=kernel, k_new=odd_k[..., 1:D + 1], v_new=odd_v[..., 1:D + 1])
+        assert torch.equal(dev["out"].view(bits), out_fused.view(bits))
+        assert torch.equal(dev["k_cache"].view(bits), full_k.view(bits)) and torch.equal(dev["v_cache"].view(bits), full_v.view(bits))
+
+
 @pytest.mark.parametrize("kernel", [GENERIC, MFMA, MFMA_BASIC])
 def test_queries_are_a_range_of_the_tree_nodes(kernel):
     """Drafting stage: the tree grows level by level; the newest nodes are the queries (ta_opts.q_node_offset), every

@@ -195,3 +195,22 @@ def test_compact_rejects_bad_arguments_before_any_launch():
     # lengths may be updated in place, but a shifted overlap of the two arrays is refused
     sl = ok["seq_lens"]
     assert rc(seq_lens_out=Desc((2,), ta.TA_I32, ptr=sl.ptr + 4)) == ta.TA_ERR_STRIDE
+
+
+def test_folded_write_back_arguments_are_checked_before_any_launch():
+    a = _good()
+    kn = Desc((2, 8, 2, 128), ta.TA_BF16)
+
+    def rc(**kw):
+        return ta.tree_attn_fwd_ex(a["q"], a["k_cache"], a["v_cache"], a["page_table"], a["seq_lens"], a["tree_parent"],
+                                   a["out"], a["lse"], stream=0, check=False, **kw)
+    assert rc(k_new=kn) == ta.TA_ERR_OPTS                                          # one without the other
+    assert rc(k_new=kn, v_new=Desc((2, 8, 2, 128), ta.TA_F32)) == ta.TA_ERR_DTYPE
+    assert rc(k_new=kn, v_new=Desc((2, 8, 2), ta.TA_BF16)) == ta.TA_ERR_RANK
+    assert rc(k_new=kn, v_new=Desc((2, 7, 2, 128), ta.TA_BF16)) == ta.TA_ERR_SHAPE   # all T tree tokens are needed
+    assert rc(k_new=Desc((2, 8, 4, 128), ta.TA_BF16), v_new=Desc((2, 8, 4, 128), ta.TA_BF16)) == ta.TA_ERR_SHAPE
+    assert rc(k_new=kn, v_new=Desc((2, 8, 2, 128), ta.TA_BF16, stride=(4096, 512, 256, 2))) == ta.TA_ERR_STRIDE
+    assert rc(k_new=kn, v_new=Desc((2, 8, 2, 128), ta.TA_BF16, ptr=0)) == ta.TA_ERR_NULL
+    # rows that are not 16-byte aligned: the matrix-core kernel refuses, the automatic choice falls back
+    odd = Desc((2, 8, 2, 128), ta.TA_BF16, stride=(8 * 2 * 132, 2 * 132, 132, 1))
+    assert rc(k_new=odd, v_new=odd, kernel=ta.TA_KERNEL_MFMA) == ta.TA_ERR_OPTS
