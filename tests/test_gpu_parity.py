@@ -767,7 +767,8 @@ def test_one_long_list_cut_over_the_whole_chip(splits):
     assert ta.tree_attn_last_status() & ta.TA_STATUS_BAD_SEQLEN
 
 
-def test_verify_loop_in_a_graph_write_back_attention_bookkeeping():
+@pytest.mark.parametrize("folded", [False, True])
+def test_verify_loop_in_a_graph_write_back_attention_bookkeeping(folded):
     """Stages 4 and 6 of section 3 as the serving loop runs them: per step the tree tokens' K/V are written back,
     the tree is verified, and the accepted path is moved behind the prefix with the lengths advanced on the device.
     The three calls are captured once in a HIP graph; each replay is checked against the oracles run on a host mirror
@@ -791,8 +792,12 @@ def test_verify_loop_in_a_graph_write_back_attention_bookkeeping():
     ta.tree_attn_reserve(ta.tree_attn_workspace_bytes(B, T, Hq, Hkv, D, ta.TA_BF16))
 
     def step(kc, vc, sl, stream):
-        ta.tree_attn_append(k_new, v_new, kc, vc, dev["page_table"], sl, stream=stream)
-        ta.tree_attn_fwd(dev["q"], kc, vc, dev["page_table"], sl, dev["tree_parent"], dev["out"], dev["lse"], stream=stream)
+        args = (dev["q"], kc, vc, dev["page_table"], sl, dev["tree_parent"], dev["out"], dev["lse"])
+        if folded:                                                 # the write-back as part of the attention call
+            ta.tree_attn_fwd_ex(*args, stream=stream, k_new=k_new, v_new=v_new)
+        else:
+            ta.tree_attn_append(k_new, v_new, kc, vc, dev["page_table"], sl, stream=stream)
+            ta.tree_attn_fwd(*args, stream=stream)
         ta.tree_attn_compact(kc, vc, dev["page_table"], sl, acc, n_acc, T, seq_lens_out=sl, stream=stream)
 
     side = torch.cuda.Stream()
