@@ -16,24 +16,26 @@ __device__ __forceinline__ float load_elem(const void *base, int64_t idx)
     return ((const float *)base)[idx];
 }
 
-#define GEN_RB 4                                  // query rows a wave carries at a time
-#define GEN_TB 8                                  // tokens a wave stages per round trip
 
 // KV pass for any shape.  A workgroup walks its share of a (request, KV head) tile list once per block of
-// GEN_WAVES * GEN_RB query rows: every tile (64 tokens; section 3.1: prefix tiles are mask-free, the tree tile
+// GEN_WAVES * RB query rows: every tile (64 tokens; section 3.1: prefix tiles are mask-free, the tree tile
 // keeps only a row's ancestors) is staged in LDS as fp32, rows of tokens read coalesced, and then each wave
 // updates its rows -- lanes are the tile's tokens for the scores, then head-dim columns for the weighted sum
 // of V.  Running max / sum per row (base-2 domain).  Tokens that do not exist are staged as zeros.
-template <bool BF16>
+// DCH = 64-column chunks of the head dimension a lane carries (1, 2 or 4).  A wave carries RB query rows at a time
+// and stages TB tokens per round trip; with one chunk the registers allow eight rows and all sixteen tokens of the
+// wave at once, which halves the passes over the tile list and the round trips per tile of the small-head shapes.
+template <bool BF16, int DCH>
 __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
 {
+    constexpr int RB = DCH == 1 ? 8 : 4, TB = DCH == 1 ? 16 : 8;
     extern __shared__ int smem_i[];
     int *cum = smem_i;                                                   // [B + 1]
     unsigned long long *masks = (unsigned long long *)(cum + ((p.B + 2) & ~1));   // [64]
     int *flag = (int *)(masks + TA_MAX_TREE);                            // flag[4], then par_s[TA_MAX_TREE]
     int *par_s = flag + 4;
-    float *qrow = (float *)(par_s + TA_MAX_TREE);                        // [GEN_WAVES * GEN_RB][D]
-    float *kt = qrow + GEN_WAVES * GEN_RB * p.D;                         // [64][D + 1]: a lane reads its token's row
+    float *qrow = (float *)(par_s + TA_MAX_TREE);                        // [GEN_WAVES * RB][D]
+    float *kt = qrow + GEN_WAVES * RB * p.D;                         // [64][D + 1]: a lane reads its token's row
     float *vt = kt + TA_TILE * (p.D + 1);                                // [64][D]
     const int ldk = p.D + 1;
 
@@ -78,25 +80,25 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                     atomicOr(p.status, TA_STATUS_BAD_PARENT);
             }
         }
-        for (int r0 = 0; r0 < rows_here; r0 += GEN_WAVES * GEN_RB) {
-            int rr[GEN_RB];
-            bool rok[GEN_RB];
-            unsigned long long mask[GEN_RB];
-            float m[GEN_RB], l[GEN_RB], acc[GEN_RB][GEN_DCHUNKS];
+        for (int r0 = 0; r0 < rows_here; r0 += GEN_WAVES * RB) {
+            int rr[RB];
+            bool rok[RB];
+            unsigned long long mask[RB];
+            float m[RB], l[RB], acc[RB][DCH];
 #pragma unroll
-            for (int i = 0; i < GEN_RB; ++i) {
-                rr[i] = r0 + wave * GEN_RB + i;
+            for (int i = 0; i < RB; ++i) {
+                rr[i] = r0 + wave * RB + i;
                 rok[i] = rr[i] < rows_here;
                 m[i] = -INFINITY;
                 l[i] = 0.f;
 #pragma unroll
-                for (int c = 0; c < GEN_DCHUNKS; ++c)
+                for (int c = 0; c < DCH; ++c)
                     acc[i][c] = 0.f;
                 mask[i] = 0ull;
             }
             if (poison) {
 #pragma unroll
-                for (int i = 0; i < GEN_RB; ++i) {
+                for (int i = 0; i < RB; ++i) {
                     if (!rok[i])
                         continue;
                     const int64_t wrow = ta_ws_row(p, slot, rg, rr[i]);
@@ -108,13 +110,13 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                 continue;
             }
 #pragma unroll
-            for (int i = 0; i < GEN_RB; ++i) {
+            for (int i = 0; i < RB; ++i) {
                 if (!rok[i])
                     continue;
                 const int R = rg * p.rows_grp + rr[i];
                 const int node = R / p.G, h = g * p.G + R % p.G;
                 const int64_t qoff = (int64_t)b * p.q_sb + (int64_t)node * p.q_st + (int64_t)h * p.q_sh;
-                float *qs = qrow + (wave * GEN_RB + i) * p.D;
+                float *qs = qrow + (wave * RB + i) * p.D;
                 for (int d = lane; d < p.D; d += TA_WAVE)
                     qs[d] = load_elem<BF16>(p.q, qoff + d);
                 mask[i] = has_tree_tile ? masks[p.q_off + node] : 0ull;
@@ -122,11 +124,11 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
             for (int j = j0; j < j1; ++j) {
                 const bool tree_tile = (j == n_b - 1);
                 __syncthreads();                                     // the previous tile has been consumed
-                // wave w stages tokens 16w .. 16w+15, GEN_TB at a time with all their loads in flight together
-                for (int tk0 = wave * (TA_TILE / GEN_WAVES); tk0 < (wave + 1) * (TA_TILE / GEN_WAVES); tk0 += GEN_TB) {
-                    float kvv[GEN_TB][GEN_DCHUNKS], vvv[GEN_TB][GEN_DCHUNKS];
+                // wave w stages tokens 16w .. 16w+15, TB at a time with all their loads in flight together
+                for (int tk0 = wave * (TA_TILE / GEN_WAVES); tk0 < (wave + 1) * (TA_TILE / GEN_WAVES); tk0 += TB) {
+                    float kvv[TB][DCH], vvv[TB][DCH];
 #pragma unroll
-                    for (int u = 0; u < GEN_TB; ++u) {
+                    for (int u = 0; u < TB; ++u) {
                         const int tk = tk0 + u;
                         const int pos = tree_tile ? L + tk : (tile0 + j) * TA_TILE + tk;
                         const bool exists = tree_tile ? tk < p.T : (pos >= S && pos < L);
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                             voff = ta_cache_offset(p, b, g, pos, p.v_sp, p.v_sh, p.v_ss);
                         }
 #pragma unroll
-                        for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                        for (int c = 0; c < DCH; ++c) {
                             const int d = lane + c * TA_WAVE;
                             const bool ld = exists && d < p.D;
                             kvv[u][c] = ld ? load_elem<BF16>(kb, koff + d) : 0.f;
@@ -150,9 +152,9 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                         }
                     }
 #pragma unroll
-                    for (int u = 0; u < GEN_TB; ++u)
+                    for (int u = 0; u < TB; ++u)
 #pragma unroll
-                        for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                        for (int c = 0; c < DCH; ++c) {
                             const int d = lane + c * TA_WAVE;
                             if (d < p.D) {
                                 kt[(tk0 + u) * ldk + d] = kvv[u][c];
@@ -163,31 +165,31 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                 __syncthreads();
                 // Scores of the wave's rows against the lane's token: one LDS read of K serves all rows; q[d]
                 // comes out of the lane that holds it as a scalar operand.
-                float qreg[GEN_RB][GEN_DCHUNKS], dot[GEN_RB];
+                float qreg[RB][DCH], dot[RB];
 #pragma unroll
-                for (int i = 0; i < GEN_RB; ++i) {
-                    const float *qs = qrow + (wave * GEN_RB + i) * p.D;
+                for (int i = 0; i < RB; ++i) {
+                    const float *qs = qrow + (wave * RB + i) * p.D;
                     dot[i] = 0.f;
 #pragma unroll
-                    for (int c = 0; c < GEN_DCHUNKS; ++c)
+                    for (int c = 0; c < DCH; ++c)
                         qreg[i][c] = (rok[i] && lane + c * TA_WAVE < p.D) ? qs[lane + c * TA_WAVE] : 0.f;
                 }
                 const float *kr = kt + lane * ldk;
 #pragma unroll
-                for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                for (int c = 0; c < DCH; ++c) {
                     const int dn = min(TA_WAVE, p.D - c * TA_WAVE);              // columns of this chunk (<= 0: none)
 #pragma unroll 4
                     for (int dd = 0; dd < dn; ++dd) {
                         const float kd = kr[c * TA_WAVE + dd];
 #pragma unroll
-                        for (int i = 0; i < GEN_RB; ++i)
+                        for (int i = 0; i < RB; ++i)
                             dot[i] = fmaf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(qreg[i][c]), dd)), kd,
                                           dot[i]);
                     }
                 }
-                float pr[GEN_RB];
+                float pr[RB];
 #pragma unroll
-                for (int i = 0; i < GEN_RB; ++i) {
+                for (int i = 0; i < RB; ++i) {
                     const int pos_l = (tile0 + j) * TA_TILE + lane;
                     const bool valid = rok[i] && (tree_tile ? (lane < p.T && ((mask[i] >> lane) & 1ull))
                                                             : (pos_l >= S && pos_l < L));
@@ -199,32 +201,32 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                     l[i] = l[i] * alpha + ta_wave_sum(pr[i]);
                     m[i] = m_new;
 #pragma unroll
-                    for (int c = 0; c < GEN_DCHUNKS; ++c)
+                    for (int c = 0; c < DCH; ++c)
                         acc[i][c] *= alpha;
                 }
 #pragma unroll 4
                 for (int jj = 0; jj < TA_TILE; ++jj) {
-                    float vj[GEN_DCHUNKS];
+                    float vj[DCH];
 #pragma unroll
-                    for (int c = 0; c < GEN_DCHUNKS; ++c)
+                    for (int c = 0; c < DCH; ++c)
                         vj[c] = lane + c * TA_WAVE < p.D ? vt[jj * p.D + lane + c * TA_WAVE] : 0.f;
 #pragma unroll
-                    for (int i = 0; i < GEN_RB; ++i) {
+                    for (int i = 0; i < RB; ++i) {
                         const float pj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr[i]), jj));  // scalar
 #pragma unroll
-                        for (int c = 0; c < GEN_DCHUNKS; ++c)
+                        for (int c = 0; c < DCH; ++c)
                             acc[i][c] = fmaf(pj, vj[c], acc[i][c]);
                     }
                 }
             }
 #pragma unroll
-            for (int i = 0; i < GEN_RB; ++i) {
+            for (int i = 0; i < RB; ++i) {
                 if (!rok[i])
                     continue;
                 const int64_t wrow = ta_ws_row(p, slot, rg, rr[i]);
                 const float inv = 1.f / l[i];
 #pragma unroll
-                for (int c = 0; c < GEN_DCHUNKS; ++c) {
+                for (int c = 0; c < DCH; ++c) {
                     const int d = lane + c * TA_WAVE;
                     if (d < p.D)
                         p.ws_o[wrow * p.D + d] = acc[i][c] * inv;
@@ -238,30 +240,41 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
     }
 }
 
-hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream)
+template <bool BF16, int DCH>
+static hipError_t launch_generic_instance(const TAParams &p, hipStream_t stream, bool *attr_done)
 {
+    constexpr int RB = DCH == 1 ? 8 : 4;
     const size_t smem = sizeof(int) * ((p.B + 2) & ~1) + sizeof(unsigned long long) * TA_MAX_TREE + 16 +
                         sizeof(int) * TA_MAX_TREE +
-                        sizeof(float) * ((size_t)GEN_WAVES * GEN_RB * p.D + (size_t)TA_TILE * (2 * p.D + 1));
+                        sizeof(float) * ((size_t)GEN_WAVES * RB * p.D + (size_t)TA_TILE * (2 * p.D + 1));
     if (smem > 160 * 1024 - 512)
         return hipErrorInvalidValue;
-    static bool attr_set[64][2] = {};
+    if (!*attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)ta_generic_kv_kernel<BF16, DCH>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+        if (e != hipSuccess)
+            return e;
+        *attr_done = true;
+    }
+    hipLaunchKernelGGL((ta_generic_kv_kernel<BF16, DCH>), dim3(p.n_wg, p.n_rg), dim3(GEN_THREADS), smem, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream)
+{
+    static bool attr_set[64][2][3] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
-    const void *fn = p.is_bf16 ? (const void *)ta_generic_kv_kernel<true> : (const void *)ta_generic_kv_kernel<false>;
-    if (!attr_set[dev][p.is_bf16 ? 1 : 0]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-        if (e != hipSuccess)
-            return e;
-        attr_set[dev][p.is_bf16 ? 1 : 0] = true;
-    }
-    dim3 grid(p.n_wg, p.n_rg);
-    if (p.is_bf16)
-        hipLaunchKernelGGL(ta_generic_kv_kernel<true>, grid, dim3(GEN_THREADS), smem, stream, p);
-    else
-        hipLaunchKernelGGL(ta_generic_kv_kernel<false>, grid, dim3(GEN_THREADS), smem, stream, p);
-    return hipGetLastError();
+    const int bf = p.is_bf16 ? 1 : 0;
+    if (p.D <= TA_WAVE)
+        return bf ? launch_generic_instance<true, 1>(p, stream, &attr_set[dev][1][0])
+                  : launch_generic_instance<false, 1>(p, stream, &attr_set[dev][0][0]);
+    if (p.D <= 2 * TA_WAVE)
+        return bf ? launch_generic_instance<true, 2>(p, stream, &attr_set[dev][1][1])
+                  : launch_generic_instance<false, 2>(p, stream, &attr_set[dev][0][1]);
+    return bf ? launch_generic_instance<true, 4>(p, stream, &attr_set[dev][1][2])
+              : launch_generic_instance<false, 4>(p, stream, &attr_set[dev][0][2]);
 }
 
 // Merge pass (section 3.1: full attention from partial attentions over disjoint chunks of the keys,
