@@ -225,6 +225,26 @@ def test_production_shapes_reduced_lengths_all_outputs(idx, div):
     _check(w)
 
 
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_full_size_production_shapes_sampled_outputs(idx):
+    """The deployment-like shapes at full size, in the launch configuration the bench times: sampled (request, node,
+    head) outputs against the oracle, plus whole-output sanity."""
+    import oracle
+    w = W.make_production(idx)
+    _announce(w.name)
+    got, got_lse = run_hip(w)
+    rng = np.random.default_rng(200 + idx)
+    n = 200
+    tri = np.stack([rng.integers(0, w.B, n), rng.integers(0, w.T, n), rng.integers(0, w.Hq, n)], axis=1)
+    tri[:min(n, w.B), 0] = np.arange(min(n, w.B))      # (nearly) every request at least once
+    ref, ref_lse = oracle.tree_attn_oracle_sample(w.q, w.k_cache, w.v_cache, w.page_table, w.seq_lens,
+                                                  w.tree_parent, tri, scale=w.scale, kv_start=w.kv_start)
+    g = got[tri[:, 0], tri[:, 1], tri[:, 2]]
+    gl = got_lse[tri[:, 0], tri[:, 2], tri[:, 1]]
+    assert_parity(g, gl, ref, ref_lse, "bf16", w.name)
+    assert np.isfinite(got).all() and np.isfinite(got_lse).all()
+
+
 @pytest.mark.parametrize("idx", [2, 3, 4])
 def test_full_size_configs_sampled_outputs(idx):
     """The benchmark configurations at full size, in the launch configuration the bench times: sampled
