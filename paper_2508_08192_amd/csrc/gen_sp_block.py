@@ -247,10 +247,10 @@ def fast_step_items(cur, label, helper=False):
         "s_add_u32 s88, s88, %s" % sg(ST + 4), "s_addc_u32 s89, s89, %s" % sg(ST + 5),
         "s_add_u32 s88, s88, %s" % sg(S_VG), "s_addc_u32 s89, s89, %s" % sg(S_VG + 1),
     ]
-    dma = [["s_add_u32 m0, %s, %%[ik]" % sg(S_KDST), "s_nop 0", "global_load_lds_dwordx4 %[koff0], s[86:87]"],
-           ["s_add_u32 m0, m0, 0x400", "s_nop 0", "global_load_lds_dwordx4 %[koff1], s[86:87]"],
-           ["s_add_u32 m0, %s, %%[iv]" % sg(S_VDST), "s_nop 0", "global_load_lds_dwordx4 %[voff0], s[88:89]"],
-           ["s_add_u32 m0, m0, 0x400", "s_nop 0", "global_load_lds_dwordx4 %[voff1], s[88:89]"]]
+    dma = [["s_add_u32 m0, %s, %%[ik]" % sg(S_KDST), "s_nop 0", "global_load_lds_dwordx4 %[koff0], s[86:87] nt"],
+           ["s_add_u32 m0, m0, 0x400", "s_nop 0", "global_load_lds_dwordx4 %[koff1], s[86:87] nt"],
+           ["s_add_u32 m0, %s, %%[iv]" % sg(S_VDST), "s_nop 0", "global_load_lds_dwordx4 %[voff0], s[88:89] nt"],
+           ["s_add_u32 m0, m0, 0x400", "s_nop 0", "global_load_lds_dwordx4 %[voff1], s[88:89] nt"]]
     def ring(reg, wrap):
         return ["s_add_u32 %s, %s, 0x4000" % (reg, reg), "s_cmp_eq_u32 %s, 0x%x" % (reg, wrap),
                 "s_cselect_b32 %s, 0, %s" % (reg, reg)]

@@ -478,7 +478,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // every lane moves 16 bytes from its own global address to LDS offset lds_wave_base + 16*lane
 __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_wave_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_wave_base)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(gptr), "s"(lds_wave_base)
                  : "memory");          // M0 is not used by anything else in these kernels
 }
 
@@ -517,7 +517,7 @@ typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
 // every lane moves 16 bytes from base + off to LDS offset lds_wave_base + 16*lane (base is wave-uniform)
 __device__ __forceinline__ void dma16s(const void *base, uint32_t off, uint32_t lds_wave_base)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base),
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(off), "s"(base),
                  "s"(lds_wave_base)
                  : "memory");
 }
