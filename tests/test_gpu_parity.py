@@ -664,6 +664,48 @@ def test_write_back_folded_into_the_call(kernel, dtype, ps, T):
 
 
 @pytest.mark.parametrize("kernel", [GENERIC, MFMA, MFMA_BASIC])
+def test_every_option_at_once(kernel):
+    """A drafting-stage call on a local-attention layer of a static tree: window start, query range, masks encoded
+    earlier, the write-back folded in, a caller workspace, a non-default scale, per-list cost and forced splits, all in
+    one call -- against the oracle, and the caches against the plain write-back."""
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+    rng = np.random.default_rng(131)
+    T, off, tq = 21, 5, 8
+    tree = W.bfs_tree(T, [4, 2, 1], 4)
+    w = W.make_workload("all", B=3, T=T, Hq=8, Hkv=2, D=128, seq_lens=[900, 70, 4100], trees=tree, page_size=32,
+                        dtype="bf16", seed=13100, scale=0.11)
+    w.kv_start = np.int32([512, 70, 4096])                        # request 1: an empty window, the path alone
+    ref, ref_lse = run_oracle(w)
+    dev = to_device(w)
+    k_new = torch.empty((w.B, T, w.Hkv, w.D), dtype=torch.bfloat16, device="cuda")
+    v_new = torch.empty_like(k_new)
+    full_k, full_v = dev["k_cache"].clone(), dev["v_cache"].clone()
+    for b in range(w.B):
+        for i in range(T):
+            pos = int(w.seq_lens[b]) + i
+            page, slot = int(w.page_table[b, pos // 32]), pos % 32
+            k_new[b, i] = full_k[page, :, slot, :]
+            v_new[b, i] = full_v[page, :, slot, :]
+            dev["k_cache"][page, :, slot, :] = -3.0
+            dev["v_cache"][page, :, slot, :] = -3.0
+    masks = torch.zeros((T,), dtype=torch.int64, device="cuda")
+    ta.tree_attn_encode(torch.from_numpy(tree).cuda(), masks)
+    dev["tree_parent"] = torch.full_like(dev["tree_parent"], -1)  # only the masks describe the tree
+    dev["q"] = dev["q"][:, off:off + tq].contiguous()
+    dev["out"] = torch.empty_like(dev["q"])
+    dev["lse"] = torch.empty((w.B, w.Hq, tq), dtype=torch.float32, device="cuda")
+    ws = torch.empty(ta.tree_attn_workspace_bytes(w.B, tq, w.Hq, w.Hkv, w.D, ta.TA_BF16), dtype=torch.uint8, device="cuda")
+    _announce("every option at once, kernel=%d" % kernel)
+    got, got_lse = run_hip(w, dev, kernel=kernel, q_node_offset=off, tree_masks=masks, k_new=k_new, v_new=v_new,
+                           workspace=ws, item_cost=3, num_splits=7)
+    assert_parity(got, got_lse, ref[:, off:off + tq], ref_lse[:, :, off:off + tq], "bf16", "every option at once")
+    assert torch.equal(dev["k_cache"].view(torch.int16), full_k.view(torch.int16))
+    assert torch.equal(dev["v_cache"].view(torch.int16), full_v.view(torch.int16))
+    assert ta.tree_attn_last_status() == 0
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA, MFMA_BASIC])
 def test_queries_are_a_range_of_the_tree_nodes(kernel):
     """Drafting stage: the tree grows level by level; the newest nodes are the queries (ta_opts.q_node_offset), every
     node so far is a key.  Each level's outputs are the corresponding rows of the whole-tree result."""
