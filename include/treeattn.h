@@ -11,8 +11,10 @@
  * suffix attention among the T tree tokens, and a merge of the partial results
  * through their log-sum-exp.  Paging applies to the cache (section 3.4, "Paged
  * KV with tree attention"); the tree tokens' K/V are expected at logical cache
- * positions L_b .. L_b+T-1, i.e. after they have been written back, and the
- * page table must already cover them (the paper's "tree padding").
+ * positions L_b .. L_b+T-1, i.e. after they have been written back (or they
+ * are handed over densely through ta_opts.k_new / v_new, which folds the
+ * write-back into the call), and the page table must already cover them (the
+ * paper's "tree padding").
  *
  * Conventions
  *   - Every `data` pointer is a DEVICE pointer unless stated otherwise; the
@@ -22,6 +24,11 @@
  *     void*; NULL = the default stream), perform no device synchronisation and
  *     no device-to-host copy, and read seq_lens / page_table / tree_parent on
  *     the device only.
+ *   - Calls that use the library-owned workspace of a device (tree_attn_fwd, and
+ *     tree_attn_fwd_ex without ta_opts.workspace) share one buffer of partial
+ *     results: they must not overlap in time, i.e. run on different streams of
+ *     that device without ordering between them.  Concurrent calls each bring a
+ *     workspace of their own.
  *   - Return value: TA_OK (0) or a negative ta_status.  Nothing throws or aborts.
  *     Problems visible on the host (null pointers, ranks, dtypes, shapes,
  *     strides) are reported before anything is launched.  Problems that only
