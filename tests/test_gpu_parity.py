@@ -210,6 +210,16 @@ def test_nan_in_unowned_slots_does_not_leak(kernel):
     _check(w, kernel=kernel)
 
 
+def test_smallest_configuration_against_the_stored_oracle_outputs():
+    """C1 (fp32) against tests/golden/c1_tiny_fp32_oracle.txt, which the oracle wrote and no GPU code ever touched."""
+    from .test_oracle_pins import _read_c1_fixture
+    w = W.make_config(0)
+    ref, ref_lse = _read_c1_fixture()
+    _announce("c1 against the stored oracle outputs")
+    got, got_lse = run_hip(w)
+    assert_parity(got, got_lse, ref, ref_lse, "f32", "c1 stored outputs")
+
+
 @pytest.mark.parametrize("idx,div", [(1, 1), (2, 8), (3, 16), (4, 64)])
 def test_benchmark_configs_reduced_lengths_all_outputs(idx, div):
     w = W.make_config(idx, length_div=div)

@@ -452,3 +452,31 @@ def test_query_subset_equals_those_rows_of_the_whole_tree():
     with pytest.raises(ValueError):
         oracle.tree_attn_oracle(q, w.k_cache, w.v_cache, w.page_table, w.seq_lens, w.tree_parent, scale=w.scale,
                                 q_node_offset=8)                 # 8 + 4 nodes do not fit a tree of 11
+
+
+def _read_c1_fixture():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "c1_tiny_fp32_oracle.txt")
+    vals, shapes = {}, {}
+    cur = None
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if line.startswith(("out ", "lse ")):
+            cur = line.split()[0]
+            shapes[cur] = tuple(int(x) for x in line.split()[1:])
+            vals[cur] = []
+        else:
+            vals[cur].append(float.fromhex(line))
+    return (np.asarray(vals["out"]).reshape(shapes["out"]), np.asarray(vals["lse"]).reshape(shapes["lse"]))
+
+
+def test_stored_outputs_of_the_smallest_configuration_have_not_drifted():
+    """tests/golden/c1_tiny_fp32_oracle.txt was written by the oracle (write_c1_fixture.py); the oracle and the seeded
+    input generator must still reproduce it."""
+    w = W.make_config(0)
+    out, lse = run_oracle(w)
+    ref, ref_lse = _read_c1_fixture()
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(lse, ref_lse, rtol=0, atol=1e-12)
