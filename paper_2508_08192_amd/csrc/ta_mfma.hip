@@ -49,6 +49,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 
 // Staging unit u of a tile: 4 consecutive tokens (quad) x 8 consecutive head-dim elements (chunk),
 // i.e. four 16-byte global loads.  Units 0..255 carry K, 256..511 carry V.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct Unit {
     uint4 r[4];
 };
@@ -85,7 +86,8 @@ __device__ __forceinline__ void load_unit(const TAParams &p, Unit &u, const uint
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         if (k < n_valid)
-            u.r[k] = *(const uint4 *)ptr[k];
+            // keys and values are read once: the non-temporal hint keeps them from displacing the partial results
+            u.r[k] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)ptr[k]));
         else
             u.r[k] = make_uint4(0, 0, 0, 0);
     }
