@@ -33,9 +33,19 @@
  *     Problems visible on the host (null pointers, ranks, dtypes, shapes,
  *     strides) are reported before anything is launched.  Problems that only
  *     the data shows (a parent id outside [-1, T), a parent cycle, L_b < 0,
- *     L_b + T beyond max_pages*page_size) cannot be seen without a
- *     synchronisation: the request's rows of `out` and `lse` are filled with NaN
- *     and a bit is set in a sticky per-device status word (tree_attn_last_status).
+ *     L_b + T beyond max_pages*page_size, a page id outside the cache) cannot be
+ *     seen without a synchronisation: the request's rows of `out` and `lse` are
+ *     filled with NaN and a bit is set in a sticky per-device status word
+ *     (tree_attn_last_status) and, if given, in the caller's own word
+ *     (ta_opts.status).
+ *   - Workspace lifetime.  A buffer of the library-owned workspace that has been
+ *     handed to a launch is never freed or reused for anything else before
+ *     tree_attn_release: when a later call needs more room the library allocates
+ *     a larger buffer and keeps the old one, so a HIP graph captured earlier may
+ *     be replayed at any time.  Under stream capture nothing is allocated: a call
+ *     that would need a larger buffer than the device holds returns
+ *     TA_ERR_WORKSPACE (call tree_attn_reserve before capturing, pass a workspace
+ *     through ta_opts).
  */
 #ifndef TREEATTN_H
 #define TREEATTN_H
@@ -47,7 +57,7 @@
 extern "C" {
 #endif
 
-#define TREEATTN_VERSION 100      /* 0.1.0 */
+#define TREEATTN_VERSION 200      /* 0.2.0 */
 #define TA_MAX_TREE 64            /* one 64-bit ancestor mask per node */
 #define TA_MAX_HEAD_DIM 256
 #define TA_MAX_BATCH 4096
@@ -80,6 +90,7 @@ typedef enum {
 #define TA_STATUS_BAD_PARENT 1   /* parent id outside [-1, T) or a parent cycle */
 #define TA_STATUS_BAD_SEQLEN 2   /* L_b < 0 or L_b + T > max_pages * page_size */
 #define TA_STATUS_BAD_PATH 4     /* tree_attn_compact: accepted length outside [0, A] or a node id outside [0, T) */
+#define TA_STATUS_BAD_PAGE 8     /* a page_table entry the call needs lies outside [0, num_pages) */
 
 typedef struct {
     void *data;           /* device pointer */
@@ -137,6 +148,10 @@ typedef struct {
                                  append followed by the plain call.  A request that is NaN-filled for a bad length
                                  is not written.  Both NULL = the tree tokens are already in the cache. */
     const ta_tensor *v_new;
+    int32_t *status;          /* optional DEVICE pointer to one 32-bit word, 4-byte aligned: the call ORs the TA_STATUS_*
+                                 bits of its own data-dependent problems into it (as well as into the device's sticky
+                                 word), so that a captured graph or a caller with several streams can carry a status
+                                 word of its own and read it whenever it likes.  The library never clears it. */
 } ta_opts;
 
 /*
@@ -181,8 +196,14 @@ size_t tree_attn_workspace_bytes(int32_t B, int32_t T, int32_t Hq, int32_t Hkv, 
                                  int32_t dtype, int32_t num_cus);
 
 /* Grow the library-owned workspace of the current device to at least `bytes` (allocates; call outside
- * stream capture).  Synchronises the device if it has to replace an existing buffer. */
+ * stream capture).  Never synchronises and never frees: a smaller buffer that earlier launches or captured graphs
+ * may still use is kept until tree_attn_release.  Also performs the per-device set-up every entry point needs, so
+ * that the first call under stream capture finds it done. */
 int tree_attn_reserve(size_t bytes);
+
+/* Free every buffer the library owns on the current device (the workspace and the buffers it outgrew).
+ * Synchronises the device first.  Graphs captured with the library-owned workspace must not be replayed afterwards. */
+int tree_attn_release(void);
 
 /*
  * Tree-topology encoder alone (section 3.1: the tree mask, here one 64-bit word per node instead of an
@@ -231,14 +252,36 @@ int tree_attn_last_status(int32_t *host_status, void *stream);
 
 /*
  * Host-only launch plan for a call (no device access): which kernel family would run and how the work
- * is cut.  `sum_tiles_hint` is unused (0).  plan[0] = kernel family, plan[1] = workgroups of the KV pass,
- * plan[2] = threads per workgroup, plan[3] = KV tokens per tile, plan[4] = row groups, plan[5] = padded
- * rows per group, plan[6] = partial slots, plan[7] = workgroups of the merge pass.  HOST pointers.
+ * is cut (section 3.4, "Attention kernel": the choice by batch size, tree size and GPU; here one row of the
+ * library's dispatch table, see tree_attn_dispatch_row).  plan[0] = kernel family, plan[1] = workgroups of the
+ * KV pass, plan[2] = threads per workgroup, plan[3] = KV tokens per tile, plan[4] = row groups, plan[5] = padded
+ * rows per group, plan[6] = partial slots, plan[7] = workgroups of the merge pass, plan[8] = smallest share of
+ * tiles per workgroup, plan[9] = schedule units a list counts (item_cost), plan[10] = merge kernel (0 general,
+ * 1 head_dim 128, 2 head_dim 128 with one workgroup per row), plan[11] = row of the dispatch table that was
+ * taken (-1: the options fixed everything), plan[12] = workspace bytes the call needs, plan[13..15] = 0.
+ * HOST pointers.
  */
 int tree_attn_plan(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
                    const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
                    const ta_tensor *out, const ta_tensor *lse, const ta_opts *opts, int32_t num_cus,
-                   int64_t plan[8]);
+                   int64_t plan[16]);
+
+/*
+ * Row `index` of the dispatch table (host-only; returns TA_ERR_OPTS past the last row): row[0] = kernel family,
+ * row[1] = applies to row groups of up to this many rows, row[2] = and to at most this many (request, KV head)
+ * lists, row[3] = KV-pass workgroups per compute unit in quarters, row[4] = smallest share of tiles,
+ * row[5] = item_cost, row[6] = partials per list from which the one-workgroup-per-row merge takes over (0 = never),
+ * row[7] = as long as the batch has at most this many output rows.  The first row that matches a call is taken.
+ */
+int tree_attn_dispatch_row(int32_t index, int64_t row[8]);
+
+/*
+ * Measurement aid (no part of the method): a plain streaming read of `bytes` bytes of device memory at `buf`
+ * (16-byte aligned, bytes a multiple of 16), one launch on `stream` -- the read rate this device attains, against
+ * which the KV pass's rate is set beside the published peak.  `sink` is a DEVICE pointer to 4 bytes the kernel may
+ * write.
+ */
+int tree_attn_stream_read(const void *buf, size_t bytes, void *sink, void *stream);
 
 const char *tree_attn_strerror(int status);
 int tree_attn_version(void);

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtreeattn.so")
-SOURCES = ["ta_api.hip", "ta_generic.hip", "ta_mfma.hip"]
+SOURCES = ["ta_api.hip", "ta_generic.hip", "ta_mfma.hip", "ta_host.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # hipcc must not form packed-fp32 instructions on these machines
@@ -38,8 +38,6 @@ def build_library(verbose=False, extra_flags=()):
     generate_blocks(verbose)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp%d" % os.getpid()
-    if os.environ.get("TREEATTN_TUNING"):      # ablation switches of the 256-row kernel (see TA_OFF)
-        extra_flags = list(extra_flags) + ["-DTA_TUNING"]
     cmd = [hipcc] + FLAGS + list(extra_flags) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -62,6 +60,30 @@ def build_library(verbose=False, extra_flags=()):
     return LIB
 
 
+HOST_CHECKED_LIB = os.path.join(HERE, "libtreeattn_hostcheck.so")
+
+
+def build_host_checked(verbose=False):
+    """The host logic alone (validation, planning, dispatch table) as a shared library built by g++ with
+    AddressSanitizer and UndefinedBehaviorSanitizer; its launching entry points stop with TA_ERR_HIP.  The CPU
+    tests load it through TREEATTN_LIB, with the sanitizer runtime preloaded.  Returns (library, runtime)."""
+    gxx = os.environ.get("CXX", "g++")
+    tmp = HOST_CHECKED_LIB + ".tmp%d" % os.getpid()
+    cmd = [gxx, "-std=c++17", "-O1", "-g", "-fPIC", "-shared", "-Wall", "-Wextra", "-Werror",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+           os.path.join(CSRC, "ta_host.cpp"), os.path.join(CSRC, "ta_host_only.cpp"), "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        if os.path.exists(tmp):
+            os.remove(tmp)
+        raise RuntimeError("g++ failed:\n" + proc.stdout)
+    os.replace(tmp, HOST_CHECKED_LIB)
+    runtime = subprocess.run([gxx, "-print-file-name=libasan.so"], stdout=subprocess.PIPE, text=True).stdout.strip()
+    return HOST_CHECKED_LIB, runtime
+
+
 def verify_register_partition(verbose=False):
     """ta_mfma_sp_kernel keeps its large operands in v32..v255, which only its asm blocks may touch: the compiler
     is confined to v0..v31 by amdgpu_num_vgpr.  That contract is checked here on the generated ISA rather than
@@ -69,8 +91,6 @@ def verify_register_partition(verbose=False):
     import re
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     flags = [f for f in FLAGS if f not in ("-fPIC", "-shared")]
-    if os.environ.get("TREEATTN_TUNING"):
-        flags.append("-DTA_TUNING")
     cmd = [hipcc] + flags + ["-S", "--cuda-device-only", "-o", "-", os.path.join(CSRC, "ta_mfma.hip")]
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True)
     if proc.returncode != 0:

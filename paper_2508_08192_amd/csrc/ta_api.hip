@@ -1,288 +1,36 @@
-// C-ABI of libtreeattn: descriptor validation on the host, launch planning, per-device state.
+// C-ABI of libtreeattn: per-device state and the entry points that launch.  Descriptor validation, planning and the
+// dispatch table are plain host code in ta_host.cpp; this file adds what needs the HIP runtime.
 // See include/treeattn.h for the contract of every entry point.
-#include <math.h>
 #include <mutex>
-#include <string.h>
-#include <stdlib.h>
+#include <vector>
 
 #include "ta_common.h"
 
 namespace {
 
+// The sticky status word of a device lives in the library image (every device holds its own copy of the array at its
+// own address), so that no entry point has to allocate it.
+__device__ __align__(256) int32_t ta_status_words[TA_STATUS_BYTES / 4];
+
 struct DeviceState {
-    bool init = false;
+    std::once_flag once;
+    int init_rc = TA_ERR_HIP;
     int num_cus = 0;
+    int32_t *status = nullptr;
+    // library-owned workspace: grown under ws_mu; buffers it outgrew stay allocated (launches and captured graphs
+    // may still hold their addresses) until tree_attn_release
+    std::mutex ws_mu;
     void *ws = nullptr;
     size_t ws_bytes = 0;
-    int32_t *status = nullptr;
+    std::vector<void *> retired;
 };
 
 constexpr int kMaxDevices = 64;
 DeviceState g_dev[kMaxDevices];
-std::mutex g_mu;
 
-size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-
-struct Plan {
-    int kernel;
-    int n_wg, threads, n_rg, rows_grp, n_slots, min_q, merge_wgs;
-};
-
-struct Problem {
-    TAParams p;
-    Plan plan;
-    size_t ws_o_bytes, ws_lse_bytes, ws_bytes;
-};
-
-bool strides_ok(const ta_tensor *t)
-{
-    for (int i = 0; i < t->ndim; ++i)
-        if (t->stride[i] < 0)
-            return false;
-    return t->stride[t->ndim - 1] == 1 || t->shape[t->ndim - 1] <= 1;
-}
-
-// rows of a dense K/V tensor as the matrix-core kernels load them: 16-byte aligned, strides within 32 bits
-bool new_rows_aligned(const ta_tensor *n)
-{
-    return ((uintptr_t)n->data % 16) == 0 && n->stride[0] % 8 == 0 && n->stride[1] % 8 == 0 && n->stride[2] % 8 == 0 &&
-           n->stride[0] < INT32_MAX && n->stride[1] < INT32_MAX;
-}
-
-int mfma_rows_group(int rows)
-{
-    // 32 rows per wave; workgroups of 1, 2, 4 or 8 such waves, at most TA_ROW_GROUP rows.
-    int grp = 32;
-    while (grp < rows && grp < TA_ROW_GROUP)
-        grp *= 2;
-    return grp;
-}
-
-// Everything that can be decided from the descriptors alone.  No HIP call in here.
-int build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tensor *v, const ta_tensor *pt,
-                  const ta_tensor *sl, const ta_tensor *par, const ta_tensor *out, const ta_tensor *lse,
-                  const ta_opts *opts, int num_cus, Problem *pr)
-{
-    if (!q || !k || !v || !sl || !par || !out)
-        return TA_ERR_NULL;
-    if (q->dtype != TA_BF16 && q->dtype != TA_F32)
-        return TA_ERR_DTYPE;
-    if (k->dtype != q->dtype || v->dtype != q->dtype || out->dtype != q->dtype)
-        return TA_ERR_DTYPE;
-    if (sl->dtype != TA_I32 || par->dtype != TA_I32 || (pt && pt->dtype != TA_I32) || (lse && lse->dtype != TA_F32))
-        return TA_ERR_DTYPE;
-    if (q->ndim != 4 || k->ndim != 4 || v->ndim != 4 || out->ndim != 4 || sl->ndim != 1 ||
-        (par->ndim != 1 && par->ndim != 2) || (pt && pt->ndim != 2) || (lse && lse->ndim != 3))
-        return TA_ERR_RANK;
-    // T: nodes of the tree, all of them keys; Tq: the nodes that ask, q_off .. q_off+Tq-1 (all of them by default)
-    const int64_t B = q->shape[0], Tq = q->shape[1], Hq = q->shape[2], D = q->shape[3];
-    const int64_t T = par->shape[par->ndim - 1], q_off = opts ? opts->q_node_offset : 0;
-    const int64_t n_pages = k->shape[0], Hkv = k->shape[1], ps = k->shape[2];
-    if (B < 0 || B > TA_MAX_BATCH)
-        return TA_ERR_BATCH;
-    if (T < 1 || T > TA_MAX_TREE || Tq < 1 || Tq > TA_MAX_TREE)
-        return TA_ERR_TREE_SIZE;
-    if (Tq > T)
-        return TA_ERR_SHAPE;                     // more query nodes than the tree has
-    if (q_off < 0 || q_off + Tq > T)
-        return TA_ERR_OPTS;
-    if (D < 1 || D > TA_MAX_HEAD_DIM)
-        return TA_ERR_HEAD_DIM;
-    if (Hq < 1 || Hkv < 1 || Hq % Hkv != 0)
-        return TA_ERR_HEADS;
-    if (Hq > 65535 || ps < 1 || ps > (1 << 30) || n_pages < 0)
-        return TA_ERR_SHAPE;
-    if (k->shape[3] != D)
-        return TA_ERR_SHAPE;
-    for (int i = 0; i < 4; ++i)
-        if (v->shape[i] != k->shape[i] || out->shape[i] != q->shape[i])
-            return TA_ERR_SHAPE;
-    if (sl->shape[0] != B)
-        return TA_ERR_SHAPE;
-    if (par->ndim == 2 && par->shape[0] != B)
-        return TA_ERR_SHAPE;
-    if (lse && (lse->shape[0] != B || lse->shape[1] != Hq || lse->shape[2] != Tq))
-        return TA_ERR_SHAPE;
-    if (pt && pt->shape[0] != B)
-        return TA_ERR_SHAPE;
-    if (!pt && n_pages < B)
-        return TA_ERR_SHAPE;
-    if (!strides_ok(q) || !strides_ok(k) || !strides_ok(v) || !strides_ok(out) || !strides_ok(par) ||
-        (pt && !strides_ok(pt)))
-        return TA_ERR_STRIDE;
-    if (lse)
-        for (int i = 0; i < 3; ++i)
-            if (lse->stride[i] < 0)
-                return TA_ERR_STRIDE;
-    if (sl->stride[0] < 0)
-        return TA_ERR_STRIDE;
-    const int64_t capacity = pt ? pt->shape[1] * ps : ps;
-    if (capacity < T)
-        return TA_ERR_PAGE_TABLE;
-    if (capacity > INT32_MAX)
-        return TA_ERR_SHAPE;
-    if (B > 0) {
-        if (!q->data || !k->data || !v->data || !sl->data || !par->data || !out->data ||
-            (pt && !pt->data) || (lse && !lse->data))
-            return TA_ERR_NULL;
-    }
-    int kernel = TA_KERNEL_AUTO, num_splits = 0, item_cost = 0;
-    const ta_tensor *kn = nullptr, *vn = nullptr;
-    float scale = 0.f;
-    void *user_ws = nullptr;
-    size_t user_ws_bytes = 0;
-    if (opts) {
-        if (opts->item_cost < 0 || opts->item_cost > 4096 || opts->reserved != 0 || opts->num_splits < 0 ||
-            opts->kernel < TA_KERNEL_AUTO ||
-            opts->kernel > TA_KERNEL_MFMA_BASIC)
-            return TA_ERR_OPTS;
-        kernel = opts->kernel;
-        num_splits = opts->num_splits;
-        item_cost = opts->item_cost;
-        if (opts->tree_masks && (((uintptr_t)opts->tree_masks % 8) != 0 || opts->tree_masks_stride < 0))
-            return TA_ERR_OPTS;
-        if (opts->kv_start && ((uintptr_t)opts->kv_start % 4) != 0)
-            return TA_ERR_OPTS;
-        if ((opts->k_new != nullptr) != (opts->v_new != nullptr))
-            return TA_ERR_OPTS;
-        if (opts->k_new) {
-            // the tree tokens' K/V of this step, dense: [B, T, Hkv, D] in the cache's dtype, rows contiguous
-            for (const ta_tensor *n : {opts->k_new, opts->v_new}) {
-                if (n->dtype != k->dtype)
-                    return TA_ERR_DTYPE;
-                if (n->ndim != 4)
-                    return TA_ERR_RANK;
-                if (n->shape[0] != B || n->shape[1] != T || n->shape[2] != Hkv || n->shape[3] != D)
-                    return TA_ERR_SHAPE;
-                if (!strides_ok(n) || n->stride[3] != 1)
-                    return TA_ERR_STRIDE;
-                if (B > 0 && !n->data)
-                    return TA_ERR_NULL;
-            }
-            kn = opts->k_new;
-            vn = opts->v_new;
-        }
-        scale = opts->scale;
-        user_ws = opts->workspace;
-        user_ws_bytes = opts->workspace_bytes;
-        if (user_ws && ((uintptr_t)user_ws % 256) != 0)
-            return TA_ERR_WORKSPACE;
-    }
-    if (!(scale > 0.f) || !isfinite(scale))
-        scale = 1.0f / sqrtf((float)D);
-
-    int ps_shift = -1;
-    for (int s = 0; s <= 30; ++s)
-        if (((int64_t)1 << s) == ps)
-            ps_shift = s;
-    const bool mfma_ok = q->dtype == TA_BF16 && D == 128 && (!pt || ps_shift >= 0) &&
-                         q->stride[2] % 8 == 0 && q->stride[1] % 8 == 0 && q->stride[0] % 8 == 0 &&
-                         k->stride[0] % 8 == 0 && k->stride[1] % 8 == 0 && k->stride[2] % 8 == 0 &&
-                         v->stride[0] % 8 == 0 && v->stride[1] % 8 == 0 && v->stride[2] % 8 == 0 &&
-                         ((uintptr_t)q->data % 16) == 0 && ((uintptr_t)k->data % 16) == 0 &&
-                         ((uintptr_t)v->data % 16) == 0 && k->stride[0] < INT32_MAX && k->stride[2] < INT32_MAX &&
-                         v->stride[0] < INT32_MAX && v->stride[2] < INT32_MAX && Hq / Hkv <= 256 &&
-                         (!kn || (new_rows_aligned(kn) && new_rows_aligned(vn)));
-    const int basic = kernel == TA_KERNEL_MFMA_BASIC ? 1 : 0;
-    if (basic)
-        kernel = TA_KERNEL_MFMA;
-    if (kernel == TA_KERNEL_MFMA && !mfma_ok)
-        return TA_ERR_OPTS;
-    if (kernel == TA_KERNEL_AUTO)
-        kernel = mfma_ok ? TA_KERNEL_MFMA : TA_KERNEL_GENERIC;
-
-    TAParams &p = pr->p;
-    memset(&p, 0, sizeof p);
-    p.basic = basic;
-    p.q = q->data; p.k = k->data; p.v = v->data; p.out = out->data;
-    p.lse = lse ? (float *)lse->data : nullptr;
-    p.page_table = pt ? (const int32_t *)pt->data : nullptr;
-    p.seq_lens = (const int32_t *)sl->data;
-    p.parent = (const int32_t *)par->data;
-    p.q_sb = q->stride[0]; p.q_st = q->stride[1]; p.q_sh = q->stride[2];
-    p.o_sb = out->stride[0]; p.o_st = out->stride[1]; p.o_sh = out->stride[2];
-    p.k_sp = k->stride[0]; p.k_sh = k->stride[1]; p.k_ss = k->stride[2];
-    p.v_sp = v->stride[0]; p.v_sh = v->stride[1]; p.v_ss = v->stride[2];
-    if (lse) { p.lse_sb = lse->stride[0]; p.lse_sh = lse->stride[1]; p.lse_st = lse->stride[2]; }
-    p.pt_sb = pt ? pt->stride[0] : 0;
-    p.par_sb = par->ndim == 2 ? par->stride[0] : 0;
-    p.sl_s = sl->stride[0];
-    p.B = (int)B; p.T = (int)T; p.Hq = (int)Hq; p.Hkv = (int)Hkv; p.G = (int)(Hq / Hkv); p.D = (int)D;
-    p.ps = (int)ps; p.ps_shift = ps_shift; p.capacity = (int)capacity;
-    p.rows = (int)Tq * p.G;
-    p.q_off = (int)q_off;
-    p.g_magic = (1u << 24) / (uint32_t)p.G + 1u;
-    p.masks_in = opts ? (const unsigned long long *)opts->tree_masks : nullptr;
-    p.masks_sb = opts ? opts->tree_masks_stride : 0;
-    p.kv_start = opts ? (const int32_t *)opts->kv_start : nullptr;
-    p.is_bf16 = q->dtype == TA_BF16;
-    if (kn) {
-        p.kn = kn->data; p.vn = vn->data;
-        p.kn_sb = kn->stride[0]; p.kn_st = kn->stride[1]; p.kn_sh = kn->stride[2];
-        p.vn_sb = vn->stride[0]; p.vn_st = vn->stride[1]; p.vn_sh = vn->stride[2];
-        const int es = p.is_bf16 ? 2 : 4;
-        const int per16 = 16 / es;
-        auto vec_ok = [&](const void *ptr, int64_t a, int64_t b2, int64_t c) {
-            return ((uintptr_t)ptr % 16) == 0 && a % per16 == 0 && b2 % per16 == 0 && c % per16 == 0;
-        };
-        p.kn_vec = D % per16 == 0 && vec_ok(kn->data, kn->stride[0], kn->stride[1], kn->stride[2]) &&
-                   vec_ok(vn->data, vn->stride[0], vn->stride[1], vn->stride[2]) &&
-                   vec_ok(k->data, k->stride[0], k->stride[1], k->stride[2]) &&
-                   vec_ok(v->data, v->stride[0], v->stride[1], v->stride[2]);
-    }
-    p.scale_log2e = scale * 1.4426950408889634f;
-
-    Plan &pl = pr->plan;
-    pl.kernel = kernel;
-    // Fixed work per (workgroup, list) overlap, in tiles' worth of time: finding the list, the tree masks, Q, the
-    // first loads' round trip, and writing the partial result.  Measured on the pipelined kernel at about 15 us
-    // against 1.3 to 2.3 us per tile; the register-staged and the scalar kernel have less to set up.
-    const int pad = item_cost > 0 ? item_cost - 1 : (kernel == TA_KERNEL_MFMA ? (basic ? 2 : 8) : 0);
-    p.pad = pad;
-    const int64_t tiles_cap = (int64_t)B * Hkv * ((capacity - T + TA_TILE - 1) / TA_TILE + 1);
-    if (tiles_cap + (int64_t)B * Hkv * pad > INT32_MAX)     // schedule units are counted in 32 bits
-        return TA_ERR_SHAPE;
-    if (kernel == TA_KERNEL_MFMA) {
-        pl.rows_grp = mfma_rows_group(p.rows);
-        pl.threads = 512;                                   // always eight waves; one workgroup per CU
-        pl.n_rg = (p.rows + pl.rows_grp - 1) / pl.rows_grp;
-        // A workgroup's partial result costs rows*D*4 bytes written and read again; a tile of keys and
-        // values costs TA_TILE*D*4 bytes.  Keep a share at least a few tiles long, so the partials stay a
-        // small fraction of the cache traffic: four tiles for 256 rows, one for 64 rows and fewer (batch size one
-        // with a small tree: the shorter the shares, the shorter the step).
-        int64_t want = (int64_t)num_cus / pl.n_rg;
-        if (want < 1)
-            want = 1;
-        pl.n_wg = (int)(num_splits > 0 ? num_splits : want);
-        pl.min_q = num_splits > 0 ? 1 : (pl.rows_grp >= 256 ? 4 : pl.rows_grp >= 128 ? 2 : 1);
-    } else {
-        pl.rows_grp = p.rows < TA_ROW_GROUP ? p.rows : TA_ROW_GROUP;
-        pl.threads = 256;
-        pl.n_rg = (p.rows + pl.rows_grp - 1) / pl.rows_grp;
-        pl.n_wg = num_splits > 0 ? num_splits : num_cus * 4;
-        pl.min_q = 1;
-    }
-    if (pl.n_wg > tiles_cap)
-        pl.n_wg = (int)(tiles_cap > 0 ? tiles_cap : 1);
-    pl.n_slots = pl.n_wg + (int)(B * Hkv);
-    p.rows_grp = pl.rows_grp; p.n_rg = pl.n_rg; p.n_wg = pl.n_wg; p.min_q = pl.min_q;
-    pl.merge_wgs = (int)(B * Hkv) * ((p.rows + ta_merge_rows(p) - 1) / ta_merge_rows(p));
-
-    const size_t rows_total = (size_t)pl.n_slots * pl.n_rg * pl.rows_grp;
-    pr->ws_o_bytes = align_up(rows_total * D * sizeof(float), 256);
-    pr->ws_lse_bytes = align_up(rows_total * sizeof(float), 256);
-    pr->ws_bytes = pr->ws_o_bytes + pr->ws_lse_bytes + align_up((size_t)(B * Hkv) * 2 * sizeof(int32_t), 256);
-    if (user_ws) {
-        if (user_ws_bytes < pr->ws_bytes)
-            return TA_ERR_WORKSPACE;
-        p.ws_o = (float *)user_ws;
-        p.ws_lse = (float *)((char *)user_ws + pr->ws_o_bytes);
-        p.ws_parts = (int32_t *)((char *)user_ws + pr->ws_o_bytes + pr->ws_lse_bytes);
-    }
-    return TA_OK;
-}
-
-int device_state(DeviceState **out)
+// State of the current device; the first call on a device resolves its status word and reads its size.  Allocates
+// nothing.
+int device_state(DeviceState **out, int *dev_out = nullptr)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
@@ -290,169 +38,58 @@ int device_state(DeviceState **out)
         return TA_ERR_HIP;
     }
     DeviceState &s = g_dev[dev];
-    if (!s.init) {
+    std::call_once(s.once, [&]() {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            return TA_ERR_HIP;
-        if (hipMalloc((void **)&s.status, TA_STATUS_BYTES) != hipSuccess)
-            return TA_ERR_HIP;
-        if (hipMemset(s.status, 0, TA_STATUS_BYTES) != hipSuccess)
-            return TA_ERR_HIP;
+            return;
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(ta_status_words)) != hipSuccess || !ptr)
+            return;
+        s.status = (int32_t *)ptr;
         s.num_cus = cus;
-        s.init = true;
+        s.init_rc = TA_OK;
+    });
+    if (s.init_rc != TA_OK) {
+        (void)hipGetLastError();
+        return s.init_rc;
     }
     *out = &s;
+    if (dev_out)
+        *dev_out = dev;
     return TA_OK;
 }
 
+// Grows the library-owned workspace (caller holds ws_mu).  The old buffer is kept, never freed here.
 int reserve_locked(DeviceState *s, size_t bytes)
 {
     if (bytes <= s->ws_bytes)
         return TA_OK;
-    if (s->ws) {
-        if (hipDeviceSynchronize() != hipSuccess)
-            return TA_ERR_HIP;
-        (void)hipFree(s->ws);
-        s->ws = nullptr;
-        s->ws_bytes = 0;
-    }
-    bytes = align_up(bytes, (size_t)1 << 20);
-    if (hipMalloc(&s->ws, bytes) != hipSuccess) {
+    bytes = ta_host_align_up(bytes, (size_t)1 << 20);
+    void *fresh = nullptr;
+    if (hipMalloc(&fresh, bytes) != hipSuccess) {
         (void)hipGetLastError();
         return TA_ERR_HIP;
     }
+    if (s->ws)
+        s->retired.push_back(s->ws);
+    s->ws = fresh;
     s->ws_bytes = bytes;
     return TA_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int tree_attn_version(void) { return TREEATTN_VERSION; }
-
-const char *tree_attn_strerror(int status)
+void place_workspace(TAProblem &pr, void *ws)
 {
-    switch (status) {
-    case TA_OK: return "ok";
-    case TA_ERR_NULL: return "a required descriptor or data pointer is NULL";
-    case TA_ERR_DTYPE: return "unsupported or mismatching element type";
-    case TA_ERR_RANK: return "wrong number of dimensions";
-    case TA_ERR_SHAPE: return "shapes disagree";
-    case TA_ERR_STRIDE: return "innermost stride must be 1 and strides must be non-negative";
-    case TA_ERR_HEADS: return "query heads must be a multiple of KV heads";
-    case TA_ERR_HEAD_DIM: return "head_dim out of range";
-    case TA_ERR_TREE_SIZE: return "tree size must be in [1, 64]";
-    case TA_ERR_PAGE_TABLE: return "page table cannot hold the tree tokens";
-    case TA_ERR_WORKSPACE: return "workspace too small or misaligned";
-    case TA_ERR_HIP: return "HIP runtime call failed";
-    case TA_ERR_BATCH: return "batch size out of range";
-    case TA_ERR_OPTS: return "invalid option";
-    default: return "unknown status";
-    }
+    pr.p.ws_o = (float *)ws;
+    pr.p.ws_lse = (float *)((char *)ws + pr.ws_o_bytes);
+    pr.p.ws_parts = (int32_t *)((char *)ws + pr.ws_o_bytes + pr.ws_lse_bytes);
 }
 
-int tree_attn_plan(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
-                   const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
-                   const ta_tensor *out, const ta_tensor *lse, const ta_opts *opts, int32_t num_cus,
-                   int64_t plan[8])
+// KV pass and merge pass of a planned call on `stream`.
+int launch_call(const TAProblem &pr, hipStream_t st, int dev, void *const *ev)
 {
-    if (!plan)
-        return TA_ERR_NULL;
-    Problem pr;
-    ta_opts o;
-    if (opts) {
-        o = *opts;
-        o.workspace = nullptr;      // planning never needs the scratch itself
-        o.workspace_bytes = 0;
-    }
-    int rc = build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts ? &o : nullptr,
-                           num_cus > 0 ? num_cus : 256, &pr);
-    if (rc != TA_OK)
-        return rc;
-    plan[0] = pr.plan.kernel;
-    plan[1] = pr.plan.n_wg;
-    plan[2] = pr.plan.threads;
-    plan[3] = TA_TILE;
-    plan[4] = pr.plan.n_rg;
-    plan[5] = pr.plan.rows_grp;
-    plan[6] = pr.plan.n_slots;
-    plan[7] = pr.plan.merge_wgs;
-    return TA_OK;
-}
-
-size_t tree_attn_workspace_bytes(int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t D, int32_t dtype,
-                                 int32_t num_cus)
-{
-    if (B < 0 || B > TA_MAX_BATCH || T < 1 || T > TA_MAX_TREE || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || D < 1 ||
-        D > TA_MAX_HEAD_DIM || (dtype != TA_BF16 && dtype != TA_F32))
-        return 0;
-    if (num_cus <= 0) {
-        DeviceState *s = nullptr;
-        std::lock_guard<std::mutex> lk(g_mu);
-        num_cus = device_state(&s) == TA_OK ? s->num_cus : 256;
-    }
-    // Worst case over both kernel families: 4 workgroups per CU, rows padded to the MFMA row group.
-    const int rows = T * (Hq / Hkv);
-    const int rows_grp = mfma_rows_group(rows);
-    const size_t n_rg = (rows + rows_grp - 1) / rows_grp;
-    const size_t slots = (size_t)num_cus * 4 + (size_t)B * Hkv;
-    const size_t rows_total = slots * n_rg * rows_grp;
-    return align_up(rows_total * D * sizeof(float), 256) + align_up(rows_total * sizeof(float), 256) +
-           align_up((size_t)B * Hkv * 2 * sizeof(int32_t), 256);
-}
-
-int tree_attn_reserve(size_t bytes)
-{
-    std::lock_guard<std::mutex> lk(g_mu);
-    DeviceState *s = nullptr;
-    int rc = device_state(&s);
-    if (rc != TA_OK)
-        return rc;
-    return reserve_locked(s, bytes);
-}
-
-int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
-                     const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
-                     ta_tensor *out, ta_tensor *lse, void *stream, const ta_opts *opts)
-{
-    Problem pr;
-    // First pass with a nominal CU count: host-visible errors are reported before any HIP call.
-    int rc = build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts, 256, &pr);
-    if (rc != TA_OK)
-        return rc;
-    if (pr.p.B == 0)
-        return TA_OK;
-    DeviceState *s = nullptr;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        rc = device_state(&s);
-        if (rc != TA_OK)
-            return rc;
-        rc = build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts, s->num_cus, &pr);
-        if (rc != TA_OK)
-            return rc;
-        if (!pr.p.ws_o) {
-            rc = reserve_locked(s, pr.ws_bytes);
-            if (rc != TA_OK)
-                return rc;
-            pr.p.ws_o = (float *)s->ws;
-            pr.p.ws_lse = (float *)((char *)s->ws + pr.ws_o_bytes);
-            pr.p.ws_parts = (int32_t *)((char *)s->ws + pr.ws_o_bytes + pr.ws_lse_bytes);
-        }
-    }
-    pr.p.status = s->status;
-#ifdef TA_TUNING
-    {
-        static const char *dbg = getenv("TREEATTN_DBG");
-        pr.p.dbg = dbg ? atoi(dbg) : 0;
-    }
-#endif
-    hipStream_t st = (hipStream_t)stream;
-    void *const *ev = opts ? opts->events : nullptr;
     if (ev && ev[0] && hipEventRecord((hipEvent_t)ev[0], st) != hipSuccess)
         return TA_ERR_HIP;
-    hipError_t e = pr.plan.kernel == TA_KERNEL_MFMA ? ta_launch_mfma(pr.p, st) : ta_launch_generic(pr.p, st);
+    hipError_t e = pr.plan.kernel == TA_KERNEL_MFMA ? ta_launch_mfma(pr.p, st, dev) : ta_launch_generic(pr.p, st, dev);
     if (e != hipSuccess)
         return TA_ERR_HIP;
     if (ev && ev[1] && hipEventRecord((hipEvent_t)ev[1], st) != hipSuccess)
@@ -465,6 +102,90 @@ int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tens
     return TA_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+size_t tree_attn_workspace_bytes(int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t D, int32_t dtype,
+                                 int32_t num_cus)
+{
+    if (num_cus <= 0) {
+        DeviceState *s = nullptr;
+        num_cus = device_state(&s) == TA_OK ? s->num_cus : 256;
+    }
+    return ta_host_workspace_bytes(B, T, Hq, Hkv, D, dtype, num_cus);
+}
+
+int tree_attn_reserve(size_t bytes)
+{
+    DeviceState *s = nullptr;
+    int rc = device_state(&s);
+    if (rc != TA_OK)
+        return rc;
+    std::lock_guard<std::mutex> lk(s->ws_mu);
+    return reserve_locked(s, bytes);
+}
+
+int tree_attn_release(void)
+{
+    DeviceState *s = nullptr;
+    int rc = device_state(&s);
+    if (rc != TA_OK)
+        return rc;
+    std::lock_guard<std::mutex> lk(s->ws_mu);
+    if (hipDeviceSynchronize() != hipSuccess)
+        return TA_ERR_HIP;
+    for (void *ptr : s->retired)
+        (void)hipFree(ptr);
+    s->retired.clear();
+    if (s->ws)
+        (void)hipFree(s->ws);
+    s->ws = nullptr;
+    s->ws_bytes = 0;
+    return TA_OK;
+}
+
+int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
+                     const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
+                     ta_tensor *out, ta_tensor *lse, void *stream, const ta_opts *opts)
+{
+    TAProblem pr;
+    // First pass with a nominal CU count: host-visible errors are reported before any HIP call.
+    int rc = ta_host_build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts, 256, &pr);
+    if (rc != TA_OK)
+        return rc;
+    if (pr.p.B == 0)
+        return TA_OK;
+    DeviceState *s = nullptr;
+    int dev = 0;
+    rc = device_state(&s, &dev);
+    if (rc != TA_OK)
+        return rc;
+    rc = ta_host_build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts, s->num_cus, &pr);
+    if (rc != TA_OK)
+        return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (!pr.p.ws_o) {
+        std::lock_guard<std::mutex> lk(s->ws_mu);
+        if (pr.ws_bytes > s->ws_bytes) {
+            // growing means hipMalloc, which stream capture forbids: such a caller reserves beforehand
+            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing(st, &cap) != hipSuccess) {
+                (void)hipGetLastError();
+                return TA_ERR_HIP;
+            }
+            if (cap != hipStreamCaptureStatusNone)
+                return TA_ERR_WORKSPACE;
+            rc = reserve_locked(s, pr.ws_bytes);
+            if (rc != TA_OK)
+                return rc;
+        }
+        place_workspace(pr, s->ws);
+    }
+    pr.p.status = s->status;
+    return launch_call(pr, st, dev, opts ? opts->events : nullptr);
+}
+
 int tree_attn_fwd(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
                   const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
                   ta_tensor *out, ta_tensor *lse, void *stream)
@@ -474,97 +195,31 @@ int tree_attn_fwd(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor 
 
 int tree_attn_encode(const ta_tensor *tree_parent, ta_tensor *masks, void *stream)
 {
-    if (!tree_parent || !masks)
-        return TA_ERR_NULL;
-    if (tree_parent->dtype != TA_I32 || masks->dtype != TA_U64)
-        return TA_ERR_DTYPE;
-    if ((tree_parent->ndim != 1 && tree_parent->ndim != 2) || masks->ndim != tree_parent->ndim)
-        return TA_ERR_RANK;
-    const int nd = tree_parent->ndim;
-    const int64_t B = nd == 2 ? tree_parent->shape[0] : 1, T = tree_parent->shape[nd - 1];
-    if (T < 1 || T > TA_MAX_TREE)
-        return TA_ERR_TREE_SIZE;
-    if (B < 0 || B > TA_MAX_BATCH)
-        return TA_ERR_BATCH;
-    for (int i = 0; i < nd; ++i)
-        if (masks->shape[i] != tree_parent->shape[i])
-            return TA_ERR_SHAPE;
-    if (!strides_ok(tree_parent) || !strides_ok(masks) || (nd == 2 && masks->stride[0] != T && B > 1))
-        return TA_ERR_STRIDE;
-    if (B == 0)
-        return TA_OK;
-    if (!tree_parent->data || !masks->data)
-        return TA_ERR_NULL;
+    int B = 0, T = 0;
+    int64_t par_sb = 0;
+    int rc = ta_host_check_encode(tree_parent, masks, &B, &T, &par_sb);
+    if (rc != TA_OK || B == 0)
+        return rc;
     DeviceState *s = nullptr;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        int rc = device_state(&s);
-        if (rc != TA_OK)
-            return rc;
-    }
-    hipError_t e = ta_launch_encode((const int32_t *)tree_parent->data, nd == 2 ? tree_parent->stride[0] : 0, (int)B,
-                                    (int)T, (unsigned long long *)masks->data, s->status, (hipStream_t)stream);
+    rc = device_state(&s);
+    if (rc != TA_OK)
+        return rc;
+    hipError_t e = ta_launch_encode((const int32_t *)tree_parent->data, par_sb, B, T, (unsigned long long *)masks->data,
+                                    s->status, (hipStream_t)stream);
     return e == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
 
 int tree_attn_append(const ta_tensor *k_new, const ta_tensor *v_new, ta_tensor *k_cache, ta_tensor *v_cache,
                      const ta_tensor *page_table, const ta_tensor *seq_lens, void *stream)
 {
-    const ta_tensor *kn = k_new, *vn = v_new, *k = k_cache, *v = v_cache, *pt = page_table, *sl = seq_lens;
-    if (!kn || !vn || !k || !v || !sl)
-        return TA_ERR_NULL;
-    if ((kn->dtype != TA_BF16 && kn->dtype != TA_F32) || vn->dtype != kn->dtype || k->dtype != kn->dtype ||
-        v->dtype != kn->dtype || sl->dtype != TA_I32 || (pt && pt->dtype != TA_I32))
-        return TA_ERR_DTYPE;
-    if (kn->ndim != 4 || vn->ndim != 4 || k->ndim != 4 || v->ndim != 4 || sl->ndim != 1 || (pt && pt->ndim != 2))
-        return TA_ERR_RANK;
-    const int64_t B = kn->shape[0], T = kn->shape[1], Hkv = kn->shape[2], D = kn->shape[3], ps = k->shape[2];
-    if (B < 0 || B > TA_MAX_BATCH)
-        return TA_ERR_BATCH;
-    if (T < 1 || T > TA_MAX_TREE)
-        return TA_ERR_TREE_SIZE;
-    if (D < 1 || D > TA_MAX_HEAD_DIM)
-        return TA_ERR_HEAD_DIM;
-    for (int i = 0; i < 4; ++i)
-        if (vn->shape[i] != kn->shape[i] || v->shape[i] != k->shape[i])
-            return TA_ERR_SHAPE;
-    if (Hkv < 1 || k->shape[1] != Hkv || k->shape[3] != D || ps < 1 || sl->shape[0] != B)
-        return TA_ERR_SHAPE;
-    if (pt ? (pt->shape[0] != B || pt->shape[1] < 1) : k->shape[0] < B)
-        return TA_ERR_PAGE_TABLE;
-    if (!strides_ok(kn) || !strides_ok(vn) || !strides_ok(k) || !strides_ok(v) || !strides_ok(sl) ||
-        (pt && !strides_ok(pt)) || kn->stride[3] != 1 || vn->stride[3] != 1 || k->stride[3] != 1 || v->stride[3] != 1 ||
-        (pt && pt->stride[1] != 1))
-        return TA_ERR_STRIDE;
-    const int64_t capacity = pt ? pt->shape[1] * ps : ps;
-    if (capacity < T)
-        return TA_ERR_PAGE_TABLE;
-    if (capacity > INT32_MAX)
-        return TA_ERR_SHAPE;
-    if (B == 0)
-        return TA_OK;
-    if (!kn->data || !vn->data || !k->data || !v->data || !sl->data || (pt && !pt->data))
-        return TA_ERR_NULL;
-    DeviceState *s = nullptr;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        int rc = device_state(&s);
-        if (rc != TA_OK)
-            return rc;
-    }
     TAAppend a;
-    memset(&a, 0, sizeof a);
-    a.k_new = kn->data; a.v_new = vn->data; a.k = k->data; a.v = v->data;
-    a.page_table = pt ? (const int32_t *)pt->data : nullptr;
-    a.seq_lens = (const int32_t *)sl->data;
-    a.kn_sb = kn->stride[0]; a.kn_st = kn->stride[1]; a.kn_sh = kn->stride[2];
-    a.vn_sb = vn->stride[0]; a.vn_st = vn->stride[1]; a.vn_sh = vn->stride[2];
-    a.k_sp = k->stride[0]; a.k_sh = k->stride[1]; a.k_ss = k->stride[2];
-    a.v_sp = v->stride[0]; a.v_sh = v->stride[1]; a.v_ss = v->stride[2];
-    a.pt_sb = pt ? pt->stride[0] : 0;
-    a.sl_s = sl->stride[0];
-    a.B = (int)B; a.T = (int)T; a.Hkv = (int)Hkv; a.D = (int)D; a.ps = (int)ps; a.capacity = (int)capacity;
-    a.elem_bytes = kn->dtype == TA_BF16 ? 2 : 4;
+    int rc = ta_host_check_append(k_new, v_new, k_cache, v_cache, page_table, seq_lens, &a);
+    if (rc != TA_OK || a.B == 0)
+        return rc;
+    DeviceState *s = nullptr;
+    rc = device_state(&s);
+    if (rc != TA_OK)
+        return rc;
     a.status = s->status;
     return ta_launch_append(a, (hipStream_t)stream) == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
@@ -573,76 +228,18 @@ int tree_attn_compact(ta_tensor *k_cache, ta_tensor *v_cache, const ta_tensor *p
                       const ta_tensor *accepted, const ta_tensor *n_accepted, int32_t tree_size,
                       ta_tensor *seq_lens_out, void *stream)
 {
-    const ta_tensor *k = k_cache, *v = v_cache, *pt = page_table, *sl = seq_lens, *ac = accepted, *na = n_accepted;
-    const ta_tensor *so = seq_lens_out;
-    if (!k || !v || !sl || !ac || !na)
-        return TA_ERR_NULL;
-    if ((k->dtype != TA_BF16 && k->dtype != TA_F32) || v->dtype != k->dtype || sl->dtype != TA_I32 ||
-        ac->dtype != TA_I32 || na->dtype != TA_I32 || (pt && pt->dtype != TA_I32) || (so && so->dtype != TA_I32))
-        return TA_ERR_DTYPE;
-    if (k->ndim != 4 || v->ndim != 4 || sl->ndim != 1 || ac->ndim != 2 || na->ndim != 1 || (pt && pt->ndim != 2) ||
-        (so && so->ndim != 1))
-        return TA_ERR_RANK;
-    const int64_t B = ac->shape[0], A = ac->shape[1], Hkv = k->shape[1], D = k->shape[3], ps = k->shape[2];
-    const int64_t T = tree_size;
-    if (B < 0 || B > TA_MAX_BATCH)
-        return TA_ERR_BATCH;
-    if (T < 1 || T > TA_MAX_TREE || A < 1 || A > TA_MAX_TREE)
-        return TA_ERR_TREE_SIZE;
-    if (D < 1 || D > TA_MAX_HEAD_DIM)
-        return TA_ERR_HEAD_DIM;
-    for (int i = 0; i < 4; ++i)
-        if (v->shape[i] != k->shape[i])
-            return TA_ERR_SHAPE;
-    if (Hkv < 1 || ps < 1 || sl->shape[0] != B || na->shape[0] != B || (so && so->shape[0] != B))
-        return TA_ERR_SHAPE;
-    if (pt ? (pt->shape[0] != B || pt->shape[1] < 1) : k->shape[0] < B)
-        return TA_ERR_PAGE_TABLE;
-    if (!strides_ok(k) || !strides_ok(v) || !strides_ok(ac) || (pt && !strides_ok(pt)) || k->stride[3] != 1 ||
-        v->stride[3] != 1 || (pt && pt->stride[1] != 1) || sl->stride[0] < 0 || na->stride[0] < 0 ||
-        (so && so->stride[0] < 0))
-        return TA_ERR_STRIDE;
-    const int64_t capacity = pt ? pt->shape[1] * ps : ps;
-    if (capacity < T)
-        return TA_ERR_PAGE_TABLE;
-    if (capacity > INT32_MAX)
-        return TA_ERR_SHAPE;
-    if (B == 0)
-        return TA_OK;
-    if (!k->data || !v->data || !sl->data || !ac->data || !na->data || (pt && !pt->data) || (so && !so->data))
-        return TA_ERR_NULL;
-    if (so && B > 1) {
-        // the lengths may be updated in place; any other overlap of the two arrays would let one request's new length
-        // be read as another's old one
-        const bool same = so->data == sl->data && so->stride[0] == sl->stride[0];
-        const char *a0 = (const char *)sl->data, *a1 = a0 + ((B - 1) * sl->stride[0] + 1) * 4;
-        const char *b0 = (const char *)so->data, *b1 = b0 + ((B - 1) * so->stride[0] + 1) * 4;
-        if (!same && a0 < b1 && b0 < a1)
-            return TA_ERR_STRIDE;
-    }
-    DeviceState *s = nullptr;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        int rc = device_state(&s);
-        if (rc != TA_OK)
-            return rc;
-    }
     TACompact c;
-    memset(&c, 0, sizeof c);
-    c.k = k->data; c.v = v->data;
-    c.page_table = pt ? (const int32_t *)pt->data : nullptr;
-    c.seq_lens = (const int32_t *)sl->data;
-    c.accepted = (const int32_t *)ac->data;
-    c.n_accepted = (const int32_t *)na->data;
-    c.seq_lens_out = so ? (int32_t *)so->data : nullptr;
-    c.k_sp = k->stride[0]; c.k_sh = k->stride[1]; c.k_ss = k->stride[2];
-    c.v_sp = v->stride[0]; c.v_sh = v->stride[1]; c.v_ss = v->stride[2];
-    c.pt_sb = pt ? pt->stride[0] : 0;
-    c.sl_s = sl->stride[0]; c.acc_sb = ac->stride[0]; c.na_s = na->stride[0]; c.slo_s = so ? so->stride[0] : 0;
-    c.B = (int)B; c.T = (int)T; c.A = (int)A; c.Hkv = (int)Hkv; c.D = (int)D; c.ps = (int)ps; c.capacity = (int)capacity;
-    c.elem_bytes = k->dtype == TA_BF16 ? 2 : 4;
+    int rc = ta_host_check_compact(k_cache, v_cache, page_table, seq_lens, accepted, n_accepted, tree_size,
+                                   seq_lens_out, &c);
+    if (rc != TA_OK || c.B == 0)
+        return rc;
+    DeviceState *s = nullptr;
+    int dev = 0;
+    rc = device_state(&s, &dev);
+    if (rc != TA_OK)
+        return rc;
     c.status = s->status;
-    return ta_launch_compact(c, (hipStream_t)stream) == hipSuccess ? TA_OK : TA_ERR_HIP;
+    return ta_launch_compact(c, (hipStream_t)stream, dev) == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
 
 int tree_attn_last_status(int32_t *host_status, void *stream)
@@ -650,12 +247,9 @@ int tree_attn_last_status(int32_t *host_status, void *stream)
     if (!host_status)
         return TA_ERR_NULL;
     DeviceState *s = nullptr;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        int rc = device_state(&s);
-        if (rc != TA_OK)
-            return rc;
-    }
+    int rc = device_state(&s);
+    if (rc != TA_OK)
+        return rc;
     hipStream_t st = (hipStream_t)stream;
     if (hipMemcpyAsync(host_status, s->status, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
         return TA_ERR_HIP;
@@ -666,17 +260,19 @@ int tree_attn_last_status(int32_t *host_status, void *stream)
     return TA_OK;
 }
 
-}  // extern "C"
-
-#ifdef TA_TUNING
-// tuning builds only: copies the status area (synchronously) to the host
-extern "C" int ta_tuning_read(void *host256)
+int tree_attn_stream_read(const void *buf, size_t bytes, void *sink, void *stream)
 {
-    std::lock_guard<std::mutex> lock(g_mu);
+    if (!buf || !sink)
+        return TA_ERR_NULL;
+    if (((uintptr_t)buf % 16) != 0 || bytes % 16 != 0 || ((uintptr_t)sink % 4) != 0)
+        return TA_ERR_STRIDE;
+    if (bytes == 0)
+        return TA_OK;
     DeviceState *s = nullptr;
     int rc = device_state(&s);
     if (rc != TA_OK)
         return rc;
-    return hipMemcpy(host256, s->status, TA_STATUS_BYTES, hipMemcpyDeviceToHost) == hipSuccess ? TA_OK : TA_ERR_HIP;
+    return ta_launch_stream_read(buf, bytes, sink, s->num_cus, (hipStream_t)stream) == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
-#endif
+
+}  // extern "C"

@@ -5,69 +5,16 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "../../include/treeattn.h"
+#include "ta_params.h"
 
-#define TA_WAVE 64
-#define TA_TILE 64            // KV tokens per tile of the KV pass (the tree tokens form one more tile)
-#define TA_MERGE_ROWS 4       // rows per workgroup of the merge pass (one per wave)
-#define TA_ROW_GROUP 256
-#ifdef TA_TUNING
-#define TA_STATUS_BYTES 65536   // room for per-workgroup timestamps
-#else
-#define TA_STATUS_BYTES 256
-#endif      // rows (tree nodes x query heads of one KV head) one workgroup keeps
-
-struct TAParams {
-    const void *q, *k, *v;
-    void *out;
-    float *lse;
-    const int32_t *page_table, *seq_lens, *parent;
-    int64_t q_sb, q_st, q_sh;
-    int64_t o_sb, o_st, o_sh;
-    int64_t k_sp, k_sh, k_ss;
-    int64_t v_sp, v_sh, v_ss;
-    int64_t lse_sb, lse_sh, lse_st;
-    int64_t pt_sb, par_sb, sl_s;
-    int32_t B, T, Hq, Hkv, G, D;
-    int32_t ps, ps_shift;      // page size; log2 of it, or -1 when it is not a power of two
-    int32_t capacity;          // logical positions one request can address
-    int32_t rows;              // T * G
-    int32_t rows_grp;          // rows per row group (the last group may hold fewer)
-    int32_t n_rg;              // row groups
-    int32_t n_wg;              // workgroups of the KV pass along x
-    int32_t min_q;             // smallest share of tiles a workgroup takes
-    int32_t pad;               // schedule units a list counts on top of its tiles (fixed cost per list)
-    uint32_t g_magic;          // 2^24 / G + 1: R / G == mulhi(R << 8, g_magic) for R * G < 2^24 (matrix-core kernels)
-    const int32_t *kv_start;   // [B] window starts, or null
-    int32_t q_off;             // row r of q, out and lse is tree node q_off + r / G (rows = Tq * G)
-    const unsigned long long *masks_in;   // ancestor masks encoded earlier (or null: walk the parents in the call)
-    int64_t masks_sb;          // words between the masks of consecutive requests
-    int32_t is_bf16;
-    float scale_log2e;         // softmax scale * log2(e): scores are kept in the base-2 domain
-    float *ws_o;               // partial outputs  [slot][rg][rows_grp][D], normalised, fp32
-    float *ws_lse;             // partial log2-sum-exp2 [slot][rg][rows_grp]
-    int32_t *ws_parts;         // [B * Hkv][2]: first and last workgroup that hold partial results of a list; written
-                               // by the KV pass (the owners of the list's first and last tile), read by the merge
-    int32_t *status;           // sticky status word
-    int32_t basic;             // 256-row groups: use the register-staged MFMA kernel, not the pipelined one
-    // write-back folded into the call: the tree tokens' K/V come from these dense tensors [B, T, Hkv, D] (element
-    // strides), the KV pass reads them there and the merge pass copies them behind the prefix in the caches
-    const void *kn, *vn;
-    int64_t kn_sb, kn_st, kn_sh, vn_sb, vn_st, vn_sh;
-    int32_t kn_vec;            // rows can be copied in 16-byte pieces
-#ifdef TA_TUNING
-    int32_t dbg;               // bit flags that switch parts of a kernel off (results become wrong)
-#endif
-};
-
-// Ablation switches for tuning builds (-DTA_TUNING, flags from the TREEATTN_DBG environment variable): a set
-// bit removes one part of the 256-row KV kernel so that its share of the time can be read off.  A regular
-// build compiles every switch to `false`.
-#ifdef TA_TUNING
-#define TA_OFF(bit) ((p.dbg & (bit)) != 0)
-#else
-#define TA_OFF(bit) false
-#endif
+// A data-dependent problem of the call: the bit goes into the device's sticky status word and into the caller's own
+// word, if it gave one (ta_opts.status).  One thread of a workgroup calls this.
+__device__ __forceinline__ void ta_raise(const TAParams &p, int bits)
+{
+    atomicOr(p.status, bits);
+    if (p.status2)
+        atomicOr(p.status2, bits);
+}
 
 // ---------------------------------------------------------------------------------------------
 // Work schedule.  The KV pass walks, for every (request b, KV head g), a list of tiles:
@@ -195,7 +142,14 @@ __device__ __forceinline__ int64_t ta_ws_row(const TAParams &p, int slot, int rg
     return ((int64_t)slot * p.n_rg + rg) * p.rows_grp + r;
 }
 
-// Element offset of logical position pos of request b, KV head g in a cache with strides (sp, sh, ss).
+// A page id comes from the caller's page table: one outside the cache must never become an address.
+__device__ __forceinline__ bool ta_page_ok(const TAParams &p, int page)
+{
+    return (uint32_t)page < (uint32_t)p.n_pages;
+}
+
+// Element offset of logical position pos of request b, KV head g in a cache with strides (sp, sh, ss); -1 if the
+// page table names a page the cache does not have.
 __device__ __forceinline__ int64_t ta_cache_offset(const TAParams &p, int b, int g, int pos,
                                                    int64_t sp, int64_t sh, int64_t ss)
 {
@@ -203,12 +157,44 @@ __device__ __forceinline__ int64_t ta_cache_offset(const TAParams &p, int b, int
     if (p.page_table) {
         int pi = p.ps_shift >= 0 ? (pos >> p.ps_shift) : (pos / p.ps);
         slot = p.ps_shift >= 0 ? (pos & (p.ps - 1)) : (pos - pi * p.ps);
-        page = p.page_table[(int64_t)b * p.pt_sb + pi];
+        const int id = p.page_table[(int64_t)b * p.pt_sb + pi];
+        if (!ta_page_ok(p, id))
+            return -1;
+        page = id;
     } else {
         page = b;
         slot = pos;
     }
     return page * sp + (int64_t)g * sh + slot * ss;
+}
+
+// Are the page-table entries that hold logical positions pos_lo .. pos_hi of request b all pages of the cache?
+// Every thread of the workgroup calls this; *flag is one int of shared memory; two barriers inside.
+__device__ __forceinline__ bool ta_pages_ok(const TAParams &p, int b, int pos_lo, int pos_hi, int *flag)
+{
+    if (!p.page_table || pos_hi < pos_lo)
+        return true;
+    if (threadIdx.x == 0)
+        *flag = 0;
+    __syncthreads();
+    const int first = p.ps_shift >= 0 ? (pos_lo >> p.ps_shift) : (pos_lo / p.ps);
+    const int last = p.ps_shift >= 0 ? (pos_hi >> p.ps_shift) : (pos_hi / p.ps);
+    for (int k = first + (int)threadIdx.x; k <= last; k += (int)blockDim.x)
+        if (!ta_page_ok(p, p.page_table[(int64_t)b * p.pt_sb + k]))
+            atomicOr(flag, 1);
+    __syncthreads();
+    return *flag == 0;
+}
+
+// First and last logical position whose pages the item (tiles j0 .. j1-1 of a list with n_b tiles, first prefix tile
+// tile0, window start S, length L) reads.
+__device__ __forceinline__ void ta_item_positions(const TAParams &p, int j0, int j1, int n_b, int tile0, int L, int S,
+                                                  int &pos_lo, int &pos_hi)
+{
+    const int first = (tile0 + j0) * TA_TILE;
+    pos_lo = j0 == n_b - 1 ? L : (first > S ? first : S);
+    const int end = (tile0 + j1) * TA_TILE;
+    pos_hi = j1 == n_b ? L + p.T - 1 : (end < L ? end : L) - 1;
 }
 
 // Ancestor masks of one request's tree into masks[0..T): bit j of masks[i] is set iff node j is on the
@@ -251,6 +237,13 @@ __device__ __forceinline__ unsigned long long ta_given_mask(const TAParams &p, i
 {
     const unsigned long long m = p.masks_in[(int64_t)b * p.masks_sb + tid];
     return p.T >= 64 ? m : m & ((1ull << p.T) - 1ull);
+}
+
+// A word of masks given by the caller is taken as it is, except that a node always lies on its own path: a word
+// without its own bit (what tree_attn_encode writes for a malformed tree) marks the request as malformed.
+__device__ __forceinline__ bool ta_given_mask_ok(unsigned long long m, int node)
+{
+    return ((m >> node) & 1ull) != 0;
 }
 
 // The walk itself: par_s[0..T) and *flag = 0 are already in LDS and visible to the workgroup.  Ends with a barrier.
@@ -363,8 +356,10 @@ __device__ __forceinline__ void ta_scatter_locate(const TAParams &p, int b, int 
     s.ok = s.mine > 0 && ta_request_ok(p, s.L, s.S);
     if (s.ok && s.live) {
         const int es = p.is_bf16 ? 2 : 4;
-        s.dst = (s.is_v ? ta_cache_offset(p, b, g, s.L + s.i, p.v_sp, p.v_sh, p.v_ss)
-                        : ta_cache_offset(p, b, g, s.L + s.i, p.k_sp, p.k_sh, p.k_ss)) * es + 16 * s.c;
+        const int64_t off = s.is_v ? ta_cache_offset(p, b, g, s.L + s.i, p.v_sp, p.v_sh, p.v_ss)
+                                   : ta_cache_offset(p, b, g, s.L + s.i, p.k_sp, p.k_sh, p.k_ss);
+        s.dst = off * es + 16 * s.c;
+        s.live = off >= 0;             // a page the cache does not have is not written (the KV pass reports it)
     }
 }
 
@@ -383,6 +378,8 @@ __device__ __forceinline__ void ta_scatter_store(const TAParams &p, int b, int g
                                  : (int64_t)b * p.kn_sb + (int64_t)i * p.kn_st + (int64_t)g * p.kn_sh;
         const int64_t dst = is_v ? ta_cache_offset(p, b, g, s.L + i, p.v_sp, p.v_sh, p.v_ss)
                                  : ta_cache_offset(p, b, g, s.L + i, p.k_sp, p.k_sh, p.k_ss);
+        if (dst < 0)
+            continue;
         const char *sp = (const char *)(is_v ? p.vn : p.kn) + src * es;
         char *dp = (char *)(is_v ? p.v : p.k) + dst * es;
         if (p.kn_vec)
@@ -395,28 +392,12 @@ __device__ __forceinline__ void ta_scatter_store(const TAParams &p, int b, int g
 }
 
 // Launchers implemented next to their kernels.
-hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream);
-hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream);
+// (`dev`: index of the current device, which the caller already knows)
+hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream, int dev);
+hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream, int dev);
 hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream);
-int ta_merge_rows(const TAParams &p);            // output rows one workgroup of the merge pass handles
-struct TAAppend {
-    const void *k_new, *v_new;         // [B, T, Hkv, D]
-    void *k, *v;                       // caches
-    const int32_t *page_table, *seq_lens;
-    int64_t kn_sb, kn_st, kn_sh, vn_sb, vn_st, vn_sh;
-    int64_t k_sp, k_sh, k_ss, v_sp, v_sh, v_ss, pt_sb, sl_s;
-    int32_t B, T, Hkv, D, ps, capacity, elem_bytes;
-    int32_t *status;
-};
 hipError_t ta_launch_append(const TAAppend &a, hipStream_t stream);
-struct TACompact {
-    void *k, *v;                       // caches
-    const int32_t *page_table, *seq_lens, *accepted, *n_accepted;
-    int32_t *seq_lens_out;             // or nullptr
-    int64_t k_sp, k_sh, k_ss, v_sp, v_sh, v_ss, pt_sb, sl_s, acc_sb, na_s, slo_s;
-    int32_t B, T, A, Hkv, D, ps, capacity, elem_bytes;
-    int32_t *status;
-};
-hipError_t ta_launch_compact(const TACompact &c, hipStream_t stream);
+hipError_t ta_launch_compact(const TACompact &c, hipStream_t stream, int dev);
+hipError_t ta_launch_stream_read(const void *buf, size_t bytes, void *sink, int num_cus, hipStream_t stream);
 hipError_t ta_launch_encode(const int32_t *parent, int64_t par_sb, int B, int T, unsigned long long *masks,
                             int32_t *status, hipStream_t stream);

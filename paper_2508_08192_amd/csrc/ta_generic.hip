@@ -67,17 +67,38 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
         bool poison = !ta_request_ok(p, L, S);
         const int tile0 = poison ? 0 : S / TA_TILE;               // absolute index of the list's first prefix tile
         if (poison && threadIdx.x == 0)
-            atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
+            ta_raise(p, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
+        if (!poison) {
+            int pos_lo, pos_hi;
+            ta_item_positions(p, j0, j1, n_b, tile0, L, S, pos_lo, pos_hi);
+            if (!ta_pages_ok(p, b, pos_lo, pos_hi, flag)) {
+                poison = true;
+                if (threadIdx.x == 0)
+                    ta_raise(p, TA_STATUS_BAD_PAGE);
+            }
+        }
         if (has_tree_tile && !poison && p.masks_in) {
-            if ((int)threadIdx.x < p.T)
-                masks[threadIdx.x] = ta_given_mask(p, b, threadIdx.x);
+            if (threadIdx.x == 0)
+                *flag = 0;
             __syncthreads();
+            if ((int)threadIdx.x < p.T) {
+                const unsigned long long m = ta_given_mask(p, b, threadIdx.x);
+                masks[threadIdx.x] = m;
+                if (!ta_given_mask_ok(m, threadIdx.x))
+                    atomicOr(flag, 1);
+            }
+            __syncthreads();
+            if (*flag != 0) {
+                poison = true;
+                if (threadIdx.x == 0)
+                    ta_raise(p, TA_STATUS_BAD_PARENT);
+            }
         } else if (has_tree_tile && !poison) {
             if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag, par_s)) {
                 poison = true;
                 if (threadIdx.x == 0)
-                    atomicOr(p.status, TA_STATUS_BAD_PARENT);
+                    ta_raise(p, TA_STATUS_BAD_PARENT);
             }
         }
         for (int r0 = 0; r0 < rows_here; r0 += GEN_WAVES * RB) {
@@ -146,7 +167,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
 #pragma unroll
                         for (int c = 0; c < DCH; ++c) {
                             const int d = lane + c * TA_WAVE;
-                            const bool ld = exists && d < p.D;
+                            const bool ld = exists && d < p.D && koff >= 0 && voff >= 0;
                             kvv[u][c] = ld ? load_elem<BF16>(kb, koff + d) : 0.f;
                             vvv[u][c] = ld ? load_elem<BF16>(vb, voff + d) : 0.f;
                         }
@@ -260,11 +281,10 @@ static hipError_t launch_generic_instance(const TAParams &p, hipStream_t stream,
     return hipGetLastError();
 }
 
-hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream)
+hipError_t ta_launch_generic(const TAParams &p, hipStream_t stream, int dev)
 {
     static bool attr_set[64][2][3] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    if (dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
     const int bf = p.is_bf16 ? 1 : 0;
     if (p.D <= TA_WAVE)
@@ -396,7 +416,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
 
 // The same merge for head_dim 128 and 16-byte aligned outputs: half a wave per output row, so that a lane holds four
 // neighbouring columns (one 16-byte load per partial and lane) and a workgroup of four waves merges eight rows.
-#define MG_ROWS 8
+#define MG_ROWS TA_MERGE128_ROWS
 
 __device__ __forceinline__ float ta_half_max(float x)          // over the 32 lanes of this lane's half-wave
 {
@@ -659,41 +679,18 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
         p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + (int64_t)node * p.lse_st] = lse2 * LN2;
 }
 
-// Partials per list the schedule produces on average: the KV pass's workgroups spread over the lists, plus the one
-// boundary each list shares with its neighbour.
-static int merge_parts_estimate(const TAParams &p)
-{
-    const int lists = p.B * p.Hkv > 0 ? p.B * p.Hkv : 1;
-    return (p.n_wg + lists - 1) / lists + 1;
-}
-
-// The row-per-workgroup merge is taken from 13 partials per list on, as long as it stays a latency problem: with
-// more than 1024 output rows (four workgroups per CU) the eight-rows-per-workgroup kernel is the faster one again
-// (measured: 8 lists x 256 rows x 33 partials 9.3 against 11.2 us; 1 list x 64 rows x 256 partials 38 against 9 us).
-constexpr int MW_FROM_PARTS = 13, MW_MAX_ROWS = 1024;
-
-int ta_merge_rows(const TAParams &p)
-{
-    const bool aligned = ((uintptr_t)p.out % 16) == 0 && p.o_sb % 4 == 0 && p.o_st % 4 == 0 && p.o_sh % 4 == 0;
-    if (p.D == 128 && aligned) {
-        const bool wide = merge_parts_estimate(p) >= MW_FROM_PARTS && (int64_t)p.B * p.Hkv * p.rows <= MW_MAX_ROWS;
-        return wide ? 1 : MG_ROWS;
-    }
-    return TA_MERGE_ROWS;
-}
-
 hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream)
 {
     const size_t smem = 0;
-    const int rows_wg = ta_merge_rows(p);
+    const int rows_wg = ta_host_merge_rows(p);             // the plan chose the kernel (p.merge_kind)
     dim3 grid(p.B * p.Hkv, (p.rows + rows_wg - 1) / rows_wg);
     // (the instances with the write-back folded in also copy the tree tokens' K/V into the caches)
-    if (rows_wg == 1) {
+    if (p.merge_kind == TA_MERGE_D128_WIDE) {
         if (p.kn)
             hipLaunchKernelGGL(ta_merge128_wide_kernel<true>, grid, dim3(256), smem, stream, p);
         else
             hipLaunchKernelGGL(ta_merge128_wide_kernel<false>, grid, dim3(256), smem, stream, p);
-    } else if (rows_wg == MG_ROWS) {
+    } else if (p.merge_kind == TA_MERGE_D128) {
         if (p.kn)
             hipLaunchKernelGGL(ta_merge128_kernel<true>, grid, dim3(256), smem, stream, p);
         else
@@ -746,6 +743,11 @@ __global__ __launch_bounds__(256) void ta_append_kernel(TAAppend a)
     if (a.page_table) {
         page = a.page_table[(int64_t)b * a.pt_sb + pos / a.ps];
         slot = pos % a.ps;
+        if (page < 0 || page >= a.n_pages) {               // no such page in the cache: this token is not written
+            if (threadIdx.x == 0)
+                atomicOr(a.status, TA_STATUS_BAD_PAGE);
+            return;
+        }
     }
     for (int x = threadIdx.x; x < a.Hkv * a.D; x += blockDim.x) {
         const int g = x / a.D, d = x % a.D;
@@ -783,10 +785,18 @@ __global__ __launch_bounds__(256) void ta_compact_kernel(TACompact c)
             atomicOr(&bad, 1);
     }
     __syncthreads();
-    const bool path_ok = n_ok && bad == 0;
-    if (!len_ok || !path_ok) {
+    const bool path_ok = n_ok && (bad & 1) == 0;
+    // every page a row may come from or go to (positions L .. L+T-1) must be a page of the cache
+    if (len_ok && c.page_table && tid < c.T) {
+        const int id = c.page_table[(int64_t)b * c.pt_sb + (L + tid) / c.ps];
+        if (id < 0 || id >= c.n_pages)
+            atomicOr(&bad, 2);
+    }
+    __syncthreads();
+    const bool pages_ok = (bad & 2) == 0;
+    if (!len_ok || !path_ok || !pages_ok) {
         if (tid == 0) {
-            atomicOr(c.status, !len_ok ? TA_STATUS_BAD_SEQLEN : TA_STATUS_BAD_PATH);
+            atomicOr(c.status, !len_ok ? TA_STATUS_BAD_SEQLEN : !path_ok ? TA_STATUS_BAD_PATH : TA_STATUS_BAD_PAGE);
             if (c.seq_lens_out)
                 c.seq_lens_out[(int64_t)b * c.slo_s] = L;
         }
@@ -823,7 +833,7 @@ __global__ __launch_bounds__(256) void ta_compact_kernel(TACompact c)
         c.seq_lens_out[(int64_t)b * c.slo_s] = L + n;
 }
 
-hipError_t ta_launch_compact(const TACompact &c, hipStream_t stream)
+hipError_t ta_launch_compact(const TACompact &c, hipStream_t stream, int dev)
 {
     // staging: one phase holds at most CP_STAGE_BYTES; a single unit (A rows of D elements) never exceeds that
     const size_t unit_bytes = (size_t)c.A * c.D * c.elem_bytes;
@@ -831,8 +841,7 @@ hipError_t ta_launch_compact(const TACompact &c, hipStream_t stream)
         return hipErrorInvalidValue;
     const size_t smem = CP_STAGE_BYTES;                            // with the static part just above the 64 KB default
     static bool attr_set[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    if (dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
     if (!attr_set[dev]) {
         for (const void *fn : {(const void *)ta_compact_kernel<uint16_t>, (const void *)ta_compact_kernel<uint32_t>}) {
@@ -855,5 +864,39 @@ hipError_t ta_launch_append(const TAAppend &a, hipStream_t stream)
         hipLaunchKernelGGL(ta_append_kernel<uint16_t>, dim3(a.B, a.T), dim3(256), 0, stream, a);
     else
         hipLaunchKernelGGL(ta_append_kernel<uint32_t>, dim3(a.B, a.T), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+// Measurement aid: a plain streaming read.  Every workgroup walks its contiguous part of the buffer with four
+// 16-byte non-temporal loads per lane in flight, the access pattern of a KV scan without any arithmetic behind it.
+__global__ __launch_bounds__(512) void ta_stream_read_kernel(const uint4 *__restrict__ src, size_t n_vec, unsigned *sink)
+{
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const size_t per = (n_vec + gridDim.x - 1) / gridDim.x;
+    const size_t lo = (size_t)blockIdx.x * per, hi = lo + per < n_vec ? lo + per : n_vec;
+    unsigned acc = 0;
+    size_t i = lo + threadIdx.x;
+    for (; i + 3 * 512 < hi; i += 4 * 512) {
+        u32x4_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            v[u] = __builtin_nontemporal_load((const u32x4_t *)(src + i + u * 512));
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < hi; i += 512) {
+        const u32x4_t v = __builtin_nontemporal_load((const u32x4_t *)(src + i));
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x9e3779b9u)            // practically never: keeps the loads alive without a store per lane
+        *sink = acc;
+}
+
+hipError_t ta_launch_stream_read(const void *buf, size_t bytes, void *sink, int num_cus, hipStream_t stream)
+{
+    const int wgs = num_cus * 4;
+    hipLaunchKernelGGL(ta_stream_read_kernel, dim3(wgs), dim3(512), 0, stream, (const uint4 *)buf, bytes / 16,
+                       (unsigned *)sink);
     return hipGetLastError();
 }

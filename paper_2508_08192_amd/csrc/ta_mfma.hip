@@ -55,20 +55,22 @@ struct Unit {
 };
 
 // Loads one unit.  tbase already points at (KV head, 8-element chunk) of the cache; pos0 = logical
-// position of the unit's first token, n_valid = how many of its four tokens exist (the others are
-// staged as zeros, so stale cache contents -- NaN included -- never reach a product).  Page and slot
+// position of the unit's first token; of its four tokens those with index n_skip .. n_valid-1 exist for
+// this call (tokens before a window start and past the end are staged as zeros and never loaded, so stale
+// cache contents -- NaN included -- never reach a product and released pages are never touched).  Page and slot
 // strides fit 32 bits (checked on the host), which keeps the address arithmetic to a few instructions.
 __device__ __forceinline__ void load_unit(const TAParams &p, Unit &u, const uint16_t *tbase, uint32_t sp, uint32_t ss,
-                                          int b, int pos0, int n_valid, bool contiguous)
+                                          int b, int pos0, int n_valid, bool contiguous, int n_skip = 0)
 {
     const uint16_t *ptr[4];
-    if (n_valid > 0) {
+    if (n_valid > n_skip) {
         if (contiguous) {
             const uint16_t *p0 = tbase + (uint64_t)(uint32_t)b * sp + (uint64_t)(uint32_t)pos0 * ss;
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 ptr[k] = p0 + (uint32_t)k * ss;
         } else if (p.ps_shift >= 2 && (pos0 & 3) == 0) {
+            // (one page holds all four tokens, and at least one of them exists: the page id is a checked one)
             const uint32_t page = (uint32_t)p.page_table[(int64_t)b * p.pt_sb + (pos0 >> p.ps_shift)];
             const uint16_t *p0 = tbase + (uint64_t)page * sp + (uint32_t)(pos0 & (p.ps - 1)) * ss;
 #pragma unroll
@@ -77,7 +79,7 @@ __device__ __forceinline__ void load_unit(const TAParams &p, Unit &u, const uint
         } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int pos = pos0 + (k < n_valid ? k : 0);
+                const int pos = pos0 + (k < n_valid && k >= n_skip ? k : n_skip);
                 const uint32_t page = (uint32_t)p.page_table[(int64_t)b * p.pt_sb + (pos >> p.ps_shift)];
                 ptr[k] = tbase + (uint64_t)page * sp + (uint32_t)(pos & (p.ps - 1)) * ss;
             }
@@ -85,7 +87,7 @@ __device__ __forceinline__ void load_unit(const TAParams &p, Unit &u, const uint
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        if (k < n_valid)
+        if (k < n_valid && k >= n_skip)
             // keys and values are read once: the non-temporal hint keeps them from displacing the partial results
             u.r[k] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)ptr[k]));
         else
@@ -261,17 +263,38 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
         bool poison = !ta_request_ok(p, L, S);
         const int tile0 = poison ? 0 : S / TA_TILE;                // absolute index of the list's first prefix tile
         if (poison && tid == 0)
-            atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
+            ta_raise(p, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
+        if (!poison) {
+            int pos_lo, pos_hi;
+            ta_item_positions(p, j0, j1, n_b, tile0, L, S, pos_lo, pos_hi);
+            if (!ta_pages_ok(p, b, pos_lo, pos_hi, flag)) {
+                poison = true;
+                if (tid == 0)
+                    ta_raise(p, TA_STATUS_BAD_PAGE);
+            }
+        }
         if (has_tree_tile && !poison && p.masks_in) {
-            if ((int)threadIdx.x < p.T)
-                masks[threadIdx.x] = ta_given_mask(p, b, threadIdx.x);
+            if (tid == 0)
+                *flag = 0;
             __syncthreads();
+            if ((int)threadIdx.x < p.T) {
+                const unsigned long long m = ta_given_mask(p, b, threadIdx.x);
+                masks[threadIdx.x] = m;
+                if (!ta_given_mask_ok(m, threadIdx.x))
+                    atomicOr(flag, 1);
+            }
+            __syncthreads();
+            if (*flag != 0) {
+                poison = true;
+                if (tid == 0)
+                    ta_raise(p, TA_STATUS_BAD_PARENT);
+            }
         } else if (has_tree_tile && !poison) {
             if (!ta_encode_tree(p.parent + (int64_t)b * p.par_sb, p.T, masks, flag, par_s)) {
                 poison = true;
                 if (tid == 0)
-                    atomicOr(p.status, TA_STATUS_BAD_PARENT);
+                    ta_raise(p, TA_STATUS_BAD_PARENT);
             }
         }
 
@@ -343,6 +366,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                 const int uu = u & 255, quad = uu >> 4, chunk = uu & 15;
                 const int pos0 = tile_pos0 + quad * 4;
                 const int n_valid = max(0, min(4, limit - pos0));
+                const int n_skip = tree_tile ? 0 : max(0, min(4, S - pos0));      // tokens before the window start
                 if (tree_tile && p.kn) {
                     // write-back folded into the call: the tree tokens sit in the dense tensors of this step, which
                     // are addressed like a contiguous cache -- request stride for the page, token stride for the slot
@@ -354,10 +378,10 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                                   (uint32_t)p.vn_sb, (uint32_t)p.vn_st, b, pos0 - L, n_valid, true);
                 } else if (u < 256) {
                     load_unit(p, stage[s], (const uint16_t *)p.k + (int64_t)g * p.k_sh + chunk * 8, (uint32_t)p.k_sp,
-                              (uint32_t)p.k_ss, b, pos0, n_valid, !p.page_table);
+                              (uint32_t)p.k_ss, b, pos0, n_valid, !p.page_table, n_skip);
                 } else {
                     load_unit(p, stage[s], (const uint16_t *)p.v + (int64_t)g * p.v_sh + chunk * 8, (uint32_t)p.v_sp,
-                              (uint32_t)p.v_ss, b, pos0, n_valid, !p.page_table);
+                              (uint32_t)p.v_ss, b, pos0, n_valid, !p.page_table, n_skip);
                 }
             }
         };
@@ -545,23 +569,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
     int *starts = lens + p.B;                                             // [B] window starts
     const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
 
-#ifdef TA_TUNING
-    const unsigned long long tun_c0 = __builtin_readcyclecounter(), tun_r0 = __builtin_amdgcn_s_memrealtime();
-    unsigned long long tun_mark[8] = {};
-#define TUN_MARK(i) do { if (tun_mark[i] == 0) tun_mark[i] = __builtin_amdgcn_s_memrealtime() - tun_r0; } while (0)
-    // time per phase, summed over the workgroup's items: 0 schedule, 1 item set-up, 2 first loads to S(0),
-    // 3 generic steps, 4 steady-state loop, 5 drain and partial result; 6 items, 7 generic steps (counts)
-    unsigned long long tun_acc[16] = {}, tun_last = tun_r0;
-#define TUN_ACC(k) do { const unsigned long long now_ = __builtin_amdgcn_s_memrealtime(); tun_acc[k] += now_ - tun_last; tun_last = now_; } while (0)
-#define TUN_CNT(k) do { tun_acc[k] += 1; } while (0)
-#else
-#define TUN_MARK(i) do { } while (0)
-#define TUN_ACC(k) do { } while (0)
-#define TUN_CNT(k) do { } while (0)
-#endif
+    if (threadIdx.x == 0)
+        flag[1] = 0;                   // set by an item that meets a bad page id or a bad given mask; see `bad` below
     ta_build_schedule(p, cum, lens, starts);
-    TUN_MARK(0);
-    TUN_ACC(0);
     const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
     const int share = ta_share(p, total);
     const int w = blockIdx.x, rg = blockIdx.y;
@@ -641,9 +651,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         bool poison = !ta_request_ok(p, L, S);
         const int tile0 = poison ? 0 : S / TA_TILE;                // absolute index of the list's first prefix tile
         if (poison && tid == 0)
-            atomicOr(p.status, TA_STATUS_BAD_SEQLEN);
+            ta_raise(p, TA_STATUS_BAD_SEQLEN);
         const bool has_tree_tile = (j1 == n_b);
-        TUN_ACC(8);
         // tile ti of this item: first logical position and number of tokens it holds
         auto tile_pos0 = [&](int ti) { return (j0 + ti == n_b - 1) ? L : (tile0 + j0 + ti) * TA_TILE; };
         auto tile_count = [&](int ti) {
@@ -676,7 +685,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             continue;
         }
 
-        TUN_ACC(9);
         if (active) {
             // Q of this lane's row goes straight into its fixed registers; it is first read after the wait for the
             // first tile, which these loads precede.  Rows past the group's end read the group's first row (their
@@ -708,7 +716,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         };
         int span_first_page = 0;
         // Cache loads of tile ti into K slot ks and V slot vs: four 16-byte loads per lane.  Rows past the tile's
-        // end re-read its first token (their probabilities are exactly zero).
+        // end, and rows before a window start, re-read its first attended token (their probabilities are exactly zero).
         auto issue_tile = [&](int ti, int ks, int vs) {
             const uint32_t kdst = lds0 + ks * MF_TILE_BYTES + wave * 2048;
             const uint32_t vdst = lds0 + SP_V_OFF + vs * MF_TILE_BYTES + wave * 2048;
@@ -731,8 +739,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 const int x = fresh_tid();
                 const int drow = (x >> 6) * 8 + ((x & 63) >> 4), dslot = x & 15;
                 const int tv0 = 16 * (x >> 7) + 4 * ((x >> 6) & 1) + ((x & 63) >> 4);
-                const int pk[2] = {pos0 + (drow < cnt ? drow : 0), pos0 + (drow + 4 < cnt ? drow + 4 : 0)};
-                const int pv[2] = {pos0 + (tv0 < cnt ? tv0 : 0), pos0 + (tv0 + 8 < cnt ? tv0 + 8 : 0)};
+                // rows past the tile's end and rows before the window start read the tile's first attended token
+                const int lo = max(0, S - pos0);
+                auto row_pos = [&](int r) { return pos0 + (r < cnt && r >= lo ? r : lo); };
+                const int pk[2] = {row_pos(drow), row_pos(drow + 4)};
+                const int pv[2] = {row_pos(tv0), row_pos(tv0 + 8)};
                 // With the write-back folded into the call the tree tokens come from the dense tensors of this step:
                 // addressed like a contiguous cache, request stride for the page, token stride for the slot.
                 bool from_new = false;
@@ -798,10 +809,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 vm_wait<0>();
         };
 
-        TUN_MARK(1);
-        TUN_ACC(1);
-        TUN_CNT(6);
-        bool bad_tree = false;
+        int bad = 0;                                       // TA_STATUS_* bits this item has to report
         float m_run = -INFINITY, l_run = 0.f, l2_run = 0.f;   // l2: sum of the bf16-rounded probabilities
 
         for (int s0 = 0; s0 < n; s0 += span_tiles) {
@@ -811,16 +819,27 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             {
                 const int x = fresh_tid();
                 if (paged) {
-                    span_first_page = tile_pos0(s0) >> p.ps_shift;
+                    // (positions before the window start are never read: their pages may be gone already)
+                    span_first_page = max(tile_pos0(s0), S) >> p.ps_shift;
                     const int last_page = (tile_pos0(s0 + ns - 1) + tile_count(s0 + ns - 1) - 1) >> p.ps_shift;
-                    for (int k = x; k <= last_page - span_first_page; k += 512)
-                        pcache[k] = p.page_table[(int64_t)b * p.pt_sb + span_first_page + k];
+                    for (int k = x; k <= last_page - span_first_page; k += 512) {
+                        int id = p.page_table[(int64_t)b * p.pt_sb + span_first_page + k];
+                        if (!ta_page_ok(p, id)) {              // must never become an address
+                            atomicOr(&flag[1], TA_STATUS_BAD_PAGE);
+                            id = 0;
+                        }
+                        pcache[k] = id;
+                    }
                 } else if (x == 0) {
                     pcache[0] = b;                             // the steady-state loop sees one page: the request's cache
                 }
                 if (s0 == 0 && has_tree_tile && p.masks_in) {
-                    if (x < p.T)
-                        masks[x] = ta_given_mask(p, b, x);         // encoded before the call
+                    if (x < p.T) {
+                        const unsigned long long gm = ta_given_mask(p, b, x);      // encoded before the call
+                        masks[x] = gm;
+                        if (!ta_given_mask_ok(gm, x))
+                            atomicOr(&flag[1], TA_STATUS_BAD_PARENT);
+                    }
                 } else if (s0 == 0 && has_tree_tile) {
                     if (x == 0)
                         *flag = 0;
@@ -829,8 +848,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 }
             }
             __syncthreads();
-            TUN_ACC(10);
-            TUN_MARK(2);
+            bad = __builtin_amdgcn_readfirstlane(flag[1]);
+            if (bad != 0) {
+                vm_wait<0>();                                  // Q is still on its way into its registers
+                break;
+            }
             // ring positions: next slots to load into, K slot of tile i+1, V slots of tiles i and i-1
             int ik = 0, iv = 0, issued = 0;
             for (; issued < min(ns, 3); ++issued) {
@@ -838,22 +860,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 ik = ik == SP_RK - 1 ? 0 : ik + 1;
                 iv = iv == SP_RV - 1 ? 0 : iv + 1;
             }
-            TUN_MARK(3);
-            TUN_ACC(11);
             if (s0 == 0) {
                 // while the first tiles are on their way: O = 0 and the ancestor masks
                 sp_zero_o();
                 if (has_tree_tile && !p.masks_in && !ta_encode_tree_lds(fresh_tid(), p.T, masks, flag, par_s)) {
-                    bad_tree = true;
+                    bad = TA_STATUS_BAD_PARENT;
                     vm_wait<0>();                              // nothing may still land in the rings after this item
                     break;
                 }
             }
-            TUN_ACC(12);
             wait_loads(issued - 1);                            // tile 0 and Q have landed
             lds_barrier();
-            TUN_ACC(13);
-            TUN_MARK(4);
             if (active)
                 sp_s_first(0u);
             if (active && tile_ragged(s0)) {
@@ -867,7 +884,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             int kn = 1, vc = 0, vp = SP_RV - 1;                // K slot of tile i+1, V slot of tile i, of tile i-1
             auto step = [&](auto tag, int i) {
                 constexpr bool A = decltype(tag)::value;       // S^T(i) sits in buffer A
-                if (i + 3 < ns && !TA_OFF(4)) {
+                if (i + 3 < ns) {
                     issue_tile(s0 + i + 3, ik, iv);
                     ik = ik == SP_RK - 1 ? 0 : ik + 1;
                     iv = iv == SP_RV - 1 ? 0 : iv + 1;
@@ -875,7 +892,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 const bool has_next = i + 1 < ns;
                 const uint32_t ska = kn * MF_TILE_BYTES, sva = vp * MF_TILE_BYTES;
                 float alpha = 1.f;
-                if (TA_OFF(1) || !active) {
+                if (!active) {
                 } else if constexpr (A) {
                     if (i == 0) {
                         if (has_next)
@@ -893,8 +910,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     else
                         sp_last_B(sva, m_run, l_run, l2_run, alpha, c);
                 }
-                if (!TA_OFF(8))
-                    relayout_v(vc);
+                relayout_v(vc);
                 if (__any(alpha != 1.0f))
                     sp_scale_o(alpha);             // O still holds sums relative to the old reference
                 if (active && has_next && tile_ragged(s0 + i + 1)) {
@@ -904,7 +920,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     else
                         sp_mask_A((uint32_t)vm, (uint32_t)(vm >> 32));
                 }
-                if (i + 2 < ns && !TA_OFF(64))
+                if (i + 2 < ns)
                     wait_loads(i + 3 < ns ? 1 : 0);            // this wave's part of tile i+2 has landed
                 lds_barrier();
                 kn = kn == SP_RK - 1 ? 0 : kn + 1;
@@ -915,14 +931,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             // block itself issues the loads of tile i+3 and re-lays V(i) out (sp_fast_*); no masks, no choices.
             // Steady state: every tile involved is a full prefix tile inside one page (or the contiguous cache), so
             // whole pairs of tiles run inside sp_fast_loop, which does its own loads, re-layout and bookkeeping.
-            TUN_MARK(5);
-            TUN_ACC(2);
             const int n_plain = max(0, min(ns, L / TA_TILE - (tile0 + j0 + s0)));     // leading full prefix tiles of the span
             int i = 0;
 #pragma unroll 1
             while (i < ns) {
-                if (!(i & 1) && i >= 2 && fast_geom && i + 4 < n_plain && !TA_OFF(256)) {
-                    TUN_ACC(3);
+                if (!(i & 1) && i >= 2 && fast_geom && i + 4 < n_plain) {
                     const uint32_t pairs = (uint32_t)((n_plain - 5 - i) / 2 + 1);
                     uint32_t cnt = pairs, pos = (uint32_t)((tile0 + j0 + s0 + i + 3) * TA_TILE);
                     uint32_t ik_o = ik * MF_TILE_BYTES, iv_o = iv * MF_TILE_BYTES, kn_o = kn * MF_TILE_BYTES;
@@ -950,9 +963,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     vp = vp_o / MF_TILE_BYTES;
                     vc = vc_o / MF_TILE_BYTES;
                     i += 2 * (int)pairs;
-                    TUN_ACC(4);
                 } else {
-                    TUN_CNT(7);
                     if (i & 1)
                         step(SpTag<false>{}, i);
                     else
@@ -960,17 +971,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     ++i;
                 }
             }
-            TUN_MARK(6);
-            TUN_ACC(3);
             if (active)
                 sp_pv(vp * MF_TILE_BYTES);
             lds_barrier();                                     // the rings are free for the next span or item
         }
-        if (bad_tree) {
+        if (bad != 0) {
             if (tid == 0)
-                atomicOr(p.status, TA_STATUS_BAD_PARENT);
+                ta_raise(p, bad);
             write_poison();
-            __syncthreads();
+            __syncthreads();                               // every thread has read flag[1] ...
+            if (tid == 0)
+                flag[1] = 0;
+            __syncthreads();                               // ... and the next item starts from a clear one
             t = seg_start + (j1 == n_b ? n_u : j1);
             continue;
         }
@@ -981,7 +993,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             // 32 x 128 block into row-major order in its 16 KB of the (now idle) K/V rings -- 16-byte chunk j of
             // row r sits at chunk j ^ r, which keeps both directions free of bank conflicts -- and then stores
             // whole 512-byte rows.
-            TUN_MARK(7);
             const int x = fresh_tid();
             const int ln = x & 63, wv = x >> 6;
             const int r32_ = ln & 31, h = ln >> 5;
@@ -1006,39 +1017,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             }
         }
         lds_barrier();                 // the staging area is ring space again; the stores themselves may still fly
-        TUN_ACC(5);
         t = seg_start + (j1 == n_b ? n_u : j1);
     }
-#ifdef TA_TUNING
-    if (blockIdx.y == 0 && threadIdx.x == 0 && blockIdx.x < 1024) {
-        unsigned long long *dbg = (unsigned long long *)(p.status + 16) + 4 * blockIdx.x;
-        unsigned xcc;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        dbg[0] = tun_r0;
-        dbg[1] = __builtin_amdgcn_s_memrealtime();
-        dbg[2] = __builtin_readcyclecounter() - tun_c0;
-        dbg[3] = xcc;
-        if (blockIdx.x < 240) {                     // 8 + 4112 + 16 * 240 words of 8 bytes fit TA_STATUS_BYTES
-            unsigned long long *d3 = (unsigned long long *)(p.status + 16) + 4096 + 16 + 16 * blockIdx.x;
-            for (int i = 0; i < 16; ++i) d3[i] = tun_acc[i];
-        }
-        if (blockIdx.x == 0) {
-            unsigned long long *d2 = (unsigned long long *)(p.status + 16) + 4 * 1024;
-            for (int i = 0; i < 8; ++i) d2[i] = tun_mark[i];
-            d2[8] = __builtin_amdgcn_s_memrealtime() - tun_r0;
-        }
-    }
-#endif
 }
 
 template <int NCW, int RB, int NT>
-static hipError_t launch_variant(const TAParams &p, hipStream_t stream)
+static hipError_t launch_variant(const TAParams &p, hipStream_t stream, int dev)
 {
     const size_t smem = MF_STAGES * 2 * MF_TILE_BYTES + sizeof(unsigned long long) * TA_MAX_TREE + 16 +
                         sizeof(int) * TA_MAX_TREE + sizeof(int) * (p.B + 2);
     static bool attr_set[64] = {};      // per device and variant; setting it twice is harmless
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    if (dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
     if (!attr_set[dev]) {
         hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_kv_kernel<NCW, RB, NT>,
@@ -1051,7 +1040,7 @@ static hipError_t launch_variant(const TAParams &p, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
+hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream, int dev)
 {
     if (p.rows_grp != 32 && p.rows_grp != 64 && p.rows_grp != 128 && p.rows_grp != 256)
         return hipErrorInvalidValue;
@@ -1059,10 +1048,9 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream)
     const size_t smem = SP_AUX_OFF + sizeof(unsigned long long) * TA_MAX_TREE + 16 + sizeof(int) * TA_MAX_TREE +
                         sizeof(int) * PP_PAGES + sizeof(int) * (3 * p.B + 2);
     if (p.basic || smem > 160 * 1024 - 512)
-        return launch_variant<8, 1, 512>(p, stream);       // register-staged kernel: very large batches, or on request
+        return launch_variant<8, 1, 512>(p, stream, dev);  // register-staged kernel: very large batches, or on request
     static bool attr_set[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    if (dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
     if (!attr_set[dev]) {
         for (const void *fn : {(const void *)ta_mfma_sp_kernel<false>, (const void *)ta_mfma_sp_kernel<true>}) {

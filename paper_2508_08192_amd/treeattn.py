@@ -9,11 +9,14 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtreeattn.so")
+# TREEATTN_LIB names another build of the same library (the sanitizer build of the host code, which has no kernels
+# behind it, is loaded that way by the host tests)
+LIB_PATH = os.environ.get("TREEATTN_LIB") or os.path.join(_HERE, "libtreeattn.so")
 
 TA_F32, TA_BF16, TA_I32, TA_U64 = 0, 1, 2, 3
 TA_KERNEL_AUTO, TA_KERNEL_GENERIC, TA_KERNEL_MFMA, TA_KERNEL_MFMA_BASIC = 0, 1, 2, 3
-TA_STATUS_BAD_PARENT, TA_STATUS_BAD_SEQLEN, TA_STATUS_BAD_PATH = 1, 2, 4
+TA_STATUS_BAD_PARENT, TA_STATUS_BAD_SEQLEN, TA_STATUS_BAD_PATH, TA_STATUS_BAD_PAGE = 1, 2, 4, 8
+TA_MERGE_GENERAL, TA_MERGE_D128, TA_MERGE_D128_WIDE = 0, 1, 2
 
 TA_OK = 0
 TA_ERR_NULL, TA_ERR_DTYPE, TA_ERR_RANK, TA_ERR_SHAPE, TA_ERR_STRIDE, TA_ERR_HEADS = -1, -2, -3, -4, -5, -6
@@ -21,10 +24,9 @@ TA_ERR_HEAD_DIM, TA_ERR_TREE_SIZE, TA_ERR_PAGE_TABLE, TA_ERR_WORKSPACE, TA_ERR_H
 TA_ERR_BATCH, TA_ERR_OPTS = -12, -13
 
 EXPORTS = (
-    "tree_attn_fwd", "tree_attn_fwd_ex", "tree_attn_workspace_bytes", "tree_attn_reserve", "tree_attn_encode",
-    "tree_attn_append",
-    "tree_attn_compact",
-    "tree_attn_last_status", "tree_attn_plan", "tree_attn_strerror", "tree_attn_version",
+    "tree_attn_fwd", "tree_attn_fwd_ex", "tree_attn_workspace_bytes", "tree_attn_reserve", "tree_attn_release",
+    "tree_attn_encode", "tree_attn_append", "tree_attn_compact", "tree_attn_last_status", "tree_attn_plan",
+    "tree_attn_dispatch_row", "tree_attn_stream_read", "tree_attn_strerror", "tree_attn_version",
 )
 
 
@@ -54,6 +56,7 @@ class ta_opts(ctypes.Structure):
         ("kv_start", ctypes.c_void_p),
         ("k_new", ctypes.POINTER(ta_tensor)),
         ("v_new", ctypes.POINTER(ta_tensor)),
+        ("status", ctypes.c_void_p),
     ]
 
 
@@ -100,6 +103,12 @@ def load_library():
         lib.tree_attn_workspace_bytes.argtypes = [ctypes.c_int32] * 7
         lib.tree_attn_reserve.restype = ctypes.c_int
         lib.tree_attn_reserve.argtypes = [ctypes.c_size_t]
+        lib.tree_attn_release.restype = ctypes.c_int
+        lib.tree_attn_release.argtypes = []
+        lib.tree_attn_dispatch_row.restype = ctypes.c_int
+        lib.tree_attn_dispatch_row.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)]
+        lib.tree_attn_stream_read.restype = ctypes.c_int
+        lib.tree_attn_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         lib.tree_attn_encode.restype = ctypes.c_int
         lib.tree_attn_encode.argtypes = [T, T, ctypes.c_void_p]
         lib.tree_attn_append.restype = ctypes.c_int
@@ -160,7 +169,7 @@ def _stream_ptr(stream):
 
 
 def _opts(scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None, item_cost=0, tree_masks=None,
-          kv_start=None, q_node_offset=0, k_new=None, v_new=None):
+          kv_start=None, q_node_offset=0, k_new=None, v_new=None, status=None):
     o = ta_opts()
     o._keep = [_desc(k_new), _desc(v_new)]             # the descriptors must outlive the call
     if o._keep[0] is not None:
@@ -183,6 +192,8 @@ def _opts(scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, event
     if kv_start is not None:                           # int32 [B], contiguous
         o.kv_start = kv_start.data_ptr()
     o.q_node_offset = int(q_node_offset)
+    if status is not None:                             # int32 [1] on the device: the call's own status word
+        o.status = status.ptr if isinstance(status, Desc) else status.data_ptr()
     return o
 
 
@@ -205,10 +216,11 @@ def tree_attn_fwd(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, l
 
 def tree_attn_fwd_ex(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse=None, stream=None,
                      scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None, check=True,
-                     item_cost=0, tree_masks=None, kv_start=None, q_node_offset=0, k_new=None, v_new=None):
+                     item_cost=0, tree_masks=None, kv_start=None, q_node_offset=0, k_new=None, v_new=None, status=None):
     """include/treeattn.h: tree_attn_fwd_ex.  `events`: up to three hipEvent_t handles (ctypes.c_void_p)."""
     ds = [_desc(x) for x in (q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse)]
-    o = _opts(scale, num_splits, kernel, workspace, events, item_cost, tree_masks, kv_start, q_node_offset, k_new, v_new)
+    o = _opts(scale, num_splits, kernel, workspace, events, item_cost, tree_masks, kv_start, q_node_offset, k_new, v_new,
+              status)
     rc = load_library().tree_attn_fwd_ex(*[_ref(d) for d in ds], _stream_ptr(stream) if stream != 0 else None,
                                          ctypes.byref(o))
     if check and rc != TA_OK:
@@ -224,6 +236,36 @@ def tree_attn_reserve(nbytes, check=True):
     rc = load_library().tree_attn_reserve(int(nbytes))
     if check and rc != TA_OK:
         raise TreeAttnError(rc, "tree_attn_reserve")
+    return rc
+
+
+def tree_attn_release(check=True):
+    """Frees the library-owned workspace buffers of the current device (synchronises it)."""
+    rc = load_library().tree_attn_release()
+    if check and rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_release")
+    return rc
+
+
+def tree_attn_dispatch_table():
+    """The library's dispatch table as a list of dicts (host-only)."""
+    keys = ("family", "rows_group_max", "lists_max", "wg_per_cu_x4", "min_share", "item_cost", "wide_from_parts",
+            "wide_max_rows")
+    rows, i = [], 0
+    while True:
+        row = (ctypes.c_int64 * 8)()
+        if load_library().tree_attn_dispatch_row(i, row) != TA_OK:
+            return rows
+        rows.append(dict(zip(keys, [int(x) for x in row])))
+        i += 1
+
+
+def tree_attn_stream_read(buf, sink, stream=None, check=True):
+    """include/treeattn.h: tree_attn_stream_read (measurement aid: one plain streaming read of `buf`)."""
+    rc = load_library().tree_attn_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(),
+                                              _stream_ptr(stream) if stream != 0 else None)
+    if check and rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_stream_read")
     return rc
 
 
@@ -266,16 +308,16 @@ def tree_attn_last_status(stream=None):
 
 
 def tree_attn_plan(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse=None, num_cus=256,
-                   scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, check=True, item_cost=0):
+                   scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, check=True, item_cost=0, status=None):
     """Host-only launch plan; returns a dict (or the negative status if check is False and it failed)."""
     ds = [_desc(x) for x in (q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse)]
-    o = _opts(scale, num_splits, kernel, None, None, item_cost)
-    plan = (ctypes.c_int64 * 8)()
+    o = _opts(scale, num_splits, kernel, None, None, item_cost, status=status)
+    plan = (ctypes.c_int64 * 16)()
     rc = load_library().tree_attn_plan(*[_ref(d) for d in ds], ctypes.byref(o), num_cus, plan)
     if rc != TA_OK:
         if check:
             raise TreeAttnError(rc, "tree_attn_plan")
         return rc
     keys = ("kernel", "kv_workgroups", "threads", "tile", "row_groups", "rows_per_group", "partial_slots",
-            "merge_workgroups")
+            "merge_workgroups", "min_share", "item_cost", "merge_kernel", "table_row", "workspace_bytes")
     return dict(zip(keys, [int(x) for x in plan]))

@@ -306,13 +306,14 @@ def make_config(idx, seed=None, length_div=1):
 # short chain above; N8 for the 70B model, N12 for Scout; one GPU's tensor-parallel share of the heads).  The paper
 # does not print the topology of its pruned trees: these are plausible stand-ins of the same sizes.
 PRODUCTION_NAMES = ("p1_70b_share_n8", "p2_70b_share_chain3", "p3_scout_share_n12", "p4_8b_n8_bs128",
-                    "p5_scout_share_local", "p6_70b_share_n8_bs1", "p7_scout_share_n12_bs1_128k")
+                    "p5_scout_share_local", "p6_70b_share_n8_bs1", "p7_scout_share_n12_bs1_128k",
+                    "u32_uniform_16k_rows32", "u64_uniform_16k_rows64", "u128_uniform_16k_rows128")
 TREE_N8 = np.asarray([-1, 0, 0, 0, 1, 1, 2, 4], dtype=np.int32)                       # 8 nodes, 4 levels
 TREE_N12 = np.asarray([-1, 0, 0, 0, 1, 1, 1, 2, 2, 4, 4, 9], dtype=np.int32)          # 12 nodes, 5 levels
 
 
 def make_production(idx, seed=None, length_div=1):
-    """Memory-bound shapes with few query rows per KV head (idx 0..6); synthetic like the five configurations.
+    """Memory-bound shapes with few query rows per KV head (idx 0..9); synthetic like the five configurations.
     length_div > 1 divides every prefix length, for tests that compare all outputs with the oracle."""
     seed = 2000 + idx if seed is None else seed
     rng = np.random.default_rng(seed)
@@ -342,4 +343,9 @@ def make_production(idx, seed=None, length_div=1):
     if idx == 6:        # batch size one at a long context: the Scout share, 12-node tree, 128k tokens
         return make_workload(name, B=1, T=12, Hq=5, Hkv=1, D=128, seq_lens=131072 // length_div, trees=TREE_N12,
                              page_size=128, seed=seed)
+    if idx in (7, 8, 9):  # uniform long prefixes, the purely memory-bound regime: 8B-shaped heads, batch 16, 16k context
+        T = (8, 16, 32)[idx - 7]                       # 8-, 16- and 32-node trees on 4 query heads per KV head: 32/64/128 rows
+        tree = TREE_N8 if T == 8 else bfs_tree(T, [3, 2], 5)
+        return make_workload(name, B=16, T=T, Hq=32, Hkv=8, D=128, seq_lens=16384 // length_div, trees=tree,
+                             page_size=64, seed=seed)
     raise IndexError(idx)

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     lib = ta.load_library()
     for name in declared:
         assert hasattr(lib, name), name
-    assert ta.tree_attn_version() == 100
+    assert ta.tree_attn_version() == 200
     assert ta.tree_attn_strerror(0) == "ok" and "NULL" in ta.tree_attn_strerror(ta.TA_ERR_NULL)
 
 
@@ -214,3 +214,119 @@ def test_folded_write_back_arguments_are_checked_before_any_launch():
     # rows that are not 16-byte aligned: the matrix-core kernel refuses, the automatic choice falls back
     odd = Desc((2, 8, 2, 128), ta.TA_BF16, stride=(8 * 2 * 132, 2 * 132, 132, 1))
     assert rc(k_new=odd, v_new=odd, kernel=ta.TA_KERNEL_MFMA) == ta.TA_ERR_OPTS
+
+
+def test_dispatch_table_rows_and_the_plans_they_give():
+    """Every row of the dispatch table is reachable, and a plan carries exactly its row's figures
+    (section 3.4, "Attention kernel": the split is chosen by batch size, tree size and GPU)."""
+    table = ta.tree_attn_dispatch_table()
+    assert len(table) >= 7
+    fam = {ta.TA_KERNEL_MFMA: ta.TA_KERNEL_MFMA, ta.TA_KERNEL_MFMA_BASIC: ta.TA_KERNEL_MFMA_BASIC,
+           ta.TA_KERNEL_GENERIC: ta.TA_KERNEL_GENERIC}
+    for f in fam:                                   # every family ends in a catch-all row
+        last = [r for r in table if r["family"] == f][-1]
+        assert last["rows_group_max"] >= 256 and last["lists_max"] == 2 ** 31 - 1
+    seen = set()
+    cus = 256
+    for B, T, Hq, Hkv in [(1, 64, 32, 8), (1, 8, 8, 1), (4, 64, 32, 8), (32, 16, 32, 8), (64, 32, 8, 1), (128, 8, 32, 8),
+                          (64, 4, 8, 1), (16, 12, 5, 1), (1, 12, 5, 1), (2, 64, 64, 8), (1, 3, 8, 1), (500, 4, 8, 2),
+                          (16, 32, 32, 8), (2, 20, 10, 2)]:
+        for kern in (ta.TA_KERNEL_AUTO, ta.TA_KERNEL_MFMA_BASIC, ta.TA_KERNEL_GENERIC):
+            a = _good(B=B, T=T, Hq=Hq, Hkv=Hkv, max_pages=129, pages=B * 129)
+            p = _plan(a, kernel=kern, num_cus=cus)
+            row = table[p["table_row"]]
+            seen.add(p["table_row"])
+            want_family = ta.TA_KERNEL_MFMA if kern == ta.TA_KERNEL_AUTO else kern
+            assert row["family"] == want_family
+            assert p["rows_per_group"] <= row["rows_group_max"] and B * Hkv <= row["lists_max"]
+            # the first matching row is the one taken
+            for r in table[:p["table_row"]]:
+                assert not (r["family"] == want_family and p["rows_per_group"] <= r["rows_group_max"]
+                            and B * Hkv <= r["lists_max"])
+            assert p["min_share"] == row["min_share"] and p["item_cost"] == row["item_cost"]
+            per_rg = cus * row["wg_per_cu_x4"] // 4
+            if want_family != ta.TA_KERNEL_GENERIC:
+                per_rg = max(1, per_rg // p["row_groups"])
+            tiles_cap = B * Hkv * ((129 * 64 - T + 63) // 64 + 1)
+            assert p["kv_workgroups"] == min(per_rg, tiles_cap)
+            parts = -(-p["kv_workgroups"] // (B * Hkv)) + 1
+            wide = row["wide_from_parts"] > 0 and parts >= row["wide_from_parts"] and \
+                B * Hkv * T * (Hq // Hkv) <= row["wide_max_rows"]
+            assert p["merge_kernel"] == (ta.TA_MERGE_D128_WIDE if wide else ta.TA_MERGE_D128)
+            assert p["workspace_bytes"] <= ta.tree_attn_workspace_bytes(B, T, Hq, Hkv, 128, ta.TA_BF16, cus)
+            # options override the row
+            p2 = _plan(a, kernel=kern, num_cus=cus, num_splits=5, item_cost=3)
+            assert p2["kv_workgroups"] == 5 and p2["min_share"] == 1 and p2["item_cost"] == 3
+    assert seen == set(range(len(table))), "rows never taken: %r" % (set(range(len(table))) - seen)
+    assert _plan(_good(D=64, dtype=ta.TA_F32))["merge_kernel"] == ta.TA_MERGE_GENERAL
+
+
+def test_status_word_option_is_checked():
+    a = _good()
+    assert _plan(a, status=Desc((1,), ta.TA_I32, ptr=0x2002), check=False) == ta.TA_ERR_OPTS     # not 4-byte aligned
+    assert _plan(a, status=Desc((1,), ta.TA_I32, ptr=0x2004))["kernel"] == ta.TA_KERNEL_MFMA
+
+
+def test_random_descriptors_never_break_the_host_code():
+    """Random ranks, shapes, strides and options through the planning and validation code: any answer is fine as
+    long as it is a status code (the sanitizer build of the same code runs this test too)."""
+    import numpy as np
+    rng = np.random.default_rng(99)
+    dtypes = [ta.TA_F32, ta.TA_BF16, ta.TA_I32, ta.TA_U64, 7]
+    seen = set()
+    for case in range(3000):
+        B, T = int(rng.integers(0, 6)), int(rng.integers(0, 70))
+        Hkv = int(rng.integers(1, 4))
+        Hq = Hkv * int(rng.integers(1, 5)) + int(rng.random() < 0.1)
+        D = int(rng.choice([0, 1, 64, 128, 128, 128, 256, 300]))
+        ps = int(rng.choice([1, 3, 16, 64, 128]))
+        dt = int(rng.choice([ta.TA_BF16, ta.TA_BF16, ta.TA_F32]))
+        a = _good(B=B, T=T, Hq=Hq, Hkv=Hkv, D=D, ps=ps, max_pages=int(rng.integers(0, 40)), dtype=dt,
+                  pages=int(rng.integers(0, 50)))
+        if rng.random() < 0.5:                       # damage one descriptor
+            key = str(rng.choice(sorted(a)))
+            d = a[key]
+            kind = int(rng.integers(0, 5))
+            if kind == 0:
+                a[key] = None
+            elif kind == 1:
+                a[key] = Desc(d.shape, int(rng.choice(dtypes)), d.stride, d.ptr)
+            elif kind == 2:
+                a[key] = Desc(d.shape[:-1] if rng.random() < 0.5 else d.shape + (2,), d.dtype)
+            elif kind == 3:
+                a[key] = Desc(d.shape, d.dtype, tuple(int(x) * int(rng.choice([-1, 1, 2, 3])) for x in d.stride), d.ptr)
+            else:
+                a[key] = Desc(tuple(int(rng.integers(0, 2 ** 33)) for _ in d.shape), d.dtype, d.stride,
+                              int(rng.choice([0, 0x1000, 0x1002])))
+        kw = dict(kernel=int(rng.integers(-1, 5)), num_splits=int(rng.integers(-1, 2000)),
+                  item_cost=int(rng.integers(-1, 5000)), num_cus=int(rng.choice([0, 1, 256, 304])), check=False)
+        r = _plan(a, **kw)
+        if isinstance(r, dict):
+            assert r["kv_workgroups"] >= 1 and r["partial_slots"] >= r["kv_workgroups"] and r["workspace_bytes"] > 0
+            seen.add(0)
+        else:
+            assert -13 <= r < 0
+            seen.add(r)
+        n = ta.tree_attn_workspace_bytes(B, T, Hq, Hkv, D, dt, 256)
+        assert n >= 0
+    assert 0 in seen and len(seen) >= 8
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers():
+    """The same host tests against a g++ build of the host logic with -fsanitize=address,undefined (its launching
+    entry points stop where the real library would touch a device).  A finding aborts the child process."""
+    import subprocess
+    import sys
+    from paper_2508_08192_amd.build import build_host_checked
+    lib, runtime = build_host_checked()
+    assert os.path.exists(lib) and os.path.exists(runtime), (lib, runtime)
+    env = dict(os.environ)
+    env["TREEATTN_LIB"] = lib
+    env["LD_PRELOAD"] = (runtime + " " + env.get("LD_PRELOAD", "")).strip()
+    env["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=1"
+    env["UBSAN_OPTIONS"] = "halt_on_error=1:print_stacktrace=1"
+    proc = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-q", "-x", "-p", "no:cacheprovider",
+                           "-k", "not sanitizers and not generated_asm"], cwd=ROOT, env=env, stdout=subprocess.PIPE,
+                          stderr=subprocess.STDOUT, text=True, timeout=600)
+    assert proc.returncode == 0, proc.stdout[-4000:]
+    assert "passed" in proc.stdout
