@@ -45,7 +45,7 @@
  *     be replayed at any time.  Under stream capture nothing is allocated: a call
  *     that would need a larger buffer than the device holds returns
  *     TA_ERR_WORKSPACE (call tree_attn_reserve before capturing, pass a workspace
- *     through ta_opts).
+ *     through ta_opts, or use tree_attn_fwd_static).
  */
 #ifndef TREEATTN_H
 #define TREEATTN_H
@@ -274,6 +274,22 @@ int tree_attn_plan(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor
  * row[7] = as long as the batch has at most this many output rows.  The first row that matches a call is taken.
  */
 int tree_attn_dispatch_row(int32_t index, int64_t row[8]);
+
+/*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): tree_attn_fwd_ex with its split-KV partial results in a fixed scratch area inside the
+ * library image (TA_STATIC_SCRATCH_BYTES of device memory that every GPU the library runs on holds until the
+ * process ends) instead of an allocated workspace.  Calls no hipMalloc / hipFree and no allocating library routine.
+ * The call needs tree_attn_plan's plan[12] bytes of scratch; beyond TA_STATIC_SCRATCH_BYTES it returns
+ * TA_ERR_WORKSPACE and launches nothing.  ta_opts.workspace must be NULL.  Every call on a device shares that
+ * device's one scratch area: calls that overlap in time on one device (different streams without ordering) race,
+ * exactly as with the library-owned workspace.  Nothing in the area has to survive from call to call.
+ * Results are bit for bit those of tree_attn_fwd_ex.
+ */
+#define TA_STATIC_SCRATCH_BYTES (48u << 20)
+int tree_attn_fwd_static(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
+                         const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
+                         ta_tensor *out, ta_tensor *lse, void *stream, const ta_opts *opts);
 
 /*
  * Measurement aid (no part of the method): a plain streaming read of `bytes` bytes of device memory at `buf`

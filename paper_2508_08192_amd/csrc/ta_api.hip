@@ -12,11 +12,16 @@ namespace {
 // own address), so that no entry point has to allocate it.
 __device__ __align__(256) int32_t ta_status_words[TA_STATUS_BYTES / 4];
 
+// Scratch of tree_attn_fwd_static: the split-KV partial results of a call, for callers that cannot allocate.  In host
+// code this name is only a handle for hipGetSymbolAddress; the device address of each GPU's copy is kept per device.
+__device__ __align__(256) unsigned char scratch[TA_STATIC_SCRATCH_BYTES];
+
 struct DeviceState {
     std::once_flag once;
     int init_rc = TA_ERR_HIP;
     int num_cus = 0;
     int32_t *status = nullptr;
+    void *scratch_ptr = nullptr;       // this device's copy of `scratch`
     // library-owned workspace: grown under ws_mu; buffers it outgrew stay allocated (launches and captured graphs
     // may still hold their addresses) until tree_attn_release
     std::mutex ws_mu;
@@ -45,6 +50,10 @@ int device_state(DeviceState **out, int *dev_out = nullptr)
         void *ptr = nullptr;
         if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(ta_status_words)) != hipSuccess || !ptr)
             return;
+        void *sptr = nullptr;
+        if (hipGetSymbolAddress(&sptr, HIP_SYMBOL(scratch)) != hipSuccess || !sptr)
+            return;
+        s.scratch_ptr = sptr;
         s.status = (int32_t *)ptr;
         s.num_cus = cus;
         s.init_rc = TA_OK;
@@ -184,6 +193,35 @@ int tree_attn_fwd_ex(const ta_tensor *q, const ta_tensor *k_cache, const ta_tens
     }
     pr.p.status = s->status;
     return launch_call(pr, st, dev, opts ? opts->events : nullptr);
+}
+
+int tree_attn_fwd_static(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
+                         const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
+                         ta_tensor *out, ta_tensor *lse, void *stream, const ta_opts *opts)
+{
+    if (opts && opts->workspace)
+        return TA_ERR_OPTS;
+    TAProblem pr;
+    int rc = ta_host_build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts, 256, &pr);
+    if (rc != TA_OK)
+        return rc;
+    if (pr.p.B == 0)
+        return TA_OK;
+    DeviceState *s = nullptr;
+    int dev = 0;
+    rc = device_state(&s, &dev);
+    if (rc != TA_OK)
+        return rc;
+    rc = ta_host_build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts, s->num_cus, &pr);
+    if (rc != TA_OK)
+        return rc;
+    if (pr.ws_bytes > (size_t)TA_STATIC_SCRATCH_BYTES)
+        return TA_ERR_WORKSPACE;
+    // Nothing in the scratch has to start at zero: the KV pass writes every partial result and every list's range of
+    // partials before the merge pass, which follows it on the same stream, reads them.
+    place_workspace(pr, s->scratch_ptr);
+    pr.p.status = s->status;
+    return launch_call(pr, (hipStream_t)stream, dev, opts ? opts->events : nullptr);
 }
 
 int tree_attn_fwd(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,

@@ -34,6 +34,22 @@ int tree_attn_fwd(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor 
     return tree_attn_fwd_ex(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, stream, nullptr);
 }
 
+int tree_attn_fwd_static(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,
+                         const ta_tensor *page_table, const ta_tensor *seq_lens, const ta_tensor *tree_parent,
+                         ta_tensor *out, ta_tensor *lse, void *stream, const ta_opts *opts)
+{
+    if (opts && opts->workspace)
+        return TA_ERR_OPTS;
+    TAProblem pr;
+    int rc = ta_host_build_problem(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse, opts, 256, &pr);
+    if (rc != TA_OK)
+        return rc;
+    if (pr.p.B == 0)
+        return TA_OK;
+    (void)stream;
+    return pr.ws_bytes > (size_t)TA_STATIC_SCRATCH_BYTES ? TA_ERR_WORKSPACE : TA_ERR_HIP;
+}
+
 int tree_attn_encode(const ta_tensor *tree_parent, ta_tensor *masks, void *)
 {
     int B = 0, T = 0;

@@ -26,7 +26,7 @@ TA_ERR_BATCH, TA_ERR_OPTS = -12, -13
 EXPORTS = (
     "tree_attn_fwd", "tree_attn_fwd_ex", "tree_attn_workspace_bytes", "tree_attn_reserve", "tree_attn_release",
     "tree_attn_encode", "tree_attn_append", "tree_attn_compact", "tree_attn_last_status", "tree_attn_plan",
-    "tree_attn_dispatch_row", "tree_attn_stream_read", "tree_attn_strerror", "tree_attn_version",
+    "tree_attn_dispatch_row", "tree_attn_stream_read", "tree_attn_fwd_static", "tree_attn_strerror", "tree_attn_version",
 )
 
 
@@ -99,6 +99,8 @@ def load_library():
         lib.tree_attn_fwd.argtypes = [T, T, T, T, T, T, T, T, ctypes.c_void_p]
         lib.tree_attn_fwd_ex.restype = ctypes.c_int
         lib.tree_attn_fwd_ex.argtypes = [T, T, T, T, T, T, T, T, ctypes.c_void_p, ctypes.POINTER(ta_opts)]
+        lib.tree_attn_fwd_static.restype = ctypes.c_int
+        lib.tree_attn_fwd_static.argtypes = [T, T, T, T, T, T, T, T, ctypes.c_void_p, ctypes.POINTER(ta_opts)]
         lib.tree_attn_workspace_bytes.restype = ctypes.c_size_t
         lib.tree_attn_workspace_bytes.argtypes = [ctypes.c_int32] * 7
         lib.tree_attn_reserve.restype = ctypes.c_int
@@ -225,6 +227,24 @@ def tree_attn_fwd_ex(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out
                                          ctypes.byref(o))
     if check and rc != TA_OK:
         raise TreeAttnError(rc, "tree_attn_fwd_ex")
+    return rc
+
+
+TA_STATIC_SCRATCH_BYTES = 48 << 20
+
+
+def tree_attn_fwd_static(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse=None, stream=None,
+                         scale=None, num_splits=0, kernel=TA_KERNEL_AUTO, workspace=None, events=None, check=True,
+                         item_cost=0, tree_masks=None, kv_start=None, q_node_offset=0, k_new=None, v_new=None,
+                         status=None):
+    """include/treeattn.h: tree_attn_fwd_static (the call that allocates nothing)."""
+    ds = [_desc(x) for x in (q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, lse)]
+    o = _opts(scale, num_splits, kernel, workspace, events, item_cost, tree_masks, kv_start, q_node_offset, k_new, v_new,
+              status)
+    rc = load_library().tree_attn_fwd_static(*[_ref(d) for d in ds], _stream_ptr(stream) if stream != 0 else None,
+                                             ctypes.byref(o))
+    if check and rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_fwd_static")
     return rc
 
 
