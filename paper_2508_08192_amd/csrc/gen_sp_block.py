@@ -6,9 +6,10 @@
 One block of tile i holds up to three streams, merged into one in-order instruction sequence so that a wave keeps
 the matrix pipe and the vector ALU busy at the same time:
 
-  PV   O^T += V^T(i-1) . P^T(i-1)        16 MFMAs (kb = r/4, db = r%4), A fragments from the token-minor V tile
+  PV   O^T += V^T(i-1) . P^T(i-1)        16 MFMAs (kb = r/4, db = r%4), A fragments by transposing LDS reads from
+                                         the row-major V tile (two ds_read_b64_tr_b16 per fragment)
   S    S^T(i+1) = K(i+1) . Q^T           16 MFMAs (kk = r/2, tb = r%2), A fragments from the swizzled K tile
-  SM   running softmax of S^T(i) -> P(i) about 140 vector instructions
+  SM   running softmax of S^T(i) -> P(i) about 150 vector instructions
 
 The large operands live in fixed physical VGPRs that the compiler never sees: the kernel is compiled with
 amdgpu_num_vgpr(16), which confines the register allocator to v0..v31 (the attribute counts in units of two on
@@ -16,12 +17,20 @@ this target), and everything from v32 up belongs to these blocks from the first 
 softmax addresses single registers of the score and probability tuples, which asm operands cannot express.)
 
   v[48:111] O (4 x 16)   v[112:143] score buffer A   v[144:175] score buffer B   v[176:191] P   v[192:223] Q
-  v[224:247] ring of 6 LDS fragments   v[248:255] softmax temporaries   v[38:47] re-layout temporaries
-  v[32:35] lane constants: LDS offsets of the lane's V fragments, K fragments, re-layout reads and writes
-  v[36:37] K fragment address and re-layout write address of the current block
+  v[224:247] ring of 6 LDS fragments   v[248:255] softmax temporaries
+  v[38:41] V fragment addresses of the current block (one per head-dim block)   v[46:47] page-lookup temporaries
+  v[32:33] lane constants: LDS offsets of the lane's V fragments and K fragments   v36 K fragment address of the
+  current block
 
-Small helpers move values between the two worlds: sp_zero_o, sp_load_q, sp_set_bases, sp_get_rl, sp_scale_o,
-sp_mask_A/B, sp_put_o.
+V fragments.  The V tile lies in LDS as it lies in the cache, one 256-byte row per token, with the 32-byte blocks of
+a row XOR-placed by (token & 7).  ds_read_b64_tr_b16 works on groups of 16 lanes: lane j names 8 bytes (four
+elements E_j[0..3]) and lane i receives E_{4k + i/4}[i % 4] for k = 0..3.  With lanes 4k..4k+3 of a group on the four
+8-byte pieces of one 32-byte block of token k, lane i receives head-dim column (16 * block + i) of four tokens: the
+A operand of the second product (rows = head-dim columns, contraction = tokens) without any re-layout.  The token
+sets (16kb + 4hf + {0..3}, then + 8) follow the contraction slots the probabilities occupy after the first product.
+
+Small helpers move values between the two worlds: sp_zero_o, sp_load_q, sp_set_bases, sp_scale_o, sp_mask_A/B,
+sp_put_o.
 
 S^T(i) and S^T(i+1) alternate between buffers A and B, so every block exists in an "A current" and a "B current"
 flavour.  P has one buffer: the PV MFMAs, which read P(i-1), come first in program order and the conversion that
@@ -31,7 +40,8 @@ when it issues).  Each MFMA consumes one 16-byte LDS fragment read issued DIST s
 Running softmax in base 2 with a lazily moved reference M (scaled units): M changes only when the tile maximum
 exceeds M + 4, so P <= 16 and the rescaling of O (done by the caller when alpha != 1) is rare.  Two row sums are
 kept: l of the fp32 probabilities (for the log-sum-exp) and l2 of their bf16 roundings, which are the weights the PV
-product actually applies -- normalising O by l2 makes the output an exact weighted mean of V rows.
+product actually applies -- normalising O by l2 makes the output an exact weighted mean of V rows.  (With l alone
+the output of a row that sees two or three keys is off by the rounding of their weights, up to 0.4 % of a value.)
 """
 O, SA, SB, P, Q, FR, TMP = 48, 112, 144, 176, 192, 224, 248
 NF = 6
@@ -39,11 +49,11 @@ DIST = NF - 1
 TM_A, TM_B, T_SWAP, T_MC, T_THR, T_TK, PS0, PS1 = (TMP + i for i in range(8))
 NTMP = 8
 
-
-RL = 38                    # v[38:47]: re-layout temporaries of the fast blocks (four 8-byte rows, two outputs);
-                           # v[38:41] double as the four V fragment addresses while the PV reads are being issued
-VA_BASE, KA_BASE, RD_BASE, WR_BASE, KADDR, WRT = 32, 33, 34, 35, 36, 37   # lane constants and per-block addresses
-
+RL = 38                    # v[38:41]: the four V fragment addresses of the current block (head-dim blocks 0..3)
+PT0, PT1 = 46, 47          # page lookup of the fast blocks: LDS address of the page id, the id itself
+VA_BASE, KA_BASE, KADDR = 32, 33, 36   # lane constants and the K fragment address of the current block
+S_CMP = 90                 # s[90:91]: lane mask of "the reference moves" (a select on an SGPR mask is a plain
+                           # vector instruction; the same select on VCC costs four times as much on this chip)
 
 
 def v(n):
@@ -55,7 +65,7 @@ def vr(n, k):
 
 
 def frag(r):
-    return vr(FR + 4 * (r % NF), 4)
+    return FR + 4 * (r % NF)
 
 
 def softmax_ops(sc):
@@ -76,8 +86,10 @@ def softmax_ops(sc):
     add("v_max_f32 %s, %s, %s" % (v(TM_A), v(TM_A), v(T_SWAP)))
     add("v_mul_f32 %s, %%[c], %s" % (v(T_MC), v(TM_A)))      # tile maximum in scaled units
     add("v_add_f32 %s, 4.0, %%[m]" % v(T_THR))
-    add("v_cmp_gt_f32 vcc, %s, %s" % (v(T_MC), v(T_THR)))
-    add("v_cndmask_b32 %s, %%[m], %s, vcc" % (v(T_THR), v(T_MC)))   # new reference
+    add("v_cmp_gt_f32 s[%d:%d], %s, %s" % (S_CMP, S_CMP + 1, v(T_MC), v(T_THR)))
+    add("s_nop 1")                                           # a lane mask written by a vector compare needs two
+                                                             # wait states before a vector instruction reads it
+    add("v_cndmask_b32 %s, %%[m], %s, s[%d:%d]" % (v(T_THR), v(T_MC), S_CMP, S_CMP + 1))   # new reference
     add("v_sub_f32 %%[al], %%[m], %s" % v(T_THR))
     add("v_exp_f32 %[al], %[al]")                            # alpha = 2^(M_old - M_new); 1 when unchanged
     add("v_mov_b32 %%[m], %s" % v(T_THR))
@@ -90,7 +102,7 @@ def softmax_ops(sc):
         for k in range(4):
             add("v_exp_f32 %s, %s" % (v(xs[k]), v(xs[k])))
 
-    def stage_b(g):                                          # row sum (unrounded) and the two packed P registers
+    def stage_b(g):                                          # row sum and the two packed P registers
         xs = [sc + 4 * g + k for k in range(4)]
         need = 4 * (g // 2) + 3                              # last PV MFMA reading P quarter g/2
         if g == 0:
@@ -126,64 +138,104 @@ def address_setup(has_pv, has_s):
     if has_pv:
         out.append("v_add_u32 %s, %%[sva], %s" % (v(RL), v(VA_BASE)))
         for db in range(1, 4):
-            out.append("v_xor_b32 %s, %d, %s" % (v(RL + db), 32 * db, v(RL)))      # head-dim block db: see V tile layout
+            out.append("v_xor_b32 %s, %d, %s" % (v(RL + db), 64 * db, v(RL)))      # head-dim block db: see V tile layout
     if has_s:
         out.append("v_add_u32 %s, %%[ska], %s" % (v(KADDR), v(KA_BASE)))
     return out
 
 
 def mfma_steps(has_pv, has_s, sn):
-    """Per MFMA: (LDS read lines, mfma line, is_pv)."""
+    """Per MFMA: (instructions that fetch its A fragment -- LDS reads carry a tag --, mfma line)."""
     steps = []
     if has_pv:
         for r in range(16):
             kb, db = r >> 2, r & 3
-            rd = ["ds_read_b128 {f}, %s offset:%d" % (v(RL + db), kb * 4096 + 512 * db)]
-            mf = "v_mfma_f32_32x32x16_bf16 %s, {f}, %s, %s" % (vr(O + 16 * db, 16), vr(P + 4 * kb, 4), vr(O + 16 * db, 16))
-            steps.append((rd, mf, True))
+            f = frag(len(steps))
+            rd = [("ds_read_b64_tr_b16 %s, %s offset:%d" % (vr(f, 2), v(RL + db), kb * 4096), True),
+                  ("ds_read_b64_tr_b16 %s, %s offset:%d" % (vr(f + 2, 2), v(RL + db), kb * 4096 + 2048), True)]
+            mf = "v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (vr(O + 16 * db, 16), vr(f, 4), vr(P + 4 * kb, 4),
+                                                              vr(O + 16 * db, 16))
+            steps.append((rd, mf))
     if has_s:
         for r in range(16):
             kk, tb = r >> 1, r & 1
+            f = frag(len(steps))
             rd = []
             if tb == 0 and kk > 0:
-                rd.append("v_xor_b32 %s, %d, %s" % (v(T_TK), kk * 32, v(KADDR)))
-            rd.append("ds_read_b128 {f}, %s offset:%d" % (v(KADDR) if kk == 0 else v(T_TK), tb * 8192))
+                rd.append(("v_xor_b32 %s, %d, %s" % (v(T_TK), kk * 32, v(KADDR)), False))
+            rd.append(("ds_read_b128 %s, %s offset:%d" % (vr(f, 4), v(KADDR) if kk == 0 else v(T_TK), tb * 8192), True))
             dst = vr(sn + 16 * tb, 16)
-            mf = "v_mfma_f32_32x32x16_bf16 %s, {f}, %s, %s" % (dst, vr(Q + 4 * kk, 4), "0" if kk == 0 else dst)
-            steps.append((rd, mf, False))
+            mf = "v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (dst, vr(f, 4), vr(Q + 4 * kk, 4), "0" if kk == 0 else dst)
+            steps.append((rd, mf))
     return steps
+
+
+def weave(steps, aux, pre):
+    """One in-order sequence: the fragment fetches run DIST MFMAs ahead, `pre` items of `aux` hide the latency of the
+    first fetches, the rest of `aux` is spread evenly between the MFMAs.  An aux item with mf = k may not come before
+    MFMA k (it overwrites what that MFMA reads).  Items are dicts: t (text), lds (tag of an LDS operation it starts),
+    needs (tags whose data it uses)."""
+    n = len(steps)
+    seq = []
+
+    def put_reads(r):
+        for text, is_lds in steps[r][0]:
+            seq.append(dict(t=text, lds=("f", r, len(seq)) if is_lds else None))
+
+    def tags(r):
+        return [x["lds"] for x in seq if x.get("lds") and x["lds"][:2] == ("f", r)]
+
+    for r in range(min(DIST, n)):
+        put_reads(r)
+    vi = 0
+    pre = min(pre, len(aux))
+    while vi < pre and aux[vi].get("mf", -1) < 0:
+        seq.append(aux[vi])
+        vi += 1
+    pre = vi
+    for r in range(n):
+        if r + DIST < n:
+            put_reads(r + DIST)
+        seq.append(dict(t=steps[r][1], needs=tags(r)))
+        target = pre + (len(aux) - pre) * (r + 1) // n
+        while vi < len(aux) and vi < target:
+            need = aux[vi].get("mf", -1)
+            if need >= 0 and need >= r and r < n - 1:
+                break                                 # this P quarter is still being read
+            seq.append(aux[vi])
+            vi += 1
+    seq += aux[vi:]
+    return seq
+
+
+def with_waits(seq):
+    """Instruction lines of a sequence, with an exact `s_waitcnt lgkmcnt` in front of every item that uses the data of
+    an LDS operation (LDS operations return in order: waiting until k younger ones are outstanding is enough)."""
+    lines, issued, done = [], [], -1
+    for it in seq:
+        needs = it.get("needs")
+        if needs:
+            pos = max(issued.index(x) for x in needs)
+            if pos > done:
+                lines.append("s_waitcnt lgkmcnt(%d)" % (len(issued) - 1 - pos))
+                done = pos
+        lines.append(it["t"])
+        if it.get("lds"):
+            issued.append(it["lds"])
+            assert len(issued) - 1 - done <= 15, "more LDS operations in flight than the counter can hold"
+        if it.get("flush"):
+            issued, done = [], -1
+    return lines
 
 
 def block(name, cur, has_pv, has_s, has_sm):
     sc, sn = (SA, SB) if cur == "A" else (SB, SA)
     steps = mfma_steps(has_pv, has_s, sn)
     ops = softmax_ops(sc) if has_sm else []
-    n = len(steps)
-    lines = ["s_nop 7"] + address_setup(has_pv, has_s)
-    reads = lambda r: [x.replace("{f}", frag(r)) for x in steps[r][0]]
-    for r in range(min(DIST, n)):
-        lines += reads(r)
-    vi = 0
-    pre = 10 if n else len(ops)                      # vector work that hides the latency of the first fragments
-    while vi < min(pre, len(ops)) and ops[vi][1] < 0:
-        lines.append(ops[vi][0])
-        vi += 1
-    n_pv = 16 if has_pv else 0
-    for r in range(n):
-        if r + DIST < n:
-            lines += reads(r + DIST)
-        lines.append("s_waitcnt lgkmcnt(%d)" % min(DIST, n - 1 - r))
-        lines.append(steps[r][1].replace("{f}", frag(r)))
-        target = pre + (len(ops) - pre) * (r + 1) // n
-        while vi < len(ops) and vi < target:
-            need = ops[vi][1]
-            if has_pv and need >= 0 and need >= r and r < n - 1:
-                break                                 # this P quarter is still being read
-            lines.append(ops[vi][0])
-            vi += 1
-    while vi < len(ops):
-        lines.append(ops[vi][0])
-        vi += 1
+    aux = [dict(t=t, mf=need) for t, need in ops]
+    seq = [dict(t="s_nop 7")] + [dict(t=t) for t in address_setup(has_pv, has_s)]
+    seq += weave(steps, aux, 10 if steps else len(aux))
+    lines = with_waits(seq)
     if has_pv and not has_s:
         lines += ["s_nop 15", "s_nop 7"]              # O is read by ordinary code next
     outs, ins, sig = [], [], []
@@ -198,14 +250,15 @@ def block(name, cur, has_pv, has_s, has_sm):
     if has_s:
         ins += ['[ska] "s"(ska)']
         sig += ["uint32_t ska"]
-    return emit(name, sig, lines, outs, ins, ['"memory"', '"vcc"'])
+    clob = ['"memory"', '"vcc"'] + (['"s%d"' % S_CMP, '"s%d"' % (S_CMP + 1)] if has_sm else [])
+    return emit(name, sig, lines, outs, ins, clob)
 
 
 # Scalar registers of the fast loop (clobbers): constants copied from the operands once, and temporaries.
 S_KG, S_VG = 60, 62                     # s[60:61], s[62:63]: cache base of this KV head (K, V)
 S_KSP, S_VSP, S_KSS, S_VSS = 64, 65, 66, 67      # page and slot strides in bytes
 S_PSHIFT, S_PMASK, S_PCADJ, S_C = 68, 69, 70, 71  # page shift/mask, LDS address of the page-id cache, softmax scale
-S_KDST, S_VDST, S_LO, S_HI = 72, 73, 74, 75       # LDS targets of this wave's loads; v_perm selectors
+S_KDST, S_VDST = 72, 73                 # LDS targets of this wave's loads
 ST = 80                                 # s80..s85 temporaries, s[86:87] K tile base, s[88:89] V tile base
 
 
@@ -214,119 +267,71 @@ def sg(n):
 
 
 def fast_step_items(cur, label, helper=False):
-    """One tile of the steady state as a list of instructions (no waits yet): the full block (PV, S, softmax)
-    plus everything else the tile needs -- page lookup and addresses of tile i+3, its four cache loads, the
-    in-place re-layout of V(i), ring bookkeeping, the (rare) rescaling of O, and the closing barrier.
+    """One tile of the steady state as a list of items (no waits yet): the full block (PV, S, softmax) plus
+    everything else the tile needs -- page lookup and addresses of tile i+3, its four cache loads, ring bookkeeping,
+    the (rare) rescaling of O, and the closing barrier.
     helper=True leaves the block itself out: a wave without query rows still moves its share of the tiles."""
     sc, sn = (SA, SB) if cur == "A" else (SB, SA)
     steps = [] if helper else mfma_steps(True, True, sn)
-    n = len(steps)
     sm = [] if helper else [(t.replace("%[c]", sg(S_C)), need) for t, need in softmax_ops(sc)]
-    rx = lambda k: RL + 2 * k          # row k, columns 0..1 (dword x)
-    ry = lambda k: RL + 2 * k + 1      # row k, columns 2..3 (dword y)
-    t0, t1 = RL + 8, RL + 9
     page_a = [  # page id of the tile to load: LDS read now, used a few MFMAs later; slot part of the addresses
-        "s_lshr_b32 %s, %%[pos], %s" % (sg(ST), sg(S_PSHIFT)),
-        "s_lshl_b32 %s, %s, 2" % (sg(ST), sg(ST)),
-        "s_add_u32 %s, %s, %s" % (sg(ST), sg(ST), sg(S_PCADJ)),
-        "v_mov_b32 %s, %s" % (v(t0), sg(ST)),
-        ("ds_read_b32 %s, %s" % (v(t1), v(t0)), ("p", 0)),
-        "s_and_b32 %s, %%[pos], %s" % (sg(ST + 1), sg(S_PMASK)),
-        "s_mul_i32 %s, %s, %s" % (sg(ST + 2), sg(ST + 1), sg(S_KSS)),
-        "s_mul_hi_u32 %s, %s, %s" % (sg(ST + 3), sg(ST + 1), sg(S_KSS)),
-        "s_mul_i32 %s, %s, %s" % (sg(ST + 4), sg(ST + 1), sg(S_VSS)),
-        "s_mul_hi_u32 %s, %s, %s" % (sg(ST + 5), sg(ST + 1), sg(S_VSS)),
+        dict(t="s_lshr_b32 %s, %%[pos], %s" % (sg(ST), sg(S_PSHIFT))),
+        dict(t="s_lshl_b32 %s, %s, 2" % (sg(ST), sg(ST))),
+        dict(t="s_add_u32 %s, %s, %s" % (sg(ST), sg(ST), sg(S_PCADJ))),
+        dict(t="v_mov_b32 %s, %s" % (v(PT0), sg(ST))),
+        dict(t="ds_read_b32 %s, %s" % (v(PT1), v(PT0)), lds=("p", 0)),
+        dict(t="s_and_b32 %s, %%[pos], %s" % (sg(ST + 1), sg(S_PMASK))),
+        dict(t="s_mul_i32 %s, %s, %s" % (sg(ST + 2), sg(ST + 1), sg(S_KSS))),
+        dict(t="s_mul_hi_u32 %s, %s, %s" % (sg(ST + 3), sg(ST + 1), sg(S_KSS))),
+        dict(t="s_mul_i32 %s, %s, %s" % (sg(ST + 4), sg(ST + 1), sg(S_VSS))),
+        dict(t="s_mul_hi_u32 %s, %s, %s" % (sg(ST + 5), sg(ST + 1), sg(S_VSS))),
     ]
     page_b = [
-        ("v_readfirstlane_b32 %s, %s" % (sg(ST), v(t1)), None, [("p", 0)]),
-        "s_nop 3",
+        dict(t="v_readfirstlane_b32 %s, %s" % (sg(ST), v(PT1)), needs=[("p", 0)]),
+        dict(t="s_nop 3"),
+    ] + [dict(t=x) for x in [
         "s_mul_i32 s86, %s, %s" % (sg(ST), sg(S_KSP)), "s_mul_hi_u32 s87, %s, %s" % (sg(ST), sg(S_KSP)),
         "s_add_u32 s86, s86, %s" % sg(ST + 2), "s_addc_u32 s87, s87, %s" % sg(ST + 3),
         "s_add_u32 s86, s86, %s" % sg(S_KG), "s_addc_u32 s87, s87, %s" % sg(S_KG + 1),
         "s_mul_i32 s88, %s, %s" % (sg(ST), sg(S_VSP)), "s_mul_hi_u32 s89, %s, %s" % (sg(ST), sg(S_VSP)),
         "s_add_u32 s88, s88, %s" % sg(ST + 4), "s_addc_u32 s89, s89, %s" % sg(ST + 5),
         "s_add_u32 s88, s88, %s" % sg(S_VG), "s_addc_u32 s89, s89, %s" % sg(S_VG + 1),
-    ]
+    ]]
     dma = [["s_add_u32 m0, %s, %%[ik]" % sg(S_KDST), "s_nop 0", "global_load_lds_dwordx4 %[koff0], s[86:87] nt"],
            ["s_add_u32 m0, m0, 0x400", "s_nop 0", "global_load_lds_dwordx4 %[koff1], s[86:87] nt"],
            ["s_add_u32 m0, %s, %%[iv]" % sg(S_VDST), "s_nop 0", "global_load_lds_dwordx4 %[voff0], s[88:89] nt"],
            ["s_add_u32 m0, m0, 0x400", "s_nop 0", "global_load_lds_dwordx4 %[voff1], s[88:89] nt"]]
+
     def ring(reg, wrap):
         return ["s_add_u32 %s, %s, 0x4000" % (reg, reg), "s_cmp_eq_u32 %s, 0x%x" % (reg, wrap),
                 "s_cselect_b32 %s, 0, %s" % (reg, reg)]
-    rings = ring("%[ik]", 0xc000) + ring("%[iv]", 0x14000) + ring("%[kn]", 0xc000) + ["s_mov_b32 %[vp], %[vc]"] + \
-            ring("%[vc]", 0x14000) + ["s_add_u32 %[pos], %[pos], 64"]
+    rings = ring("%[ik]", 0xc000) + ring("%[iv]", 0x14000) + ring("%[kn]", 0xc000) + ring("%[vp]", 0x14000) + \
+        ["s_add_u32 %[pos], %[pos], 64"]
 
-    def item(x, mf=-1):
-        if isinstance(x, tuple):
-            d = dict(t=x[0], mf=mf)
-            if x[1]:
-                d["lds"] = x[1]
-            if len(x) > 2:
-                d["needs"] = x[2]
-            return d
-        return dict(t=x, mf=mf)
-
-    aux = [item(x) for x in page_a]
-    for t, need in sm[:12]:
-        aux.append(dict(t=t, mf=need))
-    aux += [item(x) for x in page_b]
-    rl_reads = [dict(t="v_add_u32 %s, %%[vc], %s" % (v(t1), v(RD_BASE))),
-                dict(t="v_add_u32 %s, %%[vc], %s" % (v(WRT), v(WR_BASE)))]
-    for k in range(4):
-        rl_reads.append(dict(t="ds_read_b64 %s, %s offset:%d" % (vr(rx(k), 2), v(t1), 256 * k), lds=("r", k)))
-    slo, shi = sg(S_LO), sg(S_HI)
-    relay = [
-        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(t0), v(rx(1)), v(rx(0)), slo), needs=[("r", 0), ("r", 1)]),
-        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(t1), v(rx(3)), v(rx(2)), slo), needs=[("r", 2), ("r", 3)]),
-        dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(WRT), v(t0), v(t1)), lds=("w", 0)),
-        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(rx(0)), v(rx(1)), v(rx(0)), shi)),
-        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(rx(2)), v(rx(3)), v(rx(2)), shi)),
-        dict(t="v_xor_b32 %s, 16, %s" % (v(rx(1)), v(WRT))),
-        dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(rx(1)), v(rx(0)), v(rx(2))), lds=("w", 1)),
-        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(t0), v(ry(1)), v(ry(0)), slo)),
-        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(t1), v(ry(3)), v(ry(2)), slo)),
-        dict(t="v_xor_b32 %s, 32, %s" % (v(rx(3)), v(WRT))),
-        dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(rx(3)), v(t0), v(t1)), lds=("w", 2)),
-        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(ry(0)), v(ry(1)), v(ry(0)), shi)),
-        dict(t="v_perm_b32 %s, %s, %s, %s" % (v(ry(2)), v(ry(3)), v(ry(2)), shi)),
-        dict(t="v_xor_b32 %s, 48, %s" % (v(ry(1)), v(WRT))),
-        dict(t="ds_write2_b32 %s, %s, %s offset1:1" % (v(ry(1)), v(ry(0)), v(ry(2))), lds=("w", 3)),
-    ]
+    aux = list(page_a)
+    aux += [dict(t=t, mf=need) for t, need in sm[:12]]
+    aux += page_b
     rest = sm[12:]
     # Loads of tile i+3: late in the block, one every 10 softmax instructions from the 90th on (they are not needed
-    # before the end of the next block; issued early they cost the 256-row shapes 1.4 %, spread evenly 1 %).  The
-    # re-layout shares v[38:47] with the V fragment addresses and the page lookup, so it starts once the last PV read
-    # is out (MFMA 11).
-    ri, started, di, ring_at, dma_end = 0, False, 0, 0, 0
+    # before the end of the next block; issued early they cost the 256-row shapes 1.4 %, spread evenly 1 %).
+    di, dma_end = 0, 0
     if helper:
         for x in dma:
             aux += [dict(t=y) for y in x]
-        aux += rl_reads
-        started, di = True, 4
+        di = 4
     for j, (t, need) in enumerate(rest):
         aux.append(dict(t=t, mf=need))
         if j >= 90 and (j - 90) % 10 == 0 and di < 4:
             aux += [dict(t=x) for x in dma[di]]
             di += 1
             dma_end = len(aux)                     # the loads read the ring positions ik and iv
-        if j >= 50 and not started:
-            for it in rl_reads:
-                aux.append(dict(it, mf=11))
-            started = True
-            ring_at = len(aux) + 24                # ring bookkeeping: after the last use of every ring position
-        elif started and (j - 50) % 4 == 0 and ri < len(relay):
-            aux.append(dict(relay[ri], mf=11))
-            ri += 1
-    assert started and di == 4
-    for it in relay[ri:]:
-        aux.append(dict(it, mf=11))
+    assert di == 4
     if helper:
         aux += [dict(t=x) for x in rings]
     else:
-        # spread through the second half of the block, one scalar instruction after every fourth other one
-        # (a compare and the select that reads its SCC stay neighbours: other scalar work writes SCC too)
-        k, i = max(ring_at, dma_end), 0
+        # ring bookkeeping: behind the last load, one scalar instruction after every fourth other one (a compare and
+        # the select that reads its SCC stay neighbours: other scalar work writes SCC too)
+        k, i = dma_end, 0
         while i < len(rings):
             grp = rings[i:i + 2] if rings[i].startswith("s_cmp") else rings[i:i + 1]
             at = min(k, len(aux))
@@ -337,28 +342,7 @@ def fast_step_items(cur, label, helper=False):
 
     seq = [] if helper else [dict(t="s_nop 3")] + [dict(t=t.replace("%[sva]", "%[vp]").replace("%[ska]", "%[kn]"))
                                                    for t in address_setup(True, True)]
-    def put_reads(r):
-        for x in steps[r][0]:
-            seq.append(dict(t=x.replace("{f}", frag(r)), lds=("f", r) if x.startswith("ds_read") else None))
-    for r in range(min(DIST, n)):
-        put_reads(r)
-    vi = 0
-    pre = min(16, len(aux))
-    while vi < pre:
-        seq.append(aux[vi])
-        vi += 1
-    for r in range(n):
-        if r + DIST < n:
-            put_reads(r + DIST)
-        seq.append(dict(t=steps[r][1].replace("{f}", frag(r)), needs=[("f", r)]))
-        target = pre + (len(aux) - pre) * (r + 1) // n
-        while vi < len(aux) and vi < target:
-            need = aux[vi].get("mf", -1)
-            if need >= 0 and need >= r and r < n - 1:
-                break
-            seq.append(aux[vi])
-            vi += 1
-    seq += aux[vi:]
+    seq += weave(steps, aux, 16)
     if not helper:
         # O still holds sums relative to the old reference when it moved (rare): rescale, then close the tile
         seq += [dict(t="v_cmp_neq_f32 vcc, 1.0, %[al]"), dict(t="s_cbranch_vccz %df" % label), dict(t="s_nop 15"),
@@ -371,35 +355,24 @@ def fast_step_items(cur, label, helper=False):
 
 def fast_loop(name, helper=False):
     """`cnt` pairs of steady-state tiles (buffer A current, then buffer B) as one asm statement with its own loop,
-    so that the scalar bookkeeping of a tile is issued in the shadow of its matrix and vector work."""
+    so that the scalar bookkeeping of a tile is issued in the shadow of its matrix and vector work.
+    Ring positions (byte offsets): ik, iv = slots the next loads go to; kn = K slot of tile i+1; vp = V slot of
+    tile i-1."""
     head = ["s_mov_b64 s[%d:%d], %%[kg]" % (S_KG, S_KG + 1), "s_mov_b64 s[%d:%d], %%[vg]" % (S_VG, S_VG + 1),
             "s_mov_b64 s[%d:%d], %%[sp]" % (S_KSP, S_VSP), "s_mov_b64 s[%d:%d], %%[ss]" % (S_KSS, S_VSS),
             "s_mov_b64 s[%d:%d], %%[pp]" % (S_PSHIFT, S_PMASK), "s_mov_b64 s[%d:%d], %%[pc]" % (S_PCADJ, S_C),
-            "s_mov_b64 s[%d:%d], %%[dst]" % (S_KDST, S_VDST), "s_mov_b32 %s, 0x05040100" % sg(S_LO),
-            "s_mov_b32 %s, 0x07060302" % sg(S_HI), "1:"]
+            "s_mov_b64 s[%d:%d], %%[dst]" % (S_KDST, S_VDST), "1:"]
     seq = [dict(t=t) for t in head] + fast_step_items("A", 2, helper) + fast_step_items("B", 3, helper)
     seq += [dict(t="s_sub_u32 %[cnt], %[cnt], 1"), dict(t="s_cmp_lg_u32 %[cnt], 0"), dict(t="s_cbranch_scc1 1b")]
-    lines, issued, done = [], [], -1
-    for it in seq:
-        needs = it.get("needs")
-        if needs:
-            pos = max(issued.index(x) for x in needs)
-            if pos > done:
-                lines.append("s_waitcnt lgkmcnt(%d)" % (len(issued) - 1 - pos))
-                done = pos
-        lines.append(it["t"])
-        if it.get("lds"):
-            issued.append(it["lds"])
-        if it.get("flush"):
-            issued, done = [], -1
-    sig = ([] if helper else ["float &m", "float &l", "float &l2"]) + ["uint32_t &ik", "uint32_t &iv", "uint32_t &kn", "uint32_t &vp", "uint32_t &vc",
+    lines = with_waits(seq)
+    sig = ([] if helper else ["float &m", "float &l", "float &l2"]) + ["uint32_t &ik", "uint32_t &iv", "uint32_t &kn", "uint32_t &vp",
            "uint32_t &pos", "uint32_t &cnt", "uint64_t kg", "uint64_t vg", "uint64_t sp", "uint64_t ss", "uint64_t pp",
            "uint64_t pc", "uint64_t dst", "uint32_t koff0", "uint32_t koff1", "uint32_t voff0", "uint32_t voff1"]
     outs = ([] if helper else ['[m] "+v"(m)', '[l] "+v"(l)', '[l2] "+v"(l2)', '[al] "=&v"(alpha)']) + \
-           ['[%s] "+s"(%s)' % (x, x) for x in ("ik", "iv", "kn", "vp", "vc", "pos", "cnt")]
+           ['[%s] "+s"(%s)' % (x, x) for x in ("ik", "iv", "kn", "vp", "pos", "cnt")]
     ins = ['[%s] "s"(%s)' % (x, x) for x in ("kg", "vg", "sp", "ss", "pp", "pc", "dst")] + \
           ['[%s] "v"(%s)' % (x, x) for x in ("koff0", "koff1", "voff0", "voff1")]
-    clob = ['"memory"', '"vcc"', '"scc"'] + ['"s%d"' % i for i in list(range(60, 76)) + list(range(80, 90))]
+    clob = ['"memory"', '"vcc"', '"scc"'] + ['"s%d"' % i for i in list(range(60, 74)) + list(range(80, 92))]
     return emit(name, sig, lines, outs, ins, clob, pre=None if helper else "    float alpha;")
 
 
@@ -422,12 +395,9 @@ def helpers():
     # Nothing waits here; the caller's next wait on the vector-memory counter covers these loads.
     lines = ["global_load_dwordx4 %s, %%[qp], off offset:%d" % (vr(Q + 4 * k, 4), 32 * k) for k in range(8)]
     out.append(emit("sp_load_q", ["const void *qp"], lines, [], ['[qp] "v"(qp)'], ['"memory"']))
-    out.append(emit("sp_set_bases", ["uint32_t va", "uint32_t ka", "uint32_t rd", "uint32_t wr"],
-                    ["v_mov_b32 %s, %%%d" % (v(r), k) for k, r in enumerate((VA_BASE, KA_BASE, RD_BASE, WR_BASE))], [],
-                    ['"v"(va)', '"v"(ka)', '"v"(rd)', '"v"(wr)'], ['"memory"']))
-    out.append(emit("sp_get_rl", ["uint32_t &rd", "uint32_t &wr"],
-                    ["v_mov_b32 %%0, %s" % v(RD_BASE), "v_mov_b32 %%1, %s" % v(WR_BASE)], ['"=v"(rd)', '"=v"(wr)'], [],
-                    ['"memory"']))
+    out.append(emit("sp_set_bases", ["uint32_t va", "uint32_t ka"],
+                    ["v_mov_b32 %s, %%%d" % (v(r), k) for k, r in enumerate((VA_BASE, KA_BASE))], [],
+                    ['"v"(va)', '"v"(ka)'], ['"memory"']))
     lines = ["s_nop 15", "s_nop 7"] + ["v_mul_f32 %s, %%[al], %s" % (v(O + k), v(O + k)) for k in range(64)] + ["s_nop 3"]
     out.append(emit("sp_scale_o", ["float alpha"], lines, [], ['[al] "v"(alpha)'], ['"memory"']))
     for cur, base in (("A", SA), ("B", SB)):

@@ -521,15 +521,16 @@ __device__ __forceinline__ void vm_wait()
 // 16 MFMAs of S^T(i+1) = K(i+1).Q^T and the running softmax of S^T(i) (see gen_sp_block.py), so the wave feeds the
 // matrix pipe and the vector ALU at once and needs no phase skew; one workgroup barrier per tile remains.
 // K and V tiles travel global -> LDS without touching registers (global_load_lds_dwordx4), three blocks
-// ahead of their first use, into a ring of 3 K tiles and a ring of 5 V tiles.  A V tile is re-laid out
-// token-minor IN PLACE, one 8-token group per wave: the load already puts the two token quads of a group side
-// by side, so the 2 KB a wave reads are the 2 KB it writes.
+// ahead of their first use, into a ring of 3 K tiles and a ring of 5 V tiles.  Both lie there as in the cache, one
+// 256-byte row per token, with the 16-byte pieces of a row XOR-placed (K by token & 15, V in 32-byte blocks by
+// token & 7) so that the fragment reads are free of bank conflicts; the V fragments of the second product, whose
+// contraction runs over tokens, come out of the row-major tile through transposing LDS reads (see gen_sp_block.py).
 //
 //   start of block i : issue the loads of tile i+3        (K slot (i+3)%3: last read by S(i) in block i-1,
 //                                                          V slot (i+3)%5: last read by PV(i-2) in block i-1)
 //   block i          : PV(i-1) | S(i+1) | softmax(i)
-//   tail i           : re-lay V(i); rescale O if the softmax reference moved; mask S(i+1) if tile i+1 is
-//                      ragged or the tree tile; wait for this wave's part of tile i+2; barrier
+//   tail i           : rescale O if the softmax reference moved; mask S(i+1) if tile i+1 is ragged or the
+//                      tree tile; wait for this wave's part of tile i+2; barrier
 // ---------------------------------------------------------------------------------------------
 #define SP_RK 3
 #define SP_RV 5
@@ -587,18 +588,16 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
     const uint32_t ksp = (uint32_t)p.k_sp, kss = (uint32_t)p.k_ss, vsp = (uint32_t)p.v_sp, vss = (uint32_t)p.v_ss;
     // Lane constants of the blocks (LDS byte offsets), kept in their fixed registers:
     //   K fragment of step kk: row r32, 16-byte slot (2kk + hf) ^ (r32 & 15), i.e. base ^ 32kk inside the tile
-    //   V fragment of head-dim block db: (base ^ 32db) + 512db inside the token-minor tile
-    //   re-layout: token quad sec of the wave's 8-token group, head-dim columns 4*c4 .. 4*c4+3 (column e: write ^ 16e)
+    //   V fragment of head-dim block db (transposing read, groups of 16 lanes): the lane names the 8-byte piece
+    //   p = lane & 3 of 32-byte block (2db + h16) ^ tk of token row tk = 4hf + k', with h16 = (lane >> 4) & 1 the
+    //   half of the head-dim block the group serves and k' = (lane >> 2) & 3; i.e. (base ^ 64db) + 4096kb (+ 2048)
     {
-        const int sec = lane >> 5, c4 = lane & 31;
-        sp_set_bases(lds0 + SP_V_OFF + (uint32_t)((hf * 128 + (r32 ^ (r32 >> 4))) << 4),
-                     lds0 + (uint32_t)(r32 * 256 + ((hf ^ (r32 & 15)) << 4)),
-                     lds0 + (uint32_t)(SP_V_OFF + wave * 2048 + 4 * sec * 256 + c4 * 8),
-                     lds0 + (uint32_t)(SP_V_OFF + wave * 2048 + (((4 * c4) ^ ((c4 >> 2) & 7)) << 4) + sec * 8));
+        const int h16 = (lane >> 4) & 1, tk = 4 * hf + ((lane >> 2) & 3), pc = lane & 3;
+        sp_set_bases(lds0 + SP_V_OFF + (uint32_t)(tk * 256 + ((h16 ^ tk) << 5) + pc * 8),
+                     lds0 + (uint32_t)(r32 * 256 + ((hf ^ (r32 & 15)) << 4)));
     }
-    // Cache-load role of a lane.  K: tile rows drow and drow+4, 16-byte slot dslot (source chunk swizzled).
-    // V: LDS rows drow and drow+4 hold tokens tv0 and tv0+8 (bits 2 and 3 of the row index swapped), so that
-    // the two token quads of every 8-token group of the second product are neighbours.
+    // Cache-load role of a lane: tile rows drow and drow+4, 16-byte slot dslot; the source chunk is the slot
+    // XOR-ed with the row's placement (K: row & 15; V: 2 * (row & 7)).
     // Only the byte offsets of the common case stay in registers; the rare paths derive their lane roles again
     // from the thread id (fresh_tid keeps the compiler from hoisting them into long-lived registers).
     auto fresh_tid = [&]() {
@@ -612,11 +611,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         const int x = fresh_tid();
         const int wv = x >> 6, ln = x & 63;
         const int drow = wv * 8 + (ln >> 4), dslot = ln & 15;
-        const int tv0 = 16 * (wv >> 1) + 4 * (wv & 1) + (ln >> 4);
         koff0 = (uint32_t)(drow * kss + (dslot ^ (drow & 15)) * 8) * 2u;
         koff1 = (uint32_t)((drow + 4) * kss + (dslot ^ ((drow + 4) & 15)) * 8) * 2u;
-        voff0 = (uint32_t)(tv0 * vss + dslot * 8) * 2u;
-        voff1 = (uint32_t)((tv0 + 8) * vss + dslot * 8) * 2u;
+        voff0 = (uint32_t)(drow * vss + (dslot ^ (2 * (drow & 7))) * 8) * 2u;
+        voff1 = (uint32_t)((drow + 4) * vss + (dslot ^ (2 * ((drow + 4) & 7))) * 8) * 2u;
     };
     // one page (or the contiguous cache) holds a whole aligned tile, and lane offsets fit 32 bits
     const bool fast_geom = (!paged || p.ps_shift >= 6) && kss < (1u << 22) && vss < (1u << 22);
@@ -738,12 +736,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             } else {
                 const int x = fresh_tid();
                 const int drow = (x >> 6) * 8 + ((x & 63) >> 4), dslot = x & 15;
-                const int tv0 = 16 * (x >> 7) + 4 * ((x >> 6) & 1) + ((x & 63) >> 4);
                 // rows past the tile's end and rows before the window start read the tile's first attended token
                 const int lo = max(0, S - pos0);
                 auto row_pos = [&](int r) { return pos0 + (r < cnt && r >= lo ? r : lo); };
                 const int pk[2] = {row_pos(drow), row_pos(drow + 4)};
-                const int pv[2] = {row_pos(tv0), row_pos(tv0 + 8)};
                 // With the write-back folded into the call the tree tokens come from the dense tensors of this step:
                 // addressed like a contiguous cache, request stride for the page, token stride for the slot.
                 bool from_new = false;
@@ -756,48 +752,20 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 uint64_t ke[2], ve[2];
 #pragma unroll
                 for (int k = 0; k < 2; ++k) {
-                    uint32_t pgk = (uint32_t)b, slk = (uint32_t)pk[k], pgv = (uint32_t)b, slv = (uint32_t)pv[k];
+                    uint32_t pg = (uint32_t)b, sl = (uint32_t)pk[k];         // K and V rows hold the same tokens
                     if (from_new) {
-                        slk -= (uint32_t)L;
-                        slv -= (uint32_t)L;
+                        sl -= (uint32_t)L;
                     } else if (paged) {
-                        pgk = (uint32_t)pcache[(pk[k] >> p.ps_shift) - span_first_page];
-                        pgv = (uint32_t)pcache[(pv[k] >> p.ps_shift) - span_first_page];
-                        slk = (uint32_t)(pk[k] & (p.ps - 1));
-                        slv = (uint32_t)(pv[k] & (p.ps - 1));
+                        pg = (uint32_t)pcache[(pk[k] >> p.ps_shift) - span_first_page];
+                        sl = (uint32_t)(pk[k] & (p.ps - 1));
                     }
-                    ke[k] = (uint64_t)pgk * ksp_ + (uint64_t)slk * kss_ + (dslot ^ ((drow + 4 * k) & 15)) * 8;
-                    ve[k] = (uint64_t)pgv * vsp_ + (uint64_t)slv * vss_ + dslot * 8;
+                    ke[k] = (uint64_t)pg * ksp_ + (uint64_t)sl * kss_ + (dslot ^ ((drow + 4 * k) & 15)) * 8;
+                    ve[k] = (uint64_t)pg * vsp_ + (uint64_t)sl * vss_ + (dslot ^ (2 * ((drow + 4 * k) & 7))) * 8;
                 }
                 dma16(kb0 + ke[0], kdst);
                 dma16(kb0 + ke[1], kdst + 1024);
                 dma16(vb0 + ve[0], vdst);
                 dma16(vb0 + ve[1], vdst + 1024);
-            }
-        };
-        // this wave's 8-token group of the V tile in slot vs: raw rows -> token-minor, in place
-        auto relayout_v = [&](int vs) {
-            uint32_t rl_rd, rl_wr;
-            sp_get_rl(rl_rd, rl_wr);
-            char *rd = smem + vs * MF_TILE_BYTES + (rl_rd - lds0), *wr = smem + vs * MF_TILE_BYTES;
-            rl_wr -= lds0;
-            uint2 r[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                r[k] = *(const uint2 *)(rd + k * 256);
-            asm volatile("" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]));      // all reads before any write
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-                uint2 o;
-                if (e < 2) {
-                    o.x = __builtin_amdgcn_perm(r[1].x, r[0].x, sel);
-                    o.y = __builtin_amdgcn_perm(r[3].x, r[2].x, sel);
-                } else {
-                    o.x = __builtin_amdgcn_perm(r[1].y, r[0].y, sel);
-                    o.y = __builtin_amdgcn_perm(r[3].y, r[2].y, sel);
-                }
-                *(uint2 *)(wr + (rl_wr ^ (16u * e))) = o;
             }
         };
         auto wait_loads = [&](int tiles_in_flight) {       // all but the youngest tiles_in_flight*4 loads are done
@@ -881,7 +849,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 wait_loads(issued - 2);                        // tile 1 has landed
             lds_barrier();
 
-            int kn = 1, vc = 0, vp = SP_RV - 1;                // K slot of tile i+1, V slot of tile i, of tile i-1
+            int kn = 1, vp = SP_RV - 1;                        // K slot of tile i+1, V slot of tile i-1
             auto step = [&](auto tag, int i) {
                 constexpr bool A = decltype(tag)::value;       // S^T(i) sits in buffer A
                 if (i + 3 < ns) {
@@ -910,7 +878,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     else
                         sp_last_B(sva, m_run, l_run, l2_run, alpha, c);
                 }
-                relayout_v(vc);
                 if (__any(alpha != 1.0f))
                     sp_scale_o(alpha);             // O still holds sums relative to the old reference
                 if (active && has_next && tile_ragged(s0 + i + 1)) {
@@ -924,13 +891,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     wait_loads(i + 3 < ns ? 1 : 0);            // this wave's part of tile i+2 has landed
                 lds_barrier();
                 kn = kn == SP_RK - 1 ? 0 : kn + 1;
-                vp = vc;
-                vc = vc == SP_RV - 1 ? 0 : vc + 1;
+                vp = vp == SP_RV - 1 ? 0 : vp + 1;
             };
-            // Steady state, two tiles per turn: every tile involved is a full prefix tile inside one page, so the
-            // block itself issues the loads of tile i+3 and re-lays V(i) out (sp_fast_*); no masks, no choices.
             // Steady state: every tile involved is a full prefix tile inside one page (or the contiguous cache), so
-            // whole pairs of tiles run inside sp_fast_loop, which does its own loads, re-layout and bookkeeping.
+            // whole pairs of tiles run inside sp_fast_loop, which does its own loads and bookkeeping.
             const int n_plain = max(0, min(ns, L / TA_TILE - (tile0 + j0 + s0)));     // leading full prefix tiles of the span
             int i = 0;
 #pragma unroll 1
@@ -939,7 +903,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     const uint32_t pairs = (uint32_t)((n_plain - 5 - i) / 2 + 1);
                     uint32_t cnt = pairs, pos = (uint32_t)((tile0 + j0 + s0 + i + 3) * TA_TILE);
                     uint32_t ik_o = ik * MF_TILE_BYTES, iv_o = iv * MF_TILE_BYTES, kn_o = kn * MF_TILE_BYTES;
-                    uint32_t vp_o = vp * MF_TILE_BYTES, vc_o = vc * MF_TILE_BYTES;
+                    uint32_t vp_o = vp * MF_TILE_BYTES;
                     const uint32_t pshift = paged ? (uint32_t)p.ps_shift : 31u;
                     const uint32_t pmask = paged ? (uint32_t)(p.ps - 1) : 0x7fffffffu;
                     const uint32_t pc_lds = lds0 + (uint32_t)((char *)pcache - smem) - 4u * (uint32_t)span_first_page;
@@ -952,16 +916,15 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     uint32_t koff0, koff1, voff0, voff1;
                     lane_offsets(koff0, koff1, voff0, voff1);
                     if (active)
-                        sp_fast_loop(m_run, l_run, l2_run, ik_o, iv_o, kn_o, vp_o, vc_o, pos, cnt, c_kg, c_vg, c_sp, c_ss, c_pp,
-                                     c_pc, c_dst, koff0, koff1, voff0, voff1);
+                        sp_fast_loop(m_run, l_run, l2_run, ik_o, iv_o, kn_o, vp_o, pos, cnt, c_kg, c_vg, c_sp, c_ss, c_pp, c_pc, c_dst,
+                                     koff0, koff1, voff0, voff1);
                     else
-                        sp_fast_loop_helper(ik_o, iv_o, kn_o, vp_o, vc_o, pos, cnt, c_kg, c_vg, c_sp, c_ss, c_pp, c_pc, c_dst,
-                                            koff0, koff1, voff0, voff1);
+                        sp_fast_loop_helper(ik_o, iv_o, kn_o, vp_o, pos, cnt, c_kg, c_vg, c_sp, c_ss, c_pp, c_pc, c_dst, koff0,
+                                            koff1, voff0, voff1);
                     ik = ik_o / MF_TILE_BYTES;
                     iv = iv_o / MF_TILE_BYTES;
                     kn = kn_o / MF_TILE_BYTES;
                     vp = vp_o / MF_TILE_BYTES;
-                    vc = vc_o / MF_TILE_BYTES;
                     i += 2 * (int)pairs;
                 } else {
                     if (i & 1)
