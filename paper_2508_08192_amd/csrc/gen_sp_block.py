@@ -19,6 +19,7 @@ softmax addresses single registers of the score and probability tuples, which as
   v[48:111] O (4 x 16)   v[112:143] score buffer A   v[144:175] score buffer B   v[176:191] P   v[192:223] Q
   v[224:247] ring of 6 LDS fragments   v[248:255] softmax temporaries
   v[38:41] V fragment addresses of the current block (one per head-dim block)   v[46:47] page-lookup temporaries
+  v34 v35 v37 v42 v43 further softmax temporaries
   v[32:33] lane constants: LDS offsets of the lane's V fragments and K fragments   v36 K fragment address of the
   current block
 
@@ -49,6 +50,8 @@ DIST = NF - 1
 TM_A, TM_B, T_SWAP, T_MC, T_THR, T_TK, PS0, PS1 = (TMP + i for i in range(8))
 NTMP = 8
 
+X0, X1, X2, X3, X4 = 34, 35, 37, 42, 43   # more softmax temporaries: a dependent vector instruction issues 9 clocks after
+                           # its producer, an independent one after 5, so maxima and sums run as four chains
 RL = 38                    # v[38:41]: the four V fragment addresses of the current block (head-dim blocks 0..3)
 PT0, PT1 = 46, 47          # page lookup of the fast blocks: LDS address of the page id, the id itself
 VA_BASE, KA_BASE, KADDR = 32, 33, 36   # lane constants and the K fragment address of the current block
@@ -73,12 +76,14 @@ def softmax_ops(sc):
     s = lambda t: v(sc + t)
     ops = []
     add = lambda ins, need=-1: ops.append((ins, need))
-    add("v_max_f32 %s, %s, %s" % (v(TM_A), s(0), s(1)))
-    add("v_max_f32 %s, %s, %s" % (v(TM_B), s(16), s(17)))
-    for j in range(1, 8):
-        add("v_max3_f32 %s, %s, %s, %s" % (v(TM_A), v(TM_A), s(2 * j), s(2 * j + 1)))
-        add("v_max3_f32 %s, %s, %s, %s" % (v(TM_B), v(TM_B), s(16 + 2 * j), s(17 + 2 * j)))
+    mx = (TM_A, TM_B, X0, X1)                                # four chains of maxima, eight scores each
+    for q in range(4):
+        add("v_max_f32 %s, %s, %s" % (v(mx[q]), s(8 * q), s(8 * q + 1)))
+    for j in range(1, 4):
+        for q in range(4):
+            add("v_max3_f32 %s, %s, %s, %s" % (v(mx[q]), v(mx[q]), s(8 * q + 2 * j), s(8 * q + 2 * j + 1)))
     add("v_max_f32 %s, %s, %s" % (v(TM_A), v(TM_A), v(TM_B)))
+    add("v_max3_f32 %s, %s, %s, %s" % (v(TM_A), v(TM_A), v(X0), v(X1)))
     add("v_mov_b32 %s, %s" % (v(T_SWAP), v(TM_A)))
     add("s_nop 1")                                           # VALU write -> permlane swap read
     add("v_permlane32_swap_b32 %s, %s" % (v(TM_A), v(T_SWAP)))  # both halves of a row see both maxima
@@ -102,22 +107,24 @@ def softmax_ops(sc):
         for k in range(4):
             add("v_exp_f32 %s, %s" % (v(xs[k]), v(xs[k])))
 
-    def stage_b(g):                                          # row sum and the two packed P registers
+    ps = (PS0, PS1, X2, X3)                                  # four chains of the row sum
+    d2 = (TM_A, TM_B, X0, X1)                                # four chains of the sum of the rounded values
+
+    def stage_b(g):                                          # row sums and the two packed P registers
         xs = [sc + 4 * g + k for k in range(4)]
         need = 4 * (g // 2) + 3                              # last PV MFMA reading P quarter g/2
         if g == 0:
-            add("v_add_f32 %s, %s, %s" % (v(PS0), v(xs[0]), v(xs[1])))
-            add("v_add_f32 %s, %s, %s" % (v(PS1), v(xs[2]), v(xs[3])))
+            for k in range(4):
+                add("v_mov_b32 %s, %s" % (v(ps[k]), v(xs[k])))
         else:
-            add("v_add_f32 %s, %s, %s" % (v(PS0), v(PS0), v(xs[0])))
-            add("v_add_f32 %s, %s, %s" % (v(PS1), v(PS1), v(xs[1])))
-            add("v_add_f32 %s, %s, %s" % (v(PS0), v(PS0), v(xs[2])))
-            add("v_add_f32 %s, %s, %s" % (v(PS1), v(PS1), v(xs[3])))
+            for k in range(4):
+                add("v_add_f32 %s, %s, %s" % (v(ps[k]), v(ps[k]), v(xs[k])))
         add("v_cvt_pk_bf16_f32 %s, %s, %s" % (v(P + 2 * g), v(xs[0]), v(xs[1])), need)
         add("v_cvt_pk_bf16_f32 %s, %s, %s" % (v(P + 2 * g + 1), v(xs[2]), v(xs[3])), need)
         # second row sum, of the rounded values: what the PV product really weighs V with
-        add("v_dot2_f32_bf16 %s, %s, %s, %s" % (v(TM_A), v(P + 2 * g), v(T_SWAP), "0" if g == 0 else v(TM_A)), need)
-        add("v_dot2_f32_bf16 %s, %s, %s, %s" % (v(TM_B), v(P + 2 * g + 1), v(T_SWAP), "0" if g == 0 else v(TM_B)), need)
+        for h in range(2):
+            c = d2[2 * (g & 1) + h]
+            add("v_dot2_f32_bf16 %s, %s, %s, %s" % (v(c), v(P + 2 * g + h), v(T_SWAP), "0" if g < 2 else v(c)), need)
 
     stage_a(0)
     for g in range(1, 8):
@@ -125,9 +132,12 @@ def softmax_ops(sc):
         stage_b(g - 1)
     stage_b(7)
     add("v_add_f32 %s, %s, %s" % (v(PS0), v(PS0), v(PS1)))
+    add("v_add_f32 %s, %s, %s" % (v(X2), v(X2), v(X3)))
+    add("v_add_f32 %s, %s, %s" % (v(TM_A), v(TM_A), v(TM_B)))   # (the dot results are more than 3 wait states old)
+    add("v_add_f32 %s, %s, %s" % (v(X0), v(X0), v(X1)))
+    add("v_add_f32 %s, %s, %s" % (v(PS0), v(PS0), v(X2)))
+    add("v_add_f32 %s, %s, %s" % (v(TM_A), v(TM_A), v(X0)))
     add("v_fma_f32 %%[l], %%[l], %%[al], %s" % v(PS0))
-    add("s_nop 1")                                           # a dot result needs 3 wait states before another VALU reads it
-    add("v_add_f32 %s, %s, %s" % (v(TM_A), v(TM_A), v(TM_B)))
     add("v_fma_f32 %%[l2], %%[l2], %%[al], %s" % v(TM_A))
     return ops
 
