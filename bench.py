@@ -140,6 +140,31 @@ def attainable_hbm(log):
     return gbs
 
 
+def attainable_mfma(log):
+    """bf16 matrix-core rate this device sustains (TFLOP/s): the library's tree_attn_mfma_probe, back to back for
+    SETTLE_SECONDS so that the clock settles under the power limit, then 5 launches between two events."""
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    iters = 2000                                  # about 1.3 ms per launch
+    t_end = time.perf_counter() + 2 * SETTLE_SECONDS
+    while time.perf_counter() < t_end:
+        for _ in range(10):
+            ta.tree_attn_mfma_probe(iters, sink, stream=stream)
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    flop = 0
+    for _ in range(5):
+        flop += ta.tree_attn_mfma_probe(iters, sink, stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    tf = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    log("attainable bf16 matrix-core rate (registers only, sustained): %.0f TFLOP/s" % tf)
+    return tf
+
+
 def prepare(w, log, rotate=0):
     """Uploads workload w and makes the copies of its KV pool the steps cycle through."""
     import numpy as np
@@ -316,6 +341,8 @@ def main():
                     help="also time the other configurations briefly and list them under other_workloads (0 = no)")
     ap.add_argument("--dispatch-check", type=int, default=1,
                     help="with --others: time forced splits and per-list costs beside the library's own pick (0 = no)")
+    ap.add_argument("--probes", type=int, default=1,
+                    help="measure the attainable HBM read rate and matrix-core rate first (0 = skip, for profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="instead of the benchmark, run a plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB) "
                          "five times: the known traffic against which HBM byte counters are scaled")
@@ -344,7 +371,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     ta.load_library()          # fails loudly if the HIP library is not built
-    attainable = attainable_hbm(log)
+    attainable = attainable_hbm(log) if args.probes else float("nan")
+    attainable_tf = attainable_mfma(log) if args.probes else float("nan")
     t0 = time.time()
     w = make(args.workload)
     log("workload %s generated in %.1f s" % (w.name, time.time() - t0))
@@ -380,6 +408,9 @@ def main():
                  "hbm_frac": m["hbm_frac"], "mfma_frac": m["mfma_frac"],
                  "hbm_frac_median": kv_alg / (med_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                  "attainable_GBps": attainable, "frac_of_attainable": kv_alg / (kv_us * 1e-6) / 1e9 / attainable,
+                 "attainable_mfma_TFLOPs": attainable_tf,
+                 "mfma_frac_of_attainable": flops / (kv_us * 1e-6) / 1e12 / attainable_tf if w.dtype == "bf16" else 0.0,
+                 "ideal_us_at_attainable_rates": max(kv_alg / 1e9 / attainable, flops / 1e12 / attainable_tf) * 1e6,
                  "traffic_collected_at_commit": traffic_at})
 
     result = {

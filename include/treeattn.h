@@ -299,6 +299,14 @@ int tree_attn_fwd_static(const ta_tensor *q, const ta_tensor *k_cache, const ta_
  */
 int tree_attn_stream_read(const void *buf, size_t bytes, void *sink, void *stream);
 
+/*
+ * Measurement aid (no part of the method): one launch that does nothing but bf16 matrix-core instructions on
+ * registers, eight waves per compute unit, 32 * iters instructions of 32768 flop per wave (1 <= iters <= 2^20) --
+ * the matrix-core rate this device sustains, which its power limit holds below the published peak.  *flop (HOST
+ * pointer, may be NULL) receives the flop of the launch; `sink` is a DEVICE pointer to 4 bytes.
+ */
+int tree_attn_mfma_probe(int32_t iters, void *sink, int64_t *flop, void *stream);
+
 const char *tree_attn_strerror(int status);
 int tree_attn_version(void);
 

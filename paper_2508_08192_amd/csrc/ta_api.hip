@@ -313,4 +313,19 @@ int tree_attn_stream_read(const void *buf, size_t bytes, void *sink, void *strea
     return ta_launch_stream_read(buf, bytes, sink, s->num_cus, (hipStream_t)stream) == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
 
+int tree_attn_mfma_probe(int32_t iters, void *sink, int64_t *flop, void *stream)
+{
+    if (!sink)
+        return TA_ERR_NULL;
+    if (iters < 1 || iters > (1 << 20) || ((uintptr_t)sink % 4) != 0)
+        return TA_ERR_OPTS;
+    DeviceState *s = nullptr;
+    int rc = device_state(&s);
+    if (rc != TA_OK)
+        return rc;
+    if (flop)
+        *flop = (int64_t)s->num_cus * 8 * 32 * (int64_t)iters * 32768;
+    return ta_launch_mfma_probe(iters, sink, s->num_cus, (hipStream_t)stream) == hipSuccess ? TA_OK : TA_ERR_HIP;
+}
+
 }  // extern "C"

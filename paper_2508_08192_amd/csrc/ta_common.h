@@ -399,5 +399,6 @@ hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream);
 hipError_t ta_launch_append(const TAAppend &a, hipStream_t stream);
 hipError_t ta_launch_compact(const TACompact &c, hipStream_t stream, int dev);
 hipError_t ta_launch_stream_read(const void *buf, size_t bytes, void *sink, int num_cus, hipStream_t stream);
+hipError_t ta_launch_mfma_probe(int iters, void *sink, int num_cus, hipStream_t stream);
 hipError_t ta_launch_encode(const int32_t *parent, int64_t par_sb, int B, int T, unsigned long long *masks,
                             int32_t *status, hipStream_t stream);

@@ -893,6 +893,46 @@ __global__ __launch_bounds__(512) void ta_stream_read_kernel(const uint4 *__rest
         *sink = acc;
 }
 
+// Measurement aid: nothing but dependent-free chains of v_mfma_f32_32x32x16_bf16 on registers, eight waves per compute
+// unit -- the matrix-core rate this device sustains under its power limit, against which the KV pass's rate is set
+// beside the published peak.  Each wave issues 32 * iters matrix instructions (32768 flop each per wave).
+__global__ __launch_bounds__(512) void ta_mfma_probe_kernel(int iters, float *sink)
+{
+    typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+    typedef float f32x16_t __attribute__((ext_vector_type(16)));
+    f32x16_t acc[4];
+    bf16x8_t a, b;
+    // operands with the bit patterns of real data (a hash of the lane: values in (-2, 2)); matrix cores fed with
+    // zeros and ones draw far less power and would show a rate no real kernel sees
+    uint32_t h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    for (int i = 0; i < 8; ++i) {
+        h = h * 1664525u + 1013904223u;
+        a[i] = (__bf16)((float)(int)(h >> 8 & 0xffff) * (1.f / 16384.f) - 2.f);
+        h = h * 1664525u + 1013904223u;
+        b[i] = (__bf16)((float)(int)(h >> 8 & 0xffff) * (1.f / 16384.f) - 2.f);
+    }
+    for (int k = 0; k < 4; ++k)
+        for (int i = 0; i < 16; ++i)
+            acc[k][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 32; ++r)
+            acc[r & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[r & 3], 0, 0, 0);
+    }
+    float x = 0.f;
+    for (int k = 0; k < 4; ++k)
+        for (int i = 0; i < 16; ++i)
+            x += acc[k][i];
+    if (x == 1.2345678f)               // practically never: keeps the results alive without a store per lane
+        *sink = x;
+}
+
+hipError_t ta_launch_mfma_probe(int iters, void *sink, int num_cus, hipStream_t stream)
+{
+    hipLaunchKernelGGL(ta_mfma_probe_kernel, dim3(num_cus), dim3(512), 0, stream, iters, (float *)sink);
+    return hipGetLastError();
+}
+
 hipError_t ta_launch_stream_read(const void *buf, size_t bytes, void *sink, int num_cus, hipStream_t stream)
 {
     const int wgs = num_cus * 4;

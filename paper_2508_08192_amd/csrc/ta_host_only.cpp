@@ -87,4 +87,13 @@ int tree_attn_stream_read(const void *buf, size_t bytes, void *sink, void *)
     return bytes == 0 ? TA_OK : TA_ERR_HIP;
 }
 
+int tree_attn_mfma_probe(int32_t iters, void *sink, int64_t *, void *)
+{
+    if (!sink)
+        return TA_ERR_NULL;
+    if (iters < 1 || iters > (1 << 20) || ((uintptr_t)sink % 4) != 0)
+        return TA_ERR_OPTS;
+    return TA_ERR_HIP;
+}
+
 }  // extern "C"

@@ -26,7 +26,7 @@ TA_ERR_BATCH, TA_ERR_OPTS = -12, -13
 EXPORTS = (
     "tree_attn_fwd", "tree_attn_fwd_ex", "tree_attn_workspace_bytes", "tree_attn_reserve", "tree_attn_release",
     "tree_attn_encode", "tree_attn_append", "tree_attn_compact", "tree_attn_last_status", "tree_attn_plan",
-    "tree_attn_dispatch_row", "tree_attn_stream_read", "tree_attn_fwd_static", "tree_attn_strerror", "tree_attn_version",
+    "tree_attn_dispatch_row", "tree_attn_stream_read", "tree_attn_mfma_probe", "tree_attn_fwd_static", "tree_attn_strerror", "tree_attn_version",
 )
 
 
@@ -99,6 +99,8 @@ def load_library():
         lib.tree_attn_fwd.argtypes = [T, T, T, T, T, T, T, T, ctypes.c_void_p]
         lib.tree_attn_fwd_ex.restype = ctypes.c_int
         lib.tree_attn_fwd_ex.argtypes = [T, T, T, T, T, T, T, T, ctypes.c_void_p, ctypes.POINTER(ta_opts)]
+        lib.tree_attn_mfma_probe.restype = ctypes.c_int
+        lib.tree_attn_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p]
         lib.tree_attn_fwd_static.restype = ctypes.c_int
         lib.tree_attn_fwd_static.argtypes = [T, T, T, T, T, T, T, T, ctypes.c_void_p, ctypes.POINTER(ta_opts)]
         lib.tree_attn_workspace_bytes.restype = ctypes.c_size_t
@@ -287,6 +289,16 @@ def tree_attn_stream_read(buf, sink, stream=None, check=True):
     if check and rc != TA_OK:
         raise TreeAttnError(rc, "tree_attn_stream_read")
     return rc
+
+
+def tree_attn_mfma_probe(iters, sink, stream=None, check=True):
+    """include/treeattn.h: tree_attn_mfma_probe (measurement aid); returns the flop of the launch."""
+    flop = ctypes.c_int64(0)
+    rc = load_library().tree_attn_mfma_probe(int(iters), sink.data_ptr(), ctypes.byref(flop),
+                                             _stream_ptr(stream) if stream != 0 else None)
+    if check and rc != TA_OK:
+        raise TreeAttnError(rc, "tree_attn_mfma_probe")
+    return int(flop.value)
 
 
 def tree_attn_encode(tree_parent, masks, stream=None, check=True):

@@ -241,7 +241,7 @@ def test_library_workspace_outlives_a_captured_graph_and_never_grows_under_captu
     assert_parity(got, got_lse, ref, ref_lse, "bf16", "after release")
 
 
-def test_streaming_read_probe_runs():
+def test_measurement_probes_run():
     import torch
     from paper_2508_08192_amd import treeattn as ta
     buf = torch.ones(1 << 22, dtype=torch.float32, device="cuda")
@@ -249,3 +249,8 @@ def test_streaming_read_probe_runs():
     ta.tree_attn_stream_read(buf, sink)
     torch.cuda.synchronize()
     assert int(sink.item()) == 0
+    fsink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    flop = ta.tree_attn_mfma_probe(10, fsink)
+    torch.cuda.synchronize()
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert flop == cus * 8 * 32 * 10 * 32768 and float(fsink.item()) == 0.0
