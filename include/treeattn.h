@@ -103,11 +103,12 @@ typedef struct {
 /* Kernel families (ta_opts.kernel).  AUTO picks MFMA when the shape allows it. */
 #define TA_KERNEL_AUTO 0
 #define TA_KERNEL_GENERIC 1   /* scalar fp32-accumulating kernel: any dtype, head_dim, page size */
-#define TA_KERNEL_MFMA 2      /* bf16 matrix-core kernel: head_dim 128, power-of-two page size (or contiguous), 16-byte
-                                 aligned q/k/v rows, at most 256 query heads per KV head */
+#define TA_KERNEL_MFMA 2      /* bf16 matrix-core kernel: head_dim 128 or 64, power-of-two page size (or contiguous),
+                                 16-byte aligned q/k/v rows, at most 256 query heads per KV head */
 #define TA_KERNEL_MFMA_BASIC 3 /* as MFMA, but with the plain register-staged matrix-core kernel instead of the
-                                 software-pipelined one (the library falls back to it by itself when the batch
-                                 is so large, B above ~1900, that its schedule does not fit beside the tiles in LDS) */
+                                 software-pipelined one (the library takes it by itself for head_dim 64, and when the
+                                 batch is so large, B above ~1900, that the pipelined kernel's schedule does not fit
+                                 beside the tiles in LDS) */
 
 typedef struct {
     float scale;              /* softmax scale; <= 0 or NaN selects 1/sqrt(head_dim) */

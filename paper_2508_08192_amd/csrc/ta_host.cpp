@@ -196,7 +196,7 @@ int ta_host_build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tenso
     for (int s = 0; s <= 30; ++s)
         if (((int64_t)1 << s) == ps)
             ps_shift = s;
-    const bool mfma_ok = q->dtype == TA_BF16 && D == 128 && (!pt || ps_shift >= 0) &&
+    const bool mfma_ok = q->dtype == TA_BF16 && (D == 128 || D == 64) && (!pt || ps_shift >= 0) &&
                          q->stride[2] % 8 == 0 && q->stride[1] % 8 == 0 && q->stride[0] % 8 == 0 &&
                          k->stride[0] % 8 == 0 && k->stride[1] % 8 == 0 && k->stride[2] % 8 == 0 &&
                          v->stride[0] % 8 == 0 && v->stride[1] % 8 == 0 && v->stride[2] % 8 == 0 &&
@@ -204,13 +204,15 @@ int ta_host_build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tenso
                          ((uintptr_t)v->data % 16) == 0 && k->stride[0] < INT32_MAX && k->stride[2] < INT32_MAX &&
                          v->stride[0] < INT32_MAX && v->stride[2] < INT32_MAX && Hq / Hkv <= 256 &&
                          (!kn || (new_rows_aligned(kn) && new_rows_aligned(vn)));
-    const int basic = kernel == TA_KERNEL_MFMA_BASIC ? 1 : 0;
+    int basic = kernel == TA_KERNEL_MFMA_BASIC ? 1 : 0;
     if (basic)
         kernel = TA_KERNEL_MFMA;
     if (kernel == TA_KERNEL_MFMA && !mfma_ok)
         return TA_ERR_OPTS;
     if (kernel == TA_KERNEL_AUTO)
         kernel = mfma_ok ? TA_KERNEL_MFMA : TA_KERNEL_GENERIC;
+    if (kernel == TA_KERNEL_MFMA && D != 128)
+        basic = 1;                               // the pipelined kernel is written for head_dim 128 only
 
     TAParams &p = pr->p;
     memset(&p, 0, sizeof p);

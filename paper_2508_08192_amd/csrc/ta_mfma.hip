@@ -95,25 +95,27 @@ __device__ __forceinline__ void load_unit(const TAParams &p, Unit &u, const uint
     }
 }
 
-// K tile in LDS: [token 0..63][16 chunks of 16 B], chunk index XOR-swizzled with (token & 15) so that
-// the 16-byte fragment reads of 16 different tokens at one chunk hit distinct banks.
+// K tile in LDS: [token 0..63][DH / 8 chunks of 16 B], chunk index XOR-swizzled with the token's low bits so that
+// the 16-byte fragment reads of different tokens at one chunk hit distinct banks.
+template <int DH>
 __device__ __forceinline__ void store_k_unit(char *ktile, const Unit &u, int quad, int chunk)
 {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int row = quad * 4 + k;
-        *(uint4 *)(ktile + row * 256 + ((chunk ^ (row & 15)) << 4)) = u.r[k];
+        *(uint4 *)(ktile + row * (DH * 2) + ((chunk ^ (row & (DH / 8 - 1))) << 4)) = u.r[k];
     }
 }
 
-// V tile in LDS, token-minor: [kb 0..3][half 0..1][128 head-dim slots][8 tokens] of bf16, where the 8
+// V tile in LDS, token-minor: [kb 0..3][half 0..1][DH head-dim slots][8 tokens] of bf16, where the 8
 // tokens of (kb, half) are 16kb + 4half + {0,1,2,3} and 16kb + 8 + 4half + {0,1,2,3}: exactly the
 // contraction slots a lane of that half feeds to the second MFMA.  The head-dim slot of column d is
 // d ^ ((d >> 4) & 7), which spreads the eight 8-byte writes of a staging thread over the banks.
+template <int DH>
 __device__ __forceinline__ void store_v_unit(char *vtile, const Unit &u, int quad, int chunk)
 {
     const int kb = quad >> 2, half = quad & 1, sec = (quad >> 1) & 1;
-    char *base = vtile + ((kb * 2 + half) * 128) * 16 + sec * 8;
+    char *base = vtile + ((kb * 2 + half) * DH) * 16 + sec * 8;
     const uint32_t *r0 = (const uint32_t *)&u.r[0], *r1 = (const uint32_t *)&u.r[1];
     const uint32_t *r2 = (const uint32_t *)&u.r[2], *r3 = (const uint32_t *)&u.r[3];
 #pragma unroll
@@ -169,9 +171,12 @@ __device__ __forceinline__ void mask_scores(f32x16 (&acc_s)[2], unsigned long lo
 
 // Running-softmax bookkeeping of one 64-token tile for one 32-row block: s holds the lane's 32 raw
 // (unscaled) scores, c = softmax scale * log2(e).  Produces P as four bf16 B-operands and updates the
-// running max (raw units), the lane's share of the running sum, and (rarely) rescales O.
-__device__ __forceinline__ void softmax_tile(const f32x16 (&s)[2], float c, float &m_run, float &l_run,
-                                             f32x16 (&acc_o)[4], uint4 (&pb)[4])
+// running max (raw units), the lane's shares of the running sums -- l of the probabilities (for the log-sum-exp)
+// and l2 of their bf16 roundings, the weights the second product really applies (O is normalised by l2, which makes
+// the output an exact weighted mean of V rows) -- and (rarely) rescales O.
+template <int NDB>
+__device__ __forceinline__ void softmax_tile(const f32x16 (&s)[2], float c, float &m_run, float &l_run, float &l2_run,
+                                             f32x16 (&acc_o)[NDB], uint4 (&pb)[4])
 {
     float tmax = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
@@ -182,7 +187,7 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&s)[2], float c, floa
     const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
     const float neg_mc = -m_new * c;
     m_run = m_new;
-    float psum = 0.f;
+    float psum = 0.f, psum2 = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) {
         float e[8];
@@ -195,11 +200,16 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&s)[2], float c, floa
         pb[kb].y = pack_bf16(e[2], e[3]);
         pb[kb].z = pack_bf16(e[4], e[5]);
         pb[kb].w = pack_bf16(e[6], e[7]);
+        const uint32_t w4[4] = {pb[kb].x, pb[kb].y, pb[kb].z, pb[kb].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            psum2 += __uint_as_float(w4[k] << 16) + __uint_as_float(w4[k] & 0xffff0000u);
     }
     l_run = l_run * alpha + psum;
+    l2_run = l2_run * alpha + psum2;
     if (__any(alpha != 1.0f)) {
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int i = 0; i < 16; ++i)
                 acc_o[db][i] *= alpha;
@@ -207,14 +217,18 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&s)[2], float c, floa
 }
 
 // NCW compute waves of RB 32-row blocks each (rows per workgroup = 32*RB*NCW), NT threads in all
-// (NT/64 - NCW waves only help with staging).
-template <int NCW, int RB, int NT>
+// (NT/64 - NCW waves only help with staging).  DH: head dimension, 64 or 128.
+template <int NCW, int RB, int NT, int DH>
 __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
 {
-    constexpr int UPT = MF_UNITS / NT;            // staging units per thread
+    constexpr int CH = DH / 8;                    // 16-byte chunks of a row
+    constexpr int UNITS_K = 16 * CH;              // staging units of the K tile (as many again for V)
+    constexpr int UPT = (2 * UNITS_K + NT - 1) / NT;   // staging units per thread
+    constexpr int TILE_BYTES = TA_TILE * DH * 2;
+    constexpr int NKK = DH / 16, NDB = DH / 32;   // contraction steps of the first product, head-dim blocks of the second
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char *tiles = smem;                                                   // [MF_STAGES][K tile | V tile]
-    unsigned long long *masks = (unsigned long long *)(smem + MF_STAGES * 2 * MF_TILE_BYTES);   // [64]
+    unsigned long long *masks = (unsigned long long *)(smem + MF_STAGES * 2 * TILE_BYTES);   // [64]
     int *flag = (int *)(masks + TA_MAX_TREE);
     int *par_s = flag + 4;                                                // [TA_MAX_TREE]
     int *cum = par_s + TA_MAX_TREE;                                       // [B + 1]
@@ -233,13 +247,13 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
     const int rows_here = min(p.rows_grp, p.rows - rg * p.rows_grp);
     const float c = p.scale_log2e;
     // LDS byte offsets of this lane's fragments inside a tile
-    const int sw = r32 & 15;
-    const int krow_off = r32 * 256;                                       // + tb*8192 + (((2kk+hf)^sw) << 4)
-    int vcol_off[4];                                                      // + kb*4096
+    const int sw = r32 & (CH - 1);
+    const int krow_off = r32 * (DH * 2);                                  // + tb*32 rows + (((2kk+hf)^sw) << 4)
+    int vcol_off[NDB];                                                    // + kb * 2 * DH * 16
 #pragma unroll
-    for (int db = 0; db < 4; ++db) {
+    for (int db = 0; db < NDB; ++db) {
         const int d = db * 32 + r32;
-        vcol_off[db] = (hf * 128 + (d ^ ((d >> 4) & 7))) << 4;
+        vcol_off[db] = (hf * DH + (d ^ ((d >> 4) & 7))) << 4;
     }
 
     while (t < t_end) {
@@ -305,8 +319,8 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                     const int row = (wave * RB + rb) * 32 + r32;
                     if (row < rows_here) {
                         const int64_t wrow = ta_ws_row(p, slot, rg, row);
-                        for (int d = hf * 64; d < hf * 64 + 64; d += 4)
-                            *(float4 *)(p.ws_o + wrow * MF_D + d) = make_float4(0.f, 0.f, 0.f, 0.f);
+                        for (int d = hf * (DH / 2); d < hf * (DH / 2) + DH / 2; d += 4)
+                            *(float4 *)(p.ws_o + wrow * DH + d) = make_float4(0.f, 0.f, 0.f, 0.f);
                         if (hf == 0)
                             p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
                     }
@@ -318,7 +332,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
         }
 
         // Q fragments (B operand of the first product): row r32 of each block, head-dim 16kk + 8hf .. +8.
-        uint4 qf[RB][8];
+        uint4 qf[RB][NKK];
         unsigned long long tree_mask[RB];
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
@@ -330,25 +344,26 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                 const uint16_t *qp = (const uint16_t *)p.q + (int64_t)b * p.q_sb + (int64_t)node * p.q_st +
                                      (int64_t)(g * p.G + R % p.G) * p.q_sh + hf * 8;
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk)
+                for (int kk = 0; kk < NKK; ++kk)
                     qf[rb][kk] = *(const uint4 *)(qp + kk * 16);
             } else {
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk)
+                for (int kk = 0; kk < NKK; ++kk)
                     qf[rb][kk] = make_uint4(0, 0, 0, 0);
             }
             // Rows of padding keep an all-ones mask so that their (discarded) softmax stays finite.
             tree_mask[rb] = (has_tree_tile && row_ok) ? masks[p.q_off + node] : ~0ull;
         }
 
-        f32x16 acc_o[RB][4];
-        float m_run[RB], l_run[RB];
+        f32x16 acc_o[RB][NDB];
+        float m_run[RB], l_run[RB], l2_run[RB];
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
             m_run[rb] = -INFINITY;
             l_run[rb] = 0.f;
+            l2_run[rb] = 0.f;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
                     acc_o[rb][db][i] = 0.f;
@@ -363,20 +378,22 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
 #pragma unroll
             for (int s = 0; s < UPT; ++s) {
                 const int u = tid + s * NT;
-                const int uu = u & 255, quad = uu >> 4, chunk = uu & 15;
+                if (u >= 2 * UNITS_K)
+                    continue;
+                const int uu = u < UNITS_K ? u : u - UNITS_K, quad = uu / CH, chunk = uu % CH;
                 const int pos0 = tile_pos0 + quad * 4;
                 const int n_valid = max(0, min(4, limit - pos0));
                 const int n_skip = tree_tile ? 0 : max(0, min(4, S - pos0));      // tokens before the window start
                 if (tree_tile && p.kn) {
                     // write-back folded into the call: the tree tokens sit in the dense tensors of this step, which
                     // are addressed like a contiguous cache -- request stride for the page, token stride for the slot
-                    if (u < 256)
+                    if (u < UNITS_K)
                         load_unit(p, stage[s], (const uint16_t *)p.kn + (int64_t)g * p.kn_sh + chunk * 8,
                                   (uint32_t)p.kn_sb, (uint32_t)p.kn_st, b, pos0 - L, n_valid, true);
                     else
                         load_unit(p, stage[s], (const uint16_t *)p.vn + (int64_t)g * p.vn_sh + chunk * 8,
                                   (uint32_t)p.vn_sb, (uint32_t)p.vn_st, b, pos0 - L, n_valid, true);
-                } else if (u < 256) {
+                } else if (u < UNITS_K) {
                     load_unit(p, stage[s], (const uint16_t *)p.k + (int64_t)g * p.k_sh + chunk * 8, (uint32_t)p.k_sp,
                               (uint32_t)p.k_ss, b, pos0, n_valid, !p.page_table, n_skip);
                 } else {
@@ -386,15 +403,17 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
             }
         };
         auto store_tile = [&](int buf) {
-            char *kt = tiles + buf * 2 * MF_TILE_BYTES, *vt = kt + MF_TILE_BYTES;
+            char *kt = tiles + buf * 2 * TILE_BYTES, *vt = kt + TILE_BYTES;
 #pragma unroll
             for (int s = 0; s < UPT; ++s) {
                 const int u = tid + s * NT;
-                const int uu = u & 255, quad = uu >> 4, chunk = uu & 15;
-                if (u < 256)
-                    store_k_unit(kt, stage[s], quad, chunk);
+                if (u >= 2 * UNITS_K)
+                    continue;
+                const int uu = u < UNITS_K ? u : u - UNITS_K, quad = uu / CH, chunk = uu % CH;
+                if (u < UNITS_K)
+                    store_k_unit<DH>(kt, stage[s], quad, chunk);
                 else
-                    store_v_unit(vt, stage[s], quad, chunk);
+                    store_v_unit<DH>(vt, stage[s], quad, chunk);
             }
         };
 
@@ -408,7 +427,8 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                 load_tile(j + 1);                              // in flight while this tile is computed
 
             if (compute_wave) {
-                const char *kt = tiles + buf * 2 * MF_TILE_BYTES, *vt = kt + MF_TILE_BYTES;
+                const char *kt = tiles + buf * 2 * TILE_BYTES, *vt = kt + TILE_BYTES;
+                constexpr int TB_OFF = 32 * DH * 2;            // second block of 32 tokens in the K tile
                 // ---- S^T = K . Q^T for the two 32-token blocks of the tile, each K fragment feeding RB blocks
                 f32x16 acc_s[RB][2];
                 const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -417,14 +437,14 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                 for (int kk = 0; kk < 2; ++kk) {
                     const int co = ((2 * kk + hf) ^ sw) << 4;
                     kf[kk][0] = *(const uint4 *)(kt + krow_off + co);
-                    kf[kk][1] = *(const uint4 *)(kt + 8192 + krow_off + co);
+                    kf[kk][1] = *(const uint4 *)(kt + TB_OFF + krow_off + co);
                 }
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    if (kk + 2 < 8) {
+                for (int kk = 0; kk < NKK; ++kk) {
+                    if (kk + 2 < NKK) {
                         const int co = ((2 * (kk + 2) + hf) ^ sw) << 4;
                         kf[(kk + 2) % 3][0] = *(const uint4 *)(kt + krow_off + co);
-                        kf[(kk + 2) % 3][1] = *(const uint4 *)(kt + 8192 + krow_off + co);
+                        kf[(kk + 2) % 3][1] = *(const uint4 *)(kt + TB_OFF + krow_off + co);
                     }
 #pragma unroll
                     for (int tb = 0; tb < 2; ++tb)
@@ -443,21 +463,22 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                 for (int rb = 0; rb < RB; ++rb) {
                     if (tree_tile || partial)
                         mask_scores(acc_s[rb], (tree_tile ? tree_mask[rb] : ta_prefix_tile_mask(pos0, L, S)) >> (4 * hf));
-                    softmax_tile(acc_s[rb], c, m_run[rb], l_run[rb], acc_o[rb], pb[rb]);
+                    softmax_tile<NDB>(acc_s[rb], c, m_run[rb], l_run[rb], l2_run[rb], acc_o[rb], pb[rb]);
                 }
                 // ---- O^T += V^T . P^T, each V fragment feeding RB blocks
+                constexpr int KB_OFF = 2 * DH * 16;            // token slab kb of the V tile; step s = kb * NDB + db
                 uint4 vf[4];
 #pragma unroll
                 for (int s = 0; s < 3; ++s)
-                    vf[s] = *(const uint4 *)(vt + (s >> 2) * 4096 + vcol_off[s & 3]);
+                    vf[s] = *(const uint4 *)(vt + (s / NDB) * KB_OFF + vcol_off[s % NDB]);
 #pragma unroll
-                for (int s = 0; s < 16; ++s) {
-                    if (s + 3 < 16)
-                        vf[(s + 3) & 3] = *(const uint4 *)(vt + ((s + 3) >> 2) * 4096 + vcol_off[(s + 3) & 3]);
+                for (int s = 0; s < 4 * NDB; ++s) {
+                    if (s + 3 < 4 * NDB)
+                        vf[(s + 3) & 3] = *(const uint4 *)(vt + ((s + 3) / NDB) * KB_OFF + vcol_off[(s + 3) % NDB]);
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)
-                        acc_o[rb][s & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            as_bf16x8(vf[s & 3]), as_bf16x8(pb[rb][s >> 2]), acc_o[rb][s & 3], 0, 0, 0);
+                        acc_o[rb][s % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            as_bf16x8(vf[s & 3]), as_bf16x8(pb[rb][s / NDB]), acc_o[rb][s % NDB], 0, 0, 0);
                 }
             }
 
@@ -474,9 +495,9 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                 if (row < rows_here) {
                     const int64_t wrow = ta_ws_row(p, slot, rg, row);
                     const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32, TA_WAVE);
-                    const float inv = 1.f / l_tot;
+                    const float inv = 1.f / (l2_run[rb] + __shfl_xor(l2_run[rb], 32, TA_WAVE));
 #pragma unroll
-                    for (int db = 0; db < 4; ++db) {
+                    for (int db = 0; db < NDB; ++db) {
 #pragma unroll
                         for (int i4 = 0; i4 < 4; ++i4) {
                             float4 o;
@@ -484,7 +505,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                             o.y = acc_o[rb][db][4 * i4 + 1] * inv;
                             o.z = acc_o[rb][db][4 * i4 + 2] * inv;
                             o.w = acc_o[rb][db][4 * i4 + 3] * inv;
-                            *(float4 *)(p.ws_o + wrow * MF_D + db * 32 + 8 * i4 + 4 * hf) = o;
+                            *(float4 *)(p.ws_o + wrow * DH + db * 32 + 8 * i4 + 4 * hf) = o;
                         }
                     }
                     if (hf == 0)
@@ -984,22 +1005,22 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
     }
 }
 
-template <int NCW, int RB, int NT>
+template <int NCW, int RB, int NT, int DH>
 static hipError_t launch_variant(const TAParams &p, hipStream_t stream, int dev)
 {
-    const size_t smem = MF_STAGES * 2 * MF_TILE_BYTES + sizeof(unsigned long long) * TA_MAX_TREE + 16 +
+    const size_t smem = MF_STAGES * 2 * (TA_TILE * DH * 2) + sizeof(unsigned long long) * TA_MAX_TREE + 16 +
                         sizeof(int) * TA_MAX_TREE + sizeof(int) * (p.B + 2);
     static bool attr_set[64] = {};      // per device and variant; setting it twice is harmless
     if (dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
     if (!attr_set[dev]) {
-        hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_kv_kernel<NCW, RB, NT>,
+        hipError_t e = hipFuncSetAttribute((const void *)ta_mfma_kv_kernel<NCW, RB, NT, DH>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
         if (e != hipSuccess)
             return e;
         attr_set[dev] = true;
     }
-    hipLaunchKernelGGL((ta_mfma_kv_kernel<NCW, RB, NT>), dim3(p.n_wg, p.n_rg), dim3(NT), smem, stream, p);
+    hipLaunchKernelGGL((ta_mfma_kv_kernel<NCW, RB, NT, DH>), dim3(p.n_wg, p.n_rg), dim3(NT), smem, stream, p);
     return hipGetLastError();
 }
 
@@ -1007,11 +1028,13 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream, int dev)
 {
     if (p.rows_grp != 32 && p.rows_grp != 64 && p.rows_grp != 128 && p.rows_grp != 256)
         return hipErrorInvalidValue;
+    if (p.D == 64)                                         // the register-staged kernel is the only one for this head dim
+        return launch_variant<8, 1, 512, 64>(p, stream, dev);
     // One kernel for every row group: with fewer than 256 rows some of its eight waves only move tiles.
     const size_t smem = SP_AUX_OFF + sizeof(unsigned long long) * TA_MAX_TREE + 16 + sizeof(int) * TA_MAX_TREE +
                         sizeof(int) * PP_PAGES + sizeof(int) * (3 * p.B + 2);
     if (p.basic || smem > 160 * 1024 - 512)
-        return launch_variant<8, 1, 512>(p, stream, dev);  // register-staged kernel: very large batches, or on request
+        return launch_variant<8, 1, 512, 128>(p, stream, dev);   // register-staged kernel: very large batches, or on request
     static bool attr_set[64] = {};
     if (dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;

@@ -99,7 +99,11 @@ def test_option_errors():
     assert _plan(_good(Hq=514, Hkv=2))["kernel"] == ta.TA_KERNEL_GENERIC
     # the matrix-core kernel is bf16, head_dim 128, power-of-two pages only
     assert _plan(_good(dtype=ta.TA_F32), kernel=ta.TA_KERNEL_MFMA, check=False) == ta.TA_ERR_OPTS
-    assert _plan(_good(D=64), kernel=ta.TA_KERNEL_MFMA, check=False) == ta.TA_ERR_OPTS
+    assert _plan(_good(D=96), kernel=ta.TA_KERNEL_MFMA, check=False) == ta.TA_ERR_OPTS
+    # head_dim 64 runs on the matrix cores too, on the register-staged kernel (its row of the dispatch table)
+    p64 = _plan(_good(D=64))
+    assert p64["kernel"] == ta.TA_KERNEL_MFMA and p64["merge_kernel"] == ta.TA_MERGE_GENERAL
+    assert ta.tree_attn_dispatch_table()[p64["table_row"]]["family"] == ta.TA_KERNEL_MFMA_BASIC
     assert _plan(_good(ps=48), kernel=ta.TA_KERNEL_MFMA, check=False) == ta.TA_ERR_OPTS
 
 
