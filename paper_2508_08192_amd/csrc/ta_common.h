@@ -20,7 +20,7 @@ __device__ __forceinline__ void ta_raise(const TAParams &p, int bits)
 // Work schedule.  The KV pass walks, for every (request b, KV head g), a list of tiles:
 // ceil(L_b / TA_TILE) prefix tiles followed by one tile holding the T tree tokens.  A malformed
 // request owns a single tile (it only poisons its outputs).  All tile lists are laid end to end,
-// (b major, g minor), and workgroup w takes the contiguous share [w*share, (w+1)*share).  A share
+// (b major, g minor), and workgroup w takes a contiguous share of them (ta_wg_range).  A share
 // may start or end inside a list; every (workgroup, list) overlap produces one partial result in
 // slot w + (b*Hkv + g), which is unique because both terms grow along the walk.
 // The prefix lengths live on the device, so every workgroup derives the schedule itself.
@@ -49,7 +49,7 @@ __device__ __forceinline__ int ta_list_tiles(const TAParams &p, int L, int S)
 
 // The KV work of the batch is one line of schedule units: request after request, KV head after KV head, and
 // per (request, KV head) list one unit per tile (prefix tiles, then the tree tile) followed by p.pad units of
-// padding.  Workgroup w takes units [w * share, (w + 1) * share).  The padding stands for the fixed cost of starting
+// padding.  Workgroup w takes a contiguous range of units (ta_wg_range).  The padding stands for the fixed cost of starting
 // on a list: every workgroup pays that once for the list it begins in, whether at its first tile or in its middle,
 // and once more per list boundary inside its range -- which is exactly where it meets a padding.  A workgroup whose
 // range touches only the padding of a list has no work in it and writes no partial result.
@@ -95,6 +95,23 @@ __device__ __forceinline__ int ta_share(const TAParams &p, int total)
 {
     int share = (total + p.n_wg - 1) / p.n_wg;
     return share < p.min_q ? p.min_q : share;
+}
+
+// Units [t, t_end) of workgroup w.  The line is cut evenly, at floor(k * total / n_act), among the n_act workgroups
+// that have work: all of them when that gives each at least TA_EVEN_CUT_FROM units (and the smallest share), else
+// as many as whole shares of ceil(total / n_wg) units (at least min_q) fill, so that a small batch is not cut into
+// more partial results than it needs.  Whole shares alone would drift against lists of equal length whenever a list
+// is not a whole number of shares (128 lists of 265 units over 256 workgroups: shares of 133, so that workgroup 2j-1
+// ends j tiles inside list j and almost every workgroup enters a second list for a few tiles, at the full fixed cost
+// of an item); cut evenly, every second boundary falls on a list's edge.
+#define TA_EVEN_CUT_FROM 8
+__device__ __forceinline__ void ta_wg_range(const TAParams &p, int total, int w, int &t, int &t_end)
+{
+    const int share = ta_share(p, total);
+    const int floor_share = p.min_q > TA_EVEN_CUT_FROM ? p.min_q : TA_EVEN_CUT_FROM;
+    const int n_act = (int64_t)p.n_wg * floor_share <= total ? p.n_wg : (total + share - 1) / share;
+    t = w >= n_act ? total : (int)((int64_t)w * total / n_act);
+    t_end = w + 1 >= n_act ? total : (int)((int64_t)(w + 1) * total / n_act);
 }
 
 // Request whose tile lists contain global tile t (0 <= t < Hkv * cum[B]).

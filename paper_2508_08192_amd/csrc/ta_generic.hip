@@ -41,11 +41,10 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
 
     ta_build_schedule(p, cum);
     const int total = p.Hkv * cum[p.B];
-    const int share = ta_share(p, total);
     const int w = blockIdx.x, rg = blockIdx.y;
     const int lane = threadIdx.x % TA_WAVE, wave = threadIdx.x / TA_WAVE;
-    int t = w * share;
-    const int t_end = min(total, t + share);
+    int t, t_end;
+    ta_wg_range(p, total, w, t, t_end);
     const int rows_here = min(p.rows_grp, p.rows - rg * p.rows_grp);
 
     while (t < t_end) {

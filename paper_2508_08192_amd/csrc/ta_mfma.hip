@@ -235,15 +235,16 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
 
     ta_build_schedule(p, cum);
     const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
-    const int share = ta_share(p, total);
     const int w = blockIdx.x, rg = blockIdx.y;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // wave-uniform, lives in SGPRs
     const int r32 = lane & 31, hf = lane >> 5;
     const bool compute_wave = wave < NCW;
-    int t = w * share;
-    const int t_end = min(total, t + share);
+    int t, t_end;
+    ta_wg_range(p, total, w, t, t_end);
+    t = __builtin_amdgcn_readfirstlane(t);
+    t_end = __builtin_amdgcn_readfirstlane(t_end);
     const int rows_here = min(p.rows_grp, p.rows - rg * p.rows_grp);
     const float c = p.scale_log2e;
     // LDS byte offsets of this lane's fragments inside a tile
@@ -595,14 +596,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         flag[1] = 0;                   // set by an item that meets a bad page id or a bad given mask; see `bad` below
     ta_build_schedule(p, cum, lens, starts);
     const int total = __builtin_amdgcn_readfirstlane(p.Hkv * cum[p.B]);
-    const int share = ta_share(p, total);
     const int w = blockIdx.x, rg = blockIdx.y;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r32 = lane & 31, hf = lane >> 5;
-    int t = w * share;
-    const int t_end = min(total, t + share);
+    int t, t_end;
+    {
+        int t0, t1;
+        ta_wg_range(p, total, w, t0, t1);
+        t = __builtin_amdgcn_readfirstlane(t0);
+        t_end = __builtin_amdgcn_readfirstlane(t1);
+    }
     const int rows_here = min(p.rows_grp, p.rows - rg * p.rows_grp);
     const float c = p.scale_log2e;
     const bool paged = p.page_table != nullptr;
