@@ -259,7 +259,8 @@ int tree_attn_last_status(int32_t *host_status, void *stream);
  * rows per group, plan[6] = partial slots, plan[7] = workgroups of the merge pass, plan[8] = smallest share of
  * tiles per workgroup, plan[9] = schedule units a list counts (item_cost), plan[10] = merge kernel (0 general,
  * 1 head_dim 128, 2 head_dim 128 with one workgroup per row), plan[11] = row of the dispatch table that was
- * taken (-1: the options fixed everything), plan[12] = workspace bytes the call needs, plan[13..15] = 0.
+ * taken (-1: the options fixed everything), plan[12] = workspace bytes the call needs, plan[13] = format
+ * of the partial results (0: fp32; 1: 16-bit fixed point with one fp32 scale per row), plan[14..15] = 0.
  * HOST pointers.
  */
 int tree_attn_plan(const ta_tensor *q, const ta_tensor *k_cache, const ta_tensor *v_cache,

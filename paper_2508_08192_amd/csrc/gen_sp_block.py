@@ -31,7 +31,7 @@ A operand of the second product (rows = head-dim columns, contraction = tokens) 
 sets (16kb + 4hf + {0..3}, then + 8) follow the contraction slots the probabilities occupy after the first product.
 
 Small helpers move values between the two worlds: sp_zero_o, sp_load_q, sp_set_bases, sp_scale_o, sp_mask_A/B,
-sp_put_o.
+sp_put_o, sp_put_q15.
 
 S^T(i) and S^T(i+1) alternate between buffers A and B, so every block exists in an "A current" and a "B current"
 flavour.  P has one buffer: the PV MFMAs, which read P(i-1), come first in program order and the conversion that
@@ -420,9 +420,9 @@ def helpers():
                 lines.append("v_cndmask_b32 %s, %s, %s, vcc" % (v(base + 16 * tb + i), v(base + 16 * tb + i), v(TMP)))
         out.append(emit("sp_mask_" + cur, ["uint32_t lo", "uint32_t hi"], lines, [], ['[lo] "v"(lo)', '[hi] "v"(hi)'],
                         ['"memory"', '"vcc"']))
-    # Epilogue: O *= inv in place, then each lane's sixteen 16-byte pieces go to the row-major staging block in LDS;
-    # piece c of the lane lives at byte address a0 ^ (c << 5) (the caller folds the row, the lane half and the
-    # chunk swizzle into a0).
+    # Epilogue, fp32 partials: O *= inv in place, then each lane's sixteen 16-byte pieces go to the row-major staging
+    # block in LDS; piece c of the lane lives at byte address a0 ^ (c << 5) (the caller folds the row, the lane half
+    # and the chunk swizzle into a0).
     lines = ["s_nop 15", "s_nop 7"] + ["v_mul_f32 %s, %%[inv], %s" % (v(O + k), v(O + k)) for k in range(64)]
     for c in range(16):
         t = v(TMP + (c & 3))
@@ -430,6 +430,51 @@ def helpers():
         lines.append("ds_write_b128 %s, v[%d:%d]" % (t, O + 4 * c, O + 4 * c + 3))
     lines.append("s_waitcnt lgkmcnt(0)")
     out.append(emit("sp_put_o", ["float inv", "uint32_t a0"], lines, [], ['[inv] "v"(inv)', '[a0] "v"(a0)'], ['"memory"']))
+    # Epilogue, 16-bit partials: the lane's 64 values of O (its half of a query row) become 16-bit fixed point with one scale for the
+    # row -- value = scale * int16, scale = inv * (largest magnitude of the row) / 32767 -- and go to the row-major
+    # staging block in LDS, 256 bytes per row: the lane's piece c (four values, 8 bytes) lives at byte address
+    # a0 ^ (c << 4) (the caller folds row, lane half and chunk swizzle into a0).  The rounding to int16 is the
+    # "add 1.5 * 2^23" trick: the low 16 bits of the sum are the rounded value in two's complement.
+    # scale comes back NaN when the row holds a NaN (the sum of its values is one then).
+    T0, T1, T2, T3, AM, SU, XS = (TMP + i for i in range(7))
+    lines = ["s_nop 15", "s_nop 7"]
+    lines += ["v_max3_f32 %s, |%s|, |%s|, |%s|" % (v(AM), v(O), v(O + 1), v(O + 2)),
+              "v_max3_f32 %s, |%s|, |%s|, |%s|" % (v(T0), v(O + 3), v(O + 4), v(O + 5)),
+              "v_add_f32 %s, %s, %s" % (v(SU), v(O), v(O + 1)), "v_add_f32 %s, %s, %s" % (v(T1), v(O + 2), v(O + 3))]
+    for k in range(6, 64, 4):                                # two chains of maxima, two chains of sums
+        lines.append("v_max3_f32 %s, %s, |%s|, |%s|" % (v(AM), v(AM), v(O + k), v(O + k + 1)))
+        if k + 3 < 64:
+            lines.append("v_max3_f32 %s, %s, |%s|, |%s|" % (v(T0), v(T0), v(O + k + 2), v(O + k + 3)))
+    for k in range(4, 64, 2):
+        lines.append("v_add_f32 %s, %s, %s" % (v(SU) if (k // 2) % 2 == 0 else v(T1), v(SU) if (k // 2) % 2 == 0 else v(T1), v(O + k)))
+        lines.append("v_add_f32 %s, %s, %s" % (v(T1) if (k // 2) % 2 == 0 else v(SU), v(T1) if (k // 2) % 2 == 0 else v(SU), v(O + k + 1)))
+    lines += ["v_max_f32 %s, %s, %s" % (v(AM), v(AM), v(T0)), "v_add_f32 %s, %s, %s" % (v(SU), v(SU), v(T1)),
+              "v_mov_b32 %s, %s" % (v(XS), v(AM)), "s_nop 1", "v_permlane32_swap_b32 %s, %s" % (v(AM), v(XS)), "s_nop 1",
+              "v_max_f32 %s, %s, %s" % (v(AM), v(AM), v(XS)),             # both halves of a row see the row's maximum
+              "v_mov_b32 %s, %s" % (v(XS), v(SU)), "s_nop 1", "v_permlane32_swap_b32 %s, %s" % (v(SU), v(XS)), "s_nop 1",
+              "v_add_f32 %s, %s, %s" % (v(SU), v(SU), v(XS)),
+              "v_mul_f32 %s, %%[inv], %s" % (v(T0), v(AM)),
+              "v_mul_f32 %%[sc], 0x38000100, %s" % v(T0),                   # * 1/32767
+              "v_cmp_u_f32 vcc, %s, %s" % (v(SU), v(SU)),
+              "v_mov_b32 %s, 0x7fc00000" % v(T1),
+              "v_cndmask_b32 %%[sc], %%[sc], %s, vcc" % v(T1),
+              "v_rcp_f32 %s, %s" % (v(T2), v(AM)),
+              "v_cmp_gt_f32 vcc, %s, 0" % v(AM),
+              "s_nop 0",
+              "v_mul_f32 %s, 0x46fffe00, %s" % (v(T2), v(T2)),              # 32767 / max
+              "v_cndmask_b32 %s, 0, %s, vcc" % (v(AM), v(T2)),               # an all-zero row: every value stays 0
+              "v_mov_b32 %s, 0x4b400000" % v(SU),                            # 1.5 * 2^23
+              "v_mov_b32 %s, 0x05040100" % v(XS)]                            # byte selector: low halves of two registers
+    for c in range(16):
+        for j in range(4):
+            lines.append("v_fma_f32 %s, %s, %s, %s" % (v(T0 + j), v(O + 4 * c + j), v(AM), v(SU)))
+        lines.append("v_perm_b32 %s, %s, %s, %s" % (v(O + 2 * c), v(T1), v(T0), v(XS)))
+        lines.append("v_perm_b32 %s, %s, %s, %s" % (v(O + 2 * c + 1), v(T3), v(T2), v(XS)))
+        lines.append("v_xor_b32 %s, 0x%x, %%[a0]" % (v(T0), c << 4))
+        lines.append("ds_write_b64 %s, v[%d:%d]" % (v(T0), O + 2 * c, O + 2 * c + 1))
+    lines.append("s_waitcnt lgkmcnt(0)")
+    out.append(emit("sp_put_q15", ["float inv", "uint32_t a0", "float &sc"], lines, ['[sc] "=&v"(sc)'],
+                    ['[inv] "v"(inv)', '[a0] "v"(a0)'], ['"memory"', '"vcc"']))
     return "\n\n".join(out)
 
 

@@ -159,6 +159,38 @@ __device__ __forceinline__ int64_t ta_ws_row(const TAParams &p, int slot, int rg
     return ((int64_t)slot * p.n_rg + rg) * p.rows_grp + r;
 }
 
+// Partial outputs.  The matrix-core kernels keep them as 16-bit fixed point, one fp32 scale per row (value = scale *
+// int16, scale = largest magnitude of the row / 32767): every byte written here costs the KV pass several bytes of
+// its read stream (halving the partials took 4.5 % off the KV pass of batches with many short lists), the error is at
+// most 2^-16 of the row's largest value (fp16 would give 2^-11 of each value, too coarse beside the final rounding to
+// bf16 when outputs reach 2 and more), and there is no range to overflow.  A row with a NaN gets a NaN scale.
+// The scalar kernel, whose inputs may be fp32, keeps fp32 partials.
+typedef short ta_s4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ char *ta_part_row(const TAParams &p, int64_t wrow)      // first byte of partial row wrow
+{
+    return (char *)p.ws_o + wrow * (int64_t)p.D * (p.part_q15 ? 2 : 4);
+}
+
+__device__ __forceinline__ float ta_part_get(const TAParams &p, int64_t wrow, int d)
+{
+    return p.part_q15 ? p.ws_scale[wrow] * (float)((const short *)p.ws_o)[wrow * p.D + d] : p.ws_o[wrow * p.D + d];
+}
+
+// Scale of a row whose largest magnitude is amax (NaN if the row holds one), and the factor that maps its values to
+// int16.  An all-zero row keeps scale 0.
+__device__ __forceinline__ void ta_q15_scale(float amax, bool has_nan, float &scale, float &to_q)
+{
+    scale = has_nan ? __uint_as_float(0x7fc00000u) : amax * (1.f / 32767.f);
+    to_q = amax > 0.f ? 32767.f / amax : 0.f;
+}
+
+__device__ __forceinline__ uint32_t ta_q15_pack(float a, float b, float to_q)      // two values -> two int16
+{
+    const int qa = __float2int_rn(a * to_q), qb = __float2int_rn(b * to_q);
+    return ((uint32_t)qa & 0xffffu) | ((uint32_t)qb << 16);
+}
+
 // A page id comes from the caller's page table: one outside the cache must never become an address.
 __device__ __forceinline__ bool ta_page_ok(const TAParams &p, int page)
 {

@@ -347,7 +347,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
 #pragma unroll
                 for (int c = 0; c < GEN_DCHUNKS; ++c) {
                     const int d = lane + c * TA_WAVE;
-                    v[u][c] = d < p.D ? p.ws_o[(row0 + (k + u) * pstride) * p.D + d] : 0.f;
+                    v[u][c] = d < p.D ? ta_part_get(p, row0 + (k + u) * pstride, d) : 0.f;
                 }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -363,7 +363,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
             for (int c = 0; c < GEN_DCHUNKS; ++c) {
                 const int d = lane + c * TA_WAVE;
                 if (d < p.D)
-                    acc[c] = fmaf(wgt, p.ws_o[(row0 + k * pstride) * p.D + d], acc[c]);
+                    acc[c] = fmaf(wgt, ta_part_get(p, row0 + k * pstride, d), acc[c]);
             }
         }
     } else {
@@ -394,7 +394,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
             for (int c = 0; c < GEN_DCHUNKS; ++c) {
                 const int d = lane + c * TA_WAVE;
                 if (d < p.D)
-                    acc[c] = fmaf(wgt, p.ws_o[(row0 + k * pstride) * p.D + d], acc[c]);
+                    acc[c] = fmaf(wgt, ta_part_get(p, row0 + k * pstride, d), acc[c]);
             }
         }
     }
@@ -431,7 +431,19 @@ __device__ __forceinline__ float ta_half_sum(float x)
     return x;
 }
 
-template <bool NEW>
+// Four neighbouring columns of one partial row: fp32, or (HP) int16, which the caller's weight carries the scale of.
+template <bool HP>
+__device__ __forceinline__ float4 ta_part_load4(const char *ptr)
+{
+    if constexpr (HP) {
+        const ta_s4 x = *(const ta_s4 *)ptr;
+        return make_float4((float)x.x, (float)x.y, (float)x.z, (float)x.w);
+    } else {
+        return *(const float4 *)ptr;
+    }
+}
+
+template <bool NEW, bool HP>
 __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
 {
     const int seg = blockIdx.x;
@@ -460,14 +472,18 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
     const int node = R / p.G, h = g * p.G + R % p.G;
     const int64_t row0 = ta_ws_row(p, w_first + seg, rg, r);              // partial k of this row: row0 + k*pstride
     const int64_t pstride = (int64_t)p.n_rg * p.rows_grp;
-    const float *o0 = p.ws_o + row0 * 128 + 4 * hl;
-    const int64_t ostride = pstride * 128;
+    constexpr int EB = HP ? 2 : 4;                         // bytes per element of a partial output
+    const char *o0 = (const char *)p.ws_o + (row0 * 128 + 4 * hl) * EB;
+    const int64_t ostride = pstride * 128 * EB;
 
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float lse2;
     if (n_parts <= 32) {
         // lane k of the half owns partial k
         const float lk = hl < n_parts ? p.ws_lse[row0 + hl * pstride] : -INFINITY;
+        float sk = 1.f;                                                   // scale of the partial's 16-bit values
+        if constexpr (HP)
+            sk = hl < n_parts ? p.ws_scale[row0 + hl * pstride] : 1.f;
         if constexpr (NEW)
             ta_scatter_locate(p, b, g, sc);
         const bool nan_seen = ta_half_max(lk != lk ? 1.f : 0.f) > 0.f;
@@ -475,14 +491,14 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
         const float ek = exp2f(lk - mx);                                  // 0 for the idle lanes
         const float den = ta_half_sum(ek);
         lse2 = nan_seen ? QNAN : mx + log2f(den);
-        const float wk = nan_seen ? QNAN : ek / den;
+        const float wk = nan_seen ? QNAN : ek / den * sk;
         const int src0 = lane & 32;
         int k = 0;
         for (; k + 4 <= n_parts; k += 4) {
             float4 v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                v[u] = *(const float4 *)(o0 + (k + u) * ostride);
+                v[u] = ta_part_load4<HP>(o0 + (k + u) * ostride);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const float wgt = __shfl(wk, src0 + k + u, TA_WAVE);
@@ -498,7 +514,7 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
 #pragma unroll
         for (int u = 0; u < 3; ++u)
             if (k + u < n_parts)
-                v[u] = *(const float4 *)(o0 + (k + u) * ostride);
+                v[u] = ta_part_load4<HP>(o0 + (k + u) * ostride);
 #pragma unroll
         for (int u = 0; u < 3; ++u)
             if (k + u < n_parts) {
@@ -532,8 +548,10 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
         den = ta_half_sum(den);
         lse2 = nan_seen ? QNAN : mx + log2f(den);
         for (int k = 0; k < n_parts; ++k) {
-            const float wgt = exp2f(p.ws_lse[row0 + k * pstride] - lse2);  // same address in every lane of the half
-            const float4 v = *(const float4 *)(o0 + k * ostride);
+            float wgt = exp2f(p.ws_lse[row0 + k * pstride] - lse2);        // same address in every lane of the half
+            if constexpr (HP)
+                wgt *= p.ws_scale[row0 + k * pstride];
+            const float4 v = ta_part_load4<HP>(o0 + k * ostride);
             acc.x = fmaf(wgt, v.x, acc.x);
             acc.y = fmaf(wgt, v.y, acc.y);
             acc.z = fmaf(wgt, v.z, acc.z);
@@ -563,7 +581,7 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
 // (With the kernel above a half-wave walks all partials of its row alone: 256 partials took 38 us, now about 7.)
 constexpr int MW_HALVES = 8, MW_FLIGHT = 8;
 
-template <bool NEW>
+template <bool NEW, bool HP>
 __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
 {
     __shared__ float red[8];
@@ -582,18 +600,24 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
     const int node = R / p.G, h = g * p.G + R % p.G;
     const int64_t row0 = ta_ws_row(p, w_first + seg, rg, r);              // partial k of this row: row0 + k*pstride
     const int64_t pstride = (int64_t)p.n_rg * p.rows_grp;
-    const float *o0 = p.ws_o + row0 * 128 + 4 * hl;
-    const int64_t ostride = pstride * 128;
+    constexpr int EB = HP ? 2 : 4;                         // bytes per element of a partial output
+    const char *o0 = (const char *)p.ws_o + (row0 * 128 + 4 * hl) * EB;
+    const int64_t ostride = pstride * 128 * EB;
 
     // first round of this half-wave's partials (hw, hw + 8, ...): outputs and their log-sum-exps
     float4 v[MW_FLIGHT];
-    float lk[MW_FLIGHT];
+    float lk[MW_FLIGHT], sk[MW_FLIGHT];                    // log-sum-exps and (16-bit partials) scales
+#pragma unroll
+    for (int u = 0; u < MW_FLIGHT; ++u)
+        sk[u] = 1.f;
 #pragma unroll
     for (int u = 0; u < MW_FLIGHT; ++u) {
         const int k = hw + MW_HALVES * u;
         if (k < n_parts) {
-            v[u] = *(const float4 *)(o0 + k * ostride);
+            v[u] = ta_part_load4<HP>(o0 + k * ostride);
             lk[u] = p.ws_lse[row0 + k * pstride];
+            if constexpr (HP)
+                sk[u] = p.ws_scale[row0 + k * pstride];
         }
     }
     if constexpr (NEW)
@@ -634,15 +658,17 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
             for (int u = 0; u < MW_FLIGHT; ++u) {
                 const int k = k0 + MW_HALVES * u;
                 if (k < n_parts) {
-                    v[u] = *(const float4 *)(o0 + k * ostride);
+                    v[u] = ta_part_load4<HP>(o0 + k * ostride);
                     lk[u] = p.ws_lse[row0 + k * pstride];
+                    if constexpr (HP)
+                        sk[u] = p.ws_scale[row0 + k * pstride];
                 }
             }
         }
 #pragma unroll
         for (int u = 0; u < MW_FLIGHT; ++u) {
             if (k0 + MW_HALVES * u < n_parts) {
-                const float wgt = nan_seen ? QNAN : exp2f(lk[u] - lse2);
+                const float wgt = nan_seen ? QNAN : exp2f(lk[u] - lse2) * sk[u];
                 acc.x = fmaf(wgt, v[u].x, acc.x);
                 acc.y = fmaf(wgt, v[u].y, acc.y);
                 acc.z = fmaf(wgt, v[u].z, acc.z);
@@ -685,15 +711,23 @@ hipError_t ta_launch_merge(const TAParams &p, hipStream_t stream)
     dim3 grid(p.B * p.Hkv, (p.rows + rows_wg - 1) / rows_wg);
     // (the instances with the write-back folded in also copy the tree tokens' K/V into the caches)
     if (p.merge_kind == TA_MERGE_D128_WIDE) {
-        if (p.kn)
-            hipLaunchKernelGGL(ta_merge128_wide_kernel<true>, grid, dim3(256), smem, stream, p);
+        if (p.kn && p.part_q15)
+            hipLaunchKernelGGL((ta_merge128_wide_kernel<true, true>), grid, dim3(256), smem, stream, p);
+        else if (p.kn)
+            hipLaunchKernelGGL((ta_merge128_wide_kernel<true, false>), grid, dim3(256), smem, stream, p);
+        else if (p.part_q15)
+            hipLaunchKernelGGL((ta_merge128_wide_kernel<false, true>), grid, dim3(256), smem, stream, p);
         else
-            hipLaunchKernelGGL(ta_merge128_wide_kernel<false>, grid, dim3(256), smem, stream, p);
+            hipLaunchKernelGGL((ta_merge128_wide_kernel<false, false>), grid, dim3(256), smem, stream, p);
     } else if (p.merge_kind == TA_MERGE_D128) {
-        if (p.kn)
-            hipLaunchKernelGGL(ta_merge128_kernel<true>, grid, dim3(256), smem, stream, p);
+        if (p.kn && p.part_q15)
+            hipLaunchKernelGGL((ta_merge128_kernel<true, true>), grid, dim3(256), smem, stream, p);
+        else if (p.kn)
+            hipLaunchKernelGGL((ta_merge128_kernel<true, false>), grid, dim3(256), smem, stream, p);
+        else if (p.part_q15)
+            hipLaunchKernelGGL((ta_merge128_kernel<false, true>), grid, dim3(256), smem, stream, p);
         else
-            hipLaunchKernelGGL(ta_merge128_kernel<false>, grid, dim3(256), smem, stream, p);
+            hipLaunchKernelGGL((ta_merge128_kernel<false, false>), grid, dim3(256), smem, stream, p);
     } else {
         if (p.kn)
             hipLaunchKernelGGL(ta_merge_kernel<true>, grid, dim3(GEN_THREADS), smem, stream, p);

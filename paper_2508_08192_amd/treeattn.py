@@ -351,5 +351,6 @@ def tree_attn_plan(q, k_cache, v_cache, page_table, seq_lens, tree_parent, out, 
             raise TreeAttnError(rc, "tree_attn_plan")
         return rc
     keys = ("kernel", "kv_workgroups", "threads", "tile", "row_groups", "rows_per_group", "partial_slots",
-            "merge_workgroups", "min_share", "item_cost", "merge_kernel", "table_row", "workspace_bytes")
+            "merge_workgroups", "min_share", "item_cost", "merge_kernel", "table_row", "workspace_bytes",
+            "partials_q15")
     return dict(zip(keys, [int(x) for x in plan]))

@@ -967,3 +967,63 @@ def test_random_shapes_against_oracle(seed):
                         page_size=ps, dtype="bf16", seed=9100 + seed, paged=ps > 0)
     _check(w, "random seed=%d T=%d G=%d Hkv=%d B=%d ps=%d L=%r splits=%d" % (seed, T, G, Hkv, B, ps, seq_lens, splits),
            kernel=MFMA, num_splits=splits)
+
+
+def _plan_of(w, **opts):
+    from paper_2508_08192_amd import treeattn as ta
+    d = to_device(w)
+    return ta.tree_attn_plan(d["q"], d["k_cache"], d["v_cache"], d["page_table"], d["seq_lens"], d["tree_parent"],
+                             d["out"], d["lse"], scale=w.scale, **opts)
+
+
+@pytest.mark.parametrize("kernel", [0, MFMA_BASIC])
+@pytest.mark.parametrize("rows", [32, 256])
+def test_both_formats_of_the_partial_results(kernel, rows):
+    """The matrix-core kernels hand their partial results to the merge pass as fp32 or, where a workgroup writes many
+    rows, as 16-bit fixed point with one scale per row.  Both against the oracle on both kernels, with forced splits so
+    that every list has several partials, and with one KV head's values 64 times smaller than the other's (the scale
+    is per row)."""
+    rng = np.random.default_rng(rows)
+    T, Hq, Hkv = (8, 8, 2) if rows == 32 else (64, 8, 2)
+    B = 5
+    trees = np.stack([W.random_tree(T, 6, rng) for _ in range(B)])
+    w = W.make_workload("fmt", B=B, T=T, Hq=Hq, Hkv=Hkv, D=128, seq_lens=rng.integers(100, 1500, size=B), trees=trees,
+                        page_size=64, dtype="bf16", seed=900 + rows)
+    v = w.v_cache.view(np.uint16)
+    small = v[:, 1]                                      # KV head 1: exponent down by 6
+    keep = (small & 0x7f80) > (6 << 7)
+    v[:, 1] = np.where(keep, small - (6 << 7), small & 0x8000).astype(np.uint16)
+    plan = _plan_of(w, kernel=kernel)
+    assert plan["partials_q15"] == (1 if rows == 256 else 0), plan
+    _check(w, "partials rows=%d kernel=%d" % (rows, kernel), kernel=kernel)
+    _check(w, "partials rows=%d kernel=%d, 37 shares" % (rows, kernel), kernel=kernel, num_splits=37)
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA, MFMA_BASIC])
+@pytest.mark.parametrize("rows", [32, 256])
+def test_a_nan_among_the_attended_values_reaches_the_output(kernel, rows):
+    """A NaN in a value every node of a request attends to: the output column it belongs to is NaN for every row of
+    that KV head (with 16-bit partials the whole row is: the row's scale carries the NaN); other KV heads and other
+    requests stay finite and right."""
+    rng = np.random.default_rng(7 + rows)
+    T, Hq, Hkv = (8, 8, 2) if rows == 32 else (64, 8, 2)
+    B, ps = 3, 64
+    trees = np.stack([W.random_tree(T, 6, rng) for _ in range(B)])
+    w = W.make_workload("nanv", B=B, T=T, Hq=Hq, Hkv=Hkv, D=128, seq_lens=[300, 700, 450], trees=trees,
+                        page_size=ps, dtype="bf16", seed=950 + rows)
+    ref, ref_lse = run_oracle(w)
+    b, pos, g, col = 1, 133, 0, 3
+    page = int(w.page_table[b, pos // ps])
+    w.v_cache.view(np.uint16)[page, g, pos % ps, col] = 0x7fc0
+    _announce("NaN value rows=%d kernel=%d" % (rows, kernel))
+    got, got_lse = run_hip(w, kernel=kernel, num_splits=9)
+    G = Hq // Hkv
+    hit = np.zeros_like(got, dtype=bool)
+    hit[b, :, g * G:(g + 1) * G, :] = True
+    assert np.isnan(got[b, :, g * G:(g + 1) * G, col]).all()
+    assert np.isfinite(got[~hit]).all()
+    assert np.abs(got[~hit] - ref[~hit]).max() <= 1e-2
+    rest = got[b, :, g * G:(g + 1) * G, :]
+    ok = np.isnan(rest) | (np.abs(rest - ref[b, :, g * G:(g + 1) * G, :]) <= 1e-2)
+    assert ok.all()
+    assert np.abs(got_lse - ref_lse).max() <= 1e-3      # the log-sum-exps do not see the values
