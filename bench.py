@@ -466,7 +466,7 @@ def main():
                    "merge_pass_us": mo["merge_us"], "hbm_frac": mo["hbm_frac"],
                    "mfma_frac": mo["mfma_frac"], "hbm_GBps": mo["kv_alg"] / (mo["kv_us"] * 1e-6) / 1e9,
                    "algorithmic_bytes": mo["alg_bytes"], "useful_flops": mo["flops"], "kv_pools": mo["n_pools"],
-                   "table_row": mo["plan"]["table_row"]}
+                   "table_row": mo["plan"]["table_row"], "partials_q15": mo["plan"]["partials_q15"]}
             if mo["n_pools"] > 1:
                 # working set below the last-level cache: the figures above are "cold" (every step streams another
                 # copy of the KV pool from HBM); "hot" repeats the step on one pool
