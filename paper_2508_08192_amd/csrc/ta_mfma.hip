@@ -670,14 +670,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
     auto lane_offsets = [&](uint32_t &koff0, uint32_t &koff1, uint32_t &voff0, uint32_t &voff1) {
         const int x = fresh_tid();
         const int wv = x >> 6, ln = x & 63;
-        const int drow = wv * 8 + (ln >> 4), dslot = ln & 15;
-        koff0 = (uint32_t)(drow * kss + (dslot ^ (drow & 15)) * 8) * 2u;
-        koff1 = (uint32_t)((drow + 4) * kss + (dslot ^ ((drow + 4) & 15)) * 8) * 2u;
-        voff0 = (uint32_t)(drow * vss + (dslot ^ (2 * (drow & 7))) * 8) * 2u;
-        voff1 = (uint32_t)((drow + 4) * vss + (dslot ^ (2 * ((drow + 4) & 7))) * 8) * 2u;
+        // relative to the first of the wave's eight token rows (tile rows 8 wv .. 8 wv + 7): the wave's loads start
+        // from that row's address, so that a tile may span several pages as long as these eight rows share one
+        const int lrow = ln >> 4, drow = wv * 8 + lrow, dslot = ln & 15;
+        koff0 = (uint32_t)(lrow * kss + (dslot ^ (drow & 15)) * 8) * 2u;
+        koff1 = (uint32_t)((lrow + 4) * kss + (dslot ^ ((drow + 4) & 15)) * 8) * 2u;
+        voff0 = (uint32_t)(lrow * vss + (dslot ^ (2 * (drow & 7))) * 8) * 2u;
+        voff1 = (uint32_t)((lrow + 4) * vss + (dslot ^ (2 * ((drow + 4) & 7))) * 8) * 2u;
     };
-    // one page (or the contiguous cache) holds a whole aligned tile, and lane offsets fit 32 bits
-    const bool fast_geom = (!paged || p.ps_shift >= 6) && kss < (1u << 22) && vss < (1u << 22);
+    // a page (or the contiguous cache) holds the eight aligned token rows a wave loads of a tile, i.e. pages of eight
+    // tokens and more; and lane offsets fit 32 bits
+    const bool fast_geom = (!paged || p.ps_shift >= 3) && kss < (1u << 22) && vss < (1u << 22);
 
     int b_next = -1;                                   // request of the previous item
     while (t < t_end) {
@@ -781,10 +784,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             const uint32_t vdst = lds0 + SP_V_OFF + vs * MF_TILE_BYTES + wave * 2048;
             const int pos0 = tile_pos0(ti), cnt = tile_count(ti);
             if (fast_geom && !tile_ragged(ti)) {
-                uint32_t pg = (uint32_t)b, sl = (uint32_t)pos0;
+                const int posw = pos0 + 8 * wave;              // first of this wave's eight rows
+                uint32_t pg = (uint32_t)b, sl = (uint32_t)posw;
                 if (paged) {
-                    pg = (uint32_t)__builtin_amdgcn_readfirstlane(pcache[(pos0 >> p.ps_shift) - span_first_page]);
-                    sl = (uint32_t)(pos0 & (p.ps - 1));
+                    pg = (uint32_t)__builtin_amdgcn_readfirstlane(pcache[(posw >> p.ps_shift) - span_first_page]);
+                    sl = (uint32_t)(posw & (p.ps - 1));
                 }
                 const uint16_t *kb_ = kgp + (uint64_t)pg * ksp + (uint64_t)sl * kss;
                 const uint16_t *vb_ = vgp + (uint64_t)pg * vsp + (uint64_t)sl * vss;
@@ -962,7 +966,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             while (i < ns) {
                 if (!(i & 1) && i >= 2 && fast_geom && i + 4 < n_plain) {
                     const uint32_t pairs = (uint32_t)((n_plain - 5 - i) / 2 + 1);
-                    uint32_t cnt = pairs, pos = (uint32_t)((tile0 + j0 + s0 + i + 3) * TA_TILE);
+                    // (the loop looks pages up by `pos`, per wave: the position of the wave's first row of tile i+3)
+                    uint32_t cnt = pairs, pos = (uint32_t)((tile0 + j0 + s0 + i + 3) * TA_TILE + 8 * wave);
                     uint32_t ik_o = ik * MF_TILE_BYTES, iv_o = iv * MF_TILE_BYTES, kn_o = kn * MF_TILE_BYTES;
                     uint32_t vp_o = vp * MF_TILE_BYTES;
                     const uint32_t pshift = paged ? (uint32_t)p.ps_shift : 31u;
