@@ -93,6 +93,13 @@ def load_library():
             raise ImportError(
                 "libtreeattn.so is not built: run `python -m paper_2508_08192_amd.build` "
                 "(there is no CPU fallback for the tree-attention kernels)")
+        # The callers' device memory and streams come from PyTorch, which ships a HIP runtime of its own: it has to be
+        # in the process before this library is, so that both bind to the same one (loaded the other way round, the
+        # library would sit on the system's runtime, PyTorch on its own, and every call here would fail).
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = ctypes.CDLL(LIB_PATH)
         T = ctypes.POINTER(ta_tensor)
         lib.tree_attn_fwd.restype = ctypes.c_int

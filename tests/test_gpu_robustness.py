@@ -254,3 +254,21 @@ def test_measurement_probes_run():
     torch.cuda.synchronize()
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     assert flop == cus * 8 * 32 * 10 * 32768 and float(fsink.item()) == 0.0
+
+
+def test_the_binding_is_the_first_thing_a_process_uses():
+    """A process whose first GPU call goes through the binding, before it has imported PyTorch itself: the binding has
+    to bring PyTorch's HIP runtime in before the library (two runtimes in one process: every call fails)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("from paper_2508_08192_amd import treeattn as ta\n"
+            "print('status', ta.tree_attn_last_status())\n"
+            "import torch\n"
+            "x = torch.ones(1 << 20, device='cuda')\n"
+            "s = torch.zeros(64, dtype=torch.float32, device='cuda')\n"
+            "print('read', ta.tree_attn_stream_read(x, s))\n")
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, stdout=subprocess.PIPE, stderr=subprocess.STDOUT,
+                         text=True, timeout=300)
+    assert out.returncode == 0 and "status 0" in out.stdout, out.stdout

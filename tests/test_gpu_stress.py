@@ -22,7 +22,7 @@ def _case(seed):
     G = int(rng.choice([1, 2, 4, 5, 8]))
     Hkv = int(rng.choice([1, 2]))
     B = int(rng.integers(1, 4))
-    ps = int(rng.choice([0, 16, 64, 128]))
+    ps = int(rng.choice([0, 4, 8, 16, 32, 64, 128]))
     Lmax = int(rng.choice([200, 3000, 20000]))
     lens = [int(rng.integers(0, Lmax + 1)) for _ in range(B)]
     trees = np.stack([W.random_tree(T, int(rng.integers(2, 8)), rng) for _ in range(B)])
