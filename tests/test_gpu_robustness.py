@@ -272,3 +272,41 @@ def test_the_binding_is_the_first_thing_a_process_uses():
     out = subprocess.run([sys.executable, "-c", code], cwd=root, stdout=subprocess.PIPE, stderr=subprocess.STDOUT,
                          text=True, timeout=300)
     assert out.returncode == 0 and "status 0" in out.stdout, out.stdout
+
+
+def test_calls_on_two_streams_each_with_a_workspace_of_its_own():
+    """Calls that overlap in time bring their own workspaces: two different batches (one with 16-bit partial results,
+    one with fp32 ones) launched alternately on two streams, twenty times each without a synchronisation in between,
+    both against the oracle."""
+    import torch
+    from paper_2508_08192_amd import treeattn as ta
+    rng = np.random.default_rng(99)
+    wa = W.make_workload("two_a", B=4, T=64, Hq=8, Hkv=2, D=128, seq_lens=rng.integers(500, 6000, size=4),
+                         trees=W.bfs_tree(64, [4, 2], 8), page_size=16, dtype="bf16", seed=9901)
+    wb = W.make_workload("two_b", B=6, T=8, Hq=8, Hkv=2, D=128, seq_lens=rng.integers(100, 9000, size=6),
+                         trees=W.random_tree(8, 4, rng), page_size=64, dtype="bf16", seed=9902)
+    refs = [run_oracle(wa), run_oracle(wb)]
+    devs = [to_device(wa), to_device(wb)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    wss, plans = [], []
+    for w, d in zip((wa, wb), devs):
+        plan = ta.tree_attn_plan(d["q"], d["k_cache"], d["v_cache"], d["page_table"], d["seq_lens"], d["tree_parent"],
+                                 d["out"], d["lse"])
+        plans.append(plan)
+        wss.append(torch.empty(plan["workspace_bytes"], dtype=torch.uint8, device="cuda"))
+    assert plans[0]["partials_q15"] == 1 and plans[1]["partials_q15"] == 0
+    _announce("two streams, two workspaces")
+    torch.cuda.synchronize()
+    for rep in range(20):
+        for d, st, ws in zip(devs, streams, wss):
+            if rep == 19:
+                with torch.cuda.stream(st):
+                    d["out"].fill_(float("nan"))
+            ta.tree_attn_fwd_ex(d["q"], d["k_cache"], d["v_cache"], d["page_table"], d["seq_lens"], d["tree_parent"],
+                                d["out"], d["lse"], stream=st, workspace=ws)
+    torch.cuda.synchronize()
+    for (ref, ref_lse), d, w in zip(refs, devs, (wa, wb)):
+        got = d["out"].float().cpu().numpy().astype(np.float64)
+        got_lse = d["lse"].cpu().numpy().astype(np.float64)
+        assert_parity(got, got_lse, ref, ref_lse, "bf16", w.name)
+    assert ta.tree_attn_last_status() == 0
