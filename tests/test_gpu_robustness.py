@@ -310,3 +310,42 @@ def test_calls_on_two_streams_each_with_a_workspace_of_its_own():
         got_lse = d["lse"].cpu().numpy().astype(np.float64)
         assert_parity(got, got_lse, ref, ref_lse, "bf16", w.name)
     assert ta.tree_attn_last_status() == 0
+
+
+@pytest.mark.parametrize("kernel", [0, MFMA_BASIC, GENERIC])
+def test_caches_beyond_four_gigabytes(kernel):
+    """Page ids whose byte offsets need more than 32 bits: the requests' pages sit at the far end of caches of 5.2 GB
+    each (40 000 pages of 64 tokens x 8 KV heads)."""
+    import torch
+    rng = np.random.default_rng(4321)
+    B, T, ps = 3, 16, 64
+    trees = np.stack([W.random_tree(T, 5, rng) for _ in range(B)])
+    w = W.make_workload("big", B=B, T=T, Hq=32, Hkv=8, D=128, seq_lens=[3000, 64, 1500], trees=trees, page_size=ps,
+                        dtype="bf16", seed=4322)
+    ref, ref_lse = run_oracle(w)
+    dev = to_device(w)
+    n_small, n_big = dev["k_cache"].shape[0], 40000
+    big_k = torch.empty((n_big,) + tuple(dev["k_cache"].shape[1:]), dtype=torch.bfloat16, device="cuda")
+    big_v = torch.empty_like(big_k)
+    remap = torch.from_numpy(rng.permutation(np.arange(n_big - 3000, n_big))[:n_small].astype(np.int64)).cuda()
+    big_k[remap] = dev["k_cache"]
+    big_v[remap] = dev["v_cache"]
+    table = dev["page_table"].long()
+    dev["page_table"] = torch.where((table >= 0) & (table < n_small), remap[table.clamp(0, n_small - 1)], table).int()
+    dev["k_cache"], dev["v_cache"] = big_k, big_v
+    _announce("caches of 5.2 GB, kernel=%d" % kernel)
+    got, got_lse = run_hip(w, dev, kernel=kernel)
+    assert_parity(got, got_lse, ref, ref_lse, "bf16", "caches beyond 4 GB")
+    del big_k, big_v, dev
+    torch.cuda.empty_cache()
+
+
+def test_a_prefix_of_a_million_tokens():
+    """One request with 1 000 000 cached tokens (positions and tile indices far beyond 16 bits), pages of 16 tokens."""
+    rng = np.random.default_rng(1000000)
+    w = W.make_workload("million", B=1, T=4, Hq=2, Hkv=1, D=128, seq_lens=[1000000], trees=W.chain_tree(4), page_size=16,
+                        dtype="bf16", seed=1000001)
+    _announce("one million tokens")
+    ref, ref_lse = run_oracle(w)
+    got, got_lse = run_hip(w)
+    assert_parity(got, got_lse, ref, ref_lse, "bf16", "one million tokens")
