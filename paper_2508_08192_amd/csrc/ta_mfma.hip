@@ -667,9 +667,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
     };
     // (recomputed where needed rather than kept: a value that lives across the whole walk would be spilled, and a
     // reload from scratch memory waits for every cache load in flight)
-    auto lane_offsets = [&](uint32_t &koff0, uint32_t &koff1, uint32_t &voff0, uint32_t &voff1) {
-        const int x = fresh_tid();
-        const int wv = x >> 6, ln = x & 63;
+    auto lane_offsets = [&](uint32_t &koff0, uint32_t &koff1, uint32_t &voff0, uint32_t &voff1, int wv) {
+        const int ln = fresh_tid() & 63;
         // relative to the first of the wave's eight token rows (tile rows 8 wv .. 8 wv + 7): the wave's loads start
         // from that row's address, so that a tile may span several pages as long as these eight rows share one
         const int lrow = ln >> 4, drow = wv * 8 + lrow, dslot = ln & 15;
@@ -779,12 +778,13 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         int span_first_page = 0;
         // Cache loads of tile ti into K slot ks and V slot vs: four 16-byte loads per lane.  Rows past the tile's
         // end, and rows before a window start, re-read its first attended token (their probabilities are exactly zero).
-        auto issue_tile = [&](int ti, int ks, int vs) {
-            const uint32_t kdst = lds0 + ks * MF_TILE_BYTES + wave * 2048;
-            const uint32_t vdst = lds0 + SP_V_OFF + vs * MF_TILE_BYTES + wave * 2048;
+        // (wsel: the wave whose eight token rows are loaded -- this one's, or an active wave's that a helper serves)
+        auto issue_rows = [&](int ti, int ks, int vs, int wsel) {
+            const uint32_t kdst = lds0 + ks * MF_TILE_BYTES + wsel * 2048;
+            const uint32_t vdst = lds0 + SP_V_OFF + vs * MF_TILE_BYTES + wsel * 2048;
             const int pos0 = tile_pos0(ti), cnt = tile_count(ti);
             if (fast_geom && !tile_ragged(ti)) {
-                const int posw = pos0 + 8 * wave;              // first of this wave's eight rows
+                const int posw = pos0 + 8 * wsel;              // first of that wave's eight rows
                 uint32_t pg = (uint32_t)b, sl = (uint32_t)posw;
                 if (paged) {
                     pg = (uint32_t)__builtin_amdgcn_readfirstlane(pcache[(posw >> p.ps_shift) - span_first_page]);
@@ -793,14 +793,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 const uint16_t *kb_ = kgp + (uint64_t)pg * ksp + (uint64_t)sl * kss;
                 const uint16_t *vb_ = vgp + (uint64_t)pg * vsp + (uint64_t)sl * vss;
                 uint32_t koff0, koff1, voff0, voff1;
-                lane_offsets(koff0, koff1, voff0, voff1);
+                lane_offsets(koff0, koff1, voff0, voff1, wsel);
                 dma16s(kb_, koff0, kdst);
                 dma16s(kb_, koff1, kdst + 1024);
                 dma16s(vb_, voff0, vdst);
                 dma16s(vb_, voff1, vdst + 1024);
             } else {
                 const int x = fresh_tid();
-                const int drow = (x >> 6) * 8 + ((x & 63) >> 4), dslot = x & 15;
+                const int drow = wsel * 8 + ((x & 63) >> 4), dslot = x & 15;
                 // rows past the tile's end and rows before the window start read the tile's first attended token
                 const int lo = max(0, S - pos0);
                 auto row_pos = [&](int r) { return pos0 + (r < cnt && r >= lo ? r : lo); };
@@ -833,13 +833,38 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 dma16(vb0 + ve[1], vdst + 1024);
             }
         };
-        auto wait_loads = [&](int tiles_in_flight) {       // all but the youngest tiles_in_flight*4 loads are done
-            if (tiles_in_flight >= 2)
-                vm_wait<8>();
-            else if (tiles_in_flight == 1)
-                vm_wait<4>();
-            else
+        // Outside the steady-state loop, where these loads are ordinary code in front of a wave's block, the waves
+        // with query rows load nothing as long as there are as many waves without (row groups of up to 128 rows):
+        // wave 8 - n_active + w, which only moves tiles anyway, loads the rows of active wave w on top of its own.
+        const int n_active = (rows_here + 31) >> 5;
+        const bool shift_loads = n_active <= 4;
+        const int takeover = shift_loads ? wave - (8 - n_active) : -1;
+        auto issue_tile = [&](int ti, int ks, int vs) {
+            if (shift_loads && active)
+                return;
+            issue_rows(ti, ks, vs, wave);
+            if (takeover >= 0)
+                issue_rows(ti, ks, vs, takeover);
+        };
+        // all but the loads of the youngest tiles_in_flight tiles are done (four loads per tile and set of rows; a
+        // wave that loads nothing has only its Q loads and earlier stores to wait for)
+        auto wait_loads = [&](int tiles_in_flight) {
+            if (shift_loads && active) {
                 vm_wait<0>();
+            } else if (takeover >= 0) {
+                if (tiles_in_flight >= 2)
+                    vm_wait<16>();
+                else if (tiles_in_flight == 1)
+                    vm_wait<8>();
+                else
+                    vm_wait<0>();
+            } else if (tiles_in_flight >= 2) {
+                vm_wait<8>();
+            } else if (tiles_in_flight == 1) {
+                vm_wait<4>();
+            } else {
+                vm_wait<0>();
+            }
         };
 
         int bad = 0;                                       // TA_STATUS_* bits this item has to report
@@ -980,7 +1005,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     const uint64_t c_pc = (uint64_t)pc_lds | ((uint64_t)__float_as_uint(c) << 32);
                     const uint64_t c_dst = (uint64_t)(lds0 + wave * 2048) | ((uint64_t)(lds0 + SP_V_OFF + wave * 2048) << 32);
                     uint32_t koff0, koff1, voff0, voff1;
-                    lane_offsets(koff0, koff1, voff0, voff1);
+                    lane_offsets(koff0, koff1, voff0, voff1, wave);
                     if (active)
                         sp_fast_loop(m_run, l_run, l2_run, ik_o, iv_o, kn_o, vp_o, pos, cnt, c_kg, c_vg, c_sp, c_ss, c_pp, c_pc, c_dst,
                                      koff0, koff1, voff0, voff1);
