@@ -891,18 +891,19 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 } else if (x == 0) {
                     pcache[0] = b;                             // the steady-state loop sees one page: the request's cache
                 }
+                const int xt = x;
                 if (s0 == 0 && has_tree_tile && p.masks_in) {
-                    if (x < p.T) {
-                        const unsigned long long gm = ta_given_mask(p, b, x);      // encoded before the call
-                        masks[x] = gm;
-                        if (!ta_given_mask_ok(gm, x))
+                    if (xt < p.T) {
+                        const unsigned long long gm = ta_given_mask(p, b, xt);     // encoded before the call
+                        masks[xt] = gm;
+                        if (!ta_given_mask_ok(gm, xt))
                             atomicOr(&flag[1], TA_STATUS_BAD_PARENT);
                     }
                 } else if (s0 == 0 && has_tree_tile) {
                     if (x == 0)
                         *flag = 0;
-                    if (x < p.T)
-                        par_s[x] = p.parent[(int64_t)b * p.par_sb + x];
+                    if (xt < p.T)
+                        par_s[xt] = p.parent[(int64_t)b * p.par_sb + xt];
                 }
             }
             __syncthreads();
@@ -1051,50 +1052,67 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             const int r32_ = ln & 31, h = ln >> 5;
             const float l_tot = l_run + __shfl_xor(l_run, 32, TA_WAVE);
             const float l2_tot = l2_run + __shfl_xor(l2_run, 32, TA_WAVE);
+            // The wave that stores the staged rows of active wave w: w itself, or -- row groups of up to 128 rows --
+            // the helper wave that also loads w's rows, so that w goes on to the next item meanwhile.
+            const int stores_for = shift_loads ? takeover : (active ? wv : -1);
             if constexpr (Q15) {
-              if (active) {
-                const float inv = 1.f / l2_tot;
-                char *stage = smem + wv * 16384;
-                // 16-byte chunk c of row r sits at chunk c ^ (r & 15); the lane's eight bytes of it at 8 h
-                float scale;
-                sp_put_q15(inv, lds0 + (uint32_t)(wv * 16384 + r32_ * 256 + ((r32_ & 15) << 4) + 8 * h), scale);
-                __builtin_amdgcn_wave_barrier();
-                const int rw0 = wv * 32;
-                const int cc = ln & 15, rq = ln >> 4;                      // 16 lanes store one row, four rows per round
+                if (active) {
+                    // 16-byte chunk c of row r sits at chunk c ^ (r & 15); the lane's eight bytes of it at 8 h
+                    float scale;
+                    sp_put_q15(1.f / l2_tot, lds0 + (uint32_t)(wv * 16384 + r32_ * 256 + ((r32_ & 15) << 4) + 8 * h), scale);
+                    if (h == 0 && wv * 32 + r32_ < rows_here) {
+                        const int64_t wrow = ta_ws_row(p, slot, rg, wv * 32 + r32_);
+                        p.ws_lse[wrow] = m_run + log2f(l_tot);
+                        p.ws_scale[wrow] = scale;
+                    }
+                }
+                if (shift_loads)
+                    lds_barrier();                             // the staged rows are visible to the wave that stores them
+                else
+                    __builtin_amdgcn_wave_barrier();
+                if (stores_for >= 0) {
+                    const char *stage = smem + stores_for * 16384;
+                    const int rw0 = stores_for * 32;
+                    const int cc = ln & 15, rq = ln >> 4;                  // 16 lanes store one row, four rows per round
 #pragma unroll 2
-                for (int it = 0; it < 8; ++it) {
-                    const int rr = 4 * it + rq;
-                    const uint4 val = *(const uint4 *)(stage + rr * 256 + ((cc ^ (rr & 15)) << 4));
-                    if (rw0 + rr < rows_here)
-                        *(uint4 *)(ta_part_row(p, ta_ws_row(p, slot, rg, rw0 + rr)) + 16 * cc) = val;
+                    for (int it = 0; it < 8; ++it) {
+                        const int rr = 4 * it + rq;
+                        const uint4 val = *(const uint4 *)(stage + rr * 256 + ((cc ^ (rr & 15)) << 4));
+                        if (rw0 + rr < rows_here)
+                            *(uint4 *)(ta_part_row(p, ta_ws_row(p, slot, rg, rw0 + rr)) + 16 * cc) = val;
+                    }
                 }
-                if (h == 0 && rw0 + r32_ < rows_here) {
-                    const int64_t wrow = ta_ws_row(p, slot, rg, rw0 + r32_);
-                    p.ws_lse[wrow] = m_run + log2f(l_tot);
-                    p.ws_scale[wrow] = scale;
+            } else {
+                if (active) {
+                    // fp32 partials: 16-byte chunk j of row r sits at chunk j ^ r, which keeps both directions free of
+                    // bank conflicts; whole 512-byte rows are stored.  Chunk (2 c + h) ^ r32_ of row r32_: the
+                    // c-dependent part is an XOR on address bits 5..8
+                    sp_put_o(1.f / l2_tot, lds0 + (uint32_t)(wv * 16384 + r32_ * 512 + ((h ^ r32_) << 4)));
+                    if (h == 0 && wv * 32 + r32_ < rows_here)
+                        p.ws_lse[ta_ws_row(p, slot, rg, wv * 32 + r32_)] = m_run + log2f(l_tot);
                 }
-              }
-            } else if (active) {
-                // fp32 partials: 16-byte chunk j of row r sits at chunk j ^ r, which keeps both directions free of bank
-                // conflicts; whole 512-byte rows are stored
-                const float inv = 1.f / l2_tot;
-                char *stage = smem + wv * 16384;
-                // chunk (2 c + h) ^ r32_ of row r32_:  the c-dependent part is an XOR on address bits 5..8
-                sp_put_o(inv, lds0 + (uint32_t)(wv * 16384 + r32_ * 512 + ((h ^ r32_) << 4)));
-                __builtin_amdgcn_wave_barrier();
-                const int rw0 = wv * 32;
+                if (shift_loads)
+                    lds_barrier();
+                else
+                    __builtin_amdgcn_wave_barrier();
+                if (stores_for >= 0) {
+                    const char *stage = smem + stores_for * 16384;
+                    const int rw0 = stores_for * 32;
 #pragma unroll 4
-                for (int it = 0; it < 16; ++it) {
-                    const int rr = 2 * it + h;                         // row of the wave's block, chunk r32_
-                    const float4 val = *(const float4 *)(stage + rr * 512 + ((r32_ ^ rr) << 4));
-                    if (rw0 + rr < rows_here)
-                        *(float4 *)(p.ws_o + ta_ws_row(p, slot, rg, rw0 + rr) * MF_D + 4 * r32_) = val;
+                    for (int it = 0; it < 16; ++it) {
+                        const int rr = 2 * it + h;                         // row of the wave's block, chunk r32_
+                        const float4 val = *(const float4 *)(stage + rr * 512 + ((r32_ ^ rr) << 4));
+                        if (rw0 + rr < rows_here)
+                            *(float4 *)(p.ws_o + ta_ws_row(p, slot, rg, rw0 + rr) * MF_D + 4 * r32_) = val;
+                    }
                 }
-                if (h == 0 && rw0 + r32_ < rows_here)
-                    p.ws_lse[ta_ws_row(p, slot, rg, rw0 + r32_)] = m_run + log2f(l_tot);
             }
         }
-        lds_barrier();                 // the staging area is ring space again; the stores themselves may still fly
+        // The staging area is ring space again once its rows have been read: after the barrier below, or -- when helper
+        // waves store -- after the barrier that every item and every poisoned one has before it loads a tile (the waves
+        // with rows are already on their way to it).
+        if (!shift_loads)
+            lds_barrier();
         t = seg_start + (j1 == n_b ? n_u : j1);
     }
 }
