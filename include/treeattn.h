@@ -30,8 +30,8 @@
  *     that device without ordering between them.  Concurrent calls each bring a
  *     workspace of their own.
  *   - Non-finite inputs.  A NaN or an infinity among the values a row attends to makes that output column NaN
- *     (an infinity may stay one), and with the 16-bit format of the partial results (bf16 inputs and many rows
- *     per workgroup, see tree_attn_plan) the whole output row NaN; NaNs in q or k reach out and lse through the
+ *     (an infinity may stay one), and with the 16-bit format of the partial results (the matrix-core kernels,
+ *     i.e. bf16 inputs of head_dim 64 or 128; see tree_attn_plan) the whole output row NaN; NaNs in q or k reach out and lse through the
  *     scores.  Nothing else is affected.
  *   - Return value: TA_OK (0) or a negative ta_status.  Nothing throws or aborts.
  *     Problems visible on the host (null pointers, ranks, dtypes, shapes,

@@ -97,8 +97,8 @@ def verify_register_partition(verbose=False):
         raise RuntimeError("hipcc -S failed for ta_mfma.hip")
     lines = proc.stdout.split("\n")
     starts = [i for i, l in enumerate(lines) if re.match(r"_Z17ta_mfma_sp_kernel\w*:", l)]
-    if len(starts) != 4:
-        raise RuntimeError("expected the four instances of ta_mfma_sp_kernel in the ISA, found %d" % len(starts))
+    if len(starts) != 2:
+        raise RuntimeError("expected the two instances of ta_mfma_sp_kernel in the ISA, found %d" % len(starts))
     for start in starts:
         name = lines[start].split(":")[0]
         end = next(i for i in range(start, len(lines)) if ".end_amdhsa_kernel" in lines[i])

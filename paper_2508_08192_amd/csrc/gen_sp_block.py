@@ -31,7 +31,7 @@ A operand of the second product (rows = head-dim columns, contraction = tokens) 
 sets (16kb + 4hf + {0..3}, then + 8) follow the contraction slots the probabilities occupy after the first product.
 
 Small helpers move values between the two worlds: sp_zero_o, sp_load_q, sp_set_bases, sp_scale_o, sp_mask_A/B,
-sp_put_o, sp_put_q15.
+sp_put_q15.
 
 S^T(i) and S^T(i+1) alternate between buffers A and B, so every block exists in an "A current" and a "B current"
 flavour.  P has one buffer: the PV MFMAs, which read P(i-1), come first in program order and the conversion that
@@ -420,17 +420,7 @@ def helpers():
                 lines.append("v_cndmask_b32 %s, %s, %s, vcc" % (v(base + 16 * tb + i), v(base + 16 * tb + i), v(TMP)))
         out.append(emit("sp_mask_" + cur, ["uint32_t lo", "uint32_t hi"], lines, [], ['[lo] "v"(lo)', '[hi] "v"(hi)'],
                         ['"memory"', '"vcc"']))
-    # Epilogue, fp32 partials: O *= inv in place, then each lane's sixteen 16-byte pieces go to the row-major staging
-    # block in LDS; piece c of the lane lives at byte address a0 ^ (c << 5) (the caller folds the row, the lane half
-    # and the chunk swizzle into a0).
-    lines = ["s_nop 15", "s_nop 7"] + ["v_mul_f32 %s, %%[inv], %s" % (v(O + k), v(O + k)) for k in range(64)]
-    for c in range(16):
-        t = v(TMP + (c & 3))
-        lines.append("v_xor_b32 %s, 0x%x, %%[a0]" % (t, c << 5))
-        lines.append("ds_write_b128 %s, v[%d:%d]" % (t, O + 4 * c, O + 4 * c + 3))
-    lines.append("s_waitcnt lgkmcnt(0)")
-    out.append(emit("sp_put_o", ["float inv", "uint32_t a0"], lines, [], ['[inv] "v"(inv)', '[a0] "v"(a0)'], ['"memory"']))
-    # Epilogue, 16-bit partials: the lane's 64 values of O (its half of a query row) become 16-bit fixed point with one scale for the
+    # Epilogue: the lane's 64 values of O (its half of a query row) become 16-bit fixed point with one scale for the
     # row -- value = scale * int16, scale = inv * (largest magnitude of the row) / 32767 -- and go to the row-major
     # staging block in LDS, 256 bytes per row: the lane's piece c (four values, 8 bytes) lives at byte address
     # a0 ^ (c << 4) (the caller folds row, lane half and chunk swizzle into a0).  The rounding to int16 is the

@@ -89,8 +89,7 @@ int reserve_locked(DeviceState *s, size_t bytes)
 void place_workspace(TAProblem &pr, void *ws)
 {
     pr.p.ws_o = (float *)ws;
-    pr.p.ws_lse = (float *)((char *)ws + pr.ws_o_bytes);
-    pr.p.ws_scale = (float *)((char *)ws + pr.ws_scale_off);
+    pr.p.ws_lse = (float *)((char *)ws + pr.ws_ls_off);
     pr.p.ws_parts = (int32_t *)((char *)ws + pr.ws_o_bytes + pr.ws_lse_bytes);
 }
 

@@ -174,7 +174,7 @@ __device__ __forceinline__ char *ta_part_row(const TAParams &p, int64_t wrow)   
 
 __device__ __forceinline__ float ta_part_get(const TAParams &p, int64_t wrow, int d)
 {
-    return p.part_q15 ? p.ws_scale[wrow] * (float)((const short *)p.ws_o)[wrow * p.D + d] : p.ws_o[wrow * p.D + d];
+    return p.part_q15 ? p.ws_lse[2 * wrow + 1] * (float)((const short *)p.ws_o)[wrow * p.D + d] : p.ws_o[wrow * p.D + d];
 }
 
 // Scale of a row whose largest magnitude is amax (NaN if the row holds one), and the factor that maps its values to

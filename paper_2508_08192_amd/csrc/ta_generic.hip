@@ -332,7 +332,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
     float lse2;
     if (n_parts <= TA_WAVE) {
         // lane k owns partial k
-        const float lk = lane < n_parts ? p.ws_lse[row0 + lane * pstride] : -INFINITY;
+        const float lk = lane < n_parts ? p.ws_lse[(row0 + lane * pstride) * p.ls] : -INFINITY;
         const bool nan_seen = __any(lk != lk);
         const float mx = ta_wave_max(lk);
         const float ek = exp2f(lk - mx);                                  // 0 for the idle lanes
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
         for (int q0 = 0; q0 < n_parts; q0 += TA_WAVE) {
             const int k = q0 + lane;
             if (k < n_parts) {
-                const float v = p.ws_lse[row0 + k * pstride];
+                const float v = p.ws_lse[(row0 + k * pstride) * p.ls];
                 nan_seen |= (v != v);
                 mx = fmaxf(mx, v);
             }
@@ -384,12 +384,12 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_merge_kernel(TAParams p)
         for (int q0 = 0; q0 < n_parts; q0 += TA_WAVE) {
             const int k = q0 + lane;
             if (k < n_parts)
-                den += exp2f(p.ws_lse[row0 + k * pstride] - mx);
+                den += exp2f(p.ws_lse[(row0 + k * pstride) * p.ls] - mx);
         }
         den = ta_wave_sum(den);
         lse2 = nan_seen ? QNAN : mx + log2f(den);
         for (int k = 0; k < n_parts; ++k) {
-            const float wgt = exp2f(p.ws_lse[row0 + k * pstride] - lse2);  // same address in every lane
+            const float wgt = exp2f(p.ws_lse[(row0 + k * pstride) * p.ls] - lse2);  // same address in every lane
 #pragma unroll
             for (int c = 0; c < GEN_DCHUNKS; ++c) {
                 const int d = lane + c * TA_WAVE;
@@ -432,15 +432,23 @@ __device__ __forceinline__ float ta_half_sum(float x)
 }
 
 // Four neighbouring columns of one partial row: fp32, or (HP) int16, which the caller's weight carries the scale of.
+// The load returns the bits as they lie in memory and the conversion happens where the values are used: a conversion
+// next to the load would make every load wait for its data, and the loads of a round are meant to be in flight together.
 template <bool HP>
-__device__ __forceinline__ float4 ta_part_load4(const char *ptr)
+struct ta_part_raw { typedef float4 type; };
+template <>
+struct ta_part_raw<true> { typedef ta_s4 type; };
+
+template <bool HP>
+__device__ __forceinline__ typename ta_part_raw<HP>::type ta_part_load4(const char *ptr)
 {
-    if constexpr (HP) {
-        const ta_s4 x = *(const ta_s4 *)ptr;
-        return make_float4((float)x.x, (float)x.y, (float)x.z, (float)x.w);
-    } else {
-        return *(const float4 *)ptr;
-    }
+    return *(const typename ta_part_raw<HP>::type *)ptr;
+}
+
+__device__ __forceinline__ float4 ta_part_f4(const float4 &x) { return x; }
+__device__ __forceinline__ float4 ta_part_f4(const ta_s4 &x)
+{
+    return make_float4((float)x.x, (float)x.y, (float)x.z, (float)x.w);
 }
 
 template <bool NEW, bool HP>
@@ -473,6 +481,7 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
     const int64_t row0 = ta_ws_row(p, w_first + seg, rg, r);              // partial k of this row: row0 + k*pstride
     const int64_t pstride = (int64_t)p.n_rg * p.rows_grp;
     constexpr int EB = HP ? 2 : 4;                         // bytes per element of a partial output
+    constexpr int LS = HP ? 2 : 1;                         // floats per row of ws_lse: {log-sum-exp, scale} or the former
     const char *o0 = (const char *)p.ws_o + (row0 * 128 + 4 * hl) * EB;
     const int64_t ostride = pstride * 128 * EB;
 
@@ -480,10 +489,16 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
     float lse2;
     if (n_parts <= 32) {
         // lane k of the half owns partial k
-        const float lk = hl < n_parts ? p.ws_lse[row0 + hl * pstride] : -INFINITY;
-        float sk = 1.f;                                                   // scale of the partial's 16-bit values
-        if constexpr (HP)
-            sk = hl < n_parts ? p.ws_scale[row0 + hl * pstride] : 1.f;
+        float lk = -INFINITY, sk = 1.f;                                   // sk: scale of the partial's 16-bit values
+        if (hl < n_parts) {
+            if constexpr (HP) {
+                const float2 t = *(const float2 *)&p.ws_lse[(row0 + hl * pstride) * LS];
+                lk = t.x;
+                sk = t.y;
+            } else {
+                lk = p.ws_lse[(row0 + hl * pstride) * LS];
+            }
+        }
         if constexpr (NEW)
             ta_scatter_locate(p, b, g, sc);
         const bool nan_seen = ta_half_max(lk != lk ? 1.f : 0.f) > 0.f;
@@ -495,22 +510,23 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
         const int src0 = lane & 32;
         int k = 0;
         for (; k + 4 <= n_parts; k += 4) {
-            float4 v[4];
+            typename ta_part_raw<HP>::type v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
                 v[u] = ta_part_load4<HP>(o0 + (k + u) * ostride);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const float wgt = __shfl(wk, src0 + k + u, TA_WAVE);
-                acc.x = fmaf(wgt, v[u].x, acc.x);
-                acc.y = fmaf(wgt, v[u].y, acc.y);
-                acc.z = fmaf(wgt, v[u].z, acc.z);
-                acc.w = fmaf(wgt, v[u].w, acc.w);
+                const float4 x = ta_part_f4(v[u]);
+                acc.x = fmaf(wgt, x.x, acc.x);
+                acc.y = fmaf(wgt, x.y, acc.y);
+                acc.z = fmaf(wgt, x.z, acc.z);
+                acc.w = fmaf(wgt, x.w, acc.w);
             }
         }
         // The tail's loads go out together as well.  (Both halves of a wave merge rows of the same list, so
         // n_parts and with it every branch here is uniform over the wave.)
-        float4 v[3];
+        typename ta_part_raw<HP>::type v[3];
 #pragma unroll
         for (int u = 0; u < 3; ++u)
             if (k + u < n_parts)
@@ -519,10 +535,11 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
         for (int u = 0; u < 3; ++u)
             if (k + u < n_parts) {
                 const float wgt = __shfl(wk, src0 + k + u, TA_WAVE);
-                acc.x = fmaf(wgt, v[u].x, acc.x);
-                acc.y = fmaf(wgt, v[u].y, acc.y);
-                acc.z = fmaf(wgt, v[u].z, acc.z);
-                acc.w = fmaf(wgt, v[u].w, acc.w);
+                const float4 x = ta_part_f4(v[u]);
+                acc.x = fmaf(wgt, x.x, acc.x);
+                acc.y = fmaf(wgt, x.y, acc.y);
+                acc.z = fmaf(wgt, x.z, acc.z);
+                acc.w = fmaf(wgt, x.w, acc.w);
             }
     } else {
         if constexpr (NEW)
@@ -532,7 +549,7 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
         for (int q0 = 0; q0 < n_parts; q0 += 32) {
             const int k = q0 + hl;
             if (k < n_parts) {
-                const float v = p.ws_lse[row0 + k * pstride];
+                const float v = p.ws_lse[(row0 + k * pstride) * LS];
                 bad = v != v ? 1.f : bad;
                 mx = fmaxf(mx, v);
             }
@@ -543,15 +560,15 @@ __global__ __launch_bounds__(256) void ta_merge128_kernel(TAParams p)
         for (int q0 = 0; q0 < n_parts; q0 += 32) {
             const int k = q0 + hl;
             if (k < n_parts)
-                den += exp2f(p.ws_lse[row0 + k * pstride] - mx);
+                den += exp2f(p.ws_lse[(row0 + k * pstride) * LS] - mx);
         }
         den = ta_half_sum(den);
         lse2 = nan_seen ? QNAN : mx + log2f(den);
         for (int k = 0; k < n_parts; ++k) {
-            float wgt = exp2f(p.ws_lse[row0 + k * pstride] - lse2);        // same address in every lane of the half
+            float wgt = exp2f(p.ws_lse[(row0 + k * pstride) * LS] - lse2);        // same address in every lane of the half
             if constexpr (HP)
-                wgt *= p.ws_scale[row0 + k * pstride];
-            const float4 v = ta_part_load4<HP>(o0 + k * ostride);
+                wgt *= p.ws_lse[(row0 + k * pstride) * LS + 1];
+            const float4 v = ta_part_f4(ta_part_load4<HP>(o0 + k * ostride));
             acc.x = fmaf(wgt, v.x, acc.x);
             acc.y = fmaf(wgt, v.y, acc.y);
             acc.z = fmaf(wgt, v.z, acc.z);
@@ -601,33 +618,32 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
     const int64_t row0 = ta_ws_row(p, w_first + seg, rg, r);              // partial k of this row: row0 + k*pstride
     const int64_t pstride = (int64_t)p.n_rg * p.rows_grp;
     constexpr int EB = HP ? 2 : 4;                         // bytes per element of a partial output
+    constexpr int LS = HP ? 2 : 1;                         // floats per row of ws_lse: {log-sum-exp, scale} or the former
     const char *o0 = (const char *)p.ws_o + (row0 * 128 + 4 * hl) * EB;
     const int64_t ostride = pstride * 128 * EB;
 
     // first round of this half-wave's partials (hw, hw + 8, ...): outputs and their log-sum-exps
-    float4 v[MW_FLIGHT];
-    float lk[MW_FLIGHT], sk[MW_FLIGHT];                    // log-sum-exps and (16-bit partials) scales
-#pragma unroll
-    for (int u = 0; u < MW_FLIGHT; ++u)
-        sk[u] = 1.f;
+    typename ta_part_raw<HP>::type v[MW_FLIGHT];
+    float2 ls[MW_FLIGHT];                                  // log-sum-exps and (16-bit partials: one 8-byte load) scales
 #pragma unroll
     for (int u = 0; u < MW_FLIGHT; ++u) {
         const int k = hw + MW_HALVES * u;
         if (k < n_parts) {
             v[u] = ta_part_load4<HP>(o0 + k * ostride);
-            lk[u] = p.ws_lse[row0 + k * pstride];
             if constexpr (HP)
-                sk[u] = p.ws_scale[row0 + k * pstride];
+                ls[u] = *(const float2 *)&p.ws_lse[(row0 + k * pstride) * LS];
+            else
+                ls[u].x = p.ws_lse[(row0 + k * pstride) * LS];
         }
     }
     if constexpr (NEW)
         ta_scatter_locate(p, b, g, sc);
     // log-sum-exp of the row over all partials (thread t keeps partial t's value for the second sweep; only with
     // more than 256 partials is anything read twice)
-    const float x_own = tid < n_parts ? p.ws_lse[row0 + tid * pstride] : -INFINITY;
+    const float x_own = tid < n_parts ? p.ws_lse[(row0 + tid * pstride) * LS] : -INFINITY;
     float mx = x_own, bad = x_own != x_own ? 1.f : 0.f;
     for (int k = tid + 256; k < n_parts; k += 256) {
-        const float x = p.ws_lse[row0 + k * pstride];
+        const float x = p.ws_lse[(row0 + k * pstride) * LS];
         bad = x != x ? 1.f : bad;
         mx = fmaxf(mx, x);
     }
@@ -643,7 +659,7 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
     __syncthreads();
     float den = tid < n_parts ? exp2f(x_own - mx) : 0.f;
     for (int k = tid + 256; k < n_parts; k += 256)
-        den += exp2f(p.ws_lse[row0 + k * pstride] - mx);
+        den += exp2f(p.ws_lse[(row0 + k * pstride) * LS] - mx);
     den = ta_wave_sum(den);
     if ((tid & 63) == 0)
         red[wave] = den;
@@ -659,20 +675,22 @@ __global__ __launch_bounds__(256) void ta_merge128_wide_kernel(TAParams p)
                 const int k = k0 + MW_HALVES * u;
                 if (k < n_parts) {
                     v[u] = ta_part_load4<HP>(o0 + k * ostride);
-                    lk[u] = p.ws_lse[row0 + k * pstride];
                     if constexpr (HP)
-                        sk[u] = p.ws_scale[row0 + k * pstride];
+                        ls[u] = *(const float2 *)&p.ws_lse[(row0 + k * pstride) * LS];
+                    else
+                        ls[u].x = p.ws_lse[(row0 + k * pstride) * LS];
                 }
             }
         }
 #pragma unroll
         for (int u = 0; u < MW_FLIGHT; ++u) {
             if (k0 + MW_HALVES * u < n_parts) {
-                const float wgt = nan_seen ? QNAN : exp2f(lk[u] - lse2) * sk[u];
-                acc.x = fmaf(wgt, v[u].x, acc.x);
-                acc.y = fmaf(wgt, v[u].y, acc.y);
-                acc.z = fmaf(wgt, v[u].z, acc.z);
-                acc.w = fmaf(wgt, v[u].w, acc.w);
+                const float wgt = nan_seen ? QNAN : exp2f(ls[u].x - lse2) * (HP ? ls[u].y : 1.f);
+                const float4 x = ta_part_f4(v[u]);
+                acc.x = fmaf(wgt, x.x, acc.x);
+                acc.y = fmaf(wgt, x.y, acc.y);
+                acc.z = fmaf(wgt, x.z, acc.z);
+                acc.w = fmaf(wgt, x.w, acc.w);
             }
         }
     }

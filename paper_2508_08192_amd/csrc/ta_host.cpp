@@ -55,7 +55,6 @@ const TADispatchRow kTable[] = {
     {TA_KERNEL_GENERIC, 256, INT32_MAX, 16, 1, 1, 13, 1024},
 };
 constexpr int kTableRows = (int)(sizeof(kTable) / sizeof(kTable[0]));
-constexpr double kQ15FromRowItems = 100.0;   // see ta_host_build_problem
 
 int find_row(int family, int rows_grp, int64_t lists)
 {
@@ -302,15 +301,10 @@ int ta_host_build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tenso
         const bool wide = dr.wide_from_parts > 0 && parts >= dr.wide_from_parts && lists * p.rows <= dr.wide_max_rows;
         pl.merge_kind = wide ? TA_MERGE_D128_WIDE : TA_MERGE_D128;
     }
-    // Partial format of the matrix-core kernels: 16-bit fixed point halves what the KV pass writes (C3 128.6 -> 125.0 us,
-    // p4 215.1 -> 210.2, C2 26.5 -> 24.1) but its conversion costs about a microsecond per (workgroup, list) overlap, so
-    // it is taken where a workgroup writes many rows: rows per group x overlaps per workgroup (one, plus the lists it
-    // crosses) from kQ15FromRowItems on (uniform 16k lists of 32 rows, 48 row-items: 172.6 -> 174.4 us with it).
-    {
-        const int rows_wg = p.rows < pl.rows_grp ? p.rows : pl.rows_grp;
-        const double row_items = rows_wg * (1.0 + (double)lists / pl.n_wg);
-        p.part_q15 = kernel == TA_KERNEL_MFMA && row_items >= kQ15FromRowItems ? 1 : 0;
-    }
+    // Partial format of the matrix-core kernels: 16-bit fixed point with a scale per row, which halves what the KV pass
+    // writes (C3 128.6 -> 125.0 us, p4 215.1 -> 210.2, C2 26.5 -> 24.1; batch-one shapes 1 to 2 us of 35).  The scalar
+    // kernel, whose inputs may be fp32, keeps fp32 partials.
+    p.part_q15 = kernel == TA_KERNEL_MFMA ? 1 : 0;
     p.merge_kind = pl.merge_kind;
     const int mrows = ta_host_merge_rows(p);
     pl.merge_wgs = (int)lists * ((p.rows + mrows - 1) / mrows);
@@ -318,14 +312,15 @@ int ta_host_build_problem(const ta_tensor *q, const ta_tensor *k, const ta_tenso
     const size_t rows_total = (size_t)pl.n_slots * pl.n_rg * pl.rows_grp;
     pr->ws_o_bytes = ta_host_align_up(rows_total * D * sizeof(float), 256);
     pr->ws_lse_bytes = ta_host_align_up(rows_total * sizeof(float), 256);
-    pr->ws_scale_off = ta_host_align_up(rows_total * D * 2, 256);   // rows_total * 4 more bytes fit before ws_o_bytes
+    // (with 16-bit partials: rows_total * 8 bytes of {log-sum-exp, scale} fit into the unused half of the ws_o area)
+    pr->ws_ls_off = p.part_q15 ? ta_host_align_up(rows_total * D * 2, 256) : pr->ws_o_bytes;
+    p.ls = p.part_q15 ? 2 : 1;
     pr->ws_bytes = pr->ws_o_bytes + pr->ws_lse_bytes + ta_host_align_up((size_t)lists * 2 * sizeof(int32_t), 256);
     if (user_ws) {
         if (user_ws_bytes < pr->ws_bytes)
             return TA_ERR_WORKSPACE;
         p.ws_o = (float *)user_ws;
-        p.ws_lse = (float *)((char *)user_ws + pr->ws_o_bytes);
-        p.ws_scale = (float *)((char *)user_ws + pr->ws_scale_off);
+        p.ws_lse = (float *)((char *)user_ws + pr->ws_ls_off);
         p.ws_parts = (int32_t *)((char *)user_ws + pr->ws_o_bytes + pr->ws_lse_bytes);
     }
     return TA_OK;

@@ -320,11 +320,10 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                     const int row = (wave * RB + rb) * 32 + r32;
                     if (row < rows_here) {
                         const int64_t wrow = ta_ws_row(p, slot, rg, row);
-                        const int eb = p.part_q15 ? 2 : 4;             // bytes per element of a partial
-                        for (int o = hf * (DH / 2) * eb; o < (hf + 1) * (DH / 2) * eb; o += 16)
+                        for (int o = hf * DH; o < (hf + 1) * DH; o += 16)          // DH 16-bit values per row
                             *(float4 *)(ta_part_row(p, wrow) + o) = make_float4(0.f, 0.f, 0.f, 0.f);
                         if (hf == 0)
-                            p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
+                            p.ws_lse[2 * wrow] = __uint_as_float(0x7fc00000u);
                     }
                 }
             }
@@ -498,51 +497,34 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
                     const int64_t wrow = ta_ws_row(p, slot, rg, row);
                     const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32, TA_WAVE);
                     const float inv = 1.f / (l2_run[rb] + __shfl_xor(l2_run[rb], 32, TA_WAVE));
-                    if (!p.part_q15) {
+                    // 16-bit fixed point with the row's own scale: the two lanes of a row find its largest magnitude
+                    float amax = 0.f;
+                    bool has_nan = false;
 #pragma unroll
-                        for (int db = 0; db < NDB; ++db) {
+                    for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                            for (int i4 = 0; i4 < 4; ++i4) {
-                                float4 o;
-                                o.x = acc_o[rb][db][4 * i4 + 0] * inv;
-                                o.y = acc_o[rb][db][4 * i4 + 1] * inv;
-                                o.z = acc_o[rb][db][4 * i4 + 2] * inv;
-                                o.w = acc_o[rb][db][4 * i4 + 3] * inv;
-                                *(float4 *)(p.ws_o + wrow * DH + db * 32 + 8 * i4 + 4 * hf) = o;
-                            }
+                        for (int i = 0; i < 16; ++i) {
+                            const float x = acc_o[rb][db][i] * inv;
+                            amax = fmaxf(amax, fabsf(x));
+                            has_nan |= x != x;
                         }
-                    } else {
-                        // 16-bit fixed point with the row's own scale: the two lanes of a row find its largest magnitude
-                        float amax = 0.f;
-                        bool has_nan = false;
-    #pragma unroll
-                        for (int db = 0; db < NDB; ++db)
-    #pragma unroll
-                            for (int i = 0; i < 16; ++i) {
-                                const float x = acc_o[rb][db][i] * inv;
-                                amax = fmaxf(amax, fabsf(x));
-                                has_nan |= x != x;
-                            }
-                        amax = fmaxf(amax, __shfl_xor(amax, 32, TA_WAVE));
-                        has_nan |= __shfl_xor((int)has_nan, 32, TA_WAVE) != 0;
-                        float scale, to_q;
-                        ta_q15_scale(amax, has_nan, scale, to_q);
-                        to_q *= inv;
-    #pragma unroll
-                        for (int db = 0; db < NDB; ++db) {
-    #pragma unroll
-                            for (int i4 = 0; i4 < 4; ++i4) {
-                                uint2 o;
-                                o.x = ta_q15_pack(acc_o[rb][db][4 * i4 + 0], acc_o[rb][db][4 * i4 + 1], to_q);
-                                o.y = ta_q15_pack(acc_o[rb][db][4 * i4 + 2], acc_o[rb][db][4 * i4 + 3], to_q);
-                                *(uint2 *)(ta_part_row(p, wrow) + 2 * (db * 32 + 8 * i4 + 4 * hf)) = o;
-                            }
+                    amax = fmaxf(amax, __shfl_xor(amax, 32, TA_WAVE));
+                    has_nan |= __shfl_xor((int)has_nan, 32, TA_WAVE) != 0;
+                    float scale, to_q;
+                    ta_q15_scale(amax, has_nan, scale, to_q);
+                    to_q *= inv;
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db) {
+#pragma unroll
+                        for (int i4 = 0; i4 < 4; ++i4) {
+                            uint2 o;
+                            o.x = ta_q15_pack(acc_o[rb][db][4 * i4 + 0], acc_o[rb][db][4 * i4 + 1], to_q);
+                            o.y = ta_q15_pack(acc_o[rb][db][4 * i4 + 2], acc_o[rb][db][4 * i4 + 3], to_q);
+                            *(uint2 *)(ta_part_row(p, wrow) + 2 * (db * 32 + 8 * i4 + 4 * hf)) = o;
                         }
-                        if (hf == 0)
-                            p.ws_scale[wrow] = scale;
                     }
                     if (hf == 0)
-                        p.ws_lse[wrow] = m_run[rb] * c + log2f(l_tot);
+                        *(float2 *)&p.ws_lse[2 * wrow] = make_float2(m_run[rb] * c + log2f(l_tot), scale);
                 }
             }
         }
@@ -611,9 +593,7 @@ struct SpTag {
 // amdgpu_num_vgpr(16): the register allocator stays in v0..v31; v32..v255 belong to the asm blocks (see gen_sp_block.py)
 // NEW: the tree tokens' K/V come from the dense tensors of ta_opts.k_new / v_new (an instance of its own, so that the
 // ordinary call carries none of that addressing).
-// Q15: the partial results are written as 16-bit fixed point (see ta_part_row); an instance of its own as well -- with
-// both epilogues in one kernel the compiler's few registers no longer held everything that lives across an item.
-template <bool NEW, bool Q15>
+template <bool NEW>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_mfma_sp_kernel(TAParams p)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -732,11 +712,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             const int prow = (x >> 6) * 32 + (x & 31), ph = (x >> 5) & 1;
             if (prow < rows_here) {
                 const int64_t wrow = ta_ws_row(p, slot, rg, prow);
-                constexpr int eb = Q15 ? 2 : 4;                        // bytes per element of a partial
-                for (int o = ph * 64 * eb; o < (ph + 1) * 64 * eb; o += 16)
+                for (int o = ph * 128; o < (ph + 1) * 128; o += 16)    // 128 16-bit values
                     *(float4 *)(ta_part_row(p, wrow) + o) = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (ph == 0)
-                    p.ws_lse[wrow] = __uint_as_float(0x7fc00000u);
+                    p.ws_lse[2 * wrow] = __uint_as_float(0x7fc00000u);
             }
         };
         if (poison) {
@@ -1043,8 +1022,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
         }
 
         {
-            // Partial result of this (workgroup, list) overlap, as fp32 or as 16-bit fixed point with one scale per row
-            // (see ta_part_row).  A lane holds four-value pieces of one row, eight values apart; written like that,
+            // Partial result of this (workgroup, list) overlap, as 16-bit fixed point with one scale per row (see
+            // ta_part_row).  A lane holds four-value pieces of one row, eight values apart; written like that,
             // every store would touch 64 cache lines.  So each wave first turns its 32 x 128 block into row-major
             // order in its part of the (now idle) K/V rings and then stores whole rows.
             const int x = fresh_tid();
@@ -1055,56 +1034,29 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             // The wave that stores the staged rows of active wave w: w itself, or -- row groups of up to 128 rows --
             // the helper wave that also loads w's rows, so that w goes on to the next item meanwhile.
             const int stores_for = shift_loads ? takeover : (active ? wv : -1);
-            if constexpr (Q15) {
-                if (active) {
-                    // 16-byte chunk c of row r sits at chunk c ^ (r & 15); the lane's eight bytes of it at 8 h
-                    float scale;
-                    sp_put_q15(1.f / l2_tot, lds0 + (uint32_t)(wv * 16384 + r32_ * 256 + ((r32_ & 15) << 4) + 8 * h), scale);
-                    if (h == 0 && wv * 32 + r32_ < rows_here) {
-                        const int64_t wrow = ta_ws_row(p, slot, rg, wv * 32 + r32_);
-                        p.ws_lse[wrow] = m_run + log2f(l_tot);
-                        p.ws_scale[wrow] = scale;
-                    }
+            if (active) {
+                // 16-byte chunk c of row r sits at chunk c ^ (r & 15); the lane's eight bytes of it at 8 h
+                float scale;
+                sp_put_q15(1.f / l2_tot, lds0 + (uint32_t)(wv * 16384 + r32_ * 256 + ((r32_ & 15) << 4) + 8 * h), scale);
+                if (h == 0 && wv * 32 + r32_ < rows_here) {
+                    const int64_t wrow = ta_ws_row(p, slot, rg, wv * 32 + r32_);
+                    *(float2 *)&p.ws_lse[2 * wrow] = make_float2(m_run + log2f(l_tot), scale);
                 }
-                if (shift_loads)
-                    lds_barrier();                             // the staged rows are visible to the wave that stores them
-                else
-                    __builtin_amdgcn_wave_barrier();
-                if (stores_for >= 0) {
-                    const char *stage = smem + stores_for * 16384;
-                    const int rw0 = stores_for * 32;
-                    const int cc = ln & 15, rq = ln >> 4;                  // 16 lanes store one row, four rows per round
+            }
+            if (shift_loads)
+                lds_barrier();                             // the staged rows are visible to the wave that stores them
+            else
+                __builtin_amdgcn_wave_barrier();
+            if (stores_for >= 0) {
+                const char *stage = smem + stores_for * 16384;
+                const int rw0 = stores_for * 32;
+                const int cc = ln & 15, rq = ln >> 4;                  // 16 lanes store one row, four rows per round
 #pragma unroll 2
-                    for (int it = 0; it < 8; ++it) {
-                        const int rr = 4 * it + rq;
-                        const uint4 val = *(const uint4 *)(stage + rr * 256 + ((cc ^ (rr & 15)) << 4));
-                        if (rw0 + rr < rows_here)
-                            *(uint4 *)(ta_part_row(p, ta_ws_row(p, slot, rg, rw0 + rr)) + 16 * cc) = val;
-                    }
-                }
-            } else {
-                if (active) {
-                    // fp32 partials: 16-byte chunk j of row r sits at chunk j ^ r, which keeps both directions free of
-                    // bank conflicts; whole 512-byte rows are stored.  Chunk (2 c + h) ^ r32_ of row r32_: the
-                    // c-dependent part is an XOR on address bits 5..8
-                    sp_put_o(1.f / l2_tot, lds0 + (uint32_t)(wv * 16384 + r32_ * 512 + ((h ^ r32_) << 4)));
-                    if (h == 0 && wv * 32 + r32_ < rows_here)
-                        p.ws_lse[ta_ws_row(p, slot, rg, wv * 32 + r32_)] = m_run + log2f(l_tot);
-                }
-                if (shift_loads)
-                    lds_barrier();
-                else
-                    __builtin_amdgcn_wave_barrier();
-                if (stores_for >= 0) {
-                    const char *stage = smem + stores_for * 16384;
-                    const int rw0 = stores_for * 32;
-#pragma unroll 4
-                    for (int it = 0; it < 16; ++it) {
-                        const int rr = 2 * it + h;                         // row of the wave's block, chunk r32_
-                        const float4 val = *(const float4 *)(stage + rr * 512 + ((r32_ ^ rr) << 4));
-                        if (rw0 + rr < rows_here)
-                            *(float4 *)(p.ws_o + ta_ws_row(p, slot, rg, rw0 + rr) * MF_D + 4 * r32_) = val;
-                    }
+                for (int it = 0; it < 8; ++it) {
+                    const int rr = 4 * it + rq;
+                    const uint4 val = *(const uint4 *)(stage + rr * 256 + ((cc ^ (rr & 15)) << 4));
+                    if (rw0 + rr < rows_here)
+                        *(uint4 *)(ta_part_row(p, ta_ws_row(p, slot, rg, rw0 + rr)) + 16 * cc) = val;
                 }
             }
         }
@@ -1140,6 +1092,8 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream, int dev)
 {
     if (p.rows_grp != 32 && p.rows_grp != 64 && p.rows_grp != 128 && p.rows_grp != 256)
         return hipErrorInvalidValue;
+    if (!p.part_q15 || p.ls != 2)                          // the one partial format these kernels write
+        return hipErrorInvalidValue;
     if (p.D == 64)                                         // the register-staged kernel is the only one for this head dim
         return launch_variant<8, 1, 512, 64>(p, stream, dev);
     // One kernel for every row group: with fewer than 256 rows some of its eight waves only move tiles.
@@ -1151,8 +1105,7 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream, int dev)
     if (dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
     if (!attr_set[dev]) {
-        for (const void *fn : {(const void *)ta_mfma_sp_kernel<false, false>, (const void *)ta_mfma_sp_kernel<true, false>,
-                               (const void *)ta_mfma_sp_kernel<false, true>, (const void *)ta_mfma_sp_kernel<true, true>}) {
+        for (const void *fn : {(const void *)ta_mfma_sp_kernel<false>, (const void *)ta_mfma_sp_kernel<true>}) {
             hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
             if (e != hipSuccess)
                 return e;
@@ -1160,13 +1113,9 @@ hipError_t ta_launch_mfma(const TAParams &p, hipStream_t stream, int dev)
         attr_set[dev] = true;
     }
     const dim3 grid(p.n_wg, p.n_rg);
-    if (p.kn && p.part_q15)
-        hipLaunchKernelGGL((ta_mfma_sp_kernel<true, true>), grid, dim3(512), smem, stream, p);
-    else if (p.kn)
-        hipLaunchKernelGGL((ta_mfma_sp_kernel<true, false>), grid, dim3(512), smem, stream, p);
-    else if (p.part_q15)
-        hipLaunchKernelGGL((ta_mfma_sp_kernel<false, true>), grid, dim3(512), smem, stream, p);
+    if (p.kn)
+        hipLaunchKernelGGL((ta_mfma_sp_kernel<true>), grid, dim3(512), smem, stream, p);
     else
-        hipLaunchKernelGGL((ta_mfma_sp_kernel<false, false>), grid, dim3(512), smem, stream, p);
+        hipLaunchKernelGGL((ta_mfma_sp_kernel<false>), grid, dim3(512), smem, stream, p);
     return hipGetLastError();
 }

@@ -44,7 +44,9 @@ struct TAParams {
     int32_t is_bf16;
     float scale_log2e;         // softmax scale * log2(e): scores are kept in the base-2 domain
     float *ws_o;               // partial outputs  [slot][rg][rows_grp][D], normalised; fp32, or int16 when part_q15
-    float *ws_lse;             // partial log2-sum-exp2 [slot][rg][rows_grp]
+    float *ws_lse;             // partial log2-sum-exp2 [slot][rg][rows_grp]; with part_q15 [slot][rg][rows_grp][2]:
+                               // the log-sum-exp and the scale of the row's 16-bit values side by side
+    int32_t ls;                // floats per row in ws_lse: 1, or 2 with part_q15
     int32_t *ws_parts;         // [B * Hkv][2]: first and last workgroup that hold partial results of a list; written
                                // by the KV pass (the owners of the list's first and last tile), read by the merge
     int32_t *status;           // sticky status word of the device
@@ -53,7 +55,6 @@ struct TAParams {
     int32_t merge_kind;        // TA_MERGE_*: which merge kernel follows the KV pass
     int32_t part_q15;          // the partial outputs in ws_o are 16-bit fixed point with one scale per row
                                // (matrix-core kernels) rather than fp32
-    float *ws_scale;           // [slot][rg][rows_grp] scales of those rows: value = scale * int16
     // write-back folded into the call: the tree tokens' K/V come from these dense tensors [B, T, Hkv, D] (element
     // strides), the KV pass reads them there and the merge pass copies them behind the prefix in the caches
     const void *kn, *vn;
@@ -113,8 +114,8 @@ struct TAProblem {
     TAParams p;
     TAPlan plan;
     size_t ws_o_bytes, ws_lse_bytes, ws_bytes;
-    size_t ws_scale_off;       // byte offset of the row scales inside the workspace (in the half of the ws_o area that
-                               // 16-bit partials leave unused); meaningful when p.part_q15
+    size_t ws_ls_off;          // byte offset of ws_lse inside the workspace: behind the partial outputs, or with
+                               // part_q15 inside the half of their area that 16-bit rows leave unused
 };
 
 // Host logic shared by every entry point (ta_host.cpp).  None of these touches a device.

@@ -976,13 +976,12 @@ def _plan_of(w, **opts):
                              d["out"], d["lse"], scale=w.scale, **opts)
 
 
-@pytest.mark.parametrize("kernel", [0, MFMA_BASIC])
+@pytest.mark.parametrize("kernel", [0, MFMA_BASIC, GENERIC])
 @pytest.mark.parametrize("rows", [32, 256])
 def test_both_formats_of_the_partial_results(kernel, rows):
-    """The matrix-core kernels hand their partial results to the merge pass as fp32 or, where a workgroup writes many
-    rows, as 16-bit fixed point with one scale per row.  Both against the oracle on both kernels, with forced splits so
-    that every list has several partials, and with one KV head's values 64 times smaller than the other's (the scale
-    is per row)."""
+    """The matrix-core kernels hand their partial results to the merge pass as 16-bit fixed point with one scale per
+    row, the scalar kernel as fp32.  Both against the oracle, with forced splits so that every list has several
+    partials, and with one KV head's values 64 times smaller than the other's (the scale is per row)."""
     rng = np.random.default_rng(rows)
     T, Hq, Hkv = (8, 8, 2) if rows == 32 else (64, 8, 2)
     B = 5
@@ -994,7 +993,7 @@ def test_both_formats_of_the_partial_results(kernel, rows):
     keep = (small & 0x7f80) > (6 << 7)
     v[:, 1] = np.where(keep, small - (6 << 7), small & 0x8000).astype(np.uint16)
     plan = _plan_of(w, kernel=kernel)
-    assert plan["partials_q15"] == (1 if rows == 256 else 0), plan
+    assert plan["partials_q15"] == (0 if kernel == GENERIC else 1), plan
     _check(w, "partials rows=%d kernel=%d" % (rows, kernel), kernel=kernel)
     _check(w, "partials rows=%d kernel=%d, 37 shares" % (rows, kernel), kernel=kernel, num_splits=37)
 

@@ -275,9 +275,8 @@ def test_the_binding_is_the_first_thing_a_process_uses():
 
 
 def test_calls_on_two_streams_each_with_a_workspace_of_its_own():
-    """Calls that overlap in time bring their own workspaces: two different batches (one with 16-bit partial results,
-    one with fp32 ones) launched alternately on two streams, twenty times each without a synchronisation in between,
-    both against the oracle."""
+    """Calls that overlap in time bring their own workspaces: two different batches launched alternately on two
+    streams, twenty times each without a synchronisation in between, both against the oracle."""
     import torch
     from paper_2508_08192_amd import treeattn as ta
     rng = np.random.default_rng(99)
@@ -294,7 +293,6 @@ def test_calls_on_two_streams_each_with_a_workspace_of_its_own():
                                  d["out"], d["lse"])
         plans.append(plan)
         wss.append(torch.empty(plan["workspace_bytes"], dtype=torch.uint8, device="cuda"))
-    assert plans[0]["partials_q15"] == 1 and plans[1]["partials_q15"] == 0
     _announce("two streams, two workspaces")
     torch.cuda.synchronize()
     for rep in range(20):
