@@ -110,22 +110,36 @@ __device__ __forceinline__ void ta_wg_range(const TAParams &p, int total, int w,
     const int share = ta_share(p, total);
     const int floor_share = p.min_q > TA_EVEN_CUT_FROM ? p.min_q : TA_EVEN_CUT_FROM;
     const int n_act = (int64_t)p.n_wg * floor_share <= total ? p.n_wg : (total + share - 1) / share;
-    t = w >= n_act ? total : (int)((int64_t)w * total / n_act);
-    t_end = w + 1 >= n_act ? total : (int)((int64_t)(w + 1) * total / n_act);
+    // floor(k * total / n_act) = k * q + floor(k * r / n_act) with total = q * n_act + r: 32-bit divisions (k * r stays
+    // below n_act squared) instead of two 64-bit ones, which cost every workgroup most of a microsecond at its start
+    if (n_act <= 0xffff) {
+        const unsigned n = n_act > 0 ? (unsigned)n_act : 1u, q = (unsigned)total / n, r = (unsigned)total - q * n;
+        t = w >= n_act ? total : (int)((unsigned)w * q + (unsigned)w * r / n);
+        t_end = w + 1 >= n_act ? total : (int)((unsigned)(w + 1) * q + (unsigned)(w + 1) * r / n);
+    } else {
+        t = w >= n_act ? total : (int)((int64_t)w * total / n_act);
+        t_end = w + 1 >= n_act ? total : (int)((int64_t)(w + 1) * total / n_act);
+    }
 }
 
-// Request whose tile lists contain global tile t (0 <= t < Hkv * cum[B]).
+// Request whose tile lists contain global tile t (0 <= t < Hkv * cum[B]): the number of requests whose lists end at
+// or before t (cum does not decrease), counted 64 requests at a time by the lanes of each wave -- one LDS read and a
+// ballot instead of a binary search's chain of dependent reads.  Every lane of the wave calls this together.
 __device__ __forceinline__ int ta_find_request(const TAParams &p, const int *cum, int t)
 {
-    int lo = 0, hi = p.B;                 // invariant: Hkv*cum[lo] <= t < Hkv*cum[hi]
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if ((int64_t)p.Hkv * cum[mid] <= t)
-            lo = mid;
-        else
-            hi = mid;
+    int x = threadIdx.x;
+    asm volatile("" : "+v"(x));           // derived here: a caller short of registers must not keep the lane id alive
+    const int lane = x & (TA_WAVE - 1);
+    int b = 0;
+    for (int base = 0; base < p.B; base += TA_WAVE) {
+        const int idx = base + lane;
+        const bool before = idx < p.B && (int64_t)p.Hkv * cum[idx + 1] <= t;
+        const int n = __popcll(__ballot(before));
+        b += n;
+        if (n < TA_WAVE)
+            break;
     }
-    return lo;
+    return b;
 }
 
 // The KV pass tells the merge pass which workgroups hold partial results of list (b, g): the owner of the list's

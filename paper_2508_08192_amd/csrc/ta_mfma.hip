@@ -534,6 +534,7 @@ __global__ __launch_bounds__(NT) void ta_mfma_kv_kernel(TAParams p)
 }
 
 #define PP_PAGES 2048                             // page ids cached in LDS per span of tiles
+#define SP_OWN_FIRST 32                           // see issue_first in ta_mfma_sp_kernel
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -825,8 +826,23 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             if (takeover >= 0)
                 issue_rows(ti, ks, vs, takeover);
         };
+        // The first three tiles of a span of up to SP_OWN_FIRST tiles are different: every wave loads its own rows of
+        // them, the waves with query rows too -- they have nothing else to do yet, and the helper waves, which would
+        // issue twice the loads, are what the first tile waits for (half a microsecond per item; p5 20.2 -> 19.6 us,
+        // p1 33.6 -> 33.0).  Spans of a hundred tiles and more ran 1.5 % slower with it (uniform 16k lists: 168 ->
+        // 170.5 us, in their steady state), so they keep the helpers' loads from the first tile on.
+        auto issue_first = [&](int ti, int ks, int vs) { issue_rows(ti, ks, vs, wave); };
+        auto wait_first = [&](int tiles_in_flight) {           // four loads per tile in every wave; Q is older
+            if (tiles_in_flight >= 2)
+                vm_wait<8>();
+            else if (tiles_in_flight == 1)
+                vm_wait<4>();
+            else
+                vm_wait<0>();
+        };
         // all but the loads of the youngest tiles_in_flight tiles are done (four loads per tile and set of rows; a
-        // wave that loads nothing has only its Q loads and earlier stores to wait for)
+        // wave that loads nothing has only its first tiles, its Q loads and earlier stores to wait for).  The youngest
+        // tiles here are always ones that issue_tile has loaded.
         auto wait_loads = [&](int tiles_in_flight) {
             if (shift_loads && active) {
                 vm_wait<0>();
@@ -893,8 +909,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
             }
             // ring positions: next slots to load into, K slot of tile i+1, V slots of tiles i and i-1
             int ik = 0, iv = 0, issued = 0;
+            const bool own_first = ns <= SP_OWN_FIRST;
             for (; issued < min(ns, 3); ++issued) {
-                issue_tile(s0 + issued, ik, iv);
+                if (own_first)
+                    issue_first(s0 + issued, ik, iv);
+                else
+                    issue_tile(s0 + issued, ik, iv);
                 ik = ik == SP_RK - 1 ? 0 : ik + 1;
                 iv = iv == SP_RV - 1 ? 0 : iv + 1;
             }
@@ -907,7 +927,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                     break;
                 }
             }
-            wait_loads(issued - 1);                            // tile 0 and Q have landed
+            if (own_first)
+                wait_first(issued - 1);                        // tile 0 and Q have landed
+            else
+                wait_loads(issued - 1);
             lds_barrier();
             if (active)
                 sp_s_first(0u);
@@ -915,8 +938,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_num_vgpr(16))) void ta_m
                 const unsigned long long vm = tile_mask(s0);
                 sp_mask_A((uint32_t)vm, (uint32_t)(vm >> 32));
             }
-            if (ns > 1)
-                wait_loads(issued - 2);                        // tile 1 has landed
+            if (ns > 1 && own_first)
+                wait_first(issued - 2);                        // tile 1 has landed
+            else if (ns > 1)
+                wait_loads(issued - 2);
             lds_barrier();
 
             int kn = 1, vp = SP_RV - 1;                        // K slot of tile i+1, V slot of tile i-1
