@@ -16,6 +16,30 @@ __device__ __forceinline__ float load_elem(const void *base, int64_t idx)
     return ((const float *)base)[idx];
 }
 
+// The same in two steps -- the bits as they lie in memory, and their value -- for loads that stay in flight while
+// other work goes on: a conversion next to the load would wait for it.
+template <bool BF16>
+__device__ __forceinline__ uint32_t load_bits(const void *base, int64_t row, uint32_t d)   // element d of the row
+{
+    // (row start and column apart: with a wave-uniform row the address is a scalar base plus a 32-bit lane offset)
+    if (BF16)
+        return ((const uint16_t *)base + row)[d];
+    return ((const uint32_t *)base + row)[d];
+}
+
+template <bool BF16>
+__device__ __forceinline__ float bits_value(uint32_t x)
+{
+    return BF16 ? ta_bf16_to_f32((uint16_t)x) : __uint_as_float(x);
+}
+
+// Barrier for data exchanged through LDS only: this wave's LDS traffic has landed, its global loads stay in flight
+// (__syncthreads would wait for them as well).
+__device__ __forceinline__ void gen_lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 
 // KV pass for any shape.  A workgroup walks its share of a (request, KV head) tile list once per block of
 // GEN_WAVES * RB query rows: every tile (64 tokens; section 3.1: prefix tiles are mask-free, the tree tile
@@ -23,15 +47,18 @@ __device__ __forceinline__ float load_elem(const void *base, int64_t idx)
 // updates its rows -- lanes are the tile's tokens for the scores, then head-dim columns for the weighted sum
 // of V.  Running max / sum per row (base-2 domain).  Tokens that do not exist are staged as zeros.
 // DCH = 64-column chunks of the head dimension a lane carries (1, 2 or 4).  A wave carries RB query rows at a time
-// and stages TB tokens per round trip; with one chunk the registers allow eight rows and all sixteen tokens of the
-// wave at once, which halves the passes over the tile list and the round trips per tile of the small-head shapes.
+// (eight with one chunk, which halves the passes over the tile list of the small-head shapes) and stages sixteen
+// tokens of every tile; their loads go out one tile ahead, so that a tile's global round trip runs under the
+// arithmetic of the tile before it, and Q's under the first tile's.
 template <bool BF16, int DCH>
 __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
 {
-    constexpr int RB = DCH == 1 ? 8 : 4, TB = DCH == 1 ? 16 : 8;
+    constexpr int RB = DCH == 1 ? 8 : 4;
     extern __shared__ int smem_i[];
     int *cum = smem_i;                                                   // [B + 1]
-    unsigned long long *masks = (unsigned long long *)(cum + ((p.B + 2) & ~1));   // [64]
+    int *lens = cum + ((p.B + 2) & ~1);                                  // [B] prefix lengths
+    int *starts = lens + ((p.B + 1) & ~1);                               // [B] window starts
+    unsigned long long *masks = (unsigned long long *)(starts + ((p.B + 1) & ~1));   // [64]
     int *flag = (int *)(masks + TA_MAX_TREE);                            // flag[4], then par_s[TA_MAX_TREE]
     int *par_s = flag + 4;
     float *qrow = (float *)(par_s + TA_MAX_TREE);                        // [GEN_WAVES * RB][D]
@@ -39,10 +66,11 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
     float *vt = kt + TA_TILE * (p.D + 1);                                // [64][D]
     const int ldk = p.D + 1;
 
-    ta_build_schedule(p, cum);
+    ta_build_schedule(p, cum, lens, starts);
     const int total = p.Hkv * cum[p.B];
     const int w = blockIdx.x, rg = blockIdx.y;
-    const int lane = threadIdx.x % TA_WAVE, wave = threadIdx.x / TA_WAVE;
+    // (the wave index as a scalar: the addresses of a wave's rows and tokens are then scalar arithmetic)
+    const int lane = threadIdx.x % TA_WAVE, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / TA_WAVE);
     int t, t_end;
     ta_wg_range(p, total, w, t, t_end);
     const int rows_here = min(p.rows_grp, p.rows - rg * p.rows_grp);
@@ -61,8 +89,8 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
         }
         const int slot = w + b * p.Hkv + g;
         ta_note_owner(p, b, g, w, j0, j1, n_b);
-        const int L = p.seq_lens[(int64_t)b * p.sl_s];
-        const int S = ta_kv_start(p, b);
+        const int L = lens[b];                                     // read once, by the schedule
+        const int S = starts[b];
         bool poison = !ta_request_ok(p, L, S);
         const int tile0 = poison ? 0 : S / TA_TILE;               // absolute index of the list's first prefix tile
         if (poison && threadIdx.x == 0)
@@ -129,60 +157,82 @@ __global__ __launch_bounds__(GEN_THREADS) void ta_generic_kv_kernel(TAParams p)
                 }
                 continue;
             }
+            // Q of the wave's rows: loaded here, written to LDS (rows only this wave reads) once the first tile's loads
+            // are on their way as well.
+            uint32_t qbits[RB][DCH];
 #pragma unroll
             for (int i = 0; i < RB; ++i) {
+#pragma unroll
+                for (int c = 0; c < DCH; ++c)
+                    qbits[i][c] = 0u;
                 if (!rok[i])
                     continue;
                 const int R = rg * p.rows_grp + rr[i];
-                const int node = R / p.G, h = g * p.G + R % p.G;
+                const int node = (int)__umulhi((uint32_t)R << 8, p.g_magic);          // R / G
+                const int h = g * p.G + R - node * p.G;
                 const int64_t qoff = (int64_t)b * p.q_sb + (int64_t)node * p.q_st + (int64_t)h * p.q_sh;
-                float *qs = qrow + (wave * RB + i) * p.D;
-                for (int d = lane; d < p.D; d += TA_WAVE)
-                    qs[d] = load_elem<BF16>(p.q, qoff + d);
+#pragma unroll
+                for (int c = 0; c < DCH; ++c)
+                    if (lane + c * TA_WAVE < p.D)
+                        qbits[i][c] = load_bits<BF16>(p.q, qoff, (uint32_t)(lane + c * TA_WAVE));
                 mask[i] = has_tree_tile ? masks[p.q_off + node] : 0ull;
             }
-            for (int j = j0; j < j1; ++j) {
+            // Wave w stages tokens 16w .. 16w+15 of every tile: their loads are issued a tile ahead and stay in flight
+            // while the tile before is computed.  Tokens that do not exist are staged as zeros.
+            constexpr int TOK = TA_TILE / GEN_WAVES;
+            uint32_t kbits[TOK][DCH], vbits[TOK][DCH];
+            auto load_tile = [&](int j) {
                 const bool tree_tile = (j == n_b - 1);
-                __syncthreads();                                     // the previous tile has been consumed
-                // wave w stages tokens 16w .. 16w+15, TB at a time with all their loads in flight together
-                for (int tk0 = wave * (TA_TILE / GEN_WAVES); tk0 < (wave + 1) * (TA_TILE / GEN_WAVES); tk0 += TB) {
-                    float kvv[TB][DCH], vvv[TB][DCH];
 #pragma unroll
-                    for (int u = 0; u < TB; ++u) {
-                        const int tk = tk0 + u;
-                        const int pos = tree_tile ? L + tk : (tile0 + j) * TA_TILE + tk;
-                        const bool exists = tree_tile ? tk < p.T : (pos >= S && pos < L);
-                        // with the write-back folded in, the tree tokens come from the dense tensors of this step
-                        const bool from_new = tree_tile && p.kn != nullptr;
-                        const void *kb = from_new ? p.kn : p.k, *vb = from_new ? p.vn : p.v;
-                        int64_t koff = 0, voff = 0;
-                        if (exists && from_new) {
-                            koff = (int64_t)b * p.kn_sb + (int64_t)tk * p.kn_st + (int64_t)g * p.kn_sh;
-                            voff = (int64_t)b * p.vn_sb + (int64_t)tk * p.vn_st + (int64_t)g * p.vn_sh;
-                        } else if (exists) {
-                            koff = ta_cache_offset(p, b, g, pos, p.k_sp, p.k_sh, p.k_ss);
-                            voff = ta_cache_offset(p, b, g, pos, p.v_sp, p.v_sh, p.v_ss);
-                        }
-#pragma unroll
-                        for (int c = 0; c < DCH; ++c) {
-                            const int d = lane + c * TA_WAVE;
-                            const bool ld = exists && d < p.D && koff >= 0 && voff >= 0;
-                            kvv[u][c] = ld ? load_elem<BF16>(kb, koff + d) : 0.f;
-                            vvv[u][c] = ld ? load_elem<BF16>(vb, voff + d) : 0.f;
-                        }
+                for (int u = 0; u < TOK; ++u) {
+                    const int tk = wave * TOK + u;
+                    const int pos = tree_tile ? L + tk : (tile0 + j) * TA_TILE + tk;
+                    const bool exists = tree_tile ? tk < p.T : (pos >= S && pos < L);
+                    // with the write-back folded in, the tree tokens come from the dense tensors of this step
+                    const bool from_new = tree_tile && p.kn != nullptr;
+                    const void *kb = from_new ? p.kn : p.k, *vb = from_new ? p.vn : p.v;
+                    int64_t koff = 0, voff = 0;
+                    if (exists && from_new) {
+                        koff = (int64_t)b * p.kn_sb + (int64_t)tk * p.kn_st + (int64_t)g * p.kn_sh;
+                        voff = (int64_t)b * p.vn_sb + (int64_t)tk * p.vn_st + (int64_t)g * p.vn_sh;
+                    } else if (exists) {
+                        koff = ta_cache_offset(p, b, g, pos, p.k_sp, p.k_sh, p.k_ss);
+                        voff = ta_cache_offset(p, b, g, pos, p.v_sp, p.v_sh, p.v_ss);
                     }
 #pragma unroll
-                    for (int u = 0; u < TB; ++u)
-#pragma unroll
-                        for (int c = 0; c < DCH; ++c) {
-                            const int d = lane + c * TA_WAVE;
-                            if (d < p.D) {
-                                kt[(tk0 + u) * ldk + d] = kvv[u][c];
-                                vt[(tk0 + u) * p.D + d] = vvv[u][c];
-                            }
-                        }
+                    for (int c = 0; c < DCH; ++c) {
+                        const int d = lane + c * TA_WAVE;
+                        const bool ld = exists && d < p.D && koff >= 0 && voff >= 0;
+                        kbits[u][c] = ld ? load_bits<BF16>(kb, koff, (uint32_t)d) : 0u;
+                        vbits[u][c] = ld ? load_bits<BF16>(vb, voff, (uint32_t)d) : 0u;
+                    }
                 }
-                __syncthreads();
+            };
+            load_tile(j0);
+            for (int j = j0; j < j1; ++j) {
+                const bool tree_tile = (j == n_b - 1);
+                gen_lds_barrier();                                   // the previous tile has been consumed
+#pragma unroll
+                for (int u = 0; u < TOK; ++u)
+#pragma unroll
+                    for (int c = 0; c < DCH; ++c) {
+                        const int d = lane + c * TA_WAVE;
+                        if (d < p.D) {
+                            kt[(wave * TOK + u) * ldk + d] = bits_value<BF16>(kbits[u][c]);
+                            vt[(wave * TOK + u) * p.D + d] = bits_value<BF16>(vbits[u][c]);
+                        }
+                    }
+                if (j == j0) {
+#pragma unroll
+                    for (int i = 0; i < RB; ++i)
+#pragma unroll
+                        for (int c = 0; c < DCH; ++c)
+                            if (rok[i] && lane + c * TA_WAVE < p.D)
+                                qrow[(wave * RB + i) * p.D + lane + c * TA_WAVE] = bits_value<BF16>(qbits[i][c]);
+                }
+                gen_lds_barrier();
+                if (j + 1 < j1)
+                    load_tile(j + 1);
                 // Scores of the wave's rows against the lane's token: one LDS read of K serves all rows; q[d]
                 // comes out of the lane that holds it as a scalar operand.
                 float qreg[RB][DCH], dot[RB];
@@ -264,7 +314,7 @@ template <bool BF16, int DCH>
 static hipError_t launch_generic_instance(const TAParams &p, hipStream_t stream, bool *attr_done)
 {
     constexpr int RB = DCH == 1 ? 8 : 4;
-    const size_t smem = sizeof(int) * ((p.B + 2) & ~1) + sizeof(unsigned long long) * TA_MAX_TREE + 16 +
+    const size_t smem = sizeof(int) * (((p.B + 2) & ~1) + 2 * ((p.B + 1) & ~1)) + sizeof(unsigned long long) * TA_MAX_TREE + 16 +
                         sizeof(int) * TA_MAX_TREE +
                         sizeof(float) * ((size_t)GEN_WAVES * RB * p.D + (size_t)TA_TILE * (2 * p.D + 1));
     if (smem > 160 * 1024 - 512)
