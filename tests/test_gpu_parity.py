@@ -779,6 +779,21 @@ def test_very_large_batch_falls_back_to_the_register_staged_kernel():
     _check(w, "B=2100 with window starts", kernel=MFMA)
 
 
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA, MFMA_BASIC])
+@pytest.mark.parametrize("B", [64, 65, 129, 200])
+def test_batches_around_multiples_of_a_wave_of_requests(kernel, B):
+    """A workgroup finds the request of its first tile by counting, 64 requests at a time, the lists that end before
+    it: batches of exactly one wave of requests, one more, and several waves with a ragged last one, with lengths that
+    put list ends inside and between the workgroups' shares (some requests have no prefix at all)."""
+    rng = np.random.default_rng(1000 + B)
+    T = 4
+    lens = rng.integers(0, 300, size=B)
+    lens[rng.integers(0, B, size=B // 8)] = 0
+    w = W.make_workload("waves_of_requests", B=B, T=T, Hq=4, Hkv=2, D=128, seq_lens=lens, trees=W.chain_tree(T),
+                        page_size=64, dtype="bf16", seed=8800 + B)
+    _check(w, "B=%d kernel=%d" % (B, kernel), kernel=kernel)
+
+
 def test_empty_batch_and_no_lse():
     import torch
     from paper_2508_08192_amd import treeattn as ta
